@@ -1,0 +1,177 @@
+"""ctypes front end of the C oracle (oracle/gwq_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Every function takes and returns numpy arrays in host memory.  Nothing here is imported by
+the GPU package; only tests, the smoke check and the benchmark's CPU-baseline leg use it.
+The arithmetic lives in the C file; this module only marshals arguments.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build_oracle
+
+GROUP = 128
+
+
+def _load():
+    lib = ctypes.CDLL(build_oracle.build(force=False))
+    i64, u32, i32, vp = ctypes.c_int64, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p
+    lib.gwq_oracle_half_to_double.restype = ctypes.c_double
+    lib.gwq_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+    lib.gwq_oracle_outlier_count.restype = i64
+    lib.gwq_oracle_outlier_count.argtypes = [i64, i64, u32]
+    lib.gwq_oracle_select.argtypes = [vp, i32, i64, i64, u32, vp]
+    lib.gwq_oracle_csr.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+    lib.gwq_oracle_quant_group.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.gwq_oracle_pack_codes.argtypes = [vp, i64, i64, i32, vp]
+    lib.gwq_oracle_unpack_codes.argtypes = [vp, i64, i64, i32, vp]
+    lib.gwq_oracle_pack.argtypes = [vp, vp, i32, i64, i64, i32, u32, vp, vp, vp, vp, vp, vp, vp]
+    lib.gwq_oracle_decode.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed with oracle status {rc}")
+
+
+def _f16_bits(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        return a.view(np.uint16)
+    if a.dtype == np.uint16:
+        return a
+    raise TypeError("expected float16 (or its uint16 bit patterns)")
+
+
+def _score(score):
+    score = np.ascontiguousarray(score)
+    if score.dtype == np.float32:
+        return score, 0
+    if score.dtype == np.float16:
+        return score, 1
+    raise TypeError("score must be float32 or float16")
+
+
+def words_per_group(bits):
+    return {4: 16, 3: 13}[bits]
+
+
+def outlier_count(N, K, ppm):
+    return int(_lib.gwq_oracle_outlier_count(N, K, ppm))
+
+
+def half_to_double(bits):
+    return float(_lib.gwq_oracle_half_to_double(int(bits)))
+
+
+def select(score, ppm):
+    score, is16 = _score(score)
+    N, K = score.shape
+    mask = np.empty((N, K), np.uint8)
+    _chk(_lib.gwq_oracle_select(_p(score), is16, N, K, ppm, _p(mask)), "select")
+    return mask
+
+
+def csr(W, mask):
+    Wb = _f16_bits(W)
+    N, K = Wb.shape
+    mask = np.ascontiguousarray(mask, np.uint8)
+    nnz = int(mask.sum())
+    row_ptr = np.empty(N + 1, np.int32)
+    col_idx = np.empty(nnz, np.uint16)
+    val = np.empty(nnz, np.uint16)
+    _chk(_lib.gwq_oracle_csr(_p(Wb), _p(mask), N, K, _p(row_ptr), _p(col_idx), _p(val)), "csr")
+    return row_ptr, col_idx, val
+
+
+def quant_group(w, mask, bits):
+    wb = _f16_bits(w)
+    mask = np.ascontiguousarray(mask, np.uint8)
+    s = np.zeros(1, np.uint16)
+    z = np.zeros(1, np.uint8)
+    q = np.empty(wb.size, np.uint8)
+    _chk(_lib.gwq_oracle_quant_group(_p(wb), _p(mask), wb.size, bits, _p(s), _p(z), _p(q)), "quant_group")
+    return int(s[0]), int(z[0]), q
+
+
+def pack_codes(codes, bits):
+    codes = np.ascontiguousarray(codes, np.uint8)
+    N, K = codes.shape
+    out = np.empty((N, K // GROUP, words_per_group(bits)), np.uint32)
+    _chk(_lib.gwq_oracle_pack_codes(_p(codes), N, K, bits, _p(out)), "pack_codes")
+    return out
+
+
+def unpack_codes(qweight, N, K, bits):
+    qweight = np.ascontiguousarray(qweight, np.uint32)
+    out = np.empty((N, K), np.uint8)
+    _chk(_lib.gwq_oracle_unpack_codes(_p(qweight), N, K, bits, _p(out)), "unpack_codes")
+    return out
+
+
+@dataclass
+class Packed:
+    N: int
+    K: int
+    bits: int
+    ppm: int
+    qweight: np.ndarray   # uint32 [N, K/128, words_per_group]
+    scales: np.ndarray    # uint16 (FP16 bits) [N, K/128]
+    zeros: np.ndarray     # uint8 [N, K/128]
+    row_ptr: np.ndarray   # int32 [N+1]
+    col_idx: np.ndarray   # uint16 [k_out]
+    out_val: np.ndarray   # uint16 (FP16 bits) [k_out]
+    mask: np.ndarray      # uint8 [N, K] outlier indicator (not part of the stored format)
+
+
+def pack(W, score, bits, ppm=10000):
+    Wb = _f16_bits(W)
+    score, is16 = _score(score)
+    N, K = Wb.shape
+    assert score.shape == (N, K)
+    k_out = outlier_count(N, K, ppm)
+    gpr = K // GROUP
+    P = Packed(N, K, bits, ppm,
+               np.empty((N, gpr, words_per_group(bits)), np.uint32),
+               np.empty((N, gpr), np.uint16), np.empty((N, gpr), np.uint8),
+               np.empty(N + 1, np.int32), np.empty(k_out, np.uint16), np.empty(k_out, np.uint16),
+               np.empty((N, K), np.uint8))
+    _chk(_lib.gwq_oracle_pack(_p(Wb), _p(score), is16, N, K, bits, ppm, _p(P.qweight), _p(P.scales),
+                              _p(P.zeros), _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(P.mask)),
+         "pack")
+    return P
+
+
+def decode(P):
+    out = np.empty((P.N, P.K), np.float64)
+    _chk(_lib.gwq_oracle_decode(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros),
+                                _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(out)), "decode")
+    return out
+
+
+def linear_f64(P, X, rows=None):
+    """Y[M, n_rows] in fp64; rows=None gives all N output channels."""
+    Xb = _f16_bits(X)
+    M, K = Xb.shape
+    assert K == P.K
+    if rows is None:
+        rows_arr, n_rows = None, P.N
+    else:
+        rows_arr = np.ascontiguousarray(rows, np.int32)
+        n_rows = rows_arr.size
+    Y = np.empty((M, n_rows), np.float64)
+    _chk(_lib.gwq_oracle_linear_f64(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros),
+                                    _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(Xb), M,
+                                    _p(rows_arr), n_rows, _p(Y)), "linear_f64")
+    return Y

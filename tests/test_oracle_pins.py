@@ -1,0 +1,441 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test names the passage of the GWQ paper the checked function follows (Sec. 3.2, Eq. 6-10)
+and pins it to brute force, exact-rational arithmetic, a library routine or a hand-worked case.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import gwq_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- helpers
+
+def half_fraction(bits):
+    """Exact rational value of a finite FP16 pattern, from the format definition."""
+    sign = -1 if bits >> 15 else 1
+    e, f = (bits >> 10) & 31, bits & 1023
+    assert e != 31
+    if e == 0:
+        return sign * Fraction(f, 1 << 24)
+    return sign * Fraction(f | 1024) * Fraction(2) ** (e - 25)
+
+
+def round_half_even(x: Fraction) -> int:
+    return round(x)  # Python rounds Fractions half to even
+
+
+def clamp(v, lo, hi):
+    return max(lo, min(hi, v))
+
+
+ALL_POS_HALF = np.arange(1, 0x7C00, dtype=np.uint16)            # every positive finite FP16
+ALL_POS_HALF_VAL = ALL_POS_HALF.view(np.float16).astype(np.float64)
+
+
+def brute_scale(R: Fraction, maxq: int) -> int:
+    """Smallest FP16 pattern s with s*maxq >= R, by scanning every positive finite FP16 value."""
+    ok = ALL_POS_HALF_VAL * maxq >= float(R)     # exact: R is a multiple of 2^-24 below 2^17
+    return int(ALL_POS_HALF[np.argmax(ok)])
+
+
+def exact_group(w_bits, mask, bits):
+    """Group quantiser (Eq. 6, 7, 9) in exact rational arithmetic."""
+    maxq = (1 << bits) - 1
+    vals = [half_fraction(int(b)) for b in w_bits]
+    keep = [v for v, m in zip(vals, mask) if not m]
+    mn = min([Fraction(0)] + keep)
+    mx = max([Fraction(0)] + keep)
+    R = mx - mn
+    if R == 0:
+        s_bits, z = 0x3C00, 0
+    else:
+        s_bits = brute_scale(R, maxq)
+        z = clamp(round_half_even(-mn / half_fraction(s_bits)), 0, maxq)
+    s = half_fraction(s_bits)
+    q = [z if m else clamp(round_half_even(v / s) + z, 0, maxq) for v, m in zip(vals, mask)]
+    return s_bits, z, q
+
+
+def py_positions(bits):
+    """(word, shift) of every k_local in a 128-group, written from the layout statement."""
+    pos = []
+    for kl in range(128):
+        b, r = divmod(kl, 32)
+        if bits == 4:
+            j, t = divmod(r, 8)
+            pos.append((4 * b + j, 16 * (t & 1) + 4 * (t >> 1)))
+        elif r < 30:
+            i, t = divmod(r, 10)
+            pos.append((3 * b + i, 16 * (t & 1) + 3 * (t >> 1)))
+        else:
+            pos.append((12, 16 * (r - 30) + 3 * b))
+    return pos
+
+
+def py_unpack(qweight, N, K, bits):
+    pos = py_positions(bits)
+    qw = qweight.reshape(N, K // 128, -1)
+    out = np.empty((N, K // 128, 128), np.uint8)
+    for kl, (w, sh) in enumerate(pos):
+        out[:, :, kl] = (qw[:, :, w] >> np.uint32(sh)) & np.uint32((1 << bits) - 1)
+    return out.reshape(N, K)
+
+
+def numpy_select(score, k_out):
+    """Full sort by (|score| bits descending, flat index ascending); first k_out."""
+    s32 = score.astype(np.float32)
+    key = (s32.view(np.uint32) & np.uint32(0x7FFFFFFF)).ravel().astype(np.int64)
+    idx = np.arange(key.size)
+    order = np.lexsort((idx, -key))
+    mask = np.zeros(key.size, np.uint8)
+    mask[order[:k_out]] = 1
+    return mask.reshape(score.shape)
+
+
+def random_w(rng, shape, scale=0.02):
+    return (scale * rng.standard_t(4, size=shape)).astype(np.float16)
+
+
+# ----------------------------------------------------------------------------- FP16 decode
+
+def test_half_to_double_all_patterns():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([orc.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+# ----------------------------------------------------------------------------- Eq. 8: selection
+
+def test_outlier_count_is_ceil_of_fraction():
+    assert orc.outlier_count(4096, 4096, 10000) == 167773          # 1 % of 2^24 = 167772.16
+    assert orc.outlier_count(11008, 4096, 10000) == 450888
+    assert orc.outlier_count(100, 100, 10000) == 100               # exact, no rounding up
+    assert orc.outlier_count(7, 128, 0) == 0
+    assert orc.outlier_count(7, 128, 1000000) == 7 * 128
+    assert orc.outlier_count(3, 128, 1) == 1                        # any positive fraction keeps one
+
+
+@pytest.mark.parametrize("case", ["random", "all_equal", "two_valued", "fp16", "signed_zero",
+                                  "nan_inf", "negatives"])
+@pytest.mark.parametrize("ppm", [0, 1, 10000, 250000, 1000000])
+def test_select_matches_full_sort(case, ppm):
+    rng = np.random.default_rng(hash(case) % 1000 + ppm)
+    N, K = 8, 128
+    if case == "random":
+        S = rng.standard_normal((N, K)).astype(np.float32)
+    elif case == "all_equal":
+        S = np.full((N, K), 0.5, np.float32)
+    elif case == "two_valued":
+        S = rng.choice(np.array([0.25, -0.75], np.float32), size=(N, K))
+    elif case == "fp16":
+        S = (rng.standard_normal((N, K)) * 0.01).astype(np.float16)   # few distinct values: ties
+        S = (S.astype(np.float32) * 0 + np.round(S.astype(np.float32) * 200) / 200).astype(np.float16)
+    elif case == "signed_zero":
+        S = rng.choice(np.array([0.0, -0.0, 1e-30, -1e-30], np.float32), size=(N, K))
+    elif case == "nan_inf":
+        S = rng.standard_normal((N, K)).astype(np.float32)
+        S.ravel()[rng.choice(N * K, 6, replace=False)] = [np.nan, np.inf, -np.inf, np.nan, 3e38, -3e38]
+    else:
+        S = -np.abs(rng.standard_normal((N, K))).astype(np.float32)
+    k_out = orc.outlier_count(N, K, ppm)
+    got = orc.select(S, ppm)
+    want = numpy_select(S, k_out)
+    assert int(got.sum()) == k_out
+    assert np.array_equal(got, want)
+
+
+def test_select_invariants_and_tie_rule():
+    rng = np.random.default_rng(5)
+    N, K = 16, 256
+    S = (np.round(rng.standard_normal((N, K)) * 4) / 4).astype(np.float32)   # heavy ties
+    ppm = 100000
+    k_out = orc.outlier_count(N, K, ppm)
+    mask = orc.select(S, ppm).ravel().astype(bool)
+    a = np.abs(S).ravel()
+    assert mask.sum() == k_out
+    thr = a[mask].min()
+    assert a[~mask].max() <= thr
+    tie = a == thr
+    sel_tie = np.flatnonzero(tie & mask)
+    unsel_tie = np.flatnonzero(tie & ~mask)
+    assert unsel_tie.size > 0 and sel_tie.size > 0       # the case really has a tie at the cut
+    assert sel_tie.max() < unsel_tie.min()               # ties go to the lowest flat index
+
+
+def test_select_rejects_bad_ppm():
+    with pytest.raises(RuntimeError):
+        orc.select(np.zeros((2, 128), np.float32), 1000001)
+
+
+# ----------------------------------------------------------------------------- CSR
+
+def test_csr_invariants():
+    rng = np.random.default_rng(11)
+    N, K = 24, 384
+    W = random_w(rng, (N, K))
+    W[3, 7] = np.float16(-0.0)
+    S = rng.random((N, K)).astype(np.float32)
+    S[3, 7] = 9.0
+    mask = orc.select(S, 20000)
+    row_ptr, col, val = orc.csr(W, mask)
+    assert row_ptr[0] == 0 and row_ptr[-1] == mask.sum() and np.all(np.diff(row_ptr) >= 0)
+    rebuilt = np.zeros_like(mask)
+    for n in range(N):
+        c = col[row_ptr[n]:row_ptr[n + 1]].astype(np.int64)
+        assert np.all(np.diff(c) > 0)
+        rebuilt[n, c] = 1
+        assert np.array_equal(val[row_ptr[n]:row_ptr[n + 1]], W.view(np.uint16)[n, c])
+    assert np.array_equal(rebuilt, mask)
+    assert val[np.flatnonzero(col[row_ptr[3]:row_ptr[4]] == 7)[0] + row_ptr[3]] == 0x8000  # -0 kept
+
+
+# ----------------------------------------------------------------------------- Eq. 6, 7, 9: one group
+
+def _golden_groups():
+    rows = []
+    with open(os.path.join(GOLDEN, "quant_group_examples.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            b, w, m, s, z, q = [x.strip() for x in line.split(";")]
+            rows.append((int(b), [float(x) for x in w.split()], [int(x) for x in m.split()],
+                         int(s, 16), int(z), [int(x) for x in q.split()]))
+    return rows
+
+
+@pytest.mark.parametrize("row", _golden_groups())
+def test_quant_group_hand_examples(row):
+    bits, w, mask, s_want, z_want, q_want = row
+    w16 = np.array(w, np.float16)
+    assert np.array_equal(w16.astype(np.float64), np.array(w))      # fixture values are exact FP16
+    s, z, q = orc.quant_group(w16, np.array(mask, np.uint8), bits)
+    assert (s, z, list(q)) == (s_want, z_want, q_want)
+    # the hand-worked line itself agrees with exact-rational arithmetic
+    assert exact_group(w16.view(np.uint16), mask, bits) == (s_want, z_want, q_want)
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_quant_group_matches_exact_rationals(bits):
+    rng = np.random.default_rng(100 + bits)
+    for trial in range(150):
+        n = int(rng.choice([2, 8, 32, 128]))
+        kind = trial % 5
+        if kind == 0:
+            w = random_w(rng, n)
+        elif kind == 1:
+            w = random_w(rng, n, scale=30.0)                            # large magnitudes
+        elif kind == 2:
+            w = (rng.integers(-40, 40, n) * 2.0 ** -24).astype(np.float16)  # subnormals
+        elif kind == 3:
+            w = np.abs(random_w(rng, n)) * (1 if trial % 2 else -1)    # one-sided groups
+        else:
+            w = (rng.integers(-15, 16, n) / 64.0).astype(np.float16)   # many exact half-step ties
+        mask = (rng.random(n) < (0.0, 0.05, 0.5)[trial % 3]).astype(np.uint8)
+        s, z, q = orc.quant_group(w, mask, bits)
+        assert (s, z, list(q)) == exact_group(w.view(np.uint16), mask, bits), (trial, w, mask)
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_scale_is_minimal_and_error_within_half_step(bits):
+    """Invariants: s*maxq >= R > prev(s)*maxq; |s*(q-z) - w| <= s/2 for every non-outlier."""
+    rng = np.random.default_rng(7 + bits)
+    maxq = (1 << bits) - 1
+    worst = Fraction(0)
+    for trial in range(100):
+        w = random_w(rng, 128, scale=(0.02, 1.0, 200.0)[trial % 3])
+        mask = (rng.random(128) < 0.02).astype(np.uint8)
+        s_bits, z, q = orc.quant_group(w, mask, bits)
+        vals = [half_fraction(int(b)) for b in w.view(np.uint16)]
+        keep = [v for v, m in zip(vals, mask) if not m]
+        R = max([Fraction(0)] + keep) - min([Fraction(0)] + keep)
+        s = half_fraction(s_bits)
+        assert s * maxq >= R and half_fraction(s_bits - 1) * maxq < R
+        assert 0 <= z <= maxq
+        for v, m, c in zip(vals, mask, q):
+            if m:
+                assert c == z
+            else:
+                err = abs(s * (int(c) - z) - v)
+                assert err <= s / 2
+                worst = max(worst, err / s)
+        if min(keep) < 0:
+            assert q[int(np.argmin(np.where(mask, np.inf, w.astype(np.float64))))] == 0
+        assert q[int(np.argmax(np.where(mask, -np.inf, w.astype(np.float64))))] >= maxq - 1
+    assert worst > Fraction(2, 5)          # the bound is nearly attained, i.e. the test has teeth
+
+
+# ----------------------------------------------------------------------------- word layout
+
+def _golden_words():
+    rows = []
+    with open(os.path.join(GOLDEN, "word_layout_examples.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            b, kind, c, w = [x.strip() for x in line.split(";")]
+            rows.append((int(b), kind, [int(x) for x in c.split()], int(w, 16)))
+    return rows
+
+
+@pytest.mark.parametrize("row", _golden_words())
+def test_word_layout_hand_examples(row):
+    bits, kind, codes, word = row
+    full = np.zeros((1, 128), np.uint8)
+    if kind == "word":
+        per = 8 if bits == 4 else 10
+        # put the example into word 5 of the group: slot 1, second word of that slot
+        slot, j = 1, 1
+        widx = (4 if bits == 4 else 3) * slot + j
+        base = 32 * slot + per * j
+        full[0, base:base + per] = codes
+    else:
+        widx = 12
+        for b in range(4):
+            full[0, 32 * b + 30] = codes[2 * b]
+            full[0, 32 * b + 31] = codes[2 * b + 1]
+    qw = orc.pack_codes(full, bits)
+    assert qw.shape == (1, 1, 16 if bits == 4 else 13)
+    assert int(qw[0, 0, widx]) == word
+    others = np.delete(qw[0, 0], widx)
+    assert not others.any()
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_pack_unpack_roundtrip_and_padding(bits):
+    rng = np.random.default_rng(bits)
+    N, K = 5, 384
+    codes = rng.integers(0, 1 << bits, (N, K)).astype(np.uint8)
+    qw = orc.pack_codes(codes, bits)
+    assert np.array_equal(orc.unpack_codes(qw, N, K, bits), codes)
+    assert np.array_equal(py_unpack(qw, N, K, bits), codes)      # independent index map
+    if bits == 3:
+        assert not (qw[:, :, :12] & np.uint32(0x80008000)).any()  # bits 15 and 31 unused
+        assert not (qw[:, :, 12] & np.uint32(0xF000F000)).any()   # tail uses 12 bits per half
+    all_ones = orc.pack_codes(np.full((1, 128), (1 << bits) - 1, np.uint8), bits)
+    want = [0xFFFFFFFF] * 16 if bits == 4 else [0x7FFF7FFF] * 12 + [0x0FFF0FFF]
+    assert [int(x) for x in all_ones[0, 0]] == want
+
+
+# ----------------------------------------------------------------------------- whole encoding
+
+def _small_problem(seed, N=12, K=384, planted=True):
+    rng = np.random.default_rng(seed)
+    W = random_w(rng, (N, K))
+    if planted:
+        W[:, 5] = (W[:, 5].astype(np.float32) * 20).astype(np.float16)
+    S = (np.abs(rng.standard_normal((N, K))) * np.abs(W.astype(np.float32))).astype(np.float32)
+    return W, S
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("ppm", [0, 10000, 300000])
+def test_pack_is_composition_of_pinned_steps(bits, ppm):
+    W, S = _small_problem(bits * 10 + ppm % 7)
+    N, K = W.shape
+    P = orc.pack(W, S, bits, ppm)
+    k_out = orc.outlier_count(N, K, ppm)
+    mask = numpy_select(S, k_out)
+    assert np.array_equal(P.mask, mask)
+    assert P.row_ptr[-1] == k_out
+    codes = py_unpack(P.qweight, N, K, bits)
+    Wb = W.view(np.uint16)
+    for n in range(N):
+        for g in range(K // 128):
+            sl = slice(128 * g, 128 * g + 128)
+            s, z, q = exact_group(Wb[n, sl], mask[n, sl], bits)
+            assert (int(P.scales[n, g]), int(P.zeros[n, g])) == (s, z)
+            assert list(codes[n, sl]) == q
+    # outlier positions reproduced exactly, values bit-exact
+    for n in range(N):
+        c = P.col_idx[P.row_ptr[n]:P.row_ptr[n + 1]].astype(np.int64)
+        assert np.array_equal(np.flatnonzero(mask[n]), c)
+        assert np.array_equal(P.out_val[P.row_ptr[n]:P.row_ptr[n + 1]], Wb[n, c])
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_no_outliers_is_plain_group_rtn(bits):
+    """ppm = 0 reduces to group-wise min-max round-to-nearest (the quantiser the paper's first
+    table names), written here with numpy: s from the minimal-FP16 rule, codes by np.rint."""
+    W, S = _small_problem(77)
+    N, K = W.shape
+    maxq = (1 << bits) - 1
+    P = orc.pack(W, S, bits, 0)
+    assert P.row_ptr[-1] == 0 and not P.mask.any()
+    Wd = W.astype(np.float64).reshape(N, K // 128, 128)
+    mn = np.minimum(Wd.min(-1), 0.0)
+    mx = np.maximum(Wd.max(-1), 0.0)
+    s = P.scales.view(np.float16).astype(np.float64)
+    assert np.all(s * maxq >= mx - mn)
+    z = np.clip(np.rint(-mn / s), 0, maxq)
+    q = np.clip(np.rint(Wd / s[..., None]) + z[..., None], 0, maxq)
+    assert np.array_equal(P.zeros, z.astype(np.uint8))
+    assert np.array_equal(py_unpack(P.qweight, N, K, bits), q.reshape(N, K).astype(np.uint8))
+    deq = orc.decode(P)
+    assert np.all(np.abs(deq.reshape(Wd.shape) - Wd) <= s[..., None] / 2)
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_all_outliers_is_dense_fp16_matmul(bits):
+    """ppm = 1e6 keeps every weight in FP16: decode gives W itself and the layer is X W^T."""
+    W, S = _small_problem(3, N=10, K=256)
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((3, 256)).astype(np.float16)
+    P = orc.pack(W, S, bits, 1000000)
+    assert np.array_equal(orc.decode(P), W.astype(np.float64))
+    want = X.astype(np.float64) @ W.astype(np.float64).T
+    got = orc.linear_f64(P, X)
+    assert got.shape == (3, 10)
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- Eq. 10 + the layer
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_decode_and_linear_match_numpy(bits):
+    W, S = _small_problem(21 + bits, N=20, K=512)
+    N, K = W.shape
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((5, K)).astype(np.float16)
+    P = orc.pack(W, S, bits, 10000)
+    # independent decode: Python index map, s*(q-z), outliers from the CSR arrays
+    q = py_unpack(P.qweight, N, K, bits).astype(np.float64).reshape(N, K // 128, 128)
+    s = P.scales.view(np.float16).astype(np.float64)[..., None]
+    z = P.zeros.astype(np.float64)[..., None]
+    What = (s * (q - z)).reshape(N, K)
+    for n in range(N):
+        for j in range(P.row_ptr[n], P.row_ptr[n + 1]):
+            assert What[n, P.col_idx[j]] == 0.0                    # code under an outlier decodes to 0
+            What[n, P.col_idx[j]] = float(P.out_val[j:j + 1].view(np.float16)[0])
+    assert np.array_equal(orc.decode(P), What)
+    want = X.astype(np.float64) @ What.T
+    got = orc.linear_f64(P, X)
+    assert got.shape == (5, N)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    rows = np.array([19, 0, 7], np.int32)
+    assert np.allclose(orc.linear_f64(P, X, rows), want[:, rows], rtol=1e-12, atol=1e-12)
+    # sanity, not parity: the quantised layer is close to the FP16 layer, closer at 4 bits than at 3
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    assert rel < (0.25 if bits == 3 else 0.12)
+
+
+def test_four_bits_beat_three_bits():
+    W, S = _small_problem(50, N=16, K=512)
+    X = np.random.default_rng(1).standard_normal((4, 512)).astype(np.float16)
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    err = {}
+    for bits in (3, 4):
+        err[bits] = np.linalg.norm(orc.linear_f64(orc.pack(W, S, bits, 10000), X) - ref)
+    assert err[4] < err[3]
