@@ -52,7 +52,8 @@ def score_from_weight(W, rng, dtype=np.float32):
 def score_clustered(N, K, n_top, rng, axis="col", frac_hot=0.6, hot_share=0.01):
     """FP32 score [N, K] whose `n_top` largest entries are a known set: a fraction `frac_hot`
     of them lies in `hot_share` of the columns (axis="col") or rows (axis="row").
-    Entries of the set get 2 + U(0,1), all others U(0,1)."""
+    Entries of the set get 2 + U(0,1), all others U(0,1).  Returns (S, rows, cols) with the
+    positions of the set, so that a caller knows the top-n_top entries without sorting."""
     S = rng.random(size=(N, K), dtype=np.float32)
     if axis == "col":
         n_hot = int(np.ceil(hot_share * K))
@@ -75,7 +76,7 @@ def score_clustered(N, K, n_top, rng, axis="col", frac_hot=0.6, hot_share=0.01):
     rows = np.concatenate([rows_h, rows_c])
     cols = np.concatenate([cols_h, cols_c])
     S[rows, cols] += np.float32(2.0)
-    return S
+    return S, rows, cols
 
 
 def activations(M, K, rng, hot_frac=0.0, hot_gain=50.0):

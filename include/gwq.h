@@ -1,0 +1,120 @@
+/*
+ * gwq.h - C ABI of the MI355X (gfx950) library for the GWQ linear layer.
+ *
+ * Method: "Gradient-Aware Weight Quantization for Large Language Models" (GWQ).  Per linear
+ * layer the 1 % of weights with the largest |gradient| stay FP16 and the other 99 % are
+ * group-quantised to 3 or 4 bits with a per-group scale and zero point (abstract; Sec. 3.2,
+ * Eq. 6-10).  The paper describes no storage format and no inference kernel; the format below
+ * is this library's.
+ *
+ * Conventions for every call
+ *   - Pointers named in a gwq_packed, and W, score, X, Y and workspaces, are DEVICE pointers
+ *     owned by the caller.  The library never allocates or frees device memory.
+ *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*;
+ *     NULL = the default stream) and the call returns without waiting for it.
+ *   - Arguments are validated on the host before the first HIP call; errors are returned as
+ *     a gwq_status, never raised or aborted.  A failed launch returns GWQ_ERR_DEVICE.
+ *   - Weights are W[N][K] row-major FP16 (N = output features, K = input features),
+ *     activations X[M][K] row-major FP16, outputs Y[M][N] row-major FP16.  No bias
+ *     (Sec. 3.1 disables it).
+ *
+ * Packed format (group = 128 consecutive k of one output channel n; gpr = K / 128)
+ *   qweight  uint32 [N][gpr][wpg], wpg = 16 (4-bit) or 13 (3-bit).  A group is cut into four
+ *            slots of 32 codes, slot b = k_local / 32.  Inside a word, codes at even positions
+ *            sit in the low 16 bits and codes at odd positions in the high 16 bits, `bits`
+ *            bits apiece, ascending.
+ *            4-bit: word 4b+j (j = 0..3) holds codes 32b+8j+t (t = 0..7):
+ *                   t even -> bit 4*(t/2), t odd -> bit 16+4*(t/2).
+ *            3-bit: word 3b+i (i = 0..2) holds codes 32b+10i+t (t = 0..9):
+ *                   t even -> bit 3*(t/2), t odd -> bit 16+3*(t/2); bits 15 and 31 are zero.
+ *                   Word 12 (tail) holds code 32b+30 at bit 3b and code 32b+31 at bit 16+3b.
+ *   scales   FP16 bits [N][gpr]: the smallest FP16 s with s*(2^bits-1) >= max-min of the
+ *            group's non-outlier weights (range widened to contain 0); 1.0 for an empty range.
+ *   zeros    uint8 [N][gpr]: clamp(rint(-min/s), 0, 2^bits-1).
+ *   codes    clamp(rint(w/s) + z, 0, 2^bits-1), round half to even; the code under an outlier
+ *            is z, so it decodes to 0 and the outlier value is added on top.
+ *   row_ptr  int32 [N+1], col_idx uint16 [n_outliers] (ascending within a row), out_val FP16
+ *            bits [n_outliers]: CSR of the outliers, values copied bit for bit from W.
+ *   n_outliers = ceil(outlier_ppm * N * K / 1e6); the entries with the largest |score| are
+ *            kept, ties going to the lowest flat index n*K + k.  |score| is ranked by its
+ *            binary32 bit pattern (NaN ranks above +inf).
+ */
+#ifndef GWQ_H
+#define GWQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GWQ_OK = 0,
+    GWQ_ERR_NULL = -1,        /* a required pointer is NULL                               */
+    GWQ_ERR_SHAPE = -2,       /* N, K, M out of range, K not a multiple of the group, ... */
+    GWQ_ERR_UNSUPPORTED = -3, /* bits not in {3,4}, group != 128, unknown score type      */
+    GWQ_ERR_WORKSPACE = -4,   /* workspace missing or smaller than gwq_layout reports     */
+    GWQ_ERR_DEVICE = -5       /* a HIP call failed                                        */
+} gwq_status;
+
+typedef enum { GWQ_SCORE_F32 = 0, GWQ_SCORE_F16 = 1 } gwq_score_dtype;
+
+/* View of one packed layer.  Scalars are filled by the caller (n_outliers from gwq_layout). */
+typedef struct {
+    int32_t N, K;             /* 1 <= N, 128 <= K <= 65536, K % 128 == 0, N*K < 2^32      */
+    int32_t bits;             /* 3 or 4                                                   */
+    int32_t group;            /* 128                                                      */
+    uint32_t outlier_ppm;     /* 0..1000000; 10000 = 1 %                                  */
+    int64_t n_outliers;       /* ceil(outlier_ppm*N*K/1e6)                                */
+    uint32_t *qweight;
+    uint16_t *scales;
+    uint8_t *zeros;
+    int32_t *row_ptr;
+    uint16_t *col_idx;
+    uint16_t *out_val;
+} gwq_packed;
+
+/* Byte sizes of every buffer of a gwq_packed plus the workspaces of the two device calls. */
+typedef struct {
+    size_t qweight, scales, zeros, row_ptr, col_idx, out_val;
+    size_t pack_workspace;    /* for gwq_pack                                             */
+    size_t linear_workspace;  /* for gwq_linear with M <= M_max (may be 0)                */
+    int64_t n_outliers;
+} gwq_sizes;
+
+/* Sizes for a layer (pure host arithmetic, touches no device).  col_idx and out_val sizes are
+ * at least 16 bytes so that zero-outlier layers still get valid pointers.
+ * Errors: NULL out, shape limits above, unsupported bits/group, ppm > 1e6, M_max < 0. */
+gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_t outlier_ppm,
+                      int32_t M_max, gwq_sizes *out);
+
+/* Encode one layer (Eq. 8 selection, then Eq. 6, 7, 9 per group, then the word layout).
+ *   W_f16   device, FP16 [N][K]          score  device, [N][K] of `score_dtype`
+ *   dst     host struct; its scalars describe the layer, its pointers are device buffers of
+ *           the sizes gwq_layout reports; all of them are fully overwritten
+ *   workspace device scratch of >= pack_workspace bytes, 256-byte aligned
+ * The result is a function of the inputs only (bit-exact, run-to-run identical). */
+gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_dtype,
+                    gwq_packed *dst, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Y[M][N] = X[M][K] * (Q(W) + outliers)^T with Q(W) = s*(q-z) (Eq. 10), FP32 accumulation,
+ * FP16 output.  M <= 16 takes the bandwidth-bound decode kernel, larger M the MFMA GEMM.
+ *   P  host struct with device pointers   X_f16 device [M][K]   Y_f16 device [M][N]
+ * X and Y must not overlap; Y is fully overwritten.  workspace may be NULL when
+ * linear_workspace is 0.  Results are deterministic (no floating-point atomics). */
+gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
+ * Keys: "decode_tiles" (16-row tiles per wave: 1, 2, 4), "decode_waves" (waves per block,
+ * 1..16).  Unknown keys or out-of-range values return GWQ_ERR_UNSUPPORTED. */
+gwq_status gwq_tuning_set(const char *key, int32_t value);
+
+const char *gwq_status_string(gwq_status status);
+const char *gwq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GWQ_H */

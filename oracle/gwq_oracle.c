@@ -199,7 +199,7 @@ int gwq_oracle_quant_group(const uint16_t *w, const uint8_t *mask, int len, int 
         double s = gwq_oracle_half_to_double(s_bits);
         /* Eq. 7, rounded half-to-even and clamped. */
         double zr = rint(-mn / s);
-        z = zr < 0.0 ? 0 : (zr > maxq ? maxq : (int)zr);
+        z = !(zr > 0.0) ? 0 : (zr > maxq ? maxq : (int)zr);   /* NaN (non-finite weights) -> 0 */
     }
     double s = gwq_oracle_half_to_double(s_bits);
     for (int i = 0; i < len; ++i) {
@@ -300,8 +300,31 @@ int gwq_oracle_unpack_codes(const uint32_t *qweight, int64_t N, int64_t K, int b
 
 /* ---------------------------------------------------------------- gwq_pack twin ---- */
 
-/* Whole encoding: selection (Eq. 8), CSR, then per (row, group of 128 along K):
- * scale, zero, codes (Eq. 6, 7, 9) and the word layout above.
+/* Everything after the selection: CSR of the marked entries, then per (row, group of 128
+ * along K) scale, zero, codes (Eq. 6, 7, 9) and the word layout above.  `mask` is the outlier
+ * indicator [N*K]; col_idx/out_val must hold as many entries as the mask marks. */
+int gwq_oracle_encode(const uint16_t *W, const uint8_t *mask, int64_t N, int64_t K, int bits,
+                      uint32_t *qweight, uint16_t *scales, uint8_t *zeros,
+                      int32_t *row_ptr, uint16_t *col_idx, uint16_t *out_val)
+{
+    if (!W || !mask || !qweight || !scales || !zeros || !row_ptr) return GWQ_ORACLE_BAD_ARG;
+    if (N <= 0 || K <= 0 || K % GWQ_GROUP || K > 65536 || (bits != 3 && bits != 4))
+        return GWQ_ORACLE_BAD_ARG;
+    int rc = gwq_oracle_csr(W, mask, N, K, row_ptr, col_idx, out_val);
+    int nw = words_per_group(bits);
+    int64_t gpr = K / GWQ_GROUP;
+    uint8_t codes[GWQ_GROUP];
+    for (int64_t n = 0; n < N && rc == GWQ_ORACLE_OK; ++n)
+        for (int64_t g = 0; g < gpr && rc == GWQ_ORACLE_OK; ++g) {
+            int64_t off = n * K + g * GWQ_GROUP;
+            rc = gwq_oracle_quant_group(W + off, mask + off, GWQ_GROUP, bits,
+                                        &scales[n * gpr + g], &zeros[n * gpr + g], codes);
+            pack_group(codes, bits, qweight + (n * gpr + g) * nw);
+        }
+    return rc;
+}
+
+/* Whole encoding: selection (Eq. 8) followed by gwq_oracle_encode.
  * Output sizes: qweight N*(K/128)*wpg words, scales/zeros N*(K/128), row_ptr N+1,
  * col_idx/out_val k_out = gwq_oracle_outlier_count(N, K, ppm).
  * mask_out (optional, N*K bytes) receives the outlier indicator. */
@@ -310,25 +333,12 @@ int gwq_oracle_pack(const uint16_t *W, const void *score, int score_is_f16,
                     uint32_t *qweight, uint16_t *scales, uint8_t *zeros,
                     int32_t *row_ptr, uint16_t *col_idx, uint16_t *out_val, uint8_t *mask_out)
 {
-    if (!W || !score || !qweight || !scales || !zeros || !row_ptr) return GWQ_ORACLE_BAD_ARG;
-    if (N <= 0 || K <= 0 || K % GWQ_GROUP || K > 65536 || (bits != 3 && bits != 4))
-        return GWQ_ORACLE_BAD_ARG;
+    if (!W || !score || N <= 0 || K <= 0) return GWQ_ORACLE_BAD_ARG;
     uint8_t *mask = mask_out ? mask_out : (uint8_t *)malloc((size_t)(N * K));
     if (!mask) return GWQ_ORACLE_NO_MEM;
     int rc = gwq_oracle_select(score, score_is_f16, N, K, ppm, mask);
-    if (rc == GWQ_ORACLE_OK) rc = gwq_oracle_csr(W, mask, N, K, row_ptr, col_idx, out_val);
-    if (rc == GWQ_ORACLE_OK) {
-        int nw = words_per_group(bits);
-        int64_t gpr = K / GWQ_GROUP;
-        uint8_t codes[GWQ_GROUP];
-        for (int64_t n = 0; n < N && rc == GWQ_ORACLE_OK; ++n)
-            for (int64_t g = 0; g < gpr && rc == GWQ_ORACLE_OK; ++g) {
-                int64_t off = n * K + g * GWQ_GROUP;
-                rc = gwq_oracle_quant_group(W + off, mask + off, GWQ_GROUP, bits,
-                                            &scales[n * gpr + g], &zeros[n * gpr + g], codes);
-                pack_group(codes, bits, qweight + (n * gpr + g) * nw);
-            }
-    }
+    if (rc == GWQ_ORACLE_OK)
+        rc = gwq_oracle_encode(W, mask, N, K, bits, qweight, scales, zeros, row_ptr, col_idx, out_val);
     if (!mask_out) free(mask);
     return rc;
 }

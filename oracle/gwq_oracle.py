@@ -27,6 +27,7 @@ def _load():
     lib.gwq_oracle_quant_group.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.gwq_oracle_pack_codes.argtypes = [vp, i64, i64, i32, vp]
     lib.gwq_oracle_unpack_codes.argtypes = [vp, i64, i64, i32, vp]
+    lib.gwq_oracle_encode.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_pack.argtypes = [vp, vp, i32, i64, i64, i32, u32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_decode.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
@@ -150,6 +151,22 @@ def pack(W, score, bits, ppm=10000):
     _chk(_lib.gwq_oracle_pack(_p(Wb), _p(score), is16, N, K, bits, ppm, _p(P.qweight), _p(P.scales),
                               _p(P.zeros), _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(P.mask)),
          "pack")
+    return P
+
+
+def encode(W, mask, bits, ppm=-1):
+    """Everything after the selection, for a given outlier indicator `mask` [N, K]."""
+    Wb = _f16_bits(W)
+    N, K = Wb.shape
+    mask = np.ascontiguousarray(mask, np.uint8)
+    nnz = int(mask.sum())
+    gpr = K // GROUP
+    P = Packed(N, K, bits, ppm,
+               np.empty((N, gpr, words_per_group(bits)), np.uint32),
+               np.empty((N, gpr), np.uint16), np.empty((N, gpr), np.uint8),
+               np.empty(N + 1, np.int32), np.empty(nnz, np.uint16), np.empty(nnz, np.uint16), mask)
+    _chk(_lib.gwq_oracle_encode(_p(Wb), _p(mask), N, K, bits, _p(P.qweight), _p(P.scales), _p(P.zeros),
+                                _p(P.row_ptr), _p(P.col_idx), _p(P.out_val)), "encode")
     return P
 
 

@@ -1,0 +1,10 @@
+"""MI355X-native GWQ linear layer: thin Python binding over the C-ABI library libgwq.so.
+
+All arithmetic of the path runs in the HIP kernels behind `gwq_pack` and `gwq_linear`; this
+package only marshals arguments.  PyTorch is used for device memory and streams.
+"""
+from .binding import (GwqError, PackedLayer, layout, pack, linear, tuning_set, version,
+                      library_path, lib)
+
+__all__ = ["GwqError", "PackedLayer", "layout", "pack", "linear", "tuning_set", "version",
+           "library_path", "lib"]

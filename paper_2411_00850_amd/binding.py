@@ -1,0 +1,167 @@
+"""ctypes binding of libgwq.so: the same calls as include/gwq.h, argument marshalling only.
+
+The library is loaded from this directory; if it is missing it is built once with hipcc.
+There is no fallback path: without the library every call raises.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libgwq.so")
+
+GWQ_OK = 0
+SCORE_F32, SCORE_F16 = 0, 1
+
+
+class GwqError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {lib().gwq_status_string(status).decode()} (status {status})")
+
+
+class _Packed(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("K", ctypes.c_int32), ("bits", ctypes.c_int32),
+                ("group", ctypes.c_int32), ("outlier_ppm", ctypes.c_uint32),
+                ("n_outliers", ctypes.c_int64),
+                ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("out_val", ctypes.c_void_p)]
+
+
+class _Sizes(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in ("qweight", "scales", "zeros", "row_ptr", "col_idx",
+                                                "out_val", "pack_workspace", "linear_workspace")]
+    _fields_.append(("n_outliers", ctypes.c_int64))
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C library (built on first use if the shared object is not there)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint32
+        L.gwq_layout.restype = ctypes.c_int
+        L.gwq_layout.argtypes = [i32, i32, i32, i32, u32, i32, ctypes.POINTER(_Sizes)]
+        L.gwq_pack.restype = ctypes.c_int
+        L.gwq_pack.argtypes = [vp, vp, ctypes.c_int, ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
+        L.gwq_linear.restype = ctypes.c_int
+        L.gwq_linear.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.gwq_tuning_set.restype = ctypes.c_int
+        L.gwq_tuning_set.argtypes = [ctypes.c_char_p, i32]
+        L.gwq_status_string.restype = ctypes.c_char_p
+        L.gwq_status_string.argtypes = [ctypes.c_int]
+        L.gwq_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def version():
+    return lib().gwq_version().decode()
+
+
+def layout(N, K, bits, group=128, ppm=10000, M_max=0):
+    """Buffer sizes in bytes for one layer, as a dict (pure host call)."""
+    s = _Sizes()
+    rc = lib().gwq_layout(N, K, bits, group, ppm, M_max, ctypes.byref(s))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_layout")
+    return {n: getattr(s, n) for n, _ in _Sizes._fields_}
+
+
+def tuning_set(key, value):
+    rc = lib().gwq_tuning_set(key.encode(), int(value))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_tuning_set")
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class PackedLayer:
+    """Device buffers of one packed layer (torch tensors own the memory)."""
+    N: int
+    K: int
+    bits: int
+    ppm: int
+    n_outliers: int
+    qweight: "torch.Tensor"   # int32 view of the uint32 words [N, K/128, wpg]
+    scales: "torch.Tensor"    # int16 view of the FP16 bits [N, K/128]
+    zeros: "torch.Tensor"     # uint8 [N, K/128]
+    row_ptr: "torch.Tensor"   # int32 [N+1]
+    col_idx: "torch.Tensor"   # int16 view of uint16 [>= n_outliers]
+    out_val: "torch.Tensor"   # int16 view of FP16 bits [>= n_outliers]
+
+    def c_struct(self):
+        return _Packed(self.N, self.K, self.bits, 128, self.ppm, self.n_outliers,
+                       self.qweight.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(),
+                       self.row_ptr.data_ptr(), self.col_idx.data_ptr(), self.out_val.data_ptr())
+
+    def nbytes(self):
+        return sum(t.numel() * t.element_size() for t in
+                   (self.qweight, self.scales, self.zeros, self.row_ptr, self.col_idx, self.out_val))
+
+
+def alloc_packed(N, K, bits, ppm=10000, device="cuda"):
+    import torch
+    sz = layout(N, K, bits, 128, ppm)
+    gpr = K // 128
+    wpg = 16 if bits == 4 else 13
+    n_slots = sz["col_idx"] // 2
+    return PackedLayer(N, K, bits, ppm, sz["n_outliers"],
+                       torch.empty((N, gpr, wpg), dtype=torch.int32, device=device),
+                       torch.empty((N, gpr), dtype=torch.int16, device=device),
+                       torch.empty((N, gpr), dtype=torch.uint8, device=device),
+                       torch.empty(N + 1, dtype=torch.int32, device=device),
+                       torch.empty(n_slots, dtype=torch.int16, device=device),
+                       torch.empty(n_slots, dtype=torch.int16, device=device)), sz
+
+
+def pack(W, score, bits, ppm=10000, stream=None, workspace=None):
+    """gwq_pack: W FP16 [N, K] and score FP32/FP16 [N, K] on the GPU -> PackedLayer."""
+    import torch
+    assert W.is_cuda and score.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
+    assert score.shape == W.shape and score.is_contiguous()
+    if score.dtype == torch.float32:
+        st = SCORE_F32
+    elif score.dtype == torch.float16:
+        st = SCORE_F16
+    else:
+        raise TypeError("score must be float32 or float16")
+    N, K = W.shape
+    P, sz = alloc_packed(N, K, bits, ppm, W.device)
+    if workspace is None:
+        workspace = torch.empty(sz["pack_workspace"], dtype=torch.uint8, device=W.device)
+    cs = P.c_struct()
+    rc = lib().gwq_pack(W.data_ptr(), score.data_ptr(), st, ctypes.byref(cs), workspace.data_ptr(),
+                        workspace.numel(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_pack")
+    return P
+
+
+def linear(P, X, out=None, stream=None):
+    """gwq_linear: X FP16 [M, K] on the GPU -> Y FP16 [M, N]."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
+    M = X.shape[0]
+    if out is None:
+        out = torch.empty((M, P.N), dtype=torch.float16, device=X.device)
+    cs = P.c_struct()
+    rc = lib().gwq_linear(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), None, 0, _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_linear")
+    return out

@@ -1,0 +1,124 @@
+// C ABI of libgwq: host-side validation and dispatch.  Every check runs before the first HIP call,
+// so argument errors are reported on machines without a GPU as well.
+#include <string.h>
+
+#include "gwq_internal.h"
+
+namespace {
+
+int g_decode_tiles = 0;   // 0 = heuristic
+int g_decode_waves = 0;
+
+gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
+{
+    if (bits != 3 && bits != 4) return GWQ_ERR_UNSUPPORTED;
+    if (group != gwq::kGroup) return GWQ_ERR_UNSUPPORTED;
+    if (N < 1 || K < gwq::kGroup || K > 65536 || K % gwq::kGroup != 0) return GWQ_ERR_SHAPE;
+    if (N * K >= ((int64_t)1 << 32)) return GWQ_ERR_SHAPE;
+    if (ppm > 1000000u) return GWQ_ERR_SHAPE;
+    return GWQ_OK;
+}
+
+int64_t outlier_count(int64_t N, int64_t K, uint32_t ppm)
+{
+    return ((int64_t)ppm * N * K + 999999) / 1000000;
+}
+
+gwq_status check_packed(const gwq_packed *P)
+{
+    if (!P) return GWQ_ERR_NULL;
+    gwq_status s = check_shape(P->N, P->K, P->bits, P->group, P->outlier_ppm);
+    if (s != GWQ_OK) return s;
+    if (P->n_outliers != outlier_count(P->N, P->K, P->outlier_ppm)) return GWQ_ERR_SHAPE;
+    if (!P->qweight || !P->scales || !P->zeros || !P->row_ptr || !P->col_idx || !P->out_val) return GWQ_ERR_NULL;
+    return GWQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_t outlier_ppm,
+                      int32_t M_max, gwq_sizes *out)
+{
+    if (!out) return GWQ_ERR_NULL;
+    gwq_status s = check_shape(N, K, bits, group, outlier_ppm);
+    if (s != GWQ_OK) return s;
+    if (M_max < 0) return GWQ_ERR_SHAPE;
+    const int64_t groups = (int64_t)N * (K / gwq::kGroup);
+    const int64_t k_out = outlier_count(N, K, outlier_ppm);
+    memset(out, 0, sizeof(*out));
+    out->qweight = (size_t)groups * gwq::words_per_group(bits) * 4;
+    out->scales = (size_t)groups * 2;
+    out->zeros = (size_t)groups;
+    out->row_ptr = (size_t)(N + 1) * 4;
+    out->col_idx = k_out * 2 > 16 ? (size_t)k_out * 2 : 16;
+    out->out_val = out->col_idx;
+    out->pack_workspace = gwq::pack_workspace_bytes(N);
+    out->linear_workspace = 0;
+    out->n_outliers = k_out;
+    return GWQ_OK;
+}
+
+gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_dtype, gwq_packed *dst,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!W_f16 || !score) return GWQ_ERR_NULL;
+    gwq_status s = check_packed(dst);
+    if (s != GWQ_OK) return s;
+    if (score_dtype != GWQ_SCORE_F32 && score_dtype != GWQ_SCORE_F16) return GWQ_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < gwq::pack_workspace_bytes(dst->N)) return GWQ_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 3) || ((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 15)) return GWQ_ERR_SHAPE;
+    hipError_t e = gwq::launch_pack(W_f16, score, score_dtype == GWQ_SCORE_F16, *dst,
+                                    static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    gwq_status s = check_packed(P);
+    if (s != GWQ_OK) return s;
+    if (!X_f16 || !Y_f16) return GWQ_ERR_NULL;
+    if (M < 1 || (int64_t)M * P->N >= ((int64_t)1 << 40)) return GWQ_ERR_SHAPE;
+    if (((uintptr_t)X_f16 & 15) || ((uintptr_t)P->qweight & 15)) return GWQ_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_tiles, g_decode_waves, st)
+                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, st);
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_tuning_set(const char *key, int32_t value)
+{
+    if (!key) return GWQ_ERR_NULL;
+    if (!strcmp(key, "decode_tiles")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4) return GWQ_ERR_UNSUPPORTED;
+        g_decode_tiles = value;
+        return GWQ_OK;
+    }
+    if (!strcmp(key, "decode_waves")) {
+        if (value < 0 || value > 16) return GWQ_ERR_UNSUPPORTED;
+        g_decode_waves = value;
+        return GWQ_OK;
+    }
+    return GWQ_ERR_UNSUPPORTED;
+}
+
+const char *gwq_status_string(gwq_status status)
+{
+    switch (status) {
+    case GWQ_OK: return "ok";
+    case GWQ_ERR_NULL: return "null pointer";
+    case GWQ_ERR_SHAPE: return "bad shape, size or alignment";
+    case GWQ_ERR_UNSUPPORTED: return "unsupported bits, group, type or option";
+    case GWQ_ERR_WORKSPACE: return "workspace missing or too small";
+    case GWQ_ERR_DEVICE: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+const char *gwq_version(void) { return "gwq-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+// Internal declarations shared by the HIP translation units of libgwq (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gwq.h"
+
+namespace gwq {
+
+constexpr int kGroup = 128;        // codes per quantisation group along K
+constexpr int kSelBins = 2048;     // bins of one radix-select pass
+
+__host__ __device__ constexpr int words_per_group(int bits) { return bits == 4 ? 16 : 13; }
+
+// ---- gwq_pack workspace: uint32 words -------------------------------------------------------
+// [0, 3*kSelBins)        histograms of the three radix-select passes
+// kWsPrefix              key bits fixed by the passes done so far
+// kWsRemaining           how many entries are still to be taken among keys matching the prefix
+// kWsRows + 0*N ..       per row: count of keys above the threshold
+// kWsRows + 1*N ..       per row: count of keys equal to the threshold
+// kWsRows + 2*N ..       per row: how many of its threshold ties are kept
+constexpr int kWsPrefix = 3 * kSelBins;
+constexpr int kWsRemaining = kWsPrefix + 1;
+constexpr int kWsRows = kWsPrefix + 16;
+
+inline size_t pack_workspace_bytes(int64_t N) { return (size_t)(kWsRows + 3 * N) * 4 + 256; }
+
+// Launchers (defined in the .hip files).  Each enqueues on `stream` and returns the last HIP error.
+hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
+                       uint32_t *ws, hipStream_t stream);
+hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int tiles_override,
+                         int waves_override, hipStream_t stream);
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, hipStream_t stream);
+
+}  // namespace gwq

@@ -1,0 +1,406 @@
+// gwq_pack on gfx950: outlier selection (Sec. 3.2, Eq. 8) as a three-pass radix select over the
+// bit patterns of |score|, CSR build in flat-index order, then per (row, group of 128) the scale,
+// zero point and codes of Eq. 6, 7 and 9 and the word layout documented in gwq.h.
+//
+// Everything is integer work or exactly specified IEEE arithmetic (fp64 division, round half to
+// even), so the output is a function of the inputs alone.  Integer atomics are used for the
+// histograms (order-independent); there are no floating-point atomics.
+#include "gwq_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace gwq {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kElemsPerThread = 8;
+constexpr int kElemsPerIter = kThreads * kElemsPerThread;   // 2048 = 16 groups
+
+// Ranking key: bit pattern of |score| as binary32 (monotone in the magnitude, NaN on top).
+__device__ inline uint32_t key_from_f32(uint32_t bits) { return bits & 0x7FFFFFFFu; }
+
+__device__ inline uint32_t key_from_f16(uint16_t h)
+{
+    const uint32_t e = (h >> 10) & 0x1F, f = h & 0x3FF;
+    if (e == 31) return 0x7F800000u | (f << 13);                 // inf / NaN keep their payload
+    const float v = (float)__builtin_bit_cast(_Float16, (uint16_t)(h & 0x7FFF));  // exact widening
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Digit of a key in pass 0, 1, 2 (11 + 11 + 9 bits of the 31-bit key) and the bits above it.
+template <int PASS> __device__ inline uint32_t digit_of(uint32_t key)
+{
+    return PASS == 0 ? key >> 20 : PASS == 1 ? (key >> 9) & 0x7FFu : key & 0x1FFu;
+}
+template <int PASS> __device__ inline bool prefix_matches(uint32_t key, uint32_t prefix)
+{
+    return PASS == 0 ? true : PASS == 1 ? (key >> 20) == (prefix >> 20) : (key >> 9) == (prefix >> 9);
+}
+
+template <bool F16> __device__ inline void load_keys8(const void *score, size_t idx, uint32_t key[8])
+{
+    if (F16) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(score) + idx);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            key[2 * i] = key_from_f16((uint16_t)(w[i] & 0xFFFF));
+            key[2 * i + 1] = key_from_f16((uint16_t)(w[i] >> 16));
+        }
+    } else {
+        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint32_t *>(score) + idx);
+        const uint4 a = p[0], b = p[1];
+        key[0] = key_from_f32(a.x); key[1] = key_from_f32(a.y);
+        key[2] = key_from_f32(a.z); key[3] = key_from_f32(a.w);
+        key[4] = key_from_f32(b.x); key[5] = key_from_f32(b.y);
+        key[6] = key_from_f32(b.z); key[7] = key_from_f32(b.w);
+    }
+}
+
+__global__ void init_ws_kernel(uint32_t *ws, uint32_t k_out)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kWsRows; i += gridDim.x * blockDim.x)
+        ws[i] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        // With nothing to select the threshold sits above every key, so no entry qualifies.
+        ws[kWsPrefix] = k_out ? 0u : 0xFFFFFFFFu;
+        ws[kWsRemaining] = k_out;
+    }
+}
+
+// One radix-select pass: histogram of this pass's digit over the keys that match the prefix.
+// `total` is a multiple of 8 (K is a multiple of 128).
+template <int PASS, bool F16>
+__global__ __launch_bounds__(kThreads) void hist_kernel(const void *score, size_t total, uint32_t *ws)
+{
+    __shared__ uint32_t h[kSelBins];
+    for (int i = threadIdx.x; i < kSelBins; i += kThreads) h[i] = 0;
+    __syncthreads();
+    const uint32_t prefix = ws[kWsPrefix];
+    const size_t stride = (size_t)gridDim.x * kThreads * 8;
+    for (size_t idx = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 8; idx < total; idx += stride) {
+        uint32_t key[8];
+        load_keys8<F16>(score, idx, key);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (prefix_matches<PASS>(key[i], prefix)) atomicAdd(&h[digit_of<PASS>(key[i])], 1u);
+    }
+    __syncthreads();
+    uint32_t *g = ws + PASS * kSelBins;
+    for (int i = threadIdx.x; i < kSelBins; i += kThreads)
+        if (h[i]) atomicAdd(&g[i], h[i]);
+}
+
+// Pick the digit d of this pass: (#keys with digit > d) < remaining <= (#keys with digit >= d).
+// One block of kSelBins / 2 threads; suffix sums by a doubling scan in LDS.
+template <int PASS> __global__ __launch_bounds__(kSelBins / 2) void pick_kernel(uint32_t *ws)
+{
+    __shared__ uint32_t a[2][kSelBins + 1];
+    const uint32_t *g = ws + PASS * kSelBins;
+    const int t = threadIdx.x;
+    a[0][t] = g[t];
+    a[0][t + kSelBins / 2] = g[t + kSelBins / 2];
+    __syncthreads();
+    int cur = 0;
+    for (int d = 1; d < kSelBins; d <<= 1) {           // a[cur][i] becomes sum of bins i .. end
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int i = t + r * (kSelBins / 2);
+            a[cur ^ 1][i] = a[cur][i] + (i + d < kSelBins ? a[cur][i + d] : 0u);
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    const uint32_t remaining = ws[kWsRemaining];
+    const uint32_t prefix = ws[kWsPrefix];
+    __syncthreads();
+    if (remaining == 0) return;
+    constexpr int shift = PASS == 0 ? 20 : PASS == 1 ? 9 : 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int i = t + r * (kSelBins / 2);
+        const uint32_t ge = a[cur][i];
+        const uint32_t gt = i + 1 < kSelBins ? a[cur][i + 1] : 0u;
+        if (gt < remaining && remaining <= ge) {       // true for exactly one bin
+            ws[kWsPrefix] = prefix | ((uint32_t)i << shift);
+            ws[kWsRemaining] = remaining - gt;
+        }
+    }
+}
+
+__device__ inline uint32_t wave_inclusive_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(v, d);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan of one value per thread over the block, plus the block total.
+__device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *smem, uint32_t &total)
+{
+    const uint32_t inc = wave_inclusive_scan(v);
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 63) smem[w] = inc;
+    __syncthreads();
+    uint32_t base = 0, sum = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) {
+        const uint32_t s = smem[i];
+        if (i < w) base += s;
+        sum += s;
+    }
+    total = sum;
+    return base + inc - v;
+}
+
+// Per row: how many keys are above the threshold and how many are equal to it.
+template <bool F16>
+__global__ __launch_bounds__(kThreads) void row_count_kernel(const void *score, int K, uint32_t *ws, int N)
+{
+    __shared__ uint32_t red[2][kWaves];
+    const int n = blockIdx.x;
+    const uint32_t thr = ws[kWsPrefix];
+    uint32_t gt = 0, eq = 0;
+    for (int k = threadIdx.x * 8; k < K; k += kElemsPerIter) {
+        uint32_t key[8];
+        load_keys8<F16>(score, (size_t)n * K + k, key);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { gt += key[i] > thr; eq += key[i] == thr; }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d); eq += __shfl_xor(eq, d); }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = gt; red[1][threadIdx.x >> 6] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = 0, b = 0;
+        for (int i = 0; i < kWaves; ++i) { a += red[0][i]; b += red[1][i]; }
+        ws[kWsRows + n] = a;
+        ws[kWsRows + N + n] = b;
+    }
+}
+
+// Ties at the threshold are kept in flat-index order until `remaining` of them are taken;
+// row_ptr is the running count of kept entries.  One block, rows in chunks of kThreads.
+__global__ __launch_bounds__(kThreads) void row_scan_kernel(uint32_t *ws, int N, int32_t *row_ptr)
+{
+    __shared__ uint32_t smem[kWaves];
+    const uint32_t need = ws[kWsRemaining];
+    uint32_t eq_before = 0, kept_before = 0;
+    for (int n0 = 0; n0 < N; n0 += kThreads) {
+        const int n = n0 + threadIdx.x;
+        const uint32_t gt = n < N ? ws[kWsRows + n] : 0u;
+        const uint32_t eq = n < N ? ws[kWsRows + N + n] : 0u;
+        uint32_t eq_total, kept_total;
+        const uint32_t eq_rank = eq_before + block_exclusive_scan(eq, smem, eq_total);
+        const uint32_t take = eq_rank >= need ? 0u : (need - eq_rank < eq ? need - eq_rank : eq);
+        const uint32_t kept = gt + take;
+        const uint32_t pos = kept_before + block_exclusive_scan(kept, smem, kept_total);
+        if (n < N) { ws[kWsRows + 2 * N + n] = take; row_ptr[n] = (int32_t)pos; }
+        eq_before += eq_total;
+        kept_before += kept_total;
+    }
+    if (threadIdx.x == 0) row_ptr[N] = (int32_t)kept_before;
+}
+
+__device__ inline double half_bits_to_double(uint16_t h)
+{
+    return (double)(float)__builtin_bit_cast(_Float16, h);
+}
+
+// Eq. 6 / Eq. 7 for one group from its masked min and max (both already widened to contain 0).
+template <int BITS> __device__ inline void scale_and_zero(float mn, float mx, uint16_t &s_bits, int &z)
+{
+    constexpr int maxq = (1 << BITS) - 1;
+    const double R = (double)mx - (double)mn;
+    if (R == 0.0) { s_bits = 0x3C00; z = 0; return; }
+    // First guess near R/maxq, then walk to the smallest FP16 s with s*maxq >= R; the walk makes
+    // the result independent of how the guess was rounded.
+    uint16_t sb = __builtin_bit_cast(uint16_t, (_Float16)(float)(R / maxq));
+    if (sb == 0) sb = 1;
+    while (sb < 0x7BFF && half_bits_to_double(sb) * maxq < R) ++sb;
+    while (sb > 1 && half_bits_to_double((uint16_t)(sb - 1)) * maxq >= R) --sb;
+    const double zr = rint(-(double)mn / half_bits_to_double(sb));
+    z = !(zr > 0.0) ? 0 : (zr > maxq ? maxq : (int)zr);
+    s_bits = sb;
+}
+
+// One block per output channel n.  Walks the row in flat-index order: marks the kept entries,
+// appends them to the CSR arrays, and quantises + packs each group of 128.
+template <int BITS, bool F16>
+__global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__restrict__ W,
+                                                          const void *__restrict__ score, int N, int K,
+                                                          const uint32_t *__restrict__ ws,
+                                                          const int32_t *__restrict__ row_ptr,
+                                                          uint32_t *__restrict__ qweight,
+                                                          uint16_t *__restrict__ scales,
+                                                          uint8_t *__restrict__ zeros,
+                                                          uint16_t *__restrict__ col_idx,
+                                                          uint16_t *__restrict__ out_val)
+{
+    constexpr int maxq = (1 << BITS) - 1;
+    constexpr int wpg = words_per_group(BITS);
+    __shared__ uint32_t smem[kWaves];
+    __shared__ uint8_t code_lds[BITS == 3 ? kElemsPerIter : 8];
+
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const int gpr = K / kGroup;
+    const uint32_t thr = ws[kWsPrefix];
+    const uint32_t take = ws[kWsRows + 2 * N + n];
+    uint32_t ties_seen = 0;
+    uint32_t out_pos = (uint32_t)row_ptr[n];
+
+    for (int k0 = 0; k0 < K; k0 += kElemsPerIter) {
+        const int k = k0 + tid * 8;
+        const bool active = k < K;          // a group is 16 consecutive threads: all or none active
+        uint16_t w[8];
+        uint32_t key[8];
+        uint32_t gt_mask = 0, eq_mask = 0;
+        if (active) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(W + (size_t)n * K + k);
+            const uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { w[2 * i] = (uint16_t)(vw[i] & 0xFFFF); w[2 * i + 1] = (uint16_t)(vw[i] >> 16); }
+            load_keys8<F16>(score, (size_t)n * K + k, key);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                gt_mask |= (uint32_t)(key[i] > thr) << i;
+                eq_mask |= (uint32_t)(key[i] == thr) << i;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = 0;
+        }
+
+        // Rank of this thread's first threshold tie within the row, in flat-index order.
+        uint32_t ties_total;
+        const uint32_t tie_rank = ties_seen + block_exclusive_scan(__popc(eq_mask), smem, ties_total);
+        uint32_t sel_mask = gt_mask;
+        {
+            uint32_t r = tie_rank;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (eq_mask >> i & 1) { if (r < take) sel_mask |= 1u << i; ++r; }
+        }
+        uint32_t sel_total;
+        uint32_t pos = out_pos + block_exclusive_scan(__popc(sel_mask), smem, sel_total);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (sel_mask >> i & 1) { col_idx[pos] = (uint16_t)(k + i); out_val[pos] = w[i]; ++pos; }
+        ties_seen += ties_total;
+        out_pos += sel_total;
+
+        // Masked min / max of the group (range always contains 0), reduced over 16 lanes.
+        float mn = 0.f, mx = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (!(sel_mask >> i & 1)) {
+                const float v = (float)__builtin_bit_cast(_Float16, w[i]);
+                mn = v < mn ? v : mn;
+                mx = v > mx ? v : mx;
+            }
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) {
+            const float a = __shfl_xor(mn, d), b = __shfl_xor(mx, d);
+            mn = a < mn ? a : mn;
+            mx = b > mx ? b : mx;
+        }
+        uint16_t s_bits;
+        int z;
+        scale_and_zero<BITS>(mn, mx, s_bits, z);
+        const double s = half_bits_to_double(s_bits);
+
+        // Eq. 9 per weight; an outlier takes the code z.
+        uint32_t code[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double qr = rint(half_bits_to_double(w[i]) / s) + (double)z;
+            const int q = !(qr > 0.0) ? 0 : (qr > maxq ? maxq : (int)qr);
+            code[i] = (sel_mask >> i & 1) ? (uint32_t)z : (uint32_t)q;
+        }
+
+        const int g = k / kGroup;           // group index within the row
+        const int j = tid & 15;             // this thread's 8 codes are k_local = 8j .. 8j+7
+        if (BITS == 4) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) word |= code[t] << (16 * (t & 1) + 4 * (t >> 1));
+            if (active) qweight[((size_t)n * gpr + g) * wpg + j] = word;
+        } else {
+            __syncthreads();                // previous iteration's readers are done
+#pragma unroll
+            for (int t = 0; t < 8; ++t) code_lds[tid * 8 + t] = (uint8_t)code[t];
+            __syncthreads();
+            const uint8_t *c = code_lds + (tid >> 4) * kGroup;
+            if (active && j < 13) {
+                uint32_t word = 0;
+                if (j < 12) {
+                    const int base = 32 * (j / 3) + 10 * (j % 3);
+#pragma unroll
+                    for (int t = 0; t < 10; ++t) word |= (uint32_t)c[base + t] << (16 * (t & 1) + 3 * (t >> 1));
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        word |= (uint32_t)c[32 * b + 30] << (3 * b) | (uint32_t)c[32 * b + 31] << (16 + 3 * b);
+                }
+                qweight[((size_t)n * gpr + g) * wpg + j] = word;
+            }
+        }
+        if (active && j == 0) {
+            scales[(size_t)n * gpr + g] = s_bits;
+            zeros[(size_t)n * gpr + g] = (uint8_t)z;
+        }
+    }
+}
+
+template <bool F16>
+hipError_t run_select(const void *score, int N, int K, uint32_t *ws, int32_t *row_ptr, bool any, hipStream_t st)
+{
+    const size_t total = (size_t)N * K;
+    const size_t want = (total / 8 + kThreads - 1) / kThreads;
+    const int blocks = (int)(want < 2048 ? (want ? want : 1) : 2048);
+    if (any) {
+        // With nothing to keep the threshold set by init_ws_kernel already sits above every key.
+        hist_kernel<0, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
+        pick_kernel<0><<<1, kSelBins / 2, 0, st>>>(ws);
+        hist_kernel<1, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
+        pick_kernel<1><<<1, kSelBins / 2, 0, st>>>(ws);
+        hist_kernel<2, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
+        pick_kernel<2><<<1, kSelBins / 2, 0, st>>>(ws);
+    }
+    row_count_kernel<F16><<<N, kThreads, 0, st>>>(score, K, ws, N);
+    row_scan_kernel<<<1, kThreads, 0, st>>>(ws, N, row_ptr);
+    return hipGetLastError();
+}
+
+template <int BITS, bool F16>
+hipError_t run_encode(const void *W, const void *score, const gwq_packed &P, const uint32_t *ws, hipStream_t st)
+{
+    encode_kernel<BITS, F16><<<P.N, kThreads, 0, st>>>(static_cast<const uint16_t *>(W), score, P.N, P.K, ws,
+                                                       P.row_ptr, P.qweight, P.scales, P.zeros, P.col_idx,
+                                                       P.out_val);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
+                       uint32_t *ws, hipStream_t st)
+{
+    init_ws_kernel<<<8, kThreads, 0, st>>>(ws, (uint32_t)P.n_outliers);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = score_is_f16 ? run_select<true>(score, P.N, P.K, ws, P.row_ptr, P.n_outliers > 0, st)
+                     : run_select<false>(score, P.N, P.K, ws, P.row_ptr, P.n_outliers > 0, st);
+    if (e != hipSuccess) return e;
+    if (P.bits == 4)
+        return score_is_f16 ? run_encode<4, true>(W, score, P, ws, st) : run_encode<4, false>(W, score, P, ws, st);
+    return score_is_f16 ? run_encode<3, true>(W, score, P, ws, st) : run_encode<3, false>(W, score, P, ws, st);
+}
+
+}  // namespace gwq

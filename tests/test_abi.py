@@ -1,0 +1,99 @@
+"""C-ABI checks that need no GPU: exported symbols, layout arithmetic, argument validation."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_00850_amd as gwq
+from paper_2411_00850_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gwq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gwq_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_calls():
+    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_pack", "gwq_status_string",
+                                    "gwq_tuning_set", "gwq_version"]
+
+
+@pytest.mark.parametrize("name", declared_functions())
+def test_library_exports_every_declared_symbol(name):
+    lib = ctypes.CDLL(gwq.library_path())
+    assert hasattr(lib, name)
+
+
+def test_layout_sizes_7b_shapes():
+    s = gwq.layout(4096, 4096, 4)
+    assert s["qweight"] == 4096 * 32 * 16 * 4 and s["scales"] == 4096 * 32 * 2 and s["zeros"] == 4096 * 32
+    assert s["row_ptr"] == 4097 * 4 and s["n_outliers"] == 167773 and s["col_idx"] == 167773 * 2
+    s3 = gwq.layout(11008, 4096, 3)
+    assert s3["qweight"] == 11008 * 32 * 13 * 4 and s3["n_outliers"] == 450888
+    # bytes per weight of the packed layer: 4.5 bits and 3.77 bits
+    total = sum(s[k] for k in ("qweight", "scales", "zeros", "row_ptr", "col_idx", "out_val"))
+    assert abs(total / 4096 ** 2 - 0.5644) < 1e-3
+    assert gwq.layout(8, 128, 4, ppm=0)["col_idx"] == 16          # never a zero-size buffer
+
+
+@pytest.mark.parametrize("args, status", [
+    ((0, 128, 4, 128, 10000, 1), -2), ((4, 100, 4, 128, 10000, 1), -2), ((4, 0, 4, 128, 10000, 1), -2),
+    ((4, 65536 + 128, 4, 128, 10000, 1), -2), ((70000, 65536, 4, 128, 10000, 1), -2),
+    ((4, 128, 5, 128, 10000, 1), -3), ((4, 128, 2, 128, 10000, 1), -3), ((4, 128, 4, 64, 10000, 1), -3),
+    ((4, 128, 4, 128, 1000001, 1), -2), ((4, 128, 4, 128, 10000, -1), -2),
+])
+def test_layout_rejects_bad_arguments(args, status):
+    s = binding._Sizes()
+    assert binding.lib().gwq_layout(*args, ctypes.byref(s)) == status
+
+
+def test_layout_null_out():
+    assert binding.lib().gwq_layout(4, 128, 4, 128, 10000, 1, None) == -1
+
+
+def _packed(N=4, K=128, bits=4, ppm=10000, fake=0x1000, **kw):
+    n_out = (ppm * N * K + 999999) // 1000000
+    p = binding._Packed(N, K, bits, 128, ppm, n_out, fake, fake, fake, fake, fake, fake)
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_pack_and_linear_validate_before_touching_the_device():
+    """All of these return an error code on a machine with no GPU: nothing is launched."""
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ok = _packed()
+    assert L.gwq_pack(None, fake, 0, ctypes.byref(ok), fake, 1 << 20, None) == -1
+    assert L.gwq_pack(fake, None, 0, ctypes.byref(ok), fake, 1 << 20, None) == -1
+    assert L.gwq_pack(fake, fake, 0, None, fake, 1 << 20, None) == -1
+    assert L.gwq_pack(fake, fake, 7, ctypes.byref(ok), fake, 1 << 20, None) == -3
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(ok), None, 1 << 20, None) == -4
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(ok), fake, 16, None) == -4
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(_packed(bits=5)), fake, 1 << 20, None) == -3
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(_packed(K=100)), fake, 1 << 20, None) == -2
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(_packed(n_outliers=3)), fake, 1 << 20, None) == -2
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(_packed(zeros=None)), fake, 1 << 20, None) == -1
+    assert L.gwq_linear(None, fake, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear(ctypes.byref(ok), None, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear(ctypes.byref(ok), fake, 1, None, None, 0, None) == -1
+    assert L.gwq_linear(ctypes.byref(ok), fake, 0, fake, None, 0, None) == -2
+    assert L.gwq_linear(ctypes.byref(_packed(group=64)), fake, 1, fake, None, 0, None) == -3
+    assert L.gwq_linear(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
+
+
+def test_tuning_and_strings():
+    L = binding.lib()
+    assert L.gwq_tuning_set(b"decode_tiles", 3) == -3
+    assert L.gwq_tuning_set(b"decode_waves", 17) == -3
+    assert L.gwq_tuning_set(b"nonsense", 1) == -3
+    assert L.gwq_tuning_set(b"decode_tiles", 2) == 0 and L.gwq_tuning_set(b"decode_tiles", 0) == 0
+    assert L.gwq_status_string(0) == b"ok"
+    assert b"workspace" in L.gwq_status_string(-4)
+    assert gwq.version().startswith("gwq-gfx950")
+    with pytest.raises(gwq.GwqError):
+        gwq.layout(4, 100, 4)

@@ -1,0 +1,152 @@
+"""gwq_linear on the GPU against the oracle's fp64 product (Sec. 3.2, Eq. 10 plus the FP16 outliers).
+
+Tolerances (written in gpu_helpers): relative Frobenius error <= 2e-3 and
+max|Y_gpu - Y_ref| <= 1e-2 * max|Y_ref|.  The packed inputs of these tests come from the oracle,
+so the linear kernels are checked independently of the GPU packer.
+"""
+import functools
+
+import numpy as np
+import pytest
+
+import gwq_synth as gs
+from oracle import gwq_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(seed, N, K, bits, ppm=10000, planted=2):
+    rng = np.random.default_rng(seed)
+    W = gs.weight(N, K, rng, planted_cols=planted)
+    S = gs.score_from_weight(W, rng)
+    return orc.pack(W, S, bits, ppm), rng
+
+
+def _run(P, X):
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu, upload_packed
+    D = upload_packed(P)
+    return gwq.linear(D, to_gpu(X)).cpu().numpy()
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K", [(16, 128), (40, 256), (200, 1024), (72, 11008), (1, 128)])
+def test_decode_small_all_M(bits, N, K):
+    """Every M of the decode kernel (1..16), ragged N (not a multiple of 16), several K splits."""
+    from gpu_helpers import assert_close
+    P, rng = _problem(N + K + bits, N, K, bits)
+    for M in range(1, 17):
+        X = gs.activations(M, K, rng)
+        assert_close(_run(P, X), orc.linear_f64(P, X), f"decode N={N} K={K} M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("tiles,waves", [(1, 1), (1, 3), (1, 16), (2, 2), (2, 16), (4, 1), (4, 8)])
+def test_decode_launch_shapes(bits, tiles, waves):
+    """Every tile / wave split of the decode kernel gives the same answer (within tolerance)."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close
+    P, rng = _problem(77, 150, 1536, bits)
+    X = gs.activations(5, 1536, rng)
+    ref = orc.linear_f64(P, X)
+    gwq.tuning_set("decode_tiles", tiles)
+    gwq.tuning_set("decode_waves", waves)
+    try:
+        assert_close(_run(P, X), ref, f"tiles={tiles} waves={waves}")
+    finally:
+        gwq.tuning_set("decode_tiles", 0)
+        gwq.tuning_set("decode_waves", 0)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("ppm", [0, 1000000, 200000])
+def test_decode_outlier_extremes(bits, ppm):
+    """No outliers, only outliers (a dense FP16 layer in CSR form), and a heavy 20 %."""
+    from gpu_helpers import assert_close
+    P, rng = _problem(5, 48, 512, bits, ppm=ppm)
+    for M in (1, 7, 16):
+        X = gs.activations(M, 512, rng)
+        assert_close(_run(P, X), orc.linear_f64(P, X), f"ppm={ppm} M={M}")
+
+
+def test_decode_row_clustered_outliers():
+    """Outliers piled into 1 % of the output channels (the row-clustered pattern)."""
+    from gpu_helpers import assert_close
+    rng = np.random.default_rng(12)
+    N, K = 400, 1024
+    W = gs.weight(N, K, rng)
+    S, _, _ = gs.score_clustered(N, K, orc.outlier_count(N, K, 10000), rng, axis="row")
+    P = orc.pack(W, S, 4, 10000)
+    assert np.diff(P.row_ptr).max() > 200
+    X = gs.activations(3, K, rng)
+    assert_close(_run(P, X), orc.linear_f64(P, X))
+
+
+def test_linear_is_deterministic():
+    P, rng = _problem(1, 256, 2048, 4)
+    for M in (4, 100):
+        X = gs.activations(M, 2048, rng)
+        assert np.array_equal(_run(P, X), _run(P, X))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K", [(128, 256), (200, 1024), (300, 384)])
+@pytest.mark.parametrize("M", [17, 64, 65, 130, 300])
+def test_gemm_small(bits, N, K, M):
+    """The MFMA path: every tile height (64 / 128 / 256 rows), ragged M and N."""
+    from gpu_helpers import assert_close
+    P, rng = _problem(N + K + M + bits, N, K, bits)
+    X = gs.activations(M, K, rng, hot_frac=0.01)
+    assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm N={N} K={K} M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("ppm", [0, 1000000])
+def test_gemm_outlier_extremes(ppm):
+    from gpu_helpers import assert_close
+    P, rng = _problem(9, 160, 512, 4, ppm=ppm)
+    X = gs.activations(70, 512, rng)
+    assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm ppm={ppm}")
+
+
+# ----------------------------------------------------------------------------- full-size configurations
+
+def test_config1_decode_full():
+    from gpu_helpers import assert_close
+    W, S, X = gs.config1()
+    P = orc.pack(W, S, 4, 10000)
+    assert_close(_run(P, X), orc.linear_f64(P, X), "config 1")
+
+
+@functools.lru_cache(maxsize=2)
+def _layer7b(mid, N, K):
+    W, S = gs.layer_matrix(2, mid, N, K)
+    return W, orc.select(S, 10000)
+
+
+SHAPES_7B = [(0, 4096, 4096), (4, 11008, 4096), (6, 4096, 11008)]
+
+
+@pytest.mark.parametrize("mid,N,K", SHAPES_7B)
+def test_config2_and_3_decode_7b_shapes(mid, N, K):
+    """7B-shaped matrices with planted outlier columns: 4-bit at M in {1, 4, 16}, 3-bit at M in {1, 8}."""
+    from gpu_helpers import assert_close
+    W, mask = _layer7b(mid, N, K)
+    for bits, Ms in ((4, (1, 4, 16)), (3, (1, 8))):
+        P = orc.encode(W, mask, bits, 10000)
+        for M in Ms:
+            X = gs.activations(M, K, gs.rng_for(2, mid, 10 + M))
+            assert_close(_run(P, X), orc.linear_f64(P, X), f"7B N={N} K={K} bits={bits} M={M}")
+
+
+@pytest.mark.parametrize("mid,N,K", SHAPES_7B)
+def test_config4_prefill_7b_shapes_sampled(mid, N, K):
+    """Prefill M = 2048 with hot activation channels; the oracle computes 160 sampled output
+    channels (all 2048 rows of each), the GPU computes everything."""
+    from gpu_helpers import assert_close
+    W, mask = _layer7b(mid, N, K)
+    P = orc.encode(W, mask, 4, 10000)
+    X = gs.activations(2048, K, gs.rng_for(4, mid, 2), hot_frac=0.001)
+    rows = np.sort(gs.rng_for(4, mid, 3).choice(N, 160, replace=False)).astype(np.int32)
+    Y = _run(P, X)
+    assert np.isfinite(Y.astype(np.float32)).all()
+    assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"prefill N={N} K={K}")

@@ -1,0 +1,107 @@
+"""gwq_pack on the GPU must be byte-identical to the CPU oracle (Sec. 3.2, Eq. 6-9 + word layout)."""
+import numpy as np
+import pytest
+
+import gwq_synth as gs
+from oracle import gwq_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_pack(W, S, bits, ppm):
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu
+    return gwq.pack(to_gpu(W), to_gpu(S), bits, ppm)
+
+
+def _small(seed, N, K, score_dtype=np.float32, ties=False):
+    rng = np.random.default_rng(seed)
+    W = gs.weight(N, K, rng, planted_cols=min(2, K // 64))
+    S = gs.score_from_weight(W, rng)
+    if ties:
+        S = (np.round(S * 64) / 64).astype(np.float32)       # few distinct values: many ties at the cut
+    return W, S.astype(score_dtype)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K", [(1, 128), (8, 128), (37, 384), (200, 1024), (64, 2304), (16, 11008)])
+@pytest.mark.parametrize("ppm", [0, 10000, 300000, 1000000])
+def test_pack_small_shapes(bits, N, K, ppm):
+    from gpu_helpers import assert_packed_equal
+    W, S = _small(N * 7 + K + ppm % 11, N, K)
+    assert_packed_equal(_gpu_pack(W, S, bits, ppm), orc.pack(W, S, bits, ppm))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("kind", ["ties_f32", "f16_scores", "all_equal", "signed_zero_nan_inf"])
+def test_pack_tie_and_special_scores(bits, kind):
+    from gpu_helpers import assert_packed_equal
+    N, K = 96, 1280
+    if kind == "ties_f32":
+        W, S = _small(3, N, K, ties=True)
+    elif kind == "f16_scores":
+        W, S = _small(4, N, K, score_dtype=np.float16)
+    elif kind == "all_equal":
+        W, S = _small(5, N, K)
+        S[:] = 0.125
+    else:
+        W, S = _small(6, N, K)
+        rng = np.random.default_rng(0)
+        idx = rng.choice(N * K, 400, replace=False)
+        S.ravel()[idx[:100]] = np.nan
+        S.ravel()[idx[100:200]] = np.inf
+        S.ravel()[idx[200:300]] = -0.0
+        S.ravel()[idx[300:]] = -np.inf
+    for ppm in (10000, 50000):
+        assert_packed_equal(_gpu_pack(W, S, bits, ppm), orc.pack(W, S, bits, ppm))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_pack_extreme_weights(bits):
+    """Subnormal, huge and one-sided groups: the scale search and the zero point hit their edges."""
+    from gpu_helpers import assert_packed_equal
+    rng = np.random.default_rng(8)
+    N, K = 32, 512
+    W = gs.weight(N, K, rng)
+    W[0] = (rng.integers(-40, 40, K) * 2.0 ** -24).astype(np.float16)      # subnormals
+    W[1] = (rng.standard_normal(K) * 9000).astype(np.float16)               # near the FP16 maximum
+    W[2] = np.abs(W[2])                                                     # all positive
+    W[3] = -np.abs(W[3])                                                    # all negative
+    W[4] = 0                                                                # empty range
+    W[5] = (rng.integers(-15, 16, K) / 64.0).astype(np.float16)            # exact half-step ties
+    W[6, :128] = np.float16(65504.0)
+    W[6, 128:256] = np.float16(-65504.0)
+    S = gs.score_from_weight(W, rng)
+    assert_packed_equal(_gpu_pack(W, S, bits, 10000), orc.pack(W, S, bits, 10000))
+
+
+def test_pack_is_deterministic():
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu, download_packed
+    W, S = _small(9, 256, 2048, ties=True)
+    Wd, Sd = to_gpu(W), to_gpu(S)
+    a = download_packed(gwq.pack(Wd, Sd, 4, 10000))
+    b = download_packed(gwq.pack(Wd, Sd, 4, 10000))
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_pack_config1_full(bits):
+    """4096 x 4096, seed 0, 1 % outliers: the single-layer configuration at full size."""
+    from gpu_helpers import assert_packed_equal
+    W, S, _ = gs.config1()
+    P = orc.pack(W, S, bits, 10000)
+    assert int(P.row_ptr[-1]) == 167773
+    assert_packed_equal(_gpu_pack(W, S, bits, 10000), P)
+
+
+@pytest.mark.parametrize("name,N,K,mid", [("gate", 11008, 4096, 4), ("down", 4096, 11008, 6)])
+def test_pack_7b_shapes_full(name, N, K, mid):
+    """The two non-square 7B-shaped matrices with planted outlier columns, both bit widths;
+    the selection is computed once by the oracle and shared."""
+    from gpu_helpers import assert_packed_equal
+    W, S = gs.layer_matrix(2, mid, N, K)
+    mask = orc.select(S, 10000)
+    for bits in (4, 3):
+        assert_packed_equal(_gpu_pack(W, S, bits, 10000), orc.encode(W, mask, bits, 10000))
