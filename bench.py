@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the GWQ linear-layer path on one MI355X.
+
+Workload (benchmark configs[1]): one LLaMA-2-7B-shaped decoder layer, 7 matrices, 4-bit codes,
+group 128, 1 % FP16 outliers, synthetic weights with planted outlier columns.  A step is one decode
+pass (M = 1) of gwq_linear over the 7 matrices.  The packed layer exists in several copies and the
+steps rotate over them, so every step streams its weights from HBM rather than from the 256 MB
+last-level cache, as a decode pass over a whole model does.
+
+One JSON line is printed.  `value` is the algorithmic GB/s of the timed steps (packed bytes + X + Y
+per step over wall time, inputs resident in HBM).  `roofline` is the decode kernel alone: algorithmic
+bytes per launch over the average launch duration measured with HIP events on the launch stream.
+Further objects report the same pass at M = 4 and 16, the prefill GEMM (M = 2048) in TFLOP/s, gwq_pack,
+and the CPU oracle timed on a bounded sample (`cpu_baseline`).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(P, M):
+    """Bytes the method must move for one gwq_linear call: packed layer + X + Y."""
+    gpr = P.K // 128
+    wpg = 16 if P.bits == 4 else 13
+    packed = P.N * gpr * (wpg * 4 + 2 + 1) + (P.N + 1) * 4 + P.n_outliers * 4
+    return packed + 2 * M * P.K + 2 * M * P.N
+
+
+def flops(P, M):
+    return 2.0 * M * P.N * P.K + 2.0 * M * P.n_outliers
+
+
+def clone_layer(P):
+    from paper_2411_00850_amd.binding import PackedLayer
+    return PackedLayer(P.N, P.K, P.bits, P.ppm, P.n_outliers, P.qweight.clone(), P.scales.clone(),
+                       P.zeros.clone(), P.row_ptr.clone(), P.col_idx.clone(), P.out_val.clone())
+
+
+def read_traffic():
+    """HBM bytes per decode launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "decode_gemv_7b_int4_m1_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--copies", type=int, default=6, help="rotating copies of the packed layer")
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
+                    help="how the timed steps are launched: one HIP graph over all copies, or plain launches")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are out of scope.")
+
+    import torch
+    import gwq_synth as gs
+    import paper_2411_00850_amd as gwq
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- inputs: generate on the host (seeded), pack on the GPU with gwq_pack -------------------
+    t0 = time.time()
+    layers, pack_inputs = [], []
+    for mid, (name, N, K) in enumerate(gs.SHAPES_7B):
+        W, S = gs.layer_matrix(2, mid, N, K)
+        Wd, Sd = torch.from_numpy(W).to(dev), torch.from_numpy(S).to(dev)
+        layers.append(gwq.pack(Wd, Sd, 4, 10000))
+        if name in ("q", "gate", "down"):
+            pack_inputs.append((name, Wd, Sd))
+        else:
+            del Wd, Sd
+    torch.cuda.synchronize()
+    log(f"[bench] generated and packed 7 matrices in {time.time() - t0:.1f} s")
+
+    copies = [layers] + [[clone_layer(P) for P in layers] for _ in range(args.copies - 1)]
+    torch.cuda.synchronize()
+
+    def make_xy(M):
+        xs = {K: torch.from_numpy(gs.activations(M, K, gs.rng_for(2, 100, K))).to(dev) for K in (4096, 11008)}
+        ys = [torch.empty((M, P.N), dtype=torch.float16, device=dev) for P in layers]
+        return xs, ys
+
+    def decode_leg(M, steps, warmup, mode):
+        """mode "graph": all copies x 7 launches captured once into a HIP graph and replayed (the
+        launch-bound loop of a serving engine); "eager": plain launches; "events": eager with one HIP
+        event between consecutive launches, giving the per-launch duration of the decode kernel."""
+        xs, ys = make_xy(M)
+        n_launch, n_copies = len(layers), len(copies)
+        calls = [[gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(c)] for c in copies]
+        for i in range(warmup):
+            for call in calls[i % n_copies]:
+                call()
+        torch.cuda.synchronize()
+        kernel_ms = None
+        if mode == "graph":
+            ref = [y.clone() for y in ys]               # eager result of the last warm-up step
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for c in calls:
+                    for call in c:
+                        call()
+            graph.replay()
+            torch.cuda.synchronize()
+            if warmup and not all(torch.equal(a, b) for a, b in zip(ref, ys)):
+                sys.exit("bench.py: graph replay does not reproduce the eager result")
+            rounds, rest = divmod(steps, n_copies)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(rounds):
+                graph.replay()
+            for call in [c for cc in calls[:rest] for c in cc]:
+                call()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t
+        else:
+            ev = mode == "events"
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_launch + 1)] for _ in range(steps)] if ev else None
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for i in range(steps):
+                if ev:
+                    evs[i][0].record()
+                for j, call in enumerate(calls[(warmup + i) % n_copies]):
+                    call()
+                    if ev:
+                        evs[i][j + 1].record()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t
+            if ev:
+                kernel_ms = sum(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(steps) for j in range(n_launch))
+                kernel_ms /= steps * n_launch
+        bytes_step = sum(algorithmic_bytes(P, M) for P in layers)
+        return wall / steps, kernel_ms, bytes_step
+
+    # ---- the timed steps: decode M = 1 ---------------------------------------------------------------
+    step_s, _, bytes_step = decode_leg(1, args.steps, args.warmup, args.launch)
+    value = bytes_step / step_s / 1e9
+    # Same steps again with one HIP event after every launch: per-launch duration of the decode kernel.
+    _, launch_ms, _ = decode_leg(1, args.steps, args.warmup, "events")
+    bytes_launch = bytes_step / len(layers)
+    achieved = bytes_launch / (launch_ms * 1e-3) / 1e9
+    out = {
+        "metric": "gwq_linear decode GB/s (% HBM peak) & prefill TFLOP/s (% MFMA peak), 7B shapes",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_s * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
+                               "int4 g128 + 1% fp16 CSR outliers, decode M=1, 7 gwq_linear launches per step",
+                   "copies_rotated": args.copies, "bytes_per_step": bytes_step, "launch": args.launch},
+        "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel<4,1>", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": read_traffic(), "bytes_per_launch": round(bytes_launch),
+                     "avg_launch_us": round(launch_ms * 1e3, 3)},
+    }
+
+    if not args.no_extras:
+        extra = {}
+        for M in (4, 16):
+            s, _, b = decode_leg(M, max(args.steps // 3, 12), 12, args.launch)
+            extra[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5)}
+        # prefill: M = 2048 over the 7 matrices, one copy (compute-bound)
+        M = 2048
+        xs, ys = make_xy(M)
+        for _ in range(3):
+            for j, P in enumerate(layers):
+                gwq.linear(P, xs[P.K], out=ys[j])
+        torch.cuda.synchronize()
+        reps = 10
+        t = time.perf_counter()
+        for _ in range(reps):
+            for j, P in enumerate(layers):
+                gwq.linear(P, xs[P.K], out=ys[j])
+        torch.cuda.synchronize()
+        s = (time.perf_counter() - t) / reps
+        fl = sum(flops(P, M) for P in layers)
+        extra["prefill_M2048"] = {"TFLOP/s": round(fl / s / 1e12, 1), "ms_per_pass": round(s * 1e3, 4),
+                                  "pct_mfma_f16_peak": round(100 * fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 2),
+                                  "roofline": {"bound": "mfma", "achieved": round(fl / s / 1e12, 1),
+                                               "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                               "frac": round(fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
+        del xs, ys
+        # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
+        pk = {}
+        for name, Wd, Sd in pack_inputs:
+            gwq.pack(Wd, Sd, 4, 10000)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(3):
+                P = gwq.pack(Wd, Sd, 4, 10000)
+            torch.cuda.synchronize()
+            s = (time.perf_counter() - t) / 3
+            b = Wd.numel() * 6 + P.nbytes()
+            pk[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1)}
+        extra["pack_int4"] = pk
+        out["extras"] = extra
+
+    if not args.no_cpu_baseline:
+        from oracle import gwq_oracle as orc
+        name, N, K = gs.SHAPES_7B[0]
+        W, S = gs.layer_matrix(2, 0, N, K)
+        Pq = orc.pack(W, S, 4, 10000)
+        X = gs.activations(1, K, gs.rng_for(2, 100, K))
+        cores = len(os.sched_getaffinity(0))
+        orc.linear_f64(Pq, X)
+        reps, t = 0, time.perf_counter()
+        while time.perf_counter() - t < 12.0:
+            orc.linear_f64(Pq, X)
+            reps += 1
+        s = (time.perf_counter() - t) / reps
+        b = algorithmic_bytes(layers[0], 1)
+        out["cpu_baseline"] = {"value": round(b / s / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+                               "sample": f"q_proj 4096x4096 of the layer, int4, M=1, fp64 oracle linear, "
+                                         f"{reps} repetitions in {s * reps:.1f} s (OpenMP over output rows)"}
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

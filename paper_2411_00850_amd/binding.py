@@ -165,3 +165,23 @@ def linear(P, X, out=None, stream=None):
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_linear")
     return out
+
+
+def prepare_linear(P, X, out):
+    """Pre-marshalled gwq_linear call for launch-bound loops: returns a zero-argument callable that
+    enqueues the same call on whatever torch stream is current when it is invoked (so it can be
+    captured into a HIP graph).  P, X and out must stay alive while the callable is used."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
+    assert out.shape == (X.shape[0], P.N) and out.dtype == torch.float16 and out.is_contiguous()
+    cs = P.c_struct()
+    ref = ctypes.byref(cs)
+    fn = lib().gwq_linear
+    xp, yp, M = ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(out.data_ptr()), X.shape[0]
+    current_stream = torch.cuda.current_stream
+
+    def call(_keep=(cs, P, X, out)):
+        rc = fn(ref, xp, M, yp, None, 0, ctypes.c_void_p(current_stream().cuda_stream))
+        if rc != GWQ_OK:
+            raise GwqError(rc, "gwq_linear")
+    return call
