@@ -107,8 +107,8 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
- * Keys: "decode_tiles" (16-row tiles per wave: 1, 2, 4), "decode_waves" (waves per block,
- * 1..16).  Unknown keys or out-of-range values return GWQ_ERR_UNSUPPORTED. */
+ * Keys: "decode_waves" (waves per block of the decode kernel, 1..16).  Unknown keys or
+ * out-of-range values return GWQ_ERR_UNSUPPORTED. */
 gwq_status gwq_tuning_set(const char *key, int32_t value);
 
 const char *gwq_status_string(gwq_status status);

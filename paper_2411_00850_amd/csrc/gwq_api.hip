@@ -6,8 +6,7 @@
 
 namespace {
 
-int g_decode_tiles = 0;   // 0 = heuristic
-int g_decode_waves = 0;
+int g_decode_waves = 0;   // 0 = heuristic
 
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
@@ -85,7 +84,7 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     if (M < 1 || (int64_t)M * P->N >= ((int64_t)1 << 40)) return GWQ_ERR_SHAPE;
     if (((uintptr_t)X_f16 & 15) || ((uintptr_t)P->qweight & 15)) return GWQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_tiles, g_decode_waves, st)
+    hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_waves, st)
                            : gwq::launch_gemm(*P, X_f16, M, Y_f16, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
@@ -93,11 +92,6 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
 gwq_status gwq_tuning_set(const char *key, int32_t value)
 {
     if (!key) return GWQ_ERR_NULL;
-    if (!strcmp(key, "decode_tiles")) {
-        if (value != 0 && value != 1 && value != 2 && value != 4) return GWQ_ERR_UNSUPPORTED;
-        g_decode_tiles = value;
-        return GWQ_OK;
-    }
     if (!strcmp(key, "decode_waves")) {
         if (value < 0 || value > 16) return GWQ_ERR_UNSUPPORTED;
         g_decode_waves = value;

@@ -1,0 +1,127 @@
+// Register-level decoding of packed codes into FP16 MFMA operands (gfx950).
+//
+// A slot is 32 consecutive codes of one group: four 32-bit words (4-bit) or three words plus
+// the group's tail word (3-bit).  Inside a word, even positions live in the low half-word and odd
+// positions in the high half-word, so (word & mask) picks one code into each half.  OR-ing the
+// bits of a power of two whose ulp equals the code's bit weight turns the pair into the two FP16
+// numbers 2^e + q without any shift or conversion:
+//      bits 0..3  | 0x6400 -> 1024 + q        bits 4..7 | 0x5400 -> 64 + q          (4-bit)
+//      bits 0..2  | 0x6400 -> 1024 + q        bits 3..5 | 0x5800 -> 128 + q
+//      bits 6..8  | 0x4C00 -> 16 + q                                                 (3-bit)
+// One packed FP16 add of -(2^e + z) then gives the exact integers q - z (Sec. 3.2, Eq. 10 without
+// the scale).  The constants -(2^e + z) are built with integer ops from z (z < 16 fits the mantissa).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gwq {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// A constant the optimiser cannot see through.  With mask and magic in registers, (x & mask) | magic
+// selects the single three-operand v_and_or_b32; as literals it would become two instructions.
+__device__ inline uint32_t opaque(uint32_t c)
+{
+    uint32_t r;
+    asm("s_mov_b32 %0, %1" : "=s"(r) : "i"(c));
+    return r;
+}
+__device__ inline uint32_t opaque_v(uint32_t c)
+{
+    uint32_t r;
+    asm("v_mov_b32 %0, %1" : "=v"(r) : "i"(c));
+    return r;
+}
+
+// Masks (SGPR) and magic numbers (VGPR) of the decoders, materialised once per kernel.
+struct DecodeConsts {
+    uint32_t m0, m1, m2, k1024, kmid, k16;
+    __device__ inline explicit DecodeConsts(int bits)
+    {
+        if (bits == 4) {
+            m0 = opaque(0x000F000Fu); m1 = opaque(0x00F000F0u); m2 = 0;
+            k1024 = opaque_v(0x64006400u); kmid = opaque_v(0x54005400u); k16 = 0;
+        } else {
+            m0 = opaque(0x00070007u); m1 = opaque(0x00380038u); m2 = opaque(0x01C001C0u);
+            k1024 = opaque_v(0x64006400u); kmid = opaque_v(0x58005800u); k16 = opaque_v(0x4C004C00u);
+        }
+    }
+};
+
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) { return (x & mask) | magic; }
+
+__device__ inline uint32_t pk_add(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, a) + __builtin_bit_cast(half2v, b));
+}
+__device__ inline uint32_t pk_mul(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2v, a) * __builtin_bit_cast(half2v, b));
+}
+
+// Per-group constants derived from the zero point: -(2^e + z) in both halves.
+template <int BITS> struct ZeroConsts;
+template <> struct ZeroConsts<4> {
+    uint32_t c1024, c64;
+    __device__ inline explicit ZeroConsts(uint32_t z)
+    {
+        const uint32_t zz = z | z << 16;
+        c1024 = zz | 0xE400E400u;              // -(1024 + z): ulp is 1 in [1024, 2048)
+        c64 = zz << 4 | 0xD400D400u;           // -(64 + z):   ulp is 1/16 in [64, 128)
+    }
+};
+template <> struct ZeroConsts<3> {
+    uint32_t c1024, c128, c16;
+    __device__ inline explicit ZeroConsts(uint32_t z)
+    {
+        const uint32_t zz = z | z << 16;
+        c1024 = zz | 0xE400E400u;
+        c128 = zz << 3 | 0xD800D800u;          // -(128 + z): ulp is 1/8 in [128, 256)
+        c16 = zz << 6 | 0xCC00CC00u;           // -(16 + z):  ulp is 1/64 in [16, 32)
+    }
+};
+
+// One 4-bit word (8 codes) -> 8 FP16 values q - z in position order.
+__device__ inline u32x4 decode_word4(uint32_t x, const ZeroConsts<4> &c, const DecodeConsts &d)
+{
+    const uint32_t y = x >> 8;
+    u32x4 r;
+    r.x = pk_add(and_or(x, d.m0, d.k1024), c.c1024);
+    r.y = pk_add(and_or(x, d.m1, d.kmid), c.c64);
+    r.z = pk_add(and_or(y, d.m0, d.k1024), c.c1024);
+    r.w = pk_add(and_or(y, d.m1, d.kmid), c.c64);
+    return r;
+}
+
+// 4-bit slot: words w[0..3] -> operands f[0..3] (8 codes each).
+__device__ inline void decode_slot4(const uint32_t w[4], uint32_t z, const DecodeConsts &d, u32x4 f[4])
+{
+    const ZeroConsts<4> c(z);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f[j] = decode_word4(w[j], c, d);
+}
+
+// 3-bit slot: words w[0..2] hold codes 0..29 (five pairs each), `tail_pair` holds codes 30, 31 in
+// bits 0..2 and 16..18 (the caller shifts the group's tail word by 3 * slot).
+__device__ inline void decode_slot3(const uint32_t w[3], uint32_t tail_pair, uint32_t z, const DecodeConsts &d,
+                                    u32x4 f[4])
+{
+    const ZeroConsts<3> c(z);
+    uint32_t p[16];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t x = w[i], y = x >> 9;
+        p[5 * i + 0] = pk_add(and_or(x, d.m0, d.k1024), c.c1024);
+        p[5 * i + 1] = pk_add(and_or(x, d.m1, d.kmid), c.c128);
+        p[5 * i + 2] = pk_add(and_or(x, d.m2, d.k16), c.c16);
+        p[5 * i + 3] = pk_add(and_or(y, d.m0, d.k1024), c.c1024);
+        p[5 * i + 4] = pk_add(and_or(y, d.m1, d.kmid), c.c128);
+    }
+    p[15] = pk_add(and_or(tail_pair, d.m0, d.k1024), c.c1024);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f[j] = u32x4{p[4 * j], p[4 * j + 1], p[4 * j + 2], p[4 * j + 3]};
+}
+
+}  // namespace gwq

@@ -28,8 +28,8 @@ inline size_t pack_workspace_bytes(int64_t N) { return (size_t)(kWsRows + 3 * N)
 // Launchers (defined in the .hip files).  Each enqueues on `stream` and returns the last HIP error.
 hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
                        uint32_t *ws, hipStream_t stream);
-hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int tiles_override,
-                         int waves_override, hipStream_t stream);
+hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int waves_override,
+                         hipStream_t stream);
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, hipStream_t stream);
 
 }  // namespace gwq

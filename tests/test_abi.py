@@ -88,10 +88,11 @@ def test_pack_and_linear_validate_before_touching_the_device():
 
 def test_tuning_and_strings():
     L = binding.lib()
-    assert L.gwq_tuning_set(b"decode_tiles", 3) == -3
     assert L.gwq_tuning_set(b"decode_waves", 17) == -3
+    assert L.gwq_tuning_set(b"decode_waves", -1) == -3
     assert L.gwq_tuning_set(b"nonsense", 1) == -3
-    assert L.gwq_tuning_set(b"decode_tiles", 2) == 0 and L.gwq_tuning_set(b"decode_tiles", 0) == 0
+    assert L.gwq_tuning_set(None, 1) == -1
+    assert L.gwq_tuning_set(b"decode_waves", 2) == 0 and L.gwq_tuning_set(b"decode_waves", 0) == 0
     assert L.gwq_status_string(0) == b"ok"
     assert b"workspace" in L.gwq_status_string(-4)
     assert gwq.version().startswith("gwq-gfx950")
