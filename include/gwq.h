@@ -83,8 +83,10 @@ typedef struct {
     int64_t n_outliers;
 } gwq_sizes;
 
-/* Sizes for a layer (pure host arithmetic, touches no device).  col_idx and out_val sizes are
- * at least 16 bytes so that zero-outlier layers still get valid pointers.
+/* Sizes for a layer (pure host arithmetic, touches no device).  scales and zeros are rounded up
+ * to whole 16-byte vectors and col_idx / out_val carry one spare vector: gwq_linear reads them
+ * with 16-byte loads, so buffers must have these sizes and be 16-byte aligned (the padding is
+ * never interpreted).
  * Errors: NULL out, shape limits above, unsupported bits/group, ppm > 1e6, M_max < 0. */
 gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_t outlier_ppm,
                       int32_t M_max, gwq_sizes *out);

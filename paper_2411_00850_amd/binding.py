@@ -99,11 +99,11 @@ class PackedLayer:
     ppm: int
     n_outliers: int
     qweight: "torch.Tensor"   # int32 view of the uint32 words [N, K/128, wpg]
-    scales: "torch.Tensor"    # int16 view of the FP16 bits [N, K/128]
-    zeros: "torch.Tensor"     # uint8 [N, K/128]
+    scales: "torch.Tensor"    # int16 view of the FP16 bits [N * K/128], padded to 16 bytes
+    zeros: "torch.Tensor"     # uint8 [N * K/128], padded to 16 bytes
     row_ptr: "torch.Tensor"   # int32 [N+1]
-    col_idx: "torch.Tensor"   # int16 view of uint16 [>= n_outliers]
-    out_val: "torch.Tensor"   # int16 view of FP16 bits [>= n_outliers]
+    col_idx: "torch.Tensor"   # int16 view of uint16 [n_outliers + padding]
+    out_val: "torch.Tensor"   # int16 view of FP16 bits [n_outliers + padding]
 
     def c_struct(self):
         return _Packed(self.N, self.K, self.bits, 128, self.ppm, self.n_outliers,
@@ -123,8 +123,8 @@ def alloc_packed(N, K, bits, ppm=10000, device="cuda"):
     n_slots = sz["col_idx"] // 2
     return PackedLayer(N, K, bits, ppm, sz["n_outliers"],
                        torch.empty((N, gpr, wpg), dtype=torch.int32, device=device),
-                       torch.empty((N, gpr), dtype=torch.int16, device=device),
-                       torch.empty((N, gpr), dtype=torch.uint8, device=device),
+                       torch.empty(sz["scales"] // 2, dtype=torch.int16, device=device),
+                       torch.empty(sz["zeros"], dtype=torch.uint8, device=device),
                        torch.empty(N + 1, dtype=torch.int32, device=device),
                        torch.empty(n_slots, dtype=torch.int16, device=device),
                        torch.empty(n_slots, dtype=torch.int16, device=device)), sz

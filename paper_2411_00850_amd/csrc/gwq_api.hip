@@ -48,10 +48,11 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     const int64_t k_out = outlier_count(N, K, outlier_ppm);
     memset(out, 0, sizeof(*out));
     out->qweight = (size_t)groups * gwq::words_per_group(bits) * 4;
-    out->scales = (size_t)groups * 2;
-    out->zeros = (size_t)groups;
+    // Staged with 16-byte loads by the decode kernel: whole vectors, and one spare for the CSR arrays.
+    out->scales = ((size_t)groups * 2 + 15) / 16 * 16;
+    out->zeros = ((size_t)groups + 15) / 16 * 16;
     out->row_ptr = (size_t)(N + 1) * 4;
-    out->col_idx = k_out * 2 > 16 ? (size_t)k_out * 2 : 16;
+    out->col_idx = ((size_t)k_out * 2 + 15) / 16 * 16 + 16;
     out->out_val = out->col_idx;
     out->pack_workspace = gwq::pack_workspace_bytes(N);
     out->linear_workspace = 0;
@@ -82,7 +83,9 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     if (s != GWQ_OK) return s;
     if (!X_f16 || !Y_f16) return GWQ_ERR_NULL;
     if (M < 1 || (int64_t)M * P->N >= ((int64_t)1 << 40)) return GWQ_ERR_SHAPE;
-    if (((uintptr_t)X_f16 & 15) || ((uintptr_t)P->qweight & 15)) return GWQ_ERR_SHAPE;
+    if (((uintptr_t)X_f16 | (uintptr_t)P->qweight | (uintptr_t)P->scales | (uintptr_t)P->zeros |
+         (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
+        return GWQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_waves, st)
                            : gwq::launch_gemm(*P, X_f16, M, Y_f16, st);

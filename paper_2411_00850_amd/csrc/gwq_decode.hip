@@ -4,22 +4,25 @@
 //           + sum_{j in CSR row n} out_val[j] * X[m][col_idx[j]]            (the FP16 outliers)
 //
 // Mapping.  A block owns 16 output channels; its waves split K by whole groups of 128.  A wave
-// feeds v_mfma_f32_16x16x32_f16 with X as the 16 x 32 operand (rows m, zero beyond M) and the
-// dequantised codes as the 32 x 16 operand (columns n): lane (r = lane % 16, b = lane / 16) owns
-// slot b of each group of channel n0 + r, i.e. 32 consecutive codes = one 16-byte load (4-bit) or
-// a 12-byte load plus the shared tail word (3-bit).  Codes become the exact FP16 integers q - z
-// with one AND-OR and one packed add per pair (the code bits are dropped into the mantissa of a
-// power of two); the group scale is applied to the four FP32 results per lane after the group's
-// four MFMAs.  Each lane then adds its channel's outliers for its own four m, the waves' partial
-// sums meet in LDS in a fixed order, and one thread per output rounds to FP16 and stores.
+// feeds v_mfma_f32_16x16x32_f16 with X as the 16 x 32 operand (rows m) and the dequantised codes
+// as the 32 x 16 operand (columns n): lane (r = lane % 16, b = lane / 16) owns slot b of each
+// group of channel n0 + r, i.e. 32 consecutive codes = one 16-byte load (4-bit) or a 12-byte
+// load plus the shared tail word (3-bit).  Codes become the exact FP16 integers q - z with one
+// AND-OR and one packed add per pair; the group scale is applied to the four FP32 results per
+// lane after the group's four MFMAs.  The lanes then add their channel's outliers, the waves'
+// partial sums meet in LDS in a fixed order, and one thread per output rounds to FP16 and stores.
 // No atomics, no second pass: results are run-to-run identical.
 //
-// Latency.  At these sizes a whole matrix is only a few microseconds of HBM time, so the kernel is
-// organised around having every byte requested as early as possible: a wave issues the code loads
-// of U groups at once (and of the next U before it computes the current ones), the scales and
-// zero points of those groups come in as one load per lane and are handed round with
-// ds_bpermute, and the dependent chain of the outliers (row_ptr -> col/val -> X[col]) is started
-// before the dense loop so that it overlaps the code stream.
+// What bounds it.  A matrix is only a few microseconds of HBM time, and at that scale two things
+// matter more than arithmetic:
+//   * every byte must be requested at once: all loads are unconditional (clamped indices), issued
+//     before anything consumes them, and nothing is converted or combined right behind a load
+//     (loads retire in order, so waiting for a young one waits for all older ones);
+//   * the address unit of a CU handles a scattered or sub-dword load lane by lane (about 64 cycles
+//     per instruction against 16 for a coalesced 16-byte load), so everything except the code
+//     stream is fetched with block-wide coalesced 16-byte loads into LDS: the block's scales and
+//     zero points (contiguous for 16 consecutive channels), X (when it fits) and the block's
+//     contiguous CSR segment, whose bounds come in through the scalar cache.
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -28,16 +31,12 @@ namespace {
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-// Every load below is unconditional with a clamped (always valid) index, and nothing is combined
-// or converted until it is consumed: a conditional load, or arithmetic right behind a load, makes
-// the wave wait for that load - and, because loads retire in order, for every older one too.
-
 __device__ inline const uint32_t *at_byte(const uint32_t *base, uint32_t byte_off)
 {
     return reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + byte_off);
 }
 
-// Registers of one slot (32 codes) as loaded from memory; `off` is a byte offset from qweight.
+// Registers of one slot (32 codes) as loaded from memory; offsets are bytes from qweight.
 template <int BITS> struct Slot;
 template <> struct Slot<4> {
     uint4 w;
@@ -65,17 +64,11 @@ template <> struct Slot<3> {
     }
 };
 
-constexpr int kPre = 4;        // outlier entries per lane fetched ahead of the dense loop
-
-// Codes, scales and zero points of one chunk of U (4 or 8) groups of one channel.
+// Codes of one chunk of U groups of one channel.
 template <int BITS, int U> struct Chunk {
     Slot<BITS> slot[U];
-    uint16_t sc[U / 4];        // lane (r, b) holds the scale and zero point of groups g0 + b (+ 4)
-    uint8_t zp[U / 4];
-
-    // row_group = index of (channel, group 0); g_last = last valid group of this wave (clamp).
-    __device__ inline void load(const uint32_t *qweight, const uint16_t *scales, const uint8_t *zeros,
-                                uint32_t row_group, int g0, int g_last, int b)
+    // row_group = index of (channel, group 0); groups past g_last repeat g_last (always valid).
+    __device__ inline void load(const uint32_t *qweight, uint32_t row_group, int g0, int g_last, int b)
     {
         constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
 #pragma unroll
@@ -83,21 +76,22 @@ template <int BITS, int U> struct Chunk {
             const int g = g0 + u < g_last ? g0 + u : g_last;
             slot[u].load(qweight, (row_group + g) * group_bytes, b);
         }
-#pragma unroll
-        for (int h = 0; h < U / 4; ++h) {
-            const int g = g0 + 4 * h + b < g_last ? g0 + 4 * h + b : g_last;
-            sc[h] = scales[row_group + g];
-            zp[h] = zeros[row_group + g];
-        }
     }
 };
 
-// BITS: 3 or 4.  U: groups per chunk.  PIPE: a wave owns more than U groups and double-buffers its
-// chunks.  MS: 1..4 = M is exactly MS and X[M][K] is staged in LDS once per block, the four lanes
-// of a channel sharing its outliers (only without PIPE); 0 = any M <= 16, X read from global memory.
+constexpr int kPre = 4;        // outlier entries a lane handles without a loop
+constexpr int kMetaRounds = 2; // 16-byte vectors of scales / zero points a thread stages
+
+// BITS: 3 or 4.  U: groups per chunk (4 or 8).  PIPE: a wave owns more than U groups (up to 16 when
+// MS > 0) and double-buffers chunks of U = 4.  MS: 1..4 = M is exactly MS and X[M][K] is staged in
+// LDS, the four lanes of a channel sharing its outliers; 0 = any M <= 16, X read from global memory.
 //
 // Rows m >= M of the X operand are never zeroed: lanes r >= M re-read row 0, which only produces
 // result rows m >= M, and those are not stored.
+//
+// Dynamic LDS, in this order: X [MS][K] halves | scales [16][gpr] halves | zero points [16][gpr]
+// bytes | 16 spare bytes | CSR columns, blockDim * 8 entries | CSR values, same | partial sums
+// [waves][4][64] floats.  The launcher guarantees kMetaRounds * blockDim >= 3 * gpr.
 template <int BITS, int U, bool PIPE, int MS>
 __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict__ qweight,
                                                       const uint16_t *__restrict__ scales,
@@ -106,65 +100,95 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
                                                       const uint16_t *__restrict__ col_idx,
                                                       const uint16_t *__restrict__ out_val,
                                                       const _Float16 *__restrict__ X, _Float16 *__restrict__ Y,
-                                                      int N, int K, int M, int groups_per_wave, int last_entry)
+                                                      int N, int K, int M, int groups_per_wave,
+                                                      int sc_last_vec, int zp_last_vec, int csr_last_vec)
 {
     constexpr bool SMALLM = MS > 0;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x, nwaves = nthreads >> 6;
     const int r = lane & 15, b = lane >> 4;
     const int gpr = K / kGroup;
     const int row0 = blockIdx.x * 16;
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
-    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);                          // [MS][K]
-    float *red = reinterpret_cast<float *>(lds_raw + (size_t)MS * K * 2);          // [waves][4][64]
 
-    // Outlier chain, step 1: CSR row bounds of this lane's channel (the first loads issued).
+    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
+    const uint32_t sc_off = (uint32_t)MS * K * 2;
+    const uint32_t zp_off = sc_off + 32 * gpr;
+    const uint32_t spare_off = zp_off + 16 * gpr;
+    const uint32_t col_off = spare_off + 16;
+    const uint32_t val_off = col_off + 16 * nthreads;
+    const uint32_t red_off = val_off + 16 * nthreads;
+    const uint16_t *sc_lds = reinterpret_cast<const uint16_t *>(lds_raw + sc_off);
+    const uint8_t *zp_lds = lds_raw + zp_off;
+    const uint16_t *col_lds = reinterpret_cast<const uint16_t *>(lds_raw + col_off);
+    const uint16_t *val_lds = reinterpret_cast<const uint16_t *>(lds_raw + val_off);
+    float *red = reinterpret_cast<float *>(lds_raw + red_off);
+
+    // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
+    const int last_row = row0 + 16 < N ? row0 + 16 : N;
+    const int e_begin = row_ptr[row0], e_end = row_ptr[last_row];
     const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
 
-    const int g_begin = wave * groups_per_wave;
+    // This wave's groups [g_begin, g_last]; a wave past the end of K (has_groups false) walks the
+    // last group with a zero scale.
+    const bool has_groups = wave * groups_per_wave < gpr;
+    const int g_begin = has_groups ? wave * groups_per_wave : gpr - 1;
     const int g_end = g_begin + groups_per_wave < gpr ? g_begin + groups_per_wave : gpr;
-    const int g_last = g_end - 1;                       // >= g_begin: the launcher gives every wave a group
+    const int g_last = g_end - 1;
 
-    // X for LDS staging is requested next: it returns before the code stream does, and its
-    // consumers must not have to wait for the (younger) code loads.  Each wave stages the columns
-    // of its own groups (the waves partition K), U/4 16-byte vectors per lane and row; lanes past
-    // the end of a short slice repeat its last vector.
-    constexpr int kXVecs = SMALLM ? MS * (U / 4) : 1;
+    // Staging loads, all 16-byte and coalesced.  (1) X: each wave brings the columns of its own
+    // groups (the waves partition K); lanes past the end of a short slice repeat its last vector.
+    constexpr int kSliceQuads = PIPE ? 4 : U / 4;       // 64-vector rounds covering a wave's slice
+    constexpr int kXVecs = SMALLM ? MS * kSliceQuads : 1;
     u32x4 xstage[kXVecs];
-    uint32_t xvec[kXVecs];                              // vector index inside X / xs
+    uint32_t xvec[kXVecs];
     if (SMALLM) {
         const int slice_vecs = (g_end - g_begin) * (kGroup / 8);
 #pragma unroll
         for (int e = 0; e < MS; ++e)
 #pragma unroll
-            for (int i = 0; i < U / 4; ++i) {
+            for (int i = 0; i < kSliceQuads; ++i) {
                 const int q = lane + 64 * i < slice_vecs ? lane + 64 * i : slice_vecs - 1;
-                xvec[e * (U / 4) + i] = (uint32_t)e * (K / 8) + g_begin * (kGroup / 8) + q;
-                xstage[e * (U / 4) + i] = reinterpret_cast<const u32x4 *>(X)[xvec[e * (U / 4) + i]];
+                xvec[e * kSliceQuads + i] = (uint32_t)e * (K / 8) + g_begin * (kGroup / 8) + q;
+                xstage[e * kSliceQuads + i] = reinterpret_cast<const u32x4 *>(X)[xvec[e * kSliceQuads + i]];
             }
     }
+    // (2) The block's scales (32 * gpr bytes) and zero points (16 * gpr bytes), contiguous in
+    // memory for 16 consecutive channels: vector t < 2 gpr is a scales vector, the next gpr are
+    // zero-point vectors, any further thread re-reads vector 0 into the spare slot.
+    uint32_t meta_dst[kMetaRounds];
+    u32x4 meta[kMetaRounds];
+#pragma unroll
+    for (int i = 0; i < kMetaRounds; ++i) {
+        const int t = tid + i * nthreads;
+        const bool is_sc = t < 2 * gpr, is_zp = !is_sc && t < 3 * gpr;
+        int v = is_sc ? blockIdx.x * 2 * gpr + t : blockIdx.x * gpr + (t - 2 * gpr);
+        const int last = is_sc ? sc_last_vec : zp_last_vec;
+        v = (is_sc || is_zp) ? (v < last ? v : last) : 0;
+        const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
+        meta[i] = src[v];
+        meta_dst[i] = is_sc ? sc_off + 16 * t : is_zp ? zp_off + 16 * (t - 2 * gpr) : spare_off;
+    }
 
-    // The code stream: everything below overlaps its HBM latency.
+    // The code stream: everything else overlaps its HBM latency.
     const uint32_t row_group = (uint32_t)n_c * gpr;
     Chunk<BITS, U> cur;
-    cur.load(qweight, scales, zeros, row_group, g_begin, g_last, b);
+    cur.load(qweight, row_group, g_begin, g_last, b);
 
-    // Outlier chain, step 2: the first kPre entries of this lane.  SMALLM: the four lanes of a
-    // channel split its entries; otherwise lane (r, b) takes every entry for rows m = 4b .. 4b+3.
-    const int o_stride = SMALLM ? 4 * nwaves : nwaves;
-    const int o_first = SMALLM ? 4 * wave + b : wave;
-    const bool o_live = n < N && (SMALLM || 4 * b < M);
-    uint16_t pre_col[kPre], pre_val[kPre];
-    bool pre_ok[kPre];
-#pragma unroll
-    for (int i = 0; i < kPre; ++i) {
-        const int j = rp0 + o_first + i * o_stride;
-        pre_ok[i] = o_live && j < rp1;
-        const int jc = j < last_entry ? j : last_entry;     // always a valid slot of the arrays
-        pre_col[i] = col_idx[jc];
-        pre_val[i] = out_val[jc];
+    // (3) The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin:
+    // thread t brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
+    const int e0 = e_begin & ~7;
+    u32x4 seg_col, seg_val;
+    {
+        const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
+        int v = e0 / 8 + tid;
+        v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
+        v = v < csr_last_vec ? v : csr_last_vec;
+        seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
+        seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
     }
+    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
 
     // Nothing that consumes a load may be scheduled above this point.
     __builtin_amdgcn_sched_barrier(0);
@@ -172,8 +196,10 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
     if (SMALLM) {
 #pragma unroll
         for (int i = 0; i < kXVecs; ++i) reinterpret_cast<u32x4 *>(xs)[xvec[i]] = xstage[i];
-        __syncthreads();
     }
+#pragma unroll
+    for (int i = 0; i < kMetaRounds; ++i) *reinterpret_cast<u32x4 *>(lds_raw + meta_dst[i]) = meta[i];
+    __syncthreads();
 
     float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
     const int x_row = r < M ? r : 0;
@@ -183,17 +209,17 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
     auto compute = [&](const Chunk<BITS, U> &c, int g0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool valid = g0 + u <= g_last;        // wave-uniform
+            const bool valid = has_groups && g0 + u <= g_last;      // wave-uniform
             const int g = valid ? g0 + u : g_last;
             u32x4 xa[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 xa[j] = *reinterpret_cast<const u32x4 *>(xsrc + (uint32_t)g * kGroup + 8 * j);
-            const uint32_t mine = (uint32_t)c.sc[u >> 2] | (uint32_t)c.zp[u >> 2] << 16;
-            const uint32_t sz = __builtin_amdgcn_ds_bpermute((r + 16 * (u & 3)) * 4, mine);
-            const float s = valid ? (float)__builtin_bit_cast(_Float16, (uint16_t)(sz & 0xFFFF)) : 0.f;
+            const float s_raw = (float)__builtin_bit_cast(_Float16, sc_lds[r * gpr + g]);
+            const float s = valid ? s_raw : 0.f;
+            const uint32_t z = zp_lds[r * gpr + g];
             u32x4 wb[4];
-            c.slot[u].decode(sz >> 16, b, dc, wb);
+            c.slot[u].decode(z, b, dc, wb);
             float4v part = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -208,7 +234,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
         for (int g0 = g_begin; g0 <= g_last; g0 += U) {
             Chunk<BITS, U> nxt;
             const bool more = g0 + U <= g_last;
-            if (more) nxt.load(qweight, scales, zeros, row_group, g0 + U, g_last, b);
+            if (more) nxt.load(qweight, row_group, g0 + U, g_last, b);
             compute(cur, g0);
             if (more) cur = nxt;
         }
@@ -216,9 +242,17 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
         compute(cur, g_begin);
     }
 
-    // Outlier chain, step 3: X at the prefetched columns, then any entries beyond the window.
-    // SMALLM: every lane sums its share of the channel's entries for rows m = 0 .. MS-1 in `oacc`;
-    // otherwise the lane covers rows m = 4b .. 4b+3, the rows of its MFMA results.
+    // The CSR segment has arrived by now: publish it.
+    reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
+    reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+    __syncthreads();
+
+    // Outliers.  SMALLM: the four lanes of a channel split its entries and sum rows m = 0 .. MS-1;
+    // otherwise lane (r, b) takes every entry of its channel for rows m = 4b .. 4b+3, the rows of
+    // its MFMA results.  Entry j sits at LDS index j - e0 when j < staged_end.
+    const int o_stride = SMALLM ? 4 * nwaves : nwaves;
+    const int o_first = SMALLM ? 4 * wave + b : wave;
+    const bool o_live = n < N && (SMALLM || 4 * b < M);
     float4v oacc = float4v{0.f, 0.f, 0.f, 0.f};
     auto add_outlier = [&](uint32_t col, uint16_t val_bits, bool ok) {
         const float v = ok ? (float)__builtin_bit_cast(_Float16, val_bits) : 0.f;
@@ -234,9 +268,20 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
         }
     };
 #pragma unroll
-    for (int i = 0; i < kPre; ++i) add_outlier(pre_col[i], pre_val[i], pre_ok[i]);
-    if (o_live)
-        for (int j = rp0 + o_first + kPre * o_stride; j < rp1; j += o_stride) add_outlier(col_idx[j], out_val[j], true);
+    for (int i = 0; i < kPre; ++i) {
+        const int j = rp0 + o_first + i * o_stride;
+        const bool ok = o_live && j < rp1 && j < staged_end;
+        const int idx = ok ? j - e0 : 0;
+        add_outlier(col_lds[idx], val_lds[idx], ok);
+    }
+    if (o_live) {
+        int j = rp0 + o_first + kPre * o_stride;
+        for (; j < rp1 && j < staged_end; j += o_stride) add_outlier(col_lds[j - e0], val_lds[j - e0], true);
+        // Entries that did not fit the staged window (very long rows) come straight from memory.
+        j = rp0 + o_first;
+        if (j < staged_end) j += ((staged_end - j + o_stride - 1) / o_stride) * o_stride;
+        for (; j < rp1; j += o_stride) add_outlier(col_idx[j], out_val[j], true);
+    }
 
     // Fixed-order reduction over the waves (and, for SMALLM, over the four lanes of a channel),
     // then FP16 store.  SMALLM: only lanes b = 0 hold dense results for rows m < 4.
@@ -247,8 +292,8 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
     }
     __syncthreads();
     if (SMALLM) {
-        if (threadIdx.x < 16 * MS) {                    // (e, r)
-            const int e = threadIdx.x >> 4, rr = threadIdx.x & 15;
+        if (tid < 16 * MS) {                            // (e, r)
+            const int e = tid >> 4, rr = tid & 15;
             float sum = 0.f;
             for (int w = 0; w < nwaves; ++w)
 #pragma unroll
@@ -256,7 +301,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
             if (row0 + rr < N) Y[(size_t)e * N + row0 + rr] = (_Float16)sum;
         }
     } else {
-        for (int idx = threadIdx.x; idx < 256; idx += blockDim.x) {
+        for (int idx = tid; idx < 256; idx += nthreads) {
             float sum = 0.f;
             for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
             const int e = idx >> 6, l = idx & 63;
@@ -271,20 +316,25 @@ constexpr size_t kXLdsBudget = 64 * 1024;               // X[M][K] is staged in 
 template <int BITS, int U, bool PIPE, int MS>
 hipError_t launch_v(const gwq_packed &P, const void *X, int M, void *Y, int nwaves, int gpw, hipStream_t st)
 {
+    const int gpr = P.K / kGroup;
     const int blocks = (P.N + 15) / 16;
-    const size_t lds = (size_t)nwaves * 1024 + (size_t)MS * P.K * 2;
+    const size_t lds = (size_t)MS * P.K * 2 + 48 * (size_t)gpr + 16 + 32 * (size_t)nwaves * 64 + (size_t)nwaves * 1024;
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
-    if (MS > 0 && !attr_set) {
+    if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<BITS, U, PIPE, MS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)(kXLdsBudget + 16 * 1024));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int last_entry = P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0;
+    // Last 16-byte vector of each staged array (the buffers are padded to whole vectors, the CSR
+    // arrays by one more vector, so clamped reads stay inside them).
+    const int64_t groups = (int64_t)P.N * gpr;
+    const int sc_last = (int)((groups * 2 + 15) / 16) - 1;
+    const int zp_last = (int)((groups + 15) / 16) - 1;
+    const int csr_last = (int)((P.n_outliers * 2 + 15) / 16);
     decode_kernel<BITS, U, PIPE, MS><<<blocks, nwaves * 64, lds, st>>>(
         P.qweight, P.scales, P.zeros, P.row_ptr, P.col_idx, P.out_val, static_cast<const _Float16 *>(X),
-        static_cast<_Float16 *>(Y), P.N, P.K, M, gpw, last_entry);
+        static_cast<_Float16 *>(Y), P.N, P.K, M, gpw, sc_last, zp_last, csr_last);
     return hipGetLastError();
 }
 
@@ -293,6 +343,10 @@ hipError_t launch_m(const gwq_packed &P, const void *X, int M, void *Y, int nwav
 {
     if (gpw <= 4) return launch_v<BITS, 4, false, MS>(P, X, M, Y, nwaves, gpw, st);
     if (gpw <= 8) return launch_v<BITS, 8, false, MS>(P, X, M, Y, nwaves, gpw, st);
+    // Long rows: double-buffered chunks; X is staged only while its staging registers stay few.
+    if constexpr (MS == 1 || MS == 2) {
+        if (gpw <= 16) return launch_v<BITS, 4, true, MS>(P, X, M, Y, nwaves, gpw, st);
+    }
     return launch_v<BITS, 4, true, 0>(P, X, M, Y, nwaves, gpw, st);
 }
 
@@ -312,13 +366,18 @@ hipError_t launch_b(const gwq_packed &P, const void *X, int M, void *Y, int nwav
 hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int waves_override, hipStream_t st)
 {
     const int gpr = P.K / kGroup;
-    // One chunk of eight groups per wave where the row is long enough, at most 16 waves per block.
+    // One chunk of eight groups per wave where the row is long enough, at most 16 waves per block,
+    // and enough threads to stage the 3 * gpr vectors of scales and zero points in kMetaRounds.
     int nwaves = waves_override ? waves_override : (gpr + 7) / 8;
+    const int min_waves = (3 * gpr + 64 * kMetaRounds - 1) / (64 * kMetaRounds);
+    if (nwaves < min_waves) nwaves = min_waves;
     if (nwaves > 16) nwaves = 16;
     if (nwaves > gpr) nwaves = gpr;
     if (nwaves < 1) nwaves = 1;
     const int gpw = (gpr + nwaves - 1) / nwaves;
-    nwaves = (gpr + gpw - 1) / gpw;                     // drop waves that would own no group
+    const int needed = (gpr + gpw - 1) / gpw;           // waves that own at least one group
+    if (needed >= min_waves) nwaves = needed;
+    if (nwaves * 64 * kMetaRounds < 3 * gpr) return hipErrorInvalidValue;   // K <= 65536 keeps this false
     return P.bits == 4 ? launch_b<4>(P, X, M, Y, nwaves, gpw, st) : launch_b<3>(P, X, M, Y, nwaves, gpw, st);
 }
 

@@ -17,23 +17,33 @@ def upload_packed(P):
     """Oracle-packed host arrays -> device PackedLayer (so gwq_linear is tested on its own)."""
     import torch
 
-    def dev(a, dt):
-        a = np.ascontiguousarray(a)
-        if a.size == 0:
-            a = np.zeros(8, a.dtype)
+    n_out = int(P.row_ptr[-1])
+    sizes = gwq.layout(P.N, P.K, P.bits, 128, 0)       # scales / zeros sizes do not depend on ppm
+
+    def dev(a, dt, nbytes=None):
+        a = np.ascontiguousarray(a).ravel()
+        if nbytes is not None:                       # pad to the size gwq_layout prescribes
+            buf = np.full(nbytes // a.itemsize, 0x5A5A & (2 ** (8 * a.itemsize) - 1), a.dtype)
+            buf[:a.size] = a
+            a = buf
         return torch.from_numpy(a.view(dt)).cuda()
 
-    return PackedLayer(P.N, P.K, P.bits, P.ppm, int(P.row_ptr[-1]),
-                       dev(P.qweight, np.int32), dev(P.scales, np.int16), dev(P.zeros, np.uint8),
-                       dev(P.row_ptr, np.int32), dev(P.col_idx, np.int16), dev(P.out_val, np.int16))
+    csr_bytes = (2 * n_out + 15) // 16 * 16 + 16
+    D = PackedLayer(P.N, P.K, P.bits, P.ppm, n_out,
+                    dev(P.qweight, np.int32).view(P.N, P.K // 128, -1),
+                    dev(P.scales, np.int16, sizes["scales"]), dev(P.zeros, np.uint8, sizes["zeros"]),
+                    dev(P.row_ptr, np.int32), dev(P.col_idx, np.int16, csr_bytes),
+                    dev(P.out_val, np.int16, csr_bytes))
+    return D
 
 
 def download_packed(D):
     """Device PackedLayer -> dict of numpy arrays with the unsigned dtypes of the format."""
     k = D.n_outliers
+    g = D.N * (D.K // 128)
     return dict(qweight=D.qweight.cpu().numpy().view(np.uint32),
-                scales=D.scales.cpu().numpy().view(np.uint16),
-                zeros=D.zeros.cpu().numpy(),
+                scales=D.scales.cpu().numpy().view(np.uint16).ravel()[:g],
+                zeros=D.zeros.cpu().numpy().ravel()[:g],
                 row_ptr=D.row_ptr.cpu().numpy(),
                 col_idx=D.col_idx.cpu().numpy().view(np.uint16)[:k],
                 out_val=D.out_val.cpu().numpy().view(np.uint16)[:k])
