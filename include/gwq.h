@@ -79,7 +79,7 @@ typedef struct {
 typedef struct {
     size_t qweight, scales, zeros, row_ptr, col_idx, out_val;
     size_t pack_workspace;    /* for gwq_pack                                             */
-    size_t linear_workspace;  /* for gwq_linear with M <= M_max (may be 0)                */
+    size_t linear_workspace;  /* for gwq_linear with M <= M_max (0 when M_max <= 16)      */
     int64_t n_outliers;
 } gwq_sizes;
 
@@ -103,8 +103,10 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
 /* Y[M][N] = X[M][K] * (Q(W) + outliers)^T with Q(W) = s*(q-z) (Eq. 10), FP32 accumulation,
  * FP16 output.  M <= 16 takes the bandwidth-bound decode kernel, larger M the MFMA GEMM.
  *   P  host struct with device pointers   X_f16 device [M][K]   Y_f16 device [M][N]
- * X and Y must not overlap; Y is fully overwritten.  workspace may be NULL when
- * linear_workspace is 0.  Results are deterministic (no floating-point atomics). */
+ * X and Y must not overlap; Y is fully overwritten.  M > 16 needs `workspace`: device scratch of
+ * at least the linear_workspace bytes gwq_layout reports for an M_max > 16 (it is rewritten by
+ * every call; concurrent calls need separate workspaces); for M <= 16 it may be NULL.
+ * Results are deterministic (no floating-point atomics). */
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);
 

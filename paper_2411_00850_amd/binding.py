@@ -153,15 +153,26 @@ def pack(W, score, bits, ppm=10000, stream=None, workspace=None):
     return P
 
 
-def linear(P, X, out=None, stream=None):
+def linear_workspace(P, M, device="cuda"):
+    """Scratch tensor gwq_linear needs for this layer at M rows (None for the decode path)."""
+    import torch
+    nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, M)["linear_workspace"]
+    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
+def linear(P, X, out=None, stream=None, workspace=None):
     """gwq_linear: X FP16 [M, K] on the GPU -> Y FP16 [M, N]."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, P.N), dtype=torch.float16, device=X.device)
+    if workspace is None:
+        workspace = linear_workspace(P, M, X.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() if workspace is not None else 0
     cs = P.c_struct()
-    rc = lib().gwq_linear(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), None, 0, _stream_ptr(stream))
+    rc = lib().gwq_linear(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), ws_ptr, ws_len, _stream_ptr(stream))
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_linear")
     return out
@@ -178,10 +189,13 @@ def prepare_linear(P, X, out):
     ref = ctypes.byref(cs)
     fn = lib().gwq_linear
     xp, yp, M = ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(out.data_ptr()), X.shape[0]
+    ws = linear_workspace(P, M, X.device)
+    wp = ctypes.c_void_p(ws.data_ptr()) if ws is not None else None
+    wl = ws.numel() if ws is not None else 0
     current_stream = torch.cuda.current_stream
 
-    def call(_keep=(cs, P, X, out)):
-        rc = fn(ref, xp, M, yp, None, 0, ctypes.c_void_p(current_stream().cuda_stream))
+    def call(_keep=(cs, P, X, out, ws)):
+        rc = fn(ref, xp, M, yp, wp, wl, ctypes.c_void_p(current_stream().cuda_stream))
         if rc != GWQ_OK:
             raise GwqError(rc, "gwq_linear")
     return call

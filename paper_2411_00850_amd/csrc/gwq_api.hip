@@ -55,7 +55,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     out->col_idx = ((size_t)k_out * 2 + 15) / 16 * 16 + 16;
     out->out_val = out->col_idx;
     out->pack_workspace = gwq::pack_workspace_bytes(N);
-    out->linear_workspace = 0;
+    out->linear_workspace = M_max > 16 ? gwq::gemm_workspace_bytes(N, K) : 0;
     out->n_outliers = k_out;
     return GWQ_OK;
 }
@@ -77,8 +77,6 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     gwq_status s = check_packed(P);
     if (s != GWQ_OK) return s;
     if (!X_f16 || !Y_f16) return GWQ_ERR_NULL;
@@ -86,9 +84,10 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     if (((uintptr_t)X_f16 | (uintptr_t)P->qweight | (uintptr_t)P->scales | (uintptr_t)P->zeros |
          (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
         return GWQ_ERR_SHAPE;
+    if (M > 16 && (!workspace || workspace_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_waves, st)
-                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, st);
+                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 

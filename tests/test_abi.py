@@ -39,6 +39,7 @@ def test_layout_sizes_7b_shapes():
     total = sum(s[k] for k in ("qweight", "scales", "zeros", "row_ptr", "col_idx", "out_val"))
     assert abs(total / 4096 ** 2 - 0.5644) < 1e-3
     assert gwq.layout(8, 128, 4, ppm=0)["col_idx"] == 16          # never a zero-size buffer
+    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4, M_max=2048)["linear_workspace"] == 4096 * 32
     small = gwq.layout(3, 128, 4)                                  # 3 groups: padded to one vector
     assert small["scales"] == 16 and small["zeros"] == 16
 
@@ -87,6 +88,8 @@ def test_pack_and_linear_validate_before_touching_the_device():
     assert L.gwq_linear(ctypes.byref(ok), fake, 0, fake, None, 0, None) == -2
     assert L.gwq_linear(ctypes.byref(_packed(group=64)), fake, 1, fake, None, 0, None) == -3
     assert L.gwq_linear(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
+    assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4       # M > 16 needs scratch
+    assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, fake, 8, None) == -4
 
 
 def test_tuning_and_strings():
