@@ -83,9 +83,9 @@ typedef struct {
     int64_t n_outliers;
 } gwq_sizes;
 
-/* Sizes for a layer (pure host arithmetic, touches no device).  scales and zeros are rounded up
- * to whole 16-byte vectors and col_idx / out_val carry one spare vector: gwq_linear reads them
- * with 16-byte loads, so buffers must have these sizes and be 16-byte aligned (the padding is
+/* Sizes for a layer (pure host arithmetic, touches no device).  scales, zeros, col_idx and
+ * out_val are rounded up to whole 16-byte vectors plus one spare vector: gwq_linear reads them
+ * with wide loads, so buffers must have these sizes and be 16-byte aligned (the padding is
  * never interpreted).
  * Errors: NULL out, shape limits above, unsupported bits/group, ppm > 1e6, M_max < 0. */
 gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_t outlier_ppm,
@@ -111,8 +111,9 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
- * Keys: "decode_waves" (waves per block of the decode kernel, 1..16).  Unknown keys or
- * out-of-range values return GWQ_ERR_UNSUPPORTED. */
+ * Keys: "decode_waves" (waves per block of the decode kernel, 1..16), "gemm_rows" (rows of Y per
+ * block of the GEMM: 64, 128 or 256).  Unknown keys or out-of-range values return
+ * GWQ_ERR_UNSUPPORTED. */
 gwq_status gwq_tuning_set(const char *key, int32_t value);
 
 const char *gwq_status_string(gwq_status status);

@@ -7,6 +7,7 @@
 namespace {
 
 int g_decode_waves = 0;   // 0 = heuristic
+int g_gemm_ms = 0;        // 0 = heuristic
 
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
@@ -48,9 +49,9 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     const int64_t k_out = outlier_count(N, K, outlier_ppm);
     memset(out, 0, sizeof(*out));
     out->qweight = (size_t)groups * gwq::words_per_group(bits) * 4;
-    // Staged with 16-byte loads by the decode kernel: whole vectors, and one spare for the CSR arrays.
-    out->scales = ((size_t)groups * 2 + 15) / 16 * 16;
-    out->zeros = ((size_t)groups + 15) / 16 * 16;
+    // Read with wide (partly unaligned) loads by the kernels: whole 16-byte vectors plus one spare.
+    out->scales = ((size_t)groups * 2 + 15) / 16 * 16 + 16;
+    out->zeros = ((size_t)groups + 15) / 16 * 16 + 16;
     out->row_ptr = (size_t)(N + 1) * 4;
     out->col_idx = ((size_t)k_out * 2 + 15) / 16 * 16 + 16;
     out->out_val = out->col_idx;
@@ -87,7 +88,7 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     if (M > 16 && (!workspace || workspace_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_waves, st)
-                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, st);
+                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, g_gemm_ms, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 
@@ -97,6 +98,11 @@ gwq_status gwq_tuning_set(const char *key, int32_t value)
     if (!strcmp(key, "decode_waves")) {
         if (value < 0 || value > 16) return GWQ_ERR_UNSUPPORTED;
         g_decode_waves = value;
+        return GWQ_OK;
+    }
+    if (!strcmp(key, "gemm_rows")) {
+        if (value != 0 && value != 64 && value != 128 && value != 256) return GWQ_ERR_UNSUPPORTED;
+        g_gemm_ms = value / 64;
         return GWQ_OK;
     }
     return GWQ_ERR_UNSUPPORTED;

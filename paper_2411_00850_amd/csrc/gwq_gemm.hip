@@ -15,7 +15,9 @@
 // SIMD never waits for memory inside the loop.  For the outliers this needs to know, per channel
 // and group, how many CSR entries fall into the group: a small kernel counts them into the
 // workspace first (one byte per channel and group); the running sum is the index of the group's
-// first entry, and its first three entries are fetched ahead (longer runs take a slow path).
+// first entry, and its first eight entries are fetched ahead, four by each of the channel's two
+// threads in one unaligned 8-byte load per array (longer runs take a slow path).  Scales, zero
+// points and counts are fetched four groups at a time, again with one unaligned load each.
 // The staging work of the next step is cut into four parts issued between the four MFMA batches
 // of the current one.
 #include "gwq_dequant.h"
@@ -30,7 +32,7 @@ constexpr int kThreads = 256;
 constexpr int kBN = 128;
 constexpr int kBK = 64;
 constexpr int kLd = kBK + 8;            // LDS row stride in halves: 144 bytes, conflict-free b128 reads
-constexpr int kAhead = 3;               // outlier entries per (channel, group) fetched ahead
+constexpr int kAhead = 8;               // outlier entries per (channel, group) fetched ahead
 
 // ------------------------------------------------------------------------------------------------
 // Outlier counts per (channel, group), saturating at 255.  One wave per channel.
@@ -70,13 +72,21 @@ template <> __device__ inline void load_slot<3>(SlotRegs<3> &r, const uint32_t *
     r.tail = group[12] >> (3 * slot);
 }
 
-// Everything thread (n, h) needs for one group of channel n: its two slots (h and 2 + h), scale,
-// zero point, the number of outliers in the group and the first kAhead of them.
+// Loads of 8 / 4 bytes at 2-byte / 1-byte alignment (gfx950 global memory takes unaligned addresses).
+struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
+struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
+
+// What thread (n, h) fetches for one group of channel n: its two slots (h and 2 + h) and four of
+// the group's first eight outlier entries (entries 4h .. 4h+3; the other thread of the channel
+// holds the rest), as packed 16-bit pairs.
 template <int BITS> struct GroupRegs {
     SlotRegs<BITS> slot[2];
-    uint16_t sc;
-    uint8_t zp, cnt;
-    uint16_t col[kAhead], val[kAhead];
+    U64a2 col, val;
+};
+// Scales, zero points and outlier counts of four consecutive groups of channel n.
+struct MetaRegs {
+    U64a2 sc;
+    uint32_t zp, cnt;
 };
 
 // Fragment j (8 codes -> 8 FP16 values s*(q - z)) of a slot.
@@ -161,55 +171,75 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 #pragma unroll
         for (int p = 0; p < kAPasses; ++p) dst[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k0);
     };
-    // first = CSR index of the group's first entry (data-independent of anything in flight).
+    // first = CSR index of the group's first entry (it depends on counts fetched long before).
     auto issue_group = [&](int g, int first, GroupRegs<BITS> &G) {
         g = g < gpr ? g : gpr - 1;
         const uint32_t *grp = q_row + (uint32_t)g * wpg;
         load_slot<BITS>(G.slot[0], grp, b_h);
         load_slot<BITS>(G.slot[1], grp, 2 + b_h);
-        G.sc = scales[row_group + g];
-        G.zp = zeros[row_group + g];
-        const uint8_t cnt_raw = grp_cnt[row_group + g];
-        G.cnt = b_valid ? cnt_raw : (uint8_t)0;
-#pragma unroll
-        for (int i = 0; i < kAhead; ++i) {
-            const int j = first + i < last_entry ? first + i : last_entry;
-            G.col[i] = col_idx[j];
-            G.val[i] = out_val[j];
-        }
+        const int j = first + 4 * b_h < last_entry ? first + 4 * b_h : last_entry;   // arrays carry 16 spare bytes
+        G.col = *reinterpret_cast<const U64a2 *>(col_idx + j);
+        G.val = *reinterpret_cast<const U64a2 *>(out_val + j);
     };
+    // Groups 4q .. 4q+3 (reads past the row or the array stay inside the padded buffers).
+    auto issue_meta = [&](int q, MetaRegs &Q) {
+        const int g = 4 * q < gpr ? 4 * q : 0;
+        Q.sc = *reinterpret_cast<const U64a2 *>(scales + row_group + g);
+        Q.zp = reinterpret_cast<const U32a1 *>(zeros + row_group + g)->v;
+        Q.cnt = reinterpret_cast<const U32a1 *>(grp_cnt + row_group + g)->v;
+    };
+    auto meta_scale = [](const MetaRegs &Q, int g) -> uint32_t {
+        const uint32_t w = (g & 2) ? Q.sc.hi : Q.sc.lo;
+        const uint32_t h = (g & 1) ? w >> 16 : w & 0xFFFFu;
+        return h | h << 16;
+    };
+    auto meta_zero = [](const MetaRegs &Q, int g) -> uint32_t { return (Q.zp >> (8 * (g & 3))) & 0xFFu; };
+    auto meta_count = [&](const MetaRegs &Q, int g) -> int { return b_valid ? (int)((Q.cnt >> (8 * (g & 3))) & 0xFFu) : 0; };
 
     // Store part `part` (0..3) of step `step` into buffer `buf`: a quarter of the X rows and one
     // 8-column fragment of this thread's weights; part 3 also writes the outliers.
     auto store_part = [&](int part, int step, int buf, const u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G,
-                          int first) {
+                          const MetaRegs &Q, int first) {
         _Float16 *A = a_dst + buf * kBufHalves, *brow = b_dst + buf * kBufHalves;
-        const int half = step & 1;
+        const int half = step & 1, g = step >> 1;
         constexpr int per = kAPasses >= 4 ? kAPasses / 4 : 1;
 #pragma unroll
         for (int p = part * per; p < (part + 1) * per && p < kAPasses; ++p)
             *reinterpret_cast<u32x4 *>(A + p * 32 * kLd) = a_regs[p];
-        const uint32_t s2 = (uint32_t)G.sc | (uint32_t)G.sc << 16;
+        const uint32_t s2 = meta_scale(Q, g), z = meta_zero(Q, g);
         if constexpr (BITS == 4) {
-            *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * part) = dequant_frag(G.slot[half], part, G.zp, s2, dc);
+            *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * part) = dequant_frag(G.slot[half], part, z, s2, dc);
         } else {
             if (part == 0) {
                 u32x4 f[4];
-                dequant_all(G.slot[half], G.zp, s2, dc, f);
+                dequant_all(G.slot[half], z, s2, dc, f);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
             }
         }
         if (part == 3) {
             // Outliers of this channel inside this thread's 32 columns replace their decoded zeros.
-            const int k_lo = step * kBK + 32 * b_h;
+            // Entries 4h .. 4h+3 are in this lane, the other four in the lane next to it.
+            const int cnt = meta_count(Q, g);
+            const uint32_t k_lo = (uint32_t)(step * kBK + 32 * b_h);
+            const uint32_t own_c[2] = {G.col.lo, G.col.hi}, own_v[2] = {G.val.lo, G.val.hi};
+            uint32_t oth_c[2], oth_v[2];
 #pragma unroll
-            for (int i = 0; i < kAhead; ++i) {
-                const uint32_t c = (uint32_t)G.col[i] - (uint32_t)k_lo;
-                if (i < G.cnt && c < 32u) brow[32 * b_h + c] = __builtin_bit_cast(_Float16, G.val[i]);
+            for (int i = 0; i < 2; ++i) {
+                oth_c[i] = __builtin_amdgcn_mov_dpp(own_c[i], 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+                oth_v[i] = __builtin_amdgcn_mov_dpp(own_v[i], 0xB1, 0xF, 0xF, true);
             }
-            for (int i = kAhead; i < G.cnt; ++i) {      // rare: more than kAhead outliers in one group
-                const uint32_t c = (uint32_t)col_idx[first + i] - (uint32_t)k_lo;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t c0 = ((own_c[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
+                if (4 * b_h + i < cnt && c0 < 32u)
+                    brow[32 * b_h + c0] = __builtin_bit_cast(_Float16, (uint16_t)(own_v[i >> 1] >> (16 * (i & 1))));
+                const uint32_t c1 = ((oth_c[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
+                if (4 * (1 - b_h) + i < cnt && c1 < 32u)
+                    brow[32 * b_h + c1] = __builtin_bit_cast(_Float16, (uint16_t)(oth_v[i >> 1] >> (16 * (i & 1))));
+            }
+            for (int i = kAhead; i < cnt; ++i) {        // rare: more than kAhead outliers in one group
+                const uint32_t c = (uint32_t)col_idx[first + i] - k_lo;
                 if (c < 32u) brow[32 * b_h + c] = __builtin_bit_cast(_Float16, out_val[first + i]);
             }
         }
@@ -227,55 +257,71 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     const _Float16 *a_frag = lds + (wm * (BM / 2) + fi) * kLd + 8 * fk;
     const _Float16 *b_frag = lds + (BM + wn * 64 + fi) * kLd + 8 * fk;
 
-    // One step: MFMA on buffer `buf` in four k-batches, the staging of step + 1 (from a_regs, G)
-    // into the other buffer spread between them.
-    auto step_fn = [&](int step, int buf, const u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, int first) {
+    // One step: MFMA on buffer `buf` in four k-batches (the fragments of a batch are read while
+    // the previous batch multiplies), the staging of step + 1 (from a_regs, G, Q) into the other
+    // buffer spread between them.
+    auto step_fn = [&](int step, int buf, const u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
+                       int first) {
         const _Float16 *A = a_frag + buf * kBufHalves, *B = b_frag + buf * kBufHalves;
         const bool stage = step + 1 < nk;
-#pragma unroll
-        for (int s = 0; s < kBK / 16; ++s) {
-            u32x4 a[MS], b[2];
+        u32x4 fa[2][MS], fb[2][2];
+        auto read_frags = [&](int s, u32x4 a[MS], u32x4 b[2]) {
 #pragma unroll
             for (int i = 0; i < MS; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kLd + 16 * s);
 #pragma unroll
             for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
+        };
+        read_frags(0, fa[0], fb[0]);
+#pragma unroll
+        for (int s = 0; s < kBK / 16; ++s) {
+            if (s + 1 < kBK / 16) read_frags(s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
 #pragma unroll
             for (int i = 0; i < MS; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a[i]),
-                                                                       __builtin_bit_cast(half8, b[j]), acc[i][j], 0, 0, 0);
-            if (stage) store_part(s, step + 1, buf ^ 1, a_regs, G, first);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[s & 1][i]),
+                                                                       __builtin_bit_cast(half8, fb[s & 1][j]),
+                                                                       acc[i][j], 0, 0, 0);
+            if (stage) store_part(s, step + 1, buf ^ 1, a_regs, G, Q, first);
         }
     };
 
-    // Prologue: group 0 and the X rows of steps 0 and 1; step 0 staged; group 1 requested.
+    // Prologue: metadata of groups 0..7, codes and outliers of groups 0 and 1, the X rows of
+    // steps 0 and 1; step 0 staged.
+    MetaRegs Qc, Qn;                                    // groups 4q .. 4q+3 and the four after them
     GroupRegs<BITS> Gc, Gn;                             // current group, next group
     u32x4 a0[kAPasses], a1[kAPasses];                   // X rows of the even / odd step being staged
     int first_c = b_valid ? row_ptr[b_n] : 0;           // CSR index of the current group's first entry
-    issue_group(0, first_c, Gc);
+    issue_meta(0, Qc);
+    issue_meta(1, Qn);
     issue_a(0, a0);
     issue_a(1, a1);
-    int first_n = first_c + Gc.cnt;
+    issue_group(0, first_c, Gc);
+    int first_n = first_c + meta_count(Qc, 0);
     issue_group(1, first_n, Gn);
 #pragma unroll
-    for (int part = 0; part < 4; ++part) store_part(part, 0, 0, a0, Gc, first_c);
+    for (int part = 0; part < 4; ++part) store_part(part, 0, 0, a0, Gc, Qc, first_c);
     issue_a(2, a0);
     __syncthreads();
 
     // Main loop, one group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, a1
     // holds the X rows of step 2g + 1, a0 those of step 2g + 2 (in flight), Gc is group g, Gn is
-    // group g + 1 (in flight).
+    // group g + 1 (in flight), Qc covers group g, Qn the four groups after Qc's.
     for (int g = 0; g < gpr; ++g) {
-        step_fn(2 * g, 0, a1, Gc, first_c);             // stages step 2g + 1 (second half of group g)
+        step_fn(2 * g, 0, a1, Gc, Qc, first_c);         // stages step 2g + 1 (second half of group g)
         issue_a(2 * g + 3, a1);
         __syncthreads();
         // Second half: stage step 2g + 2 = first half of group g + 1, then move on to it.
-        step_fn(2 * g + 1, 1, a0, Gn, first_n);
+        const bool roll = (g & 3) == 3;                 // group g + 1 starts the next four
+        step_fn(2 * g + 1, 1, a0, Gn, roll ? Qn : Qc, first_n);
         issue_a(2 * g + 4, a0);
         Gc = Gn;
+        if (roll) {
+            Qc = Qn;
+            issue_meta((g + 1) / 4 + 1, Qn);
+        }
         first_c = first_n;
-        first_n = first_c + Gc.cnt;
+        first_n = first_c + meta_count(Qc, g + 1);
         issue_group(g + 2, first_n, Gn);
         __syncthreads();
     }
@@ -315,15 +361,16 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, uint8_t
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t N, int64_t K) { return (size_t)(N * (K / kGroup) + 255) / 256 * 256; }
+size_t gemm_workspace_bytes(int64_t N, int64_t K) { return (size_t)(N * (K / kGroup) + 255) / 256 * 256 + 256; }
 
-hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, hipStream_t st)
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,
+                       hipStream_t st)
 {
     uint8_t *cnt = static_cast<uint8_t *>(workspace);
     group_count_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.N, P.K / kGroup, cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int ms = M <= 64 ? 1 : M <= 128 ? 2 : 4;
+    const int ms = ms_override ? ms_override : M <= 64 ? 1 : M <= 128 ? 2 : 4;
     if (P.bits == 4)
         return ms == 1 ? launch_ms<4, 1>(P, X, M, Y, cnt, st) : ms == 2 ? launch_ms<4, 2>(P, X, M, Y, cnt, st)
                                                                          : launch_ms<4, 4>(P, X, M, Y, cnt, st);

@@ -32,6 +32,7 @@ hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int
                          hipStream_t stream);
 // workspace: gemm_workspace_bytes(N, K) bytes of device scratch (outlier counts per channel and group).
 size_t gemm_workspace_bytes(int64_t N, int64_t K);
-hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, hipStream_t stream);
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,
+                       hipStream_t stream);
 
 }  // namespace gwq

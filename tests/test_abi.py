@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol(name):
 
 def test_layout_sizes_7b_shapes():
     s = gwq.layout(4096, 4096, 4)
-    assert s["qweight"] == 4096 * 32 * 16 * 4 and s["scales"] == 4096 * 32 * 2 and s["zeros"] == 4096 * 32
+    assert s["qweight"] == 4096 * 32 * 16 * 4 and s["scales"] == 4096 * 32 * 2 + 16 and s["zeros"] == 4096 * 32 + 16
     assert s["row_ptr"] == 4097 * 4 and s["n_outliers"] == 167773
     assert s["col_idx"] == s["out_val"] == (167773 * 2 + 15) // 16 * 16 + 16     # whole vectors + one spare
     s3 = gwq.layout(11008, 4096, 3)
@@ -39,9 +39,9 @@ def test_layout_sizes_7b_shapes():
     total = sum(s[k] for k in ("qweight", "scales", "zeros", "row_ptr", "col_idx", "out_val"))
     assert abs(total / 4096 ** 2 - 0.5644) < 1e-3
     assert gwq.layout(8, 128, 4, ppm=0)["col_idx"] == 16          # never a zero-size buffer
-    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4, M_max=2048)["linear_workspace"] == 4096 * 32
+    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4, M_max=2048)["linear_workspace"] == 4096 * 32 + 256
     small = gwq.layout(3, 128, 4)                                  # 3 groups: padded to one vector
-    assert small["scales"] == 16 and small["zeros"] == 16
+    assert small["scales"] == 32 and small["zeros"] == 32
 
 
 @pytest.mark.parametrize("args, status", [
