@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--copies", type=int, default=6, help="rotating copies of the packed layer")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="how the timed steps are launched: one HIP graph over all copies, or plain launches")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
     args = ap.parse_args()
@@ -108,8 +110,9 @@ def main():
 
     def decode_leg(M, steps, warmup, mode):
         """mode "graph": all copies x 7 launches captured once into a HIP graph and replayed (the
-        launch-bound loop of a serving engine); "eager": plain launches; "events": eager with one HIP
-        event between consecutive launches, giving the per-launch duration of the decode kernel."""
+        launch-bound loop of a serving engine), bracketed by two HIP events on the launch stream whose
+        elapsed time over the number of launches is the per-launch duration; "eager": plain launches;
+        "events": eager with one HIP event between consecutive launches."""
         xs, ys = make_xy(M)
         n_launch, n_copies = len(layers), len(copies)
         calls = [[gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(c)] for c in copies]
@@ -130,14 +133,18 @@ def main():
             if warmup and not all(torch.equal(a, b) for a, b in zip(ref, ys)):
                 sys.exit("bench.py: graph replay does not reproduce the eager result")
             rounds, rest = divmod(steps, n_copies)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             t = time.perf_counter()
+            e0.record()                                  # HIP events on the launch stream
             for _ in range(rounds):
                 graph.replay()
             for call in [c for cc in calls[:rest] for c in cc]:
                 call()
+            e1.record()
             torch.cuda.synchronize()
             wall = time.perf_counter() - t
+            kernel_ms = e0.elapsed_time(e1) / (steps * n_launch)
         else:
             ev = mode == "events"
             evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_launch + 1)] for _ in range(steps)] if ev else None
@@ -159,10 +166,11 @@ def main():
         return wall / steps, kernel_ms, bytes_step
 
     # ---- the timed steps: decode M = 1 ---------------------------------------------------------------
-    step_s, _, bytes_step = decode_leg(1, args.steps, args.warmup, args.launch)
+    step_s, launch_ms, bytes_step = decode_leg(1, args.steps, args.warmup, args.launch)
     value = bytes_step / step_s / 1e9
-    # Same steps again with one HIP event after every launch: per-launch duration of the decode kernel.
-    _, launch_ms, _ = decode_leg(1, args.steps, args.warmup, "events")
+    if launch_ms is None:
+        # Eager launches are CPU-bound: time the kernels with one HIP event between consecutive launches.
+        _, launch_ms, _ = decode_leg(1, args.steps, args.warmup, "events")
     bytes_launch = bytes_step / len(layers)
     achieved = bytes_launch / (launch_ms * 1e-3) / 1e9
     out = {
@@ -174,11 +182,19 @@ def main():
                                "int4 g128 + 1% fp16 CSR outliers, decode M=1, 7 gwq_linear launches per step",
                    "copies_rotated": args.copies, "bytes_per_step": bytes_step, "launch": args.launch},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
-        "roofline": {"bound": "hbm", "kernel": "decode_kernel<4,1>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel (4-bit, M=1)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(), "bytes_per_launch": round(bytes_launch),
                      "avg_launch_us": round(launch_ms * 1e3, 3)},
     }
+
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)                              # one copy kernel: reads and writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_extras:
         extra = {}
