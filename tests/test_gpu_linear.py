@@ -150,3 +150,43 @@ def test_config4_prefill_7b_shapes_sampled(mid, N, K):
     Y = _run(P, X)
     assert np.isfinite(Y.astype(np.float32)).all()
     assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"prefill N={N} K={K}")
+
+
+# ----------------------------------------------------------------------------- 70B-shaped layers (config 5)
+
+@functools.lru_cache(maxsize=1)
+def _layer70b(mid, N, K):
+    """Weights plus a score whose top 1 % is a known set (60 % of it in 1 % of the columns), so the
+    oracle needs no sort at this size: the generator returns the positions and the test checks that
+    they really are the largest scores."""
+    n_top = orc.outlier_count(N, K, 10000)
+    W = gs.weight(N, K, gs.rng_for(5, mid, 0))
+    S, rows, cols = gs.score_clustered(N, K, n_top, gs.rng_for(5, mid, 1), axis="col")
+    mask = np.zeros((N, K), np.uint8)
+    mask[rows, cols] = 1
+    assert int(mask.sum()) == n_top
+    assert S[mask.astype(bool)].min() >= 2.0 > S[~mask.astype(bool)].max()     # the set is the top-k, no ties
+    return W, S, mask
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("mid,N,K", [(0, 8192, 8192), (1, 28672, 8192), (2, 8192, 28672)])
+def test_config5_70b_shapes(mid, N, K, bits):
+    """Full-size 70B-shaped matrices with column-clustered outliers: gwq_pack byte-exact against the
+    oracle's encoding of the known outlier set, gwq_linear at M in {1, 64, 2048} on 64 sampled
+    channels (all rows) against the oracle."""
+    import torch
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, assert_packed_equal, to_gpu
+    W, S, mask = _layer70b(mid, N, K)
+    P = orc.encode(W, mask, bits, 10000)
+    D = gwq.pack(to_gpu(W), to_gpu(S), bits, 10000)
+    assert_packed_equal(D, P)
+    rows = np.sort(gs.rng_for(5, mid, 3).choice(N, 64, replace=False)).astype(np.int32)
+    for M in (1, 64, 2048):
+        X = gs.activations(M, K, gs.rng_for(5, mid, 10 + M))
+        Y = gwq.linear(D, to_gpu(X)).cpu().numpy()
+        assert np.isfinite(Y.astype(np.float32)).all()
+        assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"70B N={N} K={K} bits={bits} M={M}")
+    del D
+    torch.cuda.empty_cache()
