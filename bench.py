@@ -3,9 +3,10 @@
 
 Workload (benchmark configs[1]): one LLaMA-2-7B-shaped decoder layer, 7 matrices, 4-bit codes,
 group 128, 1 % FP16 outliers, synthetic weights with planted outlier columns.  A step is one decode
-pass (M = 1) of gwq_linear over the 7 matrices.  The packed layer exists in several copies and the
-steps rotate over them, so every step streams its weights from HBM rather than from the 256 MB
-last-level cache, as a decode pass over a whole model does.
+pass (M = 1) over the 7 matrices, launched the way the layer's data flow allows: q, k and v in one
+grouped launch (gwq_linear_batch), o alone, gate and up in one, down alone - 4 launches.  The packed
+layer exists in several copies and the steps rotate over them, so every step streams its weights
+from HBM rather than from the 256 MB last-level cache, as a decode pass over a whole model does.
 
 One JSON line is printed.  `value` is the algorithmic GB/s of the timed steps (packed bytes + X + Y
 per step over wall time, inputs resident in HBM).  `roofline` is the decode kernel alone: algorithmic
@@ -67,6 +68,8 @@ def main():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--copies", type=int, default=6, help="rotating copies of the packed layer")
+    ap.add_argument("--group", choices=["deps", "none", "all"], default="deps",
+                    help="launches per step: 4 grouped by data dependence (default), 7 single, or 1 over all")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="how the timed steps are launched: one HIP graph over all copies, or plain launches")
     ap.add_argument("--copy-probe", action="store_true",
@@ -108,14 +111,19 @@ def main():
         ys = [torch.empty((M, P.N), dtype=torch.float16, device=dev) for P in layers]
         return xs, ys
 
-    def decode_leg(M, steps, warmup, mode):
+    GROUPS = {"deps": [[0, 1, 2], [3], [4, 5], [6]], "none": [[i] for i in range(7)], "all": [list(range(7))]}
+
+    def decode_leg(M, steps, warmup, mode, grouping="deps"):
         """mode "graph": all copies x 7 launches captured once into a HIP graph and replayed (the
         launch-bound loop of a serving engine), bracketed by two HIP events on the launch stream whose
         elapsed time over the number of launches is the per-launch duration; "eager": plain launches;
         "events": eager with one HIP event between consecutive launches."""
         xs, ys = make_xy(M)
-        n_launch, n_copies = len(layers), len(copies)
-        calls = [[gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(c)] for c in copies]
+        groups = GROUPS[grouping]
+        n_launch, n_copies = len(groups), len(copies)
+        calls = [[gwq.prepare_linear_batch([c[j] for j in g], [xs[c[j].K] for j in g], [ys[j] for j in g])
+                  if len(g) > 1 else gwq.prepare_linear(c[g[0]], xs[c[g[0]].K], ys[g[0]]) for g in groups]
+                 for c in copies]
         for i in range(warmup):
             for call in calls[i % n_copies]:
                 call()
@@ -163,15 +171,15 @@ def main():
                 kernel_ms = sum(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(steps) for j in range(n_launch))
                 kernel_ms /= steps * n_launch
         bytes_step = sum(algorithmic_bytes(P, M) for P in layers)
-        return wall / steps, kernel_ms, bytes_step
+        return wall / steps, kernel_ms, bytes_step, n_launch
 
     # ---- the timed steps: decode M = 1 ---------------------------------------------------------------
-    step_s, launch_ms, bytes_step = decode_leg(1, args.steps, args.warmup, args.launch)
+    step_s, launch_ms, bytes_step, n_launch = decode_leg(1, args.steps, args.warmup, args.launch, args.group)
     value = bytes_step / step_s / 1e9
     if launch_ms is None:
         # Eager launches are CPU-bound: time the kernels with one HIP event between consecutive launches.
-        _, launch_ms, _ = decode_leg(1, args.steps, args.warmup, "events")
-    bytes_launch = bytes_step / len(layers)
+        _, launch_ms, _, _ = decode_leg(1, args.steps, args.warmup, "events", args.group)
+    bytes_launch = bytes_step / n_launch
     achieved = bytes_launch / (launch_ms * 1e-3) / 1e9
     out = {
         "metric": "gwq_linear decode GB/s (% HBM peak) & prefill TFLOP/s (% MFMA peak), 7B shapes",
@@ -179,7 +187,9 @@ def main():
         "ms_per_step": round(step_s * 1e3, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": "7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
-                               "int4 g128 + 1% fp16 CSR outliers, decode M=1, 7 gwq_linear launches per step",
+                               "int4 g128 + 1% fp16 CSR outliers, decode M=1",
+                   "launches_per_step": n_launch, "grouping": {"deps": "qkv | o | gate,up | down", "none": "one launch per matrix",
+                                                               "all": "one launch over the 7 matrices"}[args.group],
                    "copies_rotated": args.copies, "bytes_per_step": bytes_step, "launch": args.launch},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "decode_kernel (4-bit, M=1)", "achieved": round(achieved, 1),
@@ -199,8 +209,13 @@ def main():
     if not args.no_extras:
         extra = {}
         for M in (4, 16):
-            s, _, b = decode_leg(M, max(args.steps // 3, 12), 12, args.launch)
+            s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), 12, args.launch, args.group)
             extra[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5)}
+        for grouping in ("none", "all"):                # the same M = 1 pass with 7 launches / 1 launch per step
+            if grouping != args.group:
+                s, _, b, nl = decode_leg(1, max(args.steps // 3, 12), 12, args.launch, grouping)
+                extra[f"decode_M1_group_{grouping}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
+                                                        "launches_per_step": nl}
         # prefill: M = 2048 over the 7 matrices, one copy (compute-bound)
         M = 2048
         xs, ys = make_xy(M)

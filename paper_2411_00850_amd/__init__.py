@@ -4,8 +4,8 @@ All arithmetic of the path runs in the HIP kernels behind `gwq_pack` and `gwq_li
 package only marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import (GwqError, PackedLayer, layout, pack, linear, linear_workspace, prepare_linear,
-                      tuning_set,
+                      linear_batch, prepare_linear_batch, tuning_set,
                       version, library_path, lib)
 
-__all__ = ["GwqError", "PackedLayer", "layout", "pack", "linear", "linear_workspace", "prepare_linear", "tuning_set", "version",
+__all__ = ["GwqError", "PackedLayer", "layout", "pack", "linear", "linear_workspace", "prepare_linear", "linear_batch", "prepare_linear_batch", "tuning_set", "version",
            "library_path", "lib"]

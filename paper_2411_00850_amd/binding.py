@@ -56,6 +56,9 @@ def lib():
         L.gwq_pack.argtypes = [vp, vp, ctypes.c_int, ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
         L.gwq_linear.restype = ctypes.c_int
         L.gwq_linear.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.gwq_linear_batch.restype = ctypes.c_int
+        L.gwq_linear_batch.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), ctypes.POINTER(vp), i32,
+                                       ctypes.POINTER(vp), vp]
         L.gwq_tuning_set.restype = ctypes.c_int
         L.gwq_tuning_set.argtypes = [ctypes.c_char_p, i32]
         L.gwq_status_string.restype = ctypes.c_char_p
@@ -199,3 +202,37 @@ def prepare_linear(P, X, out):
         if rc != GWQ_OK:
             raise GwqError(rc, "gwq_linear")
     return call
+
+
+def prepare_linear_batch(layers, Xs, outs):
+    """Pre-marshalled gwq_linear_batch call (one decode launch over several layers, M <= 16): returns a
+    zero-argument callable that enqueues it on the current torch stream.  `layers`, `Xs`, `outs` are
+    equally long sequences; entries of Xs may repeat (shared activations)."""
+    import torch
+    n = len(layers)
+    assert n == len(Xs) == len(outs) and 1 <= n
+    M = Xs[0].shape[0]
+    for P, X, Y in zip(layers, Xs, outs):
+        assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape == (M, P.K)
+        assert Y.shape == (M, P.N) and Y.dtype == torch.float16 and Y.is_contiguous()
+    structs = [P.c_struct() for P in layers]
+    parr = (ctypes.POINTER(_Packed) * n)(*[ctypes.pointer(c) for c in structs])
+    xarr = (ctypes.c_void_p * n)(*[X.data_ptr() for X in Xs])
+    yarr = (ctypes.c_void_p * n)(*[Y.data_ptr() for Y in outs])
+    fn = lib().gwq_linear_batch
+    current_stream = torch.cuda.current_stream
+
+    def call(_keep=(structs, layers, Xs, outs)):
+        rc = fn(n, parr, xarr, M, yarr, ctypes.c_void_p(current_stream().cuda_stream))
+        if rc != GWQ_OK:
+            raise GwqError(rc, "gwq_linear_batch")
+    return call
+
+
+def linear_batch(layers, Xs, outs=None):
+    """gwq_linear_batch: returns the list of outputs."""
+    import torch
+    if outs is None:
+        outs = [torch.empty((X.shape[0], P.N), dtype=torch.float16, device=X.device) for P, X in zip(layers, Xs)]
+    prepare_linear_batch(layers, Xs, outs)()
+    return outs

@@ -87,8 +87,26 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
         return GWQ_ERR_SHAPE;
     if (M > 16 && (!workspace || workspace_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = M <= 16 ? gwq::launch_decode(*P, X_f16, M, Y_f16, g_decode_waves, st)
+    hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st)
                            : gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, g_gemm_ms, st);
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const void *const *X_f16, int32_t M,
+                            void *const *Y_f16, void *stream)
+{
+    if (!P || !X_f16 || !Y_f16) return GWQ_ERR_NULL;
+    if (count < 1 || count > GWQ_MAX_BATCH || M < 1 || M > 16) return GWQ_ERR_SHAPE;
+    for (int32_t i = 0; i < count; ++i) {
+        gwq_status s = check_packed(P[i]);
+        if (s != GWQ_OK) return s;
+        if (!X_f16[i] || !Y_f16[i]) return GWQ_ERR_NULL;
+        if (P[i]->bits != P[0]->bits) return GWQ_ERR_UNSUPPORTED;
+        if (((uintptr_t)X_f16[i] | (uintptr_t)P[i]->qweight | (uintptr_t)P[i]->scales | (uintptr_t)P[i]->zeros |
+             (uintptr_t)P[i]->col_idx | (uintptr_t)P[i]->out_val) & 15)
+            return GWQ_ERR_SHAPE;
+    }
+    hipError_t e = gwq::launch_decode(count, P, X_f16, M, Y_f16, g_decode_waves, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 

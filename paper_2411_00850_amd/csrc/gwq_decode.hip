@@ -82,6 +82,25 @@ template <int BITS, int U> struct Chunk {
 constexpr int kPre = 4;        // outlier entries a lane handles without a loop
 constexpr int kMetaRounds = 2; // 16-byte vectors of scales / zero points a thread stages
 
+// One layer of a launch, and the launch: up to kMaxBatch layers, blocks [block_end[i-1], block_end[i])
+// belong to layer i.  Passed by value (kernel argument segment), read through the scalar cache.
+struct DecodeProblem {
+    const uint32_t *qweight;
+    const uint16_t *scales;
+    const uint8_t *zeros;
+    const int32_t *row_ptr;
+    const uint16_t *col_idx;
+    const uint16_t *out_val;
+    const _Float16 *X;
+    _Float16 *Y;
+    int N, K, groups_per_wave, sc_last_vec, zp_last_vec, csr_last_vec;
+};
+struct DecodeBatch {
+    int count, M;
+    int block_end[kMaxBatch];
+    DecodeProblem p[kMaxBatch];
+};
+
 // BITS: 3 or 4.  U: groups per chunk (4 or 8).  PIPE: a wave owns more than U groups (up to 16 when
 // MS > 0) and double-buffers chunks of U = 4.  MS: 1..4 = M is exactly MS and X[M][K] is staged in
 // LDS, the four lanes of a channel sharing its outliers; 0 = any M <= 16, X read from global memory.
@@ -93,22 +112,30 @@ constexpr int kMetaRounds = 2; // 16-byte vectors of scales / zero points a thre
 // bytes | 16 spare bytes | CSR columns, blockDim * 8 entries | CSR values, same | partial sums
 // [waves][4][64] floats.  The launcher guarantees kMetaRounds * blockDim >= 3 * gpr.
 template <int BITS, int U, bool PIPE, int MS>
-__global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict__ qweight,
-                                                      const uint16_t *__restrict__ scales,
-                                                      const uint8_t *__restrict__ zeros,
-                                                      const int32_t *__restrict__ row_ptr,
-                                                      const uint16_t *__restrict__ col_idx,
-                                                      const uint16_t *__restrict__ out_val,
-                                                      const _Float16 *__restrict__ X, _Float16 *__restrict__ Y,
-                                                      int N, int K, int M, int groups_per_wave,
-                                                      int sc_last_vec, int zp_last_vec, int csr_last_vec)
+__global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
 {
     constexpr bool SMALLM = MS > 0;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    // Which layer this block works on (uniform).
+    int layer = 0;
+    while (layer + 1 < batch.count && (int)blockIdx.x >= batch.block_end[layer]) ++layer;
+    const DecodeProblem &pr = batch.p[layer];
+    const int block = blockIdx.x - (layer ? batch.block_end[layer - 1] : 0);
+    const uint32_t *__restrict__ qweight = pr.qweight;
+    const uint16_t *__restrict__ scales = pr.scales;
+    const uint8_t *__restrict__ zeros = pr.zeros;
+    const int32_t *__restrict__ row_ptr = pr.row_ptr;
+    const uint16_t *__restrict__ col_idx = pr.col_idx;
+    const uint16_t *__restrict__ out_val = pr.out_val;
+    const _Float16 *__restrict__ X = pr.X;
+    _Float16 *__restrict__ Y = pr.Y;
+    const int N = pr.N, K = pr.K, M = batch.M, groups_per_wave = pr.groups_per_wave;
+    const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x, nwaves = nthreads >> 6;
     const int r = lane & 15, b = lane >> 4;
     const int gpr = K / kGroup;
-    const int row0 = blockIdx.x * 16;
+    const int row0 = block * 16;
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
 
@@ -163,7 +190,7 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
     for (int i = 0; i < kMetaRounds; ++i) {
         const int t = tid + i * nthreads;
         const bool is_sc = t < 2 * gpr, is_zp = !is_sc && t < 3 * gpr;
-        int v = is_sc ? blockIdx.x * 2 * gpr + t : blockIdx.x * gpr + (t - 2 * gpr);
+        int v = is_sc ? block * 2 * gpr + t : block * gpr + (t - 2 * gpr);
         const int last = is_sc ? sc_last_vec : zp_last_vec;
         v = (is_sc || is_zp) ? (v < last ? v : last) : 0;
         const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
@@ -314,11 +341,8 @@ __global__ __launch_bounds__(1024) void decode_kernel(const uint32_t *__restrict
 constexpr size_t kXLdsBudget = 64 * 1024;               // X[M][K] is staged in LDS up to this size
 
 template <int BITS, int U, bool PIPE, int MS>
-hipError_t launch_v(const gwq_packed &P, const void *X, int M, void *Y, int nwaves, int gpw, hipStream_t st)
+hipError_t launch_v(const DecodeBatch &batch, int blocks, int nwaves, size_t lds, hipStream_t st)
 {
-    const int gpr = P.K / kGroup;
-    const int blocks = (P.N + 15) / 16;
-    const size_t lds = (size_t)MS * P.K * 2 + 48 * (size_t)gpr + 16 + 32 * (size_t)nwaves * 64 + (size_t)nwaves * 1024;
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<BITS, U, PIPE, MS>),
@@ -326,59 +350,82 @@ hipError_t launch_v(const gwq_packed &P, const void *X, int M, void *Y, int nwav
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    // Last 16-byte vector of each staged array (the buffers are padded to whole vectors, the CSR
-    // arrays by one more vector, so clamped reads stay inside them).
-    const int64_t groups = (int64_t)P.N * gpr;
-    const int sc_last = (int)((groups * 2 + 15) / 16) - 1;
-    const int zp_last = (int)((groups + 15) / 16) - 1;
-    const int csr_last = (int)((P.n_outliers * 2 + 15) / 16);
-    decode_kernel<BITS, U, PIPE, MS><<<blocks, nwaves * 64, lds, st>>>(
-        P.qweight, P.scales, P.zeros, P.row_ptr, P.col_idx, P.out_val, static_cast<const _Float16 *>(X),
-        static_cast<_Float16 *>(Y), P.N, P.K, M, gpw, sc_last, zp_last, csr_last);
+    decode_kernel<BITS, U, PIPE, MS><<<blocks, nwaves * 64, lds, st>>>(batch);
     return hipGetLastError();
 }
 
 template <int BITS, int MS>
-hipError_t launch_m(const gwq_packed &P, const void *X, int M, void *Y, int nwaves, int gpw, hipStream_t st)
+hipError_t launch_m(const DecodeBatch &batch, int blocks, int nwaves, int max_gpw, size_t lds, hipStream_t st)
 {
-    if (gpw <= 4) return launch_v<BITS, 4, false, MS>(P, X, M, Y, nwaves, gpw, st);
-    if (gpw <= 8) return launch_v<BITS, 8, false, MS>(P, X, M, Y, nwaves, gpw, st);
+    if (max_gpw <= 4) return launch_v<BITS, 4, false, MS>(batch, blocks, nwaves, lds, st);
+    if (max_gpw <= 8) return launch_v<BITS, 8, false, MS>(batch, blocks, nwaves, lds, st);
     // Long rows: double-buffered chunks; X is staged only while its staging registers stay few.
     if constexpr (MS == 1 || MS == 2) {
-        if (gpw <= 16) return launch_v<BITS, 4, true, MS>(P, X, M, Y, nwaves, gpw, st);
+        if (max_gpw <= 16) return launch_v<BITS, 4, true, MS>(batch, blocks, nwaves, lds, st);
     }
-    return launch_v<BITS, 4, true, 0>(P, X, M, Y, nwaves, gpw, st);
-}
-
-template <int BITS>
-hipError_t launch_b(const gwq_packed &P, const void *X, int M, void *Y, int nwaves, int gpw, hipStream_t st)
-{
-    const bool stage = M <= 4 && (size_t)M * P.K * 2 <= kXLdsBudget;
-    if (stage && M == 1) return launch_m<BITS, 1>(P, X, M, Y, nwaves, gpw, st);
-    if (stage && M == 2) return launch_m<BITS, 2>(P, X, M, Y, nwaves, gpw, st);
-    if (stage && M == 3) return launch_m<BITS, 3>(P, X, M, Y, nwaves, gpw, st);
-    if (stage && M == 4) return launch_m<BITS, 4>(P, X, M, Y, nwaves, gpw, st);
-    return launch_m<BITS, 0>(P, X, M, Y, nwaves, gpw, st);
+    return launch_v<BITS, 4, true, 0>(batch, blocks, nwaves, lds, st);
 }
 
 }  // namespace
 
-hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int waves_override, hipStream_t st)
+// Decode launch over `count` layers (same bits, same M): one grid, layer i owning ceil(N_i / 16) blocks.
+hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
+                         int waves_override, hipStream_t st)
 {
-    const int gpr = P.K / kGroup;
-    // One chunk of eight groups per wave where the row is long enough, at most 16 waves per block,
-    // and enough threads to stage the 3 * gpr vectors of scales and zero points in kMetaRounds.
-    int nwaves = waves_override ? waves_override : (gpr + 7) / 8;
-    const int min_waves = (3 * gpr + 64 * kMetaRounds - 1) / (64 * kMetaRounds);
-    if (nwaves < min_waves) nwaves = min_waves;
-    if (nwaves > 16) nwaves = 16;
-    if (nwaves > gpr) nwaves = gpr;
-    if (nwaves < 1) nwaves = 1;
-    const int gpw = (gpr + nwaves - 1) / nwaves;
-    const int needed = (gpr + gpw - 1) / gpw;           // waves that own at least one group
-    if (needed >= min_waves) nwaves = needed;
-    if (nwaves * 64 * kMetaRounds < 3 * gpr) return hipErrorInvalidValue;   // K <= 65536 keeps this false
-    return P.bits == 4 ? launch_b<4>(P, X, M, Y, nwaves, gpw, st) : launch_b<3>(P, X, M, Y, nwaves, gpw, st);
+    DecodeBatch batch;
+    batch.count = count;
+    batch.M = M;
+    // Waves per block: one chunk of eight groups per wave where the rows are long enough, at most 16,
+    // and enough threads to stage every layer's 3 * gpr vectors of scales and zero points.
+    int nwaves = 1, max_k = 0;
+    for (int i = 0; i < count; ++i) {
+        const int gpr = P[i]->K / kGroup;
+        int w = waves_override ? waves_override : (gpr + 7) / 8;
+        const int min_waves = (3 * gpr + 64 * kMetaRounds - 1) / (64 * kMetaRounds);
+        if (w < min_waves) w = min_waves;
+        if (w > 16) w = 16;
+        if (w > gpr && gpr >= min_waves) w = gpr;
+        if (count == 1) {                               // a single layer drops waves that would own no group
+            const int gpw = (gpr + w - 1) / w, needed = (gpr + gpw - 1) / gpw;
+            if (needed >= min_waves) w = needed;
+        }
+        if (w > nwaves) nwaves = w;
+        if (P[i]->K > max_k) max_k = P[i]->K;
+    }
+    int blocks = 0, max_gpw = 1;
+    size_t max_meta = 0;
+    for (int i = 0; i < count; ++i) {
+        const gwq_packed &L = *P[i];
+        const int gpr = L.K / kGroup;
+        if (nwaves * 64 * kMetaRounds < 3 * gpr) return hipErrorInvalidValue;      // K <= 65536 keeps this false
+        DecodeProblem &d = batch.p[i];
+        d.qweight = L.qweight; d.scales = L.scales; d.zeros = L.zeros;
+        d.row_ptr = L.row_ptr; d.col_idx = L.col_idx; d.out_val = L.out_val;
+        d.X = static_cast<const _Float16 *>(X[i]);
+        d.Y = static_cast<_Float16 *>(Y[i]);
+        d.N = L.N; d.K = L.K;
+        d.groups_per_wave = (gpr + nwaves - 1) / nwaves;
+        if (d.groups_per_wave > max_gpw) max_gpw = d.groups_per_wave;
+        // Last 16-byte vector of each staged array (the buffers are padded, so clamped reads stay inside).
+        const int64_t groups = (int64_t)L.N * gpr;
+        d.sc_last_vec = (int)((groups * 2 + 15) / 16) - 1;
+        d.zp_last_vec = (int)((groups + 15) / 16) - 1;
+        d.csr_last_vec = (int)((L.n_outliers * 2 + 15) / 16);
+        blocks += (L.N + 15) / 16;
+        batch.block_end[i] = blocks;
+        if ((size_t)48 * gpr > max_meta) max_meta = (size_t)48 * gpr;
+    }
+    for (int i = count; i < kMaxBatch; ++i) { batch.block_end[i] = blocks; batch.p[i] = batch.p[0]; }
+
+    int ms = (M <= 4 && (size_t)M * max_k * 2 <= kXLdsBudget) ? M : 0;
+    if (max_gpw > 8 && !((ms == 1 || ms == 2) && max_gpw <= 16)) ms = 0;            // mirrors launch_m
+    const size_t lds = (size_t)ms * max_k * 2 + max_meta + 16 + 32 * (size_t)nwaves * 64 + (size_t)nwaves * 1024;
+    const int bits = P[0]->bits;
+#define GWQ_MS(B, MM) if (bits == B && ms == MM) return launch_m<B, MM>(batch, blocks, nwaves, max_gpw, lds, st)
+    GWQ_MS(4, 0); GWQ_MS(4, 1); GWQ_MS(4, 2); GWQ_MS(4, 3); GWQ_MS(4, 4);
+    GWQ_MS(3, 0); GWQ_MS(3, 1); GWQ_MS(3, 2); GWQ_MS(3, 3); GWQ_MS(3, 4);
+#undef GWQ_MS
+    return hipErrorInvalidValue;
 }
 
 }  // namespace gwq

@@ -9,6 +9,7 @@ namespace gwq {
 
 constexpr int kGroup = 128;        // codes per quantisation group along K
 constexpr int kSelBins = 2048;     // bins of one radix-select pass
+constexpr int kMaxBatch = GWQ_MAX_BATCH;   // layers per grouped decode launch
 
 __host__ __device__ constexpr int words_per_group(int bits) { return bits == 4 ? 16 : 13; }
 
@@ -28,8 +29,8 @@ inline size_t pack_workspace_bytes(int64_t N) { return (size_t)(kWsRows + 3 * N)
 // Launchers (defined in the .hip files).  Each enqueues on `stream` and returns the last HIP error.
 hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
                        uint32_t *ws, hipStream_t stream);
-hipError_t launch_decode(const gwq_packed &P, const void *X, int M, void *Y, int waves_override,
-                         hipStream_t stream);
+hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
+                         int waves_override, hipStream_t stream);
 // workspace: gemm_workspace_bytes(N, K) bytes of device scratch (outlier counts per channel and group).
 size_t gemm_workspace_bytes(int64_t N, int64_t K);
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,

@@ -18,8 +18,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_calls():
-    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_pack", "gwq_status_string",
-                                    "gwq_tuning_set", "gwq_version"]
+    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_pack",
+                                    "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
 
 @pytest.mark.parametrize("name", declared_functions())
@@ -90,6 +90,23 @@ def test_pack_and_linear_validate_before_touching_the_device():
     assert L.gwq_linear(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4       # M > 16 needs scratch
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, fake, 8, None) == -4
+
+
+def test_linear_batch_validates_before_touching_the_device():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ok, other = _packed(), _packed(bits=3)
+    P = (ctypes.POINTER(binding._Packed) * 2)(ctypes.pointer(ok), ctypes.pointer(ok))
+    Pmixed = (ctypes.POINTER(binding._Packed) * 2)(ctypes.pointer(ok), ctypes.pointer(other))
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    holes = (ctypes.c_void_p * 2)(0x1000, None)
+    assert L.gwq_linear_batch(2, None, ptrs, 1, ptrs, None) == -1
+    assert L.gwq_linear_batch(2, P, None, 1, ptrs, None) == -1
+    assert L.gwq_linear_batch(2, P, ptrs, 1, holes, None) == -1
+    assert L.gwq_linear_batch(0, P, ptrs, 1, ptrs, None) == -2
+    assert L.gwq_linear_batch(9, P, ptrs, 1, ptrs, None) == -2
+    assert L.gwq_linear_batch(2, P, ptrs, 17, ptrs, None) == -2         # the grouped launch is decode only
+    assert L.gwq_linear_batch(2, Pmixed, ptrs, 1, ptrs, None) == -3     # mixed bit widths
 
 
 def test_tuning_and_strings():

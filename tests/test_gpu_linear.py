@@ -82,6 +82,27 @@ def test_decode_row_clustered_outliers():
     assert_close(_run(P, X), orc.linear_f64(P, X))
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("M", [1, 3, 8, 16])
+def test_decode_grouped_launch(bits, M):
+    """gwq_linear_batch over layers of different N and K (short and long rows, shared activations)
+    matches the oracle layer by layer, and agrees with gwq_linear on each layer alone up to the
+    rounding of a different split of K over the waves."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    shapes = [(200, 1024), (72, 2304), (48, 1024), (16, 128), (130, 11008)]
+    rng = np.random.default_rng(bits * 100 + M)
+    Xh = {K: gs.activations(M, K, rng) for K in {k for _, k in shapes}}
+    Xd = {K: to_gpu(x) for K, x in Xh.items()}
+    Ps = [_problem(i + bits, N, K, bits)[0] for i, (N, K) in enumerate(shapes)]
+    Ds = [upload_packed(P) for P in Ps]
+    outs = gwq.linear_batch(Ds, [Xd[P.K] for P in Ps])
+    for P, D, Y in zip(Ps, Ds, outs):
+        alone = gwq.linear(D, Xd[P.K]).cpu().numpy().astype(np.float64)
+        assert_close(Y.cpu().numpy(), orc.linear_f64(P, Xh[P.K]), f"grouped N={P.N} K={P.K} M={M}")
+        assert_close(Y.cpu().numpy(), alone, f"grouped vs alone N={P.N} K={P.K} M={M}")
+
+
 def test_linear_is_deterministic():
     P, rng = _problem(1, 256, 2048, 4)
     for M in (4, 100):
