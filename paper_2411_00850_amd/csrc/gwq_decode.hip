@@ -44,6 +44,12 @@ template <> struct Slot<4> {
     {
         w = *reinterpret_cast<const uint4 *>(at_byte(q, group_off + 16 * b));
     }
+    // The same for a group that may lie past the last one: the read stops at `end` (bytes of qweight).
+    __device__ inline void load_clamped(const uint32_t *q, uint32_t group_off, int b, uint32_t end)
+    {
+        const uint32_t off = group_off + 16 * b;
+        w = *reinterpret_cast<const uint4 *>(at_byte(q, off < end - 16 ? off : end - 16));
+    }
     __device__ inline void decode(uint32_t z, int /*b*/, const DecodeConsts &d, u32x4 f[4]) const
     {
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
@@ -57,6 +63,13 @@ template <> struct Slot<3> {
         const uint32_t *p = at_byte(q, group_off + 12 * b);
         w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
         tail = *at_byte(q, group_off + 48);
+    }
+    __device__ inline void load_clamped(const uint32_t *q, uint32_t group_off, int b, uint32_t end)
+    {
+        const uint32_t off = group_off + 12 * b;
+        const uint32_t *p = at_byte(q, off < end - 12 ? off : end - 12);
+        w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
+        tail = *at_byte(q, group_off + 48 < end - 4 ? group_off + 48 : end - 4);
     }
     __device__ inline void decode(uint32_t z, int b, const DecodeConsts &d, u32x4 f[4]) const
     {
@@ -80,10 +93,10 @@ template <int BITS, int U> struct Chunk {
 };
 
 constexpr int kPre = 4;        // outlier entries a lane handles without a loop
-constexpr int kMetaRounds = 2; // 16-byte vectors of scales / zero points a thread stages
 
-// One layer of a launch, and the launch: up to kMaxBatch layers, blocks [block_end[i-1], block_end[i])
-// belong to layer i.  Passed by value (kernel argument segment), read through the scalar cache.
+// One layer of a launch, and the launch: up to kMaxBatch layers, layer i = blockIdx.y.  Passed by
+// value (kernel argument segment) and read through the scalar cache: the descriptor's offset follows
+// from blockIdx.y alone, so one scalar load separates the start of a wave from its first vector load.
 struct DecodeProblem {
     const uint32_t *qweight;
     const uint16_t *scales;
@@ -96,31 +109,35 @@ struct DecodeProblem {
     int N, K, groups_per_wave, sc_last_vec, zp_last_vec, csr_last_vec;
 };
 struct DecodeBatch {
-    int count, M;
-    int block_end[kMaxBatch];
+    int M, nwaves;
     DecodeProblem p[kMaxBatch];
 };
 
-// BITS: 3 or 4.  U: groups per chunk (4 or 8).  PIPE: a wave owns more than U groups (up to 16 when
-// MS > 0) and double-buffers chunks of U = 4.  MS: 1..4 = M is exactly MS and X[M][K] is staged in
-// LDS, the four lanes of a channel sharing its outliers; 0 = any M <= 16, X read from global memory.
+// ---- M <= 4 with X[M][K] in LDS: the lean kernel ------------------------------------------------
 //
-// Rows m >= M of the X operand are never zeroed: lanes r >= M re-read row 0, which only produces
-// result rows m >= M, and those are not stored.
+// A kernel this short is bounded as much by the instructions a wave issues as by the bytes it moves,
+// so this one is straight-line code with compile-time offsets:
+//   * wave w owns exactly the U groups [wU, wU + U) of the block's 16 channels (the launcher starts
+//     ceil(gpr / U) waves); its index and everything derived from it live in scalar registers;
+//   * groups at or beyond gpr exist only in the last wave.  Nothing is predicated for them: their
+//     codes are whatever follows in memory (the next channel; the address is only kept from
+//     passing the end of qweight), their scales whatever follows in LDS (finite numbers), and they
+//     meet zeros in the LDS copy of X, whose rows are padded to waves * U groups;
+//   * a launch over several layers has as many waves as its longest rows need; the surplus waves of
+//     a shorter layer repeat wave 0's work and drop the result.
 //
-// Dynamic LDS, in this order: X [MS][K] halves | scales [16][gpr] halves | zero points [16][gpr]
-// bytes | 16 spare bytes | CSR columns, blockDim * 8 entries | CSR values, same | partial sums
-// [waves][4][64] floats.  The launcher guarantees kMetaRounds * blockDim >= 3 * gpr.
-template <int BITS, int U, bool PIPE, int MS>
-__global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
+// Dynamic LDS, in this order: X [MS][k_pad] halves | scales [16][gpr] halves | zero points [16][gpr]
+// bytes | 16 spare bytes | CSR columns, blockDim * 8 entries + 8 zero entries | CSR values, same |
+// partial sums [waves][MS][64] floats.  blockDim >= 3 gpr holds by construction (64 ceil(gpr / U)
+// threads, U <= 16), so one 16-byte vector per thread stages all scales and zero points.
+template <int BITS, int U, int MS>
+__global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
 {
-    constexpr bool SMALLM = MS > 0;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    // Which layer this block works on (uniform).
-    int layer = 0;
-    while (layer + 1 < batch.count && (int)blockIdx.x >= batch.block_end[layer]) ++layer;
-    const DecodeProblem &pr = batch.p[layer];
-    const int block = blockIdx.x - (layer ? batch.block_end[layer - 1] : 0);
+    const DecodeProblem &pr = batch.p[blockIdx.y];
+    const int N = pr.N, K = pr.K;
+    const int block = blockIdx.x;
+    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
     const uint32_t *__restrict__ qweight = pr.qweight;
     const uint16_t *__restrict__ scales = pr.scales;
     const uint8_t *__restrict__ zeros = pr.zeros;
@@ -129,27 +146,244 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     const uint16_t *__restrict__ out_val = pr.out_val;
     const _Float16 *__restrict__ X = pr.X;
     _Float16 *__restrict__ Y = pr.Y;
-    const int N = pr.N, K = pr.K, M = batch.M, groups_per_wave = pr.groups_per_wave;
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthreads = blockDim.x, nwaves = nthreads >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = batch.nwaves, nthreads = nwaves * 64;
+    const int r = lane & 15, b = lane >> 4;
+    const int gpr = K / kGroup;
+    const int my_waves = (gpr + U - 1) / U;             // waves of this layer that own groups
+    const bool active = wave < my_waves;
+    const int g_begin = active ? wave * U : 0;
+    const int k_pad = my_waves * U * kGroup;            // row length of the LDS copy of X
+    const int row0 = block * 16;
+    const int n = row0 + r;
+    const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
+
+    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
+    const uint32_t sc_off = (uint32_t)MS * k_pad * 2;
+    const uint32_t zp_off = sc_off + 32 * gpr;
+    const uint32_t spare_off = zp_off + 16 * gpr;
+    const uint32_t col_off = spare_off + 16;
+    const uint32_t val_off = col_off + 16 * nthreads + 16;
+    const uint32_t red_off = val_off + 16 * nthreads + 16;
+    float *red = reinterpret_cast<float *>(lds_raw + red_off);
+
+    // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
+    const int last_row = row0 + 16 < N ? row0 + 16 : N;
+    const int e_begin = row_ptr[row0], e_end = row_ptr[last_row];
+    const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
+
+    // Staging loads, all 16-byte and coalesced.  (1) X: each wave brings the columns of its own
+    // groups; vectors beyond K are loaded from column 0 and replaced by zeros when stored.
+    constexpr int kQ = U / 4;                           // 64-vector rounds covering U groups
+    u32x4 xstage[MS * kQ];
+#pragma unroll
+    for (int e = 0; e < MS; ++e)
+#pragma unroll
+        for (int i = 0; i < kQ; ++i) {
+            const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+            xstage[e * kQ + i] = reinterpret_cast<const u32x4 *>(X)[e * (K / 8) + (kv < K / 8 ? kv : 0)];
+        }
+    // (2) The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for
+    // 16 consecutive channels: thread t < 2 gpr takes a scales vector, the next gpr threads a
+    // zero-point vector, any further thread re-reads vector 0 into the spare slot.
+    // The LDS copies of the two arrays are adjacent, so thread t stores to vector t of that range
+    // (the spare slot follows at vector 3 gpr).
+    u32x4 meta;
+    {
+        const bool is_sc = tid < 2 * gpr, is_zp = !is_sc && tid < 3 * gpr;
+        const int v_sc = block * 2 * gpr + tid < sc_last_vec ? block * 2 * gpr + tid : sc_last_vec;
+        const int v_zp = block * gpr + (tid - 2 * gpr) < zp_last_vec ? block * gpr + (tid - 2 * gpr) : zp_last_vec;
+        const int v = is_sc ? v_sc : is_zp ? v_zp : 0;
+        const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
+        meta = src[v];
+    }
+    const uint32_t meta_dst = sc_off + 16 * (tid < 3 * gpr ? tid : 3 * gpr);
+
+    // The code stream: everything else overlaps its HBM latency.
+    constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
+    const uint32_t code_off = ((uint32_t)n_c * gpr + g_begin) * group_bytes;
+    const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
+    Slot<BITS> slot[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
+
+    // (3) The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin:
+    // thread t brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
+    const int e0 = e_begin & ~7;
+    u32x4 seg_col, seg_val;
+    {
+        const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
+        int v = e0 / 8 + tid;
+        v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
+        v = v < csr_last_vec ? v : csr_last_vec;
+        seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
+        seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
+    }
+    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+
+    // Nothing that consumes a load may be scheduled above this point.
+    __builtin_amdgcn_sched_barrier(0);
+    const DecodeConsts dc(BITS);
+#pragma unroll
+    for (int e = 0; e < MS; ++e)
+#pragma unroll
+        for (int i = 0; i < kQ; ++i) {
+            const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+            reinterpret_cast<u32x4 *>(xs)[e * (k_pad / 8) + kv] =
+                kv < K / 8 ? xstage[e * kQ + i] : u32x4{0u, 0u, 0u, 0u};
+        }
+    *reinterpret_cast<u32x4 *>(lds_raw + meta_dst) = meta;
+    __syncthreads();
+
+    float acc[MS];
+#pragma unroll
+    for (int e = 0; e < MS; ++e) acc[e] = 0.f;
+    {
+        const int x_row = r < MS ? r : 0;
+        const _Float16 *x_lane = xs + (uint32_t)x_row * k_pad + g_begin * kGroup + 32 * b;
+        const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
+        const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            u32x4 xa[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xa[j] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * j);
+            const _Float16 s = __builtin_bit_cast(_Float16, sc_lane[u]);
+            const uint32_t z = zp_lane[u];
+            u32x4 wb[4];
+            slot[u].decode(z, b, dc, wb);
+            float4v part = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[j]),
+                                                              __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < MS; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
+        }
+    }
+
+    // The CSR segment has arrived by now: publish it, followed by one vector of zero entries that
+    // lanes without an entry read instead.
+    reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
+    reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+    if (tid == 0) {
+        reinterpret_cast<u32x4 *>(lds_raw + col_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4 *>(lds_raw + val_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
+    }
+    __syncthreads();
+
+    // Outliers: the 4 * waves lanes of a channel split its entries and sum rows m = 0 .. MS-1.
+    // Entry j sits at LDS index j - e0 when j < staged_end.
+    const int o_stride = 4 * nwaves;
+    const bool o_live = n < N;
+    const int o_end = o_live ? (rp1 < staged_end ? rp1 : staged_end) : 0;   // end of the lane's staged entries
+    const unsigned char *col_base = lds_raw + col_off;
+    const uint32_t val_delta = val_off - col_off;
+    float oacc[MS];
+#pragma unroll
+    for (int e = 0; e < MS; ++e) oacc[e] = 0.f;
+    auto add_outlier = [&](uint32_t col, uint16_t val_bits) {
+        const _Float16 v = __builtin_bit_cast(_Float16, val_bits);
+#pragma unroll
+        for (int e = 0; e < MS; ++e) oacc[e] = __builtin_fmaf((float)v, (float)xs[(uint32_t)e * k_pad + col], oacc[e]);
+    };
+    auto staged = [&](int idx) {
+        const unsigned char *p = col_base + 2 * idx;
+        add_outlier(*reinterpret_cast<const uint16_t *>(p), *reinterpret_cast<const uint16_t *>(p + val_delta));
+    };
+    const int j_first = rp0 + 4 * wave + b;
+#pragma unroll
+    for (int i = 0; i < kPre; ++i) {
+        const int j = j_first + i * o_stride;
+        staged(j < o_end ? j - e0 : 8 * nthreads);      // the zero entry when the lane has none
+    }
+    if (j_first + kPre * o_stride < o_end || (o_live && rp1 > staged_end)) {
+        int j = j_first + kPre * o_stride;
+        for (; j < o_end; j += o_stride) staged(j - e0);
+        // Entries that did not fit the staged window (very long rows) come straight from memory.
+        j = j_first;
+        if (j < staged_end) j += ((staged_end - j + o_stride - 1) / o_stride) * o_stride;
+        if (o_live)
+            for (; j < rp1; j += o_stride) add_outlier(col_idx[j], out_val[j]);
+    }
+
+    // Fixed-order reduction over the waves and the four lanes of a channel, then FP16 store.
+    // Only lanes b = 0 of a wave that owns groups hold dense results (rows m < 4).
+#pragma unroll
+    for (int e = 0; e < MS; ++e) {
+        const float dense = (active && b == 0) ? acc[e] : 0.f;
+        red[(wave * MS + e) * 64 + lane] = dense + oacc[e];
+    }
+    __syncthreads();
+    // Wave e (or the wave that reaches it by striding) sums row e: every lane adds its column of
+    // partial sums over the waves, then the four lanes of a channel meet.
+    for (int e = wave; e < MS; e += nwaves) {
+        float s0 = 0.f, s1 = 0.f;
+        int w = 0;
+        for (; w + 1 < nwaves; w += 2) {
+            s0 += red[(w * MS + e) * 64 + lane];
+            s1 += red[((w + 1) * MS + e) * 64 + lane];
+        }
+        if (w < nwaves) s0 += red[(w * MS + e) * 64 + lane];
+        float sum = s0 + s1;
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (_Float16)sum;
+    }
+}
+
+// ---- any M <= 16, X read from global memory: the general kernel --------------------------------
+//
+// BITS: 3 or 4.  U: groups per chunk (4 or 8).  PIPE: a wave owns more than U groups and
+// double-buffers chunks of U = 4.  Waves split K by groups_per_wave; indices past a wave's last
+// group are clamped and the repeated data dropped by a zero scale, so no branch sits between the
+// loads and their use.
+//
+// Rows m >= M of the X operand are never zeroed: lanes r >= M re-read row 0, which only produces
+// result rows m >= M, and those are not stored.
+//
+// Dynamic LDS, in this order: scales [16][gpr] halves | zero points [16][gpr] bytes | 16 spare bytes
+// | CSR columns, blockDim * 8 entries + 8 zero entries | CSR values, same | partial sums
+// [waves][4][64] floats.  The launcher guarantees kMetaRounds * blockDim >= 3 * gpr.
+constexpr int kMetaRounds = 2; // 16-byte vectors of scales / zero points a thread stages
+
+template <int BITS, int U, bool PIPE>
+__global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const DecodeProblem &pr = batch.p[blockIdx.y];
+    const int N = pr.N, K = pr.K;
+    const int block = blockIdx.x;
+    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
+    const uint32_t *__restrict__ qweight = pr.qweight;
+    const uint16_t *__restrict__ scales = pr.scales;
+    const uint8_t *__restrict__ zeros = pr.zeros;
+    const int32_t *__restrict__ row_ptr = pr.row_ptr;
+    const uint16_t *__restrict__ col_idx = pr.col_idx;
+    const uint16_t *__restrict__ out_val = pr.out_val;
+    const _Float16 *__restrict__ X = pr.X;
+    _Float16 *__restrict__ Y = pr.Y;
+    const int M = batch.M, groups_per_wave = pr.groups_per_wave;
+    const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nwaves = batch.nwaves, nthreads = nwaves * 64;
     const int r = lane & 15, b = lane >> 4;
     const int gpr = K / kGroup;
     const int row0 = block * 16;
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
 
-    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
-    const uint32_t sc_off = (uint32_t)MS * K * 2;
+    const uint32_t sc_off = 0;
     const uint32_t zp_off = sc_off + 32 * gpr;
     const uint32_t spare_off = zp_off + 16 * gpr;
     const uint32_t col_off = spare_off + 16;
-    const uint32_t val_off = col_off + 16 * nthreads;
-    const uint32_t red_off = val_off + 16 * nthreads;
-    const uint16_t *sc_lds = reinterpret_cast<const uint16_t *>(lds_raw + sc_off);
-    const uint8_t *zp_lds = lds_raw + zp_off;
-    const uint16_t *col_lds = reinterpret_cast<const uint16_t *>(lds_raw + col_off);
-    const uint16_t *val_lds = reinterpret_cast<const uint16_t *>(lds_raw + val_off);
+    const uint32_t val_off = col_off + 16 * nthreads + 16;
+    const uint32_t red_off = val_off + 16 * nthreads + 16;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
 
     // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
@@ -164,26 +398,10 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     const int g_end = g_begin + groups_per_wave < gpr ? g_begin + groups_per_wave : gpr;
     const int g_last = g_end - 1;
 
-    // Staging loads, all 16-byte and coalesced.  (1) X: each wave brings the columns of its own
-    // groups (the waves partition K); lanes past the end of a short slice repeat its last vector.
-    constexpr int kSliceQuads = PIPE ? 4 : U / 4;       // 64-vector rounds covering a wave's slice
-    constexpr int kXVecs = SMALLM ? MS * kSliceQuads : 1;
-    u32x4 xstage[kXVecs];
-    uint32_t xvec[kXVecs];
-    if (SMALLM) {
-        const int slice_vecs = (g_end - g_begin) * (kGroup / 8);
-#pragma unroll
-        for (int e = 0; e < MS; ++e)
-#pragma unroll
-            for (int i = 0; i < kSliceQuads; ++i) {
-                const int q = lane + 64 * i < slice_vecs ? lane + 64 * i : slice_vecs - 1;
-                xvec[e * kSliceQuads + i] = (uint32_t)e * (K / 8) + g_begin * (kGroup / 8) + q;
-                xstage[e * kSliceQuads + i] = reinterpret_cast<const u32x4 *>(X)[xvec[e * kSliceQuads + i]];
-            }
-    }
-    // (2) The block's scales (32 * gpr bytes) and zero points (16 * gpr bytes), contiguous in
-    // memory for 16 consecutive channels: vector t < 2 gpr is a scales vector, the next gpr are
-    // zero-point vectors, any further thread re-reads vector 0 into the spare slot.
+    // The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for 16
+    // consecutive channels, staged with coalesced 16-byte loads: vector t < 2 gpr is a scales
+    // vector, the next gpr are zero-point vectors, any further thread re-reads vector 0 into the
+    // spare slot.
     uint32_t meta_dst[kMetaRounds];
     u32x4 meta[kMetaRounds];
 #pragma unroll
@@ -203,8 +421,8 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     Chunk<BITS, U> cur;
     cur.load(qweight, row_group, g_begin, g_last, b);
 
-    // (3) The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin:
-    // thread t brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
+    // The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin: thread t
+    // brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
     const int e0 = e_begin & ~7;
     u32x4 seg_col, seg_val;
     {
@@ -220,19 +438,15 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     // Nothing that consumes a load may be scheduled above this point.
     __builtin_amdgcn_sched_barrier(0);
     const DecodeConsts dc(BITS);
-    if (SMALLM) {
-#pragma unroll
-        for (int i = 0; i < kXVecs; ++i) reinterpret_cast<u32x4 *>(xs)[xvec[i]] = xstage[i];
-    }
 #pragma unroll
     for (int i = 0; i < kMetaRounds; ++i) *reinterpret_cast<u32x4 *>(lds_raw + meta_dst[i]) = meta[i];
     __syncthreads();
 
     float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
     const int x_row = r < M ? r : 0;
-    const _Float16 *xsrc = (SMALLM ? xs : X) + (uint32_t)x_row * K + 32 * b;
-    // Groups past the wave's last one (a short final wave) are computed on the clamped, repeated
-    // data and dropped by a zero scale: no branch sits between the loads and their use.
+    const _Float16 *xsrc = X + (uint32_t)x_row * K + 32 * b;
+    const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr;
+    const uint8_t *zp_lane = lds_raw + zp_off + r * gpr;
     auto compute = [&](const Chunk<BITS, U> &c, int g0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -242,9 +456,9 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 xa[j] = *reinterpret_cast<const u32x4 *>(xsrc + (uint32_t)g * kGroup + 8 * j);
-            const float s_raw = (float)__builtin_bit_cast(_Float16, sc_lds[r * gpr + g]);
-            const float s = valid ? s_raw : 0.f;
-            const uint32_t z = zp_lds[r * gpr + g];
+            const _Float16 s_raw = __builtin_bit_cast(_Float16, sc_lane[g]);
+            const float s = valid ? (float)s_raw : 0.f;
+            const uint32_t z = zp_lane[g];
             u32x4 wb[4];
             c.slot[u].decode(z, b, dc, wb);
             float4v part = float4v{0.f, 0.f, 0.f, 0.f};
@@ -269,115 +483,158 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
         compute(cur, g_begin);
     }
 
-    // The CSR segment has arrived by now: publish it.
+    // The CSR segment has arrived by now: publish it, followed by one vector of zero entries that
+    // lanes without an entry read instead.
     reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
     reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+    if (tid == 0) {
+        reinterpret_cast<u32x4 *>(lds_raw + col_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4 *>(lds_raw + val_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
+    }
     __syncthreads();
 
-    // Outliers.  SMALLM: the four lanes of a channel split its entries and sum rows m = 0 .. MS-1;
-    // otherwise lane (r, b) takes every entry of its channel for rows m = 4b .. 4b+3, the rows of
-    // its MFMA results.  Entry j sits at LDS index j - e0 when j < staged_end.
-    const int o_stride = SMALLM ? 4 * nwaves : nwaves;
-    const int o_first = SMALLM ? 4 * wave + b : wave;
-    const bool o_live = n < N && (SMALLM || 4 * b < M);
+    // Outliers: lane (r, b) of every wave takes a share of its channel's entries for rows
+    // m = 4b .. 4b+3, the rows of its MFMA results.  Entry j sits at LDS index j - e0 when
+    // j < staged_end.
+    const int o_stride = nwaves;
+    const bool o_live = n < N && 4 * b < M;
+    const int o_end = o_live ? (rp1 < staged_end ? rp1 : staged_end) : 0;   // end of the lane's staged entries
+    const unsigned char *col_base = lds_raw + col_off;
+    const uint32_t val_delta = val_off - col_off;
     float4v oacc = float4v{0.f, 0.f, 0.f, 0.f};
-    auto add_outlier = [&](uint32_t col, uint16_t val_bits, bool ok) {
-        const float v = ok ? (float)__builtin_bit_cast(_Float16, val_bits) : 0.f;
-        if (SMALLM) {
+    auto add_outlier = [&](uint32_t col, uint16_t val_bits) {
+        const float v = (float)__builtin_bit_cast(_Float16, val_bits);
 #pragma unroll
-            for (int e = 0; e < MS; ++e) oacc[e] = __builtin_fmaf(v, (float)xs[(uint32_t)e * K + col], oacc[e]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int m = 4 * b + e < M ? 4 * b + e : 0;         // rows m >= M are not stored
-                oacc[e] = __builtin_fmaf(v, (float)X[(uint32_t)m * K + col], oacc[e]);
-            }
+        for (int e = 0; e < 4; ++e) {
+            const int m = 4 * b + e < M ? 4 * b + e : 0;             // rows m >= M are not stored
+            oacc[e] = __builtin_fmaf(v, (float)X[(uint32_t)m * K + col], oacc[e]);
         }
     };
+    auto staged = [&](int idx) {
+        const unsigned char *p = col_base + 2 * idx;
+        add_outlier(*reinterpret_cast<const uint16_t *>(p), *reinterpret_cast<const uint16_t *>(p + val_delta));
+    };
+    const int j_first = rp0 + wave;
 #pragma unroll
     for (int i = 0; i < kPre; ++i) {
-        const int j = rp0 + o_first + i * o_stride;
-        const bool ok = o_live && j < rp1 && j < staged_end;
-        const int idx = ok ? j - e0 : 0;
-        add_outlier(col_lds[idx], val_lds[idx], ok);
+        const int j = j_first + i * o_stride;
+        staged(j < o_end ? j - e0 : 8 * nthreads);      // the zero entry when the lane has none
     }
-    if (o_live) {
-        int j = rp0 + o_first + kPre * o_stride;
-        for (; j < rp1 && j < staged_end; j += o_stride) add_outlier(col_lds[j - e0], val_lds[j - e0], true);
+    if (j_first + kPre * o_stride < o_end || (o_live && rp1 > staged_end)) {
+        int j = j_first + kPre * o_stride;
+        for (; j < o_end; j += o_stride) staged(j - e0);
         // Entries that did not fit the staged window (very long rows) come straight from memory.
-        j = rp0 + o_first;
+        j = j_first;
         if (j < staged_end) j += ((staged_end - j + o_stride - 1) / o_stride) * o_stride;
-        for (; j < rp1; j += o_stride) add_outlier(col_idx[j], out_val[j], true);
+        if (o_live)
+            for (; j < rp1; j += o_stride) add_outlier(col_idx[j], out_val[j]);
     }
 
-    // Fixed-order reduction over the waves (and, for SMALLM, over the four lanes of a channel),
-    // then FP16 store.  SMALLM: only lanes b = 0 hold dense results for rows m < 4.
+    // Fixed-order reduction over the waves, then FP16 store.
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float dense = (!SMALLM || b == 0) ? acc[e] : 0.f;
-        red[(wave * 4 + e) * 64 + lane] = dense + oacc[e];
-    }
+    for (int e = 0; e < 4; ++e) red[(wave * 4 + e) * 64 + lane] = acc[e] + oacc[e];
     __syncthreads();
-    if (SMALLM) {
-        if (tid < 16 * MS) {                            // (e, r)
-            const int e = tid >> 4, rr = tid & 15;
-            float sum = 0.f;
-            for (int w = 0; w < nwaves; ++w)
-#pragma unroll
-                for (int bb = 0; bb < 4; ++bb) sum += red[(w * 4 + e) * 64 + 16 * bb + rr];
-            if (row0 + rr < N) Y[(size_t)e * N + row0 + rr] = (_Float16)sum;
-        }
-    } else {
-        for (int idx = tid; idx < 256; idx += nthreads) {
-            float sum = 0.f;
-            for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
-            const int e = idx >> 6, l = idx & 63;
-            const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
-            if (nn < N && m < M) Y[(size_t)m * N + nn] = (_Float16)sum;
-        }
+    for (int idx = tid; idx < 256; idx += nthreads) {
+        float sum = 0.f;
+        for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
+        const int e = idx >> 6, l = idx & 63;
+        const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
+        if (nn < N && m < M) Y[(size_t)m * N + nn] = (_Float16)sum;
     }
 }
 
-constexpr size_t kXLdsBudget = 64 * 1024;               // X[M][K] is staged in LDS up to this size
+constexpr size_t kXLdsBudget = 64 * 1024;               // X[M][k_pad] is staged in LDS up to this size
 
-template <int BITS, int U, bool PIPE, int MS>
-hipError_t launch_v(const DecodeBatch &batch, int blocks, int nwaves, size_t lds, hipStream_t st)
+template <auto Kernel>
+hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nwaves, size_t lds, hipStream_t st)
 {
-    static bool attr_set = false;                       // per instantiation; idempotent HIP call
+    static bool attr_set = false;                       // per kernel; the HIP call is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<BITS, U, PIPE, MS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    decode_kernel<BITS, U, PIPE, MS><<<blocks, nwaves * 64, lds, st>>>(batch);
+    Kernel<<<dim3(blocks, count), nwaves * 64, lds, st>>>(batch);
     return hipGetLastError();
 }
 
-template <int BITS, int MS>
-hipError_t launch_m(const DecodeBatch &batch, int blocks, int nwaves, int max_gpw, size_t lds, hipStream_t st)
+template <int BITS>
+hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwaves, int u, int ms, size_t lds,
+                        hipStream_t st)
 {
-    if (max_gpw <= 4) return launch_v<BITS, 4, false, MS>(batch, blocks, nwaves, lds, st);
-    if (max_gpw <= 8) return launch_v<BITS, 8, false, MS>(batch, blocks, nwaves, lds, st);
-    // Long rows: double-buffered chunks; X is staged only while its staging registers stay few.
-    if constexpr (MS == 1 || MS == 2) {
-        if (max_gpw <= 16) return launch_v<BITS, 4, true, MS>(batch, blocks, nwaves, lds, st);
-    }
-    return launch_v<BITS, 4, true, 0>(batch, blocks, nwaves, lds, st);
+#define GWQ_SMALL(UU, MM) \
+    if (u == UU && ms == MM) return launch_kernel<&decode_small_kernel<BITS, UU, MM>>(batch, count, blocks, nwaves, lds, st)
+    GWQ_SMALL(4, 1); GWQ_SMALL(4, 2); GWQ_SMALL(4, 3); GWQ_SMALL(4, 4);
+    GWQ_SMALL(8, 1); GWQ_SMALL(8, 2); GWQ_SMALL(8, 3); GWQ_SMALL(8, 4);
+    GWQ_SMALL(16, 1); GWQ_SMALL(16, 2);
+#undef GWQ_SMALL
+    return hipErrorInvalidValue;
+}
+
+template <int BITS>
+hipError_t launch_general(const DecodeBatch &batch, int count, int blocks, int nwaves, int max_gpw, size_t lds,
+                          hipStream_t st)
+{
+    if (max_gpw <= 4) return launch_kernel<&decode_kernel<BITS, 4, false>>(batch, count, blocks, nwaves, lds, st);
+    if (max_gpw <= 8) return launch_kernel<&decode_kernel<BITS, 8, false>>(batch, count, blocks, nwaves, lds, st);
+    return launch_kernel<&decode_kernel<BITS, 4, true>>(batch, count, blocks, nwaves, lds, st);
 }
 
 }  // namespace
 
-// Decode launch over `count` layers (same bits, same M): one grid, layer i owning ceil(N_i / 16) blocks.
+// Decode launch over `count` layers (same bits, same M): grid row i works on layer i; the grid is as
+// wide as the layer with most channels needs and the surplus blocks of smaller layers exit at once.
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
                          int waves_override, hipStream_t st)
 {
     DecodeBatch batch;
-    batch.count = count;
     batch.M = M;
-    // Waves per block: one chunk of eight groups per wave where the rows are long enough, at most 16,
-    // and enough threads to stage every layer's 3 * gpr vectors of scales and zero points.
-    int nwaves = 1, max_k = 0;
+    int blocks = 0, max_gpr = 1;
+    for (int i = 0; i < count; ++i) {
+        const gwq_packed &L = *P[i];
+        const int gpr = L.K / kGroup;
+        DecodeProblem &d = batch.p[i];
+        d.qweight = L.qweight; d.scales = L.scales; d.zeros = L.zeros;
+        d.row_ptr = L.row_ptr; d.col_idx = L.col_idx; d.out_val = L.out_val;
+        d.X = static_cast<const _Float16 *>(X[i]);
+        d.Y = static_cast<_Float16 *>(Y[i]);
+        d.N = L.N; d.K = L.K;
+        d.groups_per_wave = 0;
+        // Last 16-byte vector of each staged array (the buffers are padded, so clamped reads stay inside).
+        const int64_t groups = (int64_t)L.N * gpr;
+        d.sc_last_vec = (int)((groups * 2 + 15) / 16) - 1;
+        d.zp_last_vec = (int)((groups + 15) / 16) - 1;
+        d.csr_last_vec = (int)((L.n_outliers * 2 + 15) / 16);
+        if ((L.N + 15) / 16 > blocks) blocks = (L.N + 15) / 16;
+        if (gpr > max_gpr) max_gpr = gpr;
+    }
+    for (int i = count; i < kMaxBatch; ++i) batch.p[i] = batch.p[0];
+    const int bits = P[0]->bits;
+    const size_t meta = (size_t)48 * max_gpr + 16;
+
+    // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
+    if (M <= 4) {
+        int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
+        if (waves_override > 0) {                       // the most waves that do not exceed the request
+            u = 4;
+            while (u < 16 && (max_gpr + u - 1) / u > waves_override) u *= 2;
+        }
+        while (u < 16 && (max_gpr + u - 1) / u > 16) u *= 2;
+        const int nwaves = (max_gpr + u - 1) / u;
+        const size_t x_bytes = (size_t)M * nwaves * u * kGroup * 2;
+        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget) {
+            batch.nwaves = nwaves;
+            const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256;
+            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, st)
+                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, st);
+        }
+    }
+
+    // The general kernel.  Waves per block: one chunk of eight groups per wave where the rows are
+    // long enough, at most 16, and enough threads to stage every layer's 3 gpr vectors of scales
+    // and zero points.
+    int nwaves = 1;
     for (int i = 0; i < count; ++i) {
         const int gpr = P[i]->K / kGroup;
         int w = waves_override ? waves_override : (gpr + 7) / 8;
@@ -390,42 +647,18 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
             if (needed >= min_waves) w = needed;
         }
         if (w > nwaves) nwaves = w;
-        if (P[i]->K > max_k) max_k = P[i]->K;
     }
-    int blocks = 0, max_gpw = 1;
-    size_t max_meta = 0;
+    int max_gpw = 1;
     for (int i = 0; i < count; ++i) {
-        const gwq_packed &L = *P[i];
-        const int gpr = L.K / kGroup;
+        const int gpr = P[i]->K / kGroup;
         if (nwaves * 64 * kMetaRounds < 3 * gpr) return hipErrorInvalidValue;      // K <= 65536 keeps this false
-        DecodeProblem &d = batch.p[i];
-        d.qweight = L.qweight; d.scales = L.scales; d.zeros = L.zeros;
-        d.row_ptr = L.row_ptr; d.col_idx = L.col_idx; d.out_val = L.out_val;
-        d.X = static_cast<const _Float16 *>(X[i]);
-        d.Y = static_cast<_Float16 *>(Y[i]);
-        d.N = L.N; d.K = L.K;
-        d.groups_per_wave = (gpr + nwaves - 1) / nwaves;
-        if (d.groups_per_wave > max_gpw) max_gpw = d.groups_per_wave;
-        // Last 16-byte vector of each staged array (the buffers are padded, so clamped reads stay inside).
-        const int64_t groups = (int64_t)L.N * gpr;
-        d.sc_last_vec = (int)((groups * 2 + 15) / 16) - 1;
-        d.zp_last_vec = (int)((groups + 15) / 16) - 1;
-        d.csr_last_vec = (int)((L.n_outliers * 2 + 15) / 16);
-        blocks += (L.N + 15) / 16;
-        batch.block_end[i] = blocks;
-        if ((size_t)48 * gpr > max_meta) max_meta = (size_t)48 * gpr;
+        batch.p[i].groups_per_wave = (gpr + nwaves - 1) / nwaves;
+        if (batch.p[i].groups_per_wave > max_gpw) max_gpw = batch.p[i].groups_per_wave;
     }
-    for (int i = count; i < kMaxBatch; ++i) { batch.block_end[i] = blocks; batch.p[i] = batch.p[0]; }
-
-    int ms = (M <= 4 && (size_t)M * max_k * 2 <= kXLdsBudget) ? M : 0;
-    if (max_gpw > 8 && !((ms == 1 || ms == 2) && max_gpw <= 16)) ms = 0;            // mirrors launch_m
-    const size_t lds = (size_t)ms * max_k * 2 + max_meta + 16 + 32 * (size_t)nwaves * 64 + (size_t)nwaves * 1024;
-    const int bits = P[0]->bits;
-#define GWQ_MS(B, MM) if (bits == B && ms == MM) return launch_m<B, MM>(batch, blocks, nwaves, max_gpw, lds, st)
-    GWQ_MS(4, 0); GWQ_MS(4, 1); GWQ_MS(4, 2); GWQ_MS(4, 3); GWQ_MS(4, 4);
-    GWQ_MS(3, 0); GWQ_MS(3, 1); GWQ_MS(3, 2); GWQ_MS(3, 3); GWQ_MS(3, 4);
-#undef GWQ_MS
-    return hipErrorInvalidValue;
+    batch.nwaves = nwaves;
+    const size_t lds = meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * 1024;
+    return bits == 4 ? launch_general<4>(batch, count, blocks, nwaves, max_gpw, lds, st)
+                     : launch_general<3>(batch, count, blocks, nwaves, max_gpw, lds, st);
 }
 
 }  // namespace gwq

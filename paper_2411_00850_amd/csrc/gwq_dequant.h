@@ -67,19 +67,18 @@ template <> struct ZeroConsts<4> {
     uint32_t c1024, c64;
     __device__ inline explicit ZeroConsts(uint32_t z)
     {
-        const uint32_t zz = z | z << 16;
-        c1024 = zz | 0xE400E400u;              // -(1024 + z): ulp is 1 in [1024, 2048)
-        c64 = zz << 4 | 0xD400D400u;           // -(64 + z):   ulp is 1/16 in [64, 128)
+        // one 24-bit multiply-add each: the products never carry into the constants' set bits
+        c1024 = z * 0x10001u + 0xE400E400u;    // -(1024 + z): ulp is 1 in [1024, 2048)
+        c64 = z * 0x100010u + 0xD400D400u;     // -(64 + z):   ulp is 1/16 in [64, 128)
     }
 };
 template <> struct ZeroConsts<3> {
     uint32_t c1024, c128, c16;
     __device__ inline explicit ZeroConsts(uint32_t z)
     {
-        const uint32_t zz = z | z << 16;
-        c1024 = zz | 0xE400E400u;
-        c128 = zz << 3 | 0xD800D800u;          // -(128 + z): ulp is 1/8 in [128, 256)
-        c16 = zz << 6 | 0xCC00CC00u;           // -(16 + z):  ulp is 1/64 in [16, 32)
+        c1024 = z * 0x10001u + 0xE400E400u;
+        c128 = z * 0x80008u + 0xD800D800u;     // -(128 + z): ulp is 1/8 in [128, 256)
+        c16 = z * 0x400040u + 0xCC00CC00u;     // -(16 + z):  ulp is 1/64 in [16, 32)
     }
 };
 
