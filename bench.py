@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--copies", type=int, default=6, help="rotating copies of the packed layer")
     ap.add_argument("--group", choices=["deps", "none", "all"], default="deps",
                     help="launches per step: 4 grouped by data dependence (default), 7 single, or 1 over all")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="gwq_tuning_set before the run (e.g. decode_waves=8); repeatable")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="how the timed steps are launched: one HIP graph over all copies, or plain launches")
     ap.add_argument("--copy-probe", action="store_true",
@@ -83,6 +85,9 @@ def main():
     import torch
     import gwq_synth as gs
     import paper_2411_00850_amd as gwq
+    for kv in args.tune:
+        key, _, val = kv.partition("=")
+        gwq.tuning_set(key, int(val))
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")

@@ -137,7 +137,6 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     const DecodeProblem &pr = batch.p[blockIdx.y];
     const int N = pr.N, K = pr.K;
     const int block = blockIdx.x;
-    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
     const uint32_t *__restrict__ qweight = pr.qweight;
     const uint16_t *__restrict__ scales = pr.scales;
     const uint8_t *__restrict__ zeros = pr.zeros;
@@ -147,6 +146,11 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     const _Float16 *__restrict__ X = pr.X;
     _Float16 *__restrict__ Y = pr.Y;
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+    // The whole descriptor is requested in one go and only then looked at (the empty statement
+    // keeps the compiler from moving the other loads behind the branch on N).
+    asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
+                 "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec));
+    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -202,27 +206,22 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     }
     const uint32_t meta_dst = sc_off + 16 * (tid < 3 * gpr ? tid : 3 * gpr);
 
-    // The code stream: everything else overlaps its HBM latency.
+    // Every wave has queued its staging loads before any wave queues code: the memory pipe of the
+    // CU serves requests in order, and the first barrier below waits for the slowest staging load.
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // The code stream.  The first kAhead groups are requested here, each further one while the
+    // group kAhead places before it is being multiplied: a wave that had all its requests queued
+    // at once would sit in the queue while its early groups wait in registers.
     constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
+    constexpr int kAhead = U < 4 ? U : 4;
     const uint32_t code_off = ((uint32_t)n_c * gpr + g_begin) * group_bytes;
     const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
     Slot<BITS> slot[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
-
-    // (3) The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin:
-    // thread t brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
-    const int e0 = e_begin & ~7;
-    u32x4 seg_col, seg_val;
-    {
-        const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
-        int v = e0 / 8 + tid;
-        v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
-        v = v < csr_last_vec ? v : csr_last_vec;
-        seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
-        seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
-    }
-    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+    for (int u = 0; u < kAhead; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
 
     // Nothing that consumes a load may be scheduled above this point.
     __builtin_amdgcn_sched_barrier(0);
@@ -238,6 +237,22 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     *reinterpret_cast<u32x4 *>(lds_raw + meta_dst) = meta;
     __syncthreads();
 
+    // (3) The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin:
+    // thread t brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
+    // Requested only now: its bounds have arrived in the meantime, and it is used last.
+    const int e0 = e_begin & ~7;
+    u32x4 seg_col, seg_val;
+    {
+        const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
+        int v = e0 / 8 + tid;
+        v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
+        v = v < csr_last_vec ? v : csr_last_vec;
+        seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
+        seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
+    }
+    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+    __builtin_amdgcn_sched_barrier(0);
+
     float acc[MS];
 #pragma unroll
     for (int e = 0; e < MS; ++e) acc[e] = 0.f;
@@ -248,6 +263,10 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
         const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            if (u + kAhead < U) {
+                slot[u + kAhead].load_clamped(qweight, code_off + (u + kAhead) * group_bytes, b, code_end);
+                __builtin_amdgcn_sched_barrier(0);      // the request stays ahead of this group's arithmetic
+            }
             u32x4 xa[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) xa[j] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * j);
@@ -357,7 +376,6 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     const DecodeProblem &pr = batch.p[blockIdx.y];
     const int N = pr.N, K = pr.K;
     const int block = blockIdx.x;
-    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
     const uint32_t *__restrict__ qweight = pr.qweight;
     const uint16_t *__restrict__ scales = pr.scales;
     const uint8_t *__restrict__ zeros = pr.zeros;
@@ -368,6 +386,10 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     _Float16 *__restrict__ Y = pr.Y;
     const int M = batch.M, groups_per_wave = pr.groups_per_wave;
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+    // The whole descriptor is requested in one go and only then looked at.
+    asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
+                 "s"(K), "s"(groups_per_wave), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec));
+    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
