@@ -20,6 +20,8 @@
 // points and counts are fetched four groups at a time, again with one unaligned load each.
 // The staging work of the next step is cut into four parts issued between the four MFMA batches
 // of the current one.
+#include <type_traits>
+
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -81,11 +83,12 @@ struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
 // holds the rest), as packed 16-bit pairs.
 template <int BITS> struct GroupRegs {
     SlotRegs<BITS> slot[2];
-    U64a2 col, val;
+    uint32_t col_lo, col_hi, val_lo, val_hi;
 };
-// Scales, zero points and outlier counts of four consecutive groups of channel n.
+// Scales, zero points and outlier counts of four consecutive groups of channel n.  (Plain words:
+// the unaligned loads go through temporaries, so these stay in registers.)
 struct MetaRegs {
-    U64a2 sc;
+    uint64_t sc;
     uint32_t zp, cnt;
 };
 
@@ -178,71 +181,86 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         load_slot<BITS>(G.slot[0], grp, b_h);
         load_slot<BITS>(G.slot[1], grp, 2 + b_h);
         const int j = first + 4 * b_h < last_entry ? first + 4 * b_h : last_entry;   // arrays carry 16 spare bytes
-        G.col = *reinterpret_cast<const U64a2 *>(col_idx + j);
-        G.val = *reinterpret_cast<const U64a2 *>(out_val + j);
+        const U64a2 c = *reinterpret_cast<const U64a2 *>(col_idx + j), v = *reinterpret_cast<const U64a2 *>(out_val + j);
+        G.col_lo = c.lo; G.col_hi = c.hi; G.val_lo = v.lo; G.val_hi = v.hi;
     };
     // Groups 4q .. 4q+3 (reads past the row or the array stay inside the padded buffers).
     auto issue_meta = [&](int q, MetaRegs &Q) {
         const int g = 4 * q < gpr ? 4 * q : 0;
-        Q.sc = *reinterpret_cast<const U64a2 *>(scales + row_group + g);
+        const U64a2 sc = *reinterpret_cast<const U64a2 *>(scales + row_group + g);
+        Q.sc = (uint64_t)sc.hi << 32 | sc.lo;
         Q.zp = reinterpret_cast<const U32a1 *>(zeros + row_group + g)->v;
         Q.cnt = reinterpret_cast<const U32a1 *>(grp_cnt + row_group + g)->v;
     };
     auto meta_scale = [](const MetaRegs &Q, int g) -> uint32_t {
-        const uint32_t w = (g & 2) ? Q.sc.hi : Q.sc.lo;
-        const uint32_t h = (g & 1) ? w >> 16 : w & 0xFFFFu;
+        const uint32_t h = (uint32_t)(Q.sc >> (16 * (g & 3))) & 0xFFFFu;      // a shift, not a choice of fields
         return h | h << 16;
     };
     auto meta_zero = [](const MetaRegs &Q, int g) -> uint32_t { return (Q.zp >> (8 * (g & 3))) & 0xFFu; };
     auto meta_count = [&](const MetaRegs &Q, int g) -> int { return b_valid ? (int)((Q.cnt >> (8 * (g & 3))) & 0xFFu) : 0; };
 
-    // Store part `part` (0..3) of step `step` into buffer `buf`: a quarter of the X rows and one
-    // 8-column fragment of this thread's weights; part 3 also writes the outliers.
-    auto store_part = [&](int part, int step, int buf, const u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G,
-                          const MetaRegs &Q, int first) {
-        _Float16 *A = a_dst + buf * kBufHalves, *brow = b_dst + buf * kBufHalves;
-        const int half = step & 1, g = step >> 1;
-        constexpr int per = kAPasses >= 4 ? kAPasses / 4 : 1;
+    // Staging of step `step` into buffer `buf`, cut into pieces that the step function spreads over
+    // its MFMA batches.  stage_x: X rows of pass p go to LDS, and the registers are refilled with
+    // the rows of two steps later.  stage_w: two of this thread's four 8-column weight fragments.
+    // stage_outliers: entries i0 .. i1-1 of the group's first eight, then (at i1 == 8) the rare rest.
+    auto stage_x = [&](int p0, int p1, int step, int buf, u32x4 a_regs[kAPasses]) {
+        _Float16 *A = a_dst + buf * kBufHalves;
+        const int k2 = (step + 2 < nk ? step + 2 : nk - 1) * kBK;
 #pragma unroll
-        for (int p = part * per; p < (part + 1) * per && p < kAPasses; ++p)
+        for (int p = p0; p < p1 && p < kAPasses; ++p) {
             *reinterpret_cast<u32x4 *>(A + p * 32 * kLd) = a_regs[p];
+            a_regs[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k2);
+        }
+    };
+    auto stage_w = [&](int pair, int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q) {
+        _Float16 *brow = b_dst + buf * kBufHalves;
+        const int half = step & 1, g = step >> 1;
         const uint32_t s2 = meta_scale(Q, g), z = meta_zero(Q, g);
         if constexpr (BITS == 4) {
-            *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * part) = dequant_frag(G.slot[half], part, z, s2, dc);
+#pragma unroll
+            for (int part = 2 * pair; part < 2 * pair + 2; ++part)
+                *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * part) = dequant_frag(G.slot[half], part, z, s2, dc);
         } else {
-            if (part == 0) {
+            if (pair == 0) {
                 u32x4 f[4];
                 dequant_all(G.slot[half], z, s2, dc, f);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
             }
         }
-        if (part == 3) {
-            // Outliers of this channel inside this thread's 32 columns replace their decoded zeros.
-            // Entries 4h .. 4h+3 are in this lane, the other four in the lane next to it.
-            const int cnt = meta_count(Q, g);
-            const uint32_t k_lo = (uint32_t)(step * kBK + 32 * b_h);
-            const uint32_t own_c[2] = {G.col.lo, G.col.hi}, own_v[2] = {G.val.lo, G.val.hi};
-            uint32_t oth_c[2], oth_v[2];
+    };
+    // Outliers of this channel inside this thread's 32 columns replace their decoded zeros (the
+    // same thread wrote those, so the order is kept).  Entries 4h .. 4h+3 are in this lane, the
+    // other four in the lane next to it.
+    auto stage_outliers = [&](int i0, int i1, int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q,
+                              int first) {
+        _Float16 *brow = b_dst + buf * kBufHalves;
+        const int g = step >> 1;
+        const int cnt = step < nk ? meta_count(Q, g) : 0;       // nothing to patch behind the last step
+        const uint32_t k_lo = (uint32_t)(step * kBK + 32 * b_h);
+        const uint32_t own_c[2] = {G.col_lo, G.col_hi}, own_v[2] = {G.val_lo, G.val_hi};
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                oth_c[i] = __builtin_amdgcn_mov_dpp(own_c[i], 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
-                oth_v[i] = __builtin_amdgcn_mov_dpp(own_v[i], 0xB1, 0xF, 0xF, true);
+        for (int e = i0; e < i1; ++e) {
+            const bool mine = (e >> 2) == 0;                    // entries 0..3: own registers; 4..7: the neighbour's
+            const int i = e & 3;
+            uint32_t c = own_c[i >> 1], v = own_v[i >> 1];
+            if (!mine) {
+                c = __builtin_amdgcn_mov_dpp(c, 0xB1, 0xF, 0xF, true);          // quad_perm [1,0,3,2]
+                v = __builtin_amdgcn_mov_dpp(v, 0xB1, 0xF, 0xF, true);
             }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t c0 = ((own_c[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
-                if (4 * b_h + i < cnt && c0 < 32u)
-                    brow[32 * b_h + c0] = __builtin_bit_cast(_Float16, (uint16_t)(own_v[i >> 1] >> (16 * (i & 1))));
-                const uint32_t c1 = ((oth_c[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
-                if (4 * (1 - b_h) + i < cnt && c1 < 32u)
-                    brow[32 * b_h + c1] = __builtin_bit_cast(_Float16, (uint16_t)(oth_v[i >> 1] >> (16 * (i & 1))));
-            }
-            for (int i = kAhead; i < cnt; ++i) {        // rare: more than kAhead outliers in one group
+            // this lane's registers hold entries 4h + i, the neighbour's 4(1-h) + i
+            const int idx = (mine ? 4 * b_h : 4 * (1 - b_h)) + i;
+            const uint32_t col = ((c >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
+            // No predication (it would fence the MFMAs off): an entry that is not ours to write goes
+            // to this thread's share of the row's padding instead.
+            const uint32_t dst = (idx < cnt && col < 32u) ? 32 * b_h + col : kBK + 4 * b_h;
+            brow[dst] = __builtin_bit_cast(_Float16, (uint16_t)(v >> (16 * (i & 1))));
+        }
+        if (i1 == 8)
+            for (int i = kAhead; i < cnt; ++i) {                // rare: more than kAhead outliers in one group
                 const uint32_t c = (uint32_t)col_idx[first + i] - k_lo;
                 if (c < 32u) brow[32 * b_h + c] = __builtin_bit_cast(_Float16, out_val[first + i]);
             }
-        }
     };
 
     float16v acc[MS][2];
@@ -257,33 +275,77 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     const _Float16 *a_frag = lds + (wm * (BM / 2) + fi) * kLd + 8 * fk;
     const _Float16 *b_frag = lds + (BM + wn * 64 + fi) * kLd + 8 * fk;
 
-    // One step: MFMA on buffer `buf` in four k-batches (the fragments of a batch are read while
-    // the previous batch multiplies), the staging of step + 1 (from a_regs, G, Q) into the other
-    // buffer spread between them.
-    auto step_fn = [&](int step, int buf, const u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
-                       int first) {
+    // Fragments of the k-batch being multiplied and of the one after it (16 columns each).
+    u32x4 fa[2][MS], fb[2][2];
+    auto read_frags = [&](int buf, int s, u32x4 a[MS], u32x4 b[2]) {
         const _Float16 *A = a_frag + buf * kBufHalves, *B = b_frag + buf * kBufHalves;
-        const bool stage = step + 1 < nk;
-        u32x4 fa[2][MS], fb[2][2];
-        auto read_frags = [&](int s, u32x4 a[MS], u32x4 b[2]) {
 #pragma unroll
-            for (int i = 0; i < MS; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kLd + 16 * s);
+        for (int i = 0; i < MS; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kLd + 16 * s);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
-        };
-        read_frags(0, fa[0], fb[0]);
+        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
+    };
+    auto mfma_rows = [&](int s, int i0, int i1) {
 #pragma unroll
-        for (int s = 0; s < kBK / 16; ++s) {
-            if (s + 1 < kBK / 16) read_frags(s + 1, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+        for (int i = i0; i < i1; ++i)
 #pragma unroll
-            for (int i = 0; i < MS; ++i)
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[s & 1][i]),
+                                                                   __builtin_bit_cast(half8, fb[s & 1][j]),
+                                                                   acc[i][j], 0, 0, 0);
+    };
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+    // Scheduling pattern for the region since the last fence: `count` times one MFMA followed by
+    // `others` of the staging instructions (vector ALU, scalar ALU, global loads, LDS writes).  An
+    // MFMA keeps the matrix pipe busy for 32 cycles, 8 issue slots; a wave that issued its MFMAs in
+    // a row and the staging after them would leave one of the two pipes idle all the time.
+    auto interleave = [](auto count, auto others) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[s & 1][i]),
-                                                                       __builtin_bit_cast(half8, fb[s & 1][j]),
-                                                                       acc[i][j], 0, 0, 0);
-            if (stage) store_part(s, step + 1, buf ^ 1, a_regs, G, Q, first);
+        for (int k = 0; k < decltype(count)::value; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002 | 0x004 | 0x020 | 0x200, decltype(others)::value, 0);
         }
+    };
+    using std::integral_constant;
+
+    // One step.  On entry the fragments of its first k-batch are in fa[0], fb[0].  Each k-batch
+    // first requests the fragments of the batch after it, then multiplies with a piece of the
+    // staging of step + 1 (into the other buffer, from a_regs, G, Q) scheduled among its MFMAs:
+    // the weights in batch 0, the outliers and the X rows in batches 1 and 2.  The block's barrier
+    // sits in the middle of the last batch: behind it the first fragments of step + 1 are requested
+    // while the rest of the batch still multiplies.
+    auto step_fn = [&](int step, int buf, u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
+                       int first) {
+        constexpr int half_passes = kAPasses >= 2 ? kAPasses / 2 : 1;
+        constexpr int h = MS >= 2 ? MS / 2 : 1;                 // rows of the last batch ahead of the barrier
+        constexpr int kMfma = 2 * MS;                           // MFMAs of one batch
+        read_frags(buf, 1, fa[1], fb[1]);
+        fence();
+        mfma_rows(0, 0, MS);
+        stage_w(0, step + 1, buf ^ 1, G, Q);
+        stage_w(1, step + 1, buf ^ 1, G, Q);
+        interleave(integral_constant<int, kMfma>{}, integral_constant<int, 72 / kMfma>{});
+        fence();
+        read_frags(buf, 2, fa[0], fb[0]);
+        fence();
+        mfma_rows(1, 0, MS);
+        stage_outliers(0, 4, step + 1, buf ^ 1, G, Q, first);
+        stage_x(0, half_passes, step + 1, buf ^ 1, a_regs);
+        interleave(integral_constant<int, kMfma>{}, integral_constant<int, (40 + 4 * half_passes) / kMfma>{});
+        fence();
+        read_frags(buf, 3, fa[1], fb[1]);
+        fence();
+        mfma_rows(2, 0, MS);
+        stage_outliers(4, 7, step + 1, buf ^ 1, G, Q, first);
+        stage_x(half_passes, kAPasses, step + 1, buf ^ 1, a_regs);
+        interleave(integral_constant<int, kMfma>{}, integral_constant<int, (40 + 4 * half_passes) / kMfma>{});
+        fence();
+        mfma_rows(3, 0, h);
+        stage_outliers(7, 8, step + 1, buf ^ 1, G, Q, first);  // the last entry and the rare overflow loop
+        fence();
+        __syncthreads();
+        read_frags(buf ^ 1, 0, fa[0], fb[0]);
+        fence();
+        mfma_rows(3, h, MS);
     };
 
     // Prologue: metadata of groups 0..7, codes and outliers of groups 0 and 1, the X rows of
@@ -299,22 +361,24 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     issue_group(0, first_c, Gc);
     int first_n = first_c + meta_count(Qc, 0);
     issue_group(1, first_n, Gn);
-#pragma unroll
-    for (int part = 0; part < 4; ++part) store_part(part, 0, 0, a0, Gc, Qc, first_c);
-    issue_a(2, a0);
+    stage_w(0, 0, 0, Gc, Qc);
+    stage_w(1, 0, 0, Gc, Qc);
+    stage_outliers(0, 8, 0, 0, Gc, Qc, first_c);
+    stage_x(0, kAPasses, 0, 0, a0);                     // refills a0 with the rows of step 2
     __syncthreads();
+    read_frags(0, 0, fa[0], fb[0]);
 
     // Main loop, one group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, a1
     // holds the X rows of step 2g + 1, a0 those of step 2g + 2 (in flight), Gc is group g, Gn is
     // group g + 1 (in flight), Qc covers group g, Qn the four groups after Qc's.
     for (int g = 0; g < gpr; ++g) {
         step_fn(2 * g, 0, a1, Gc, Qc, first_c);         // stages step 2g + 1 (second half of group g)
-        issue_a(2 * g + 3, a1);
-        __syncthreads();
         // Second half: stage step 2g + 2 = first half of group g + 1, then move on to it.
         const bool roll = (g & 3) == 3;                 // group g + 1 starts the next four
-        step_fn(2 * g + 1, 1, a0, Gn, roll ? Qn : Qc, first_n);
-        issue_a(2 * g + 4, a0);
+        MetaRegs Qs;                                    // selected by value: a reference would pin both in memory
+        Qs.sc = roll ? Qn.sc : Qc.sc;
+        Qs.zp = roll ? Qn.zp : Qc.zp; Qs.cnt = roll ? Qn.cnt : Qc.cnt;
+        step_fn(2 * g + 1, 1, a0, Gn, Qs, first_n);
         Gc = Gn;
         if (roll) {
             Qc = Qn;
@@ -323,7 +387,6 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         first_c = first_n;
         first_n = first_c + meta_count(Qc, g + 1);
         issue_group(g + 2, first_n, Gn);
-        __syncthreads();
     }
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
