@@ -3,23 +3,27 @@
 //   Y[m][n] = sum_k X[m][k] * What[n][k],  What = s*(q - z) (Sec. 3.2, Eq. 10) with the FP16
 //   outliers written over their (zero-decoding) codes.
 //
-// A block of 4 waves owns a BM x 128 tile of Y and walks K in steps of 64 (half a group).  Per
-// step the block stages X[BM][64] and the dequantised weights What[128][64] as FP16 in LDS
-// (double-buffered).  Thread (n = tid / 2, h = tid % 2) owns 32 columns of the step for channel n:
-// it turns 32 codes into FP16 (exact q - z, one multiply by the scale), stores them, and then
-// overwrites the positions of channel n's outliers that fall into those columns.  The waves
-// (2 x 2) multiply 32x32x16 FP16 MFMA tiles with FP32 accumulators and store FP16.
+// A block of 8 waves owns a BM x 128 tile of Y (BM = 256, or 128 for small M) and walks K in steps
+// of 64 (half a group).  Per step the block stages X[BM][64] and the dequantised weights
+// What[128][64] as FP16 in LDS (double-buffered): a thread turns its codes into FP16 (exact q - z,
+// one multiply by the scale), stores them, and then overwrites the positions of the channel's
+// outliers.  The waves (4 along m, 2 along n) multiply 32x32x16 FP16 MFMA tiles with FP32
+// accumulators and store FP16.
 //
-// Everything a step needs from memory is requested one step (X) or one group (codes, scale, zero
-// point, outliers) ahead, with addresses that do not depend on loaded data, so the only wave of a
-// SIMD never waits for memory inside the loop.  For the outliers this needs to know, per channel
-// and group, how many CSR entries fall into the group: a small kernel counts them into the
-// workspace first (one byte per channel and group); the running sum is the index of the group's
-// first entry, and its first eight entries are fetched ahead, four by each of the channel's two
-// threads in one unaligned 8-byte load per array (longer runs take a slow path).  Scales, zero
-// points and counts are fetched four groups at a time, again with one unaligned load each.
-// The staging work of the next step is cut into four parts issued between the four MFMA batches
-// of the current one.
+// Two waves share a SIMD because a wave can issue next to nothing while one of its own MFMAs runs
+// (measured: about a quarter of the MFMA's 32 cycles): the staging work of one wave hides behind
+// the MFMAs of the other.  LDS stores are the scarcest resource (about 64 bytes per clock and CU,
+// a quarter of the load rate), so no lane ever stores data that is not needed.
+//
+// Everything a step needs from memory is requested two steps (X) or one group (codes, scale, zero
+// point, outliers) ahead, with addresses that do not depend on loaded data, so no wave waits for
+// memory inside the loop.  For the outliers this needs to know, per channel and group, how many
+// CSR entries fall into the group: a small kernel counts them into the workspace first (one byte
+// per channel and group); the running sum is the index of the group's first entry, and its first
+// eight entries are fetched ahead by the channel's threads with unaligned loads (longer runs take a
+// slow path).  Scales, zero points and counts are fetched four groups at a time, again with one
+// unaligned load each.  The staging work of the next step is cut into pieces issued between the
+// MFMA batches of the current one.
 #include <type_traits>
 
 #include "gwq_dequant.h"
@@ -30,7 +34,7 @@ namespace {
 
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kBN = 128;
 constexpr int kBK = 64;
 constexpr int kLd = kBK + 8;            // LDS row stride in halves: 144 bytes, conflict-free b128 reads
@@ -76,13 +80,22 @@ template <> __device__ inline void load_slot<3>(SlotRegs<3> &r, const uint32_t *
 
 // Loads of 8 / 4 bytes at 2-byte / 1-byte alignment (gfx950 global memory takes unaligned addresses).
 struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
+struct __attribute__((packed, aligned(2))) U32a2 { uint32_t v; };
 struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
 
-// What thread (n, h) fetches for one group of channel n: its two slots (h and 2 + h) and four of
-// the group's first eight outlier entries (entries 4h .. 4h+3; the other thread of the channel
-// holds the rest), as packed 16-bit pairs.
-template <int BITS> struct GroupRegs {
-    SlotRegs<BITS> slot[2];
+// What a thread fetches for one group of its channel.
+//   4-bit: thread q of the channel's four owns columns 16q .. 16q+15 of every step: two words per
+//   half of the group, and entries 2q, 2q+1 of the group's first eight outliers.
+//   3-bit (words do not end on 16-column boundaries): thread (s, r) owns slot 2r + s of the group,
+//   i.e. columns 32s .. 32s+31 of the steps of parity r, and entries 4s .. 4s+3; it idles in the
+//   steps of the other parity.
+template <int BITS> struct GroupRegs;
+template <> struct GroupRegs<4> {
+    uint32_t w[2][2];
+    uint32_t col, val;
+};
+template <> struct GroupRegs<3> {
+    SlotRegs<3> slot;
     uint32_t col_lo, col_hi, val_lo, val_hi;
 };
 // Scales, zero points and outlier counts of four consecutive groups of channel n.  (Plain words:
@@ -93,10 +106,10 @@ struct MetaRegs {
 };
 
 // Fragment j (8 codes -> 8 FP16 values s*(q - z)) of a slot.
-__device__ inline u32x4 dequant_frag(const SlotRegs<4> &r, int j, uint32_t z, uint32_t s2, const DecodeConsts &d)
+__device__ inline u32x4 dequant_word(uint32_t w, uint32_t z, uint32_t s2, const DecodeConsts &d)
 {
     const ZeroConsts<4> c(z);
-    u32x4 f = decode_word4(r.w[j], c, d);
+    u32x4 f = decode_word4(w, c, d);
     f.x = pk_mul(f.x, s2); f.y = pk_mul(f.y, s2); f.z = pk_mul(f.z, s2); f.w = pk_mul(f.w, s2);
     return f;
 }
@@ -110,8 +123,11 @@ __device__ inline void dequant_all(const SlotRegs<3> &r, uint32_t z, uint32_t s2
     }
 }
 
-// MS = 32-row sub-tiles per wave along m; the block tile is BM = 64 * MS rows by 128 channels.
-template <int BITS, int MS>
+// MSW = 32-row sub-tiles per wave along m; the block tile is BM = 128 * MSW rows by 128 channels,
+// worked on by 8 waves (4 along m, 2 along n), two per SIMD: a wave cannot issue anything else for
+// most of the time one of its MFMAs runs, so the staging work of one wave overlaps the MFMAs of
+// the other wave on its SIMD, not its own.
+template <int BITS, int MSW>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
                                                         const uint16_t *__restrict__ scales,
                                                         const uint8_t *__restrict__ zeros,
@@ -122,9 +138,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                                                         const _Float16 *__restrict__ X, _Float16 *__restrict__ Y,
                                                         int N, int K, int M, int tiles_m, int tiles_n, int last_entry)
 {
-    constexpr int BM = 64 * MS;
+    constexpr int BM = 128 * MSW;
     constexpr int wpg = words_per_group(BITS);
-    constexpr int kAPasses = BM / 32;                   // 256 threads move 32 rows x 128 bytes per pass
+    constexpr int kAPasses = BM / 64;                   // 512 threads move 64 rows x 128 bytes per pass
     extern __shared__ _Float16 lds[];                   // [2][BM + 128][kLd]
     constexpr int kBufHalves = (BM + kBN) * kLd;        // one buffer: X rows, then weight rows
 
@@ -149,9 +165,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     const int gpr = K / kGroup;
     const int nk = K / kBK;                             // steps; two per group
 
-    // Staging roles.
-    const int a_row = tid >> 3, a_chunk = tid & 7;      // 8 threads cover one 128-byte row of a step
-    const int b_n_local = tid >> 1, b_h = tid & 1;
+    // Staging roles.  X: 8 threads cover one 128-byte row of a step.  Weights: the four threads of
+    // channel n are neighbours in a wave (see GroupRegs for what each owns).
+    const int a_row = tid >> 3, a_chunk = tid & 7;
+    const int b_n_local = tid >> 2, b_q = tid & 3, b_s = (tid >> 1) & 1, b_r = tid & 1;
     int b_n = n0 + b_n_local;
     const bool b_valid = b_n < N;
     b_n = b_valid ? b_n : N - 1;                        // clamped: loads stay in bounds, tile row unused
@@ -160,13 +177,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     const _Float16 *a_src[kAPasses];
 #pragma unroll
     for (int p = 0; p < kAPasses; ++p) {
-        int m = m0 + p * 32 + a_row;
+        int m = m0 + p * 64 + a_row;
         m = m < M ? m : M - 1;
         a_src[p] = X + (size_t)m * K + 8 * a_chunk;
     }
     const uint32_t row_group = (uint32_t)b_n * gpr;
     const uint32_t *q_row = qweight + (size_t)row_group * wpg;
-    _Float16 *const a_dst = lds + a_row * kLd + 8 * a_chunk;            // + buffer, + pass * 32 rows
+    _Float16 *const a_dst = lds + a_row * kLd + 8 * a_chunk;            // + buffer, + pass * 64 rows
     _Float16 *const b_dst = lds + (BM + b_n_local) * kLd;               // + buffer
 
     auto issue_a = [&](int step, u32x4 dst[kAPasses]) {
@@ -178,11 +195,19 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     auto issue_group = [&](int g, int first, GroupRegs<BITS> &G) {
         g = g < gpr ? g : gpr - 1;
         const uint32_t *grp = q_row + (uint32_t)g * wpg;
-        load_slot<BITS>(G.slot[0], grp, b_h);
-        load_slot<BITS>(G.slot[1], grp, 2 + b_h);
-        const int j = first + 4 * b_h < last_entry ? first + 4 * b_h : last_entry;   // arrays carry 16 spare bytes
-        const U64a2 c = *reinterpret_cast<const U64a2 *>(col_idx + j), v = *reinterpret_cast<const U64a2 *>(out_val + j);
-        G.col_lo = c.lo; G.col_hi = c.hi; G.val_lo = v.lo; G.val_hi = v.hi;
+        if constexpr (BITS == 4) {
+            const uint2 v0 = *reinterpret_cast<const uint2 *>(grp + 4 * (b_q >> 1) + 2 * (b_q & 1));
+            const uint2 v1 = *reinterpret_cast<const uint2 *>(grp + 8 + 4 * (b_q >> 1) + 2 * (b_q & 1));
+            G.w[0][0] = v0.x; G.w[0][1] = v0.y; G.w[1][0] = v1.x; G.w[1][1] = v1.y;
+            const int j = first + 2 * b_q < last_entry ? first + 2 * b_q : last_entry;   // arrays carry 16 spare bytes
+            G.col = reinterpret_cast<const U32a2 *>(col_idx + j)->v;
+            G.val = reinterpret_cast<const U32a2 *>(out_val + j)->v;
+        } else {
+            load_slot<3>(G.slot, grp, 2 * b_r + b_s);
+            const int j = first + 4 * b_s < last_entry ? first + 4 * b_s : last_entry;
+            const U64a2 c = *reinterpret_cast<const U64a2 *>(col_idx + j), v = *reinterpret_cast<const U64a2 *>(out_val + j);
+            G.col_lo = c.lo; G.col_hi = c.hi; G.val_lo = v.lo; G.val_hi = v.hi;
+        }
     };
     // Groups 4q .. 4q+3 (reads past the row or the array stay inside the padded buffers).
     auto issue_meta = [&](int q, MetaRegs &Q) {
@@ -199,88 +224,90 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     auto meta_zero = [](const MetaRegs &Q, int g) -> uint32_t { return (Q.zp >> (8 * (g & 3))) & 0xFFu; };
     auto meta_count = [&](const MetaRegs &Q, int g) -> int { return b_valid ? (int)((Q.cnt >> (8 * (g & 3))) & 0xFFu) : 0; };
 
-    // Staging of step `step` into buffer `buf`, cut into pieces that the step function spreads over
-    // its MFMA batches.  stage_x: X rows of pass p go to LDS, and the registers are refilled with
-    // the rows of two steps later.  stage_w: two of this thread's four 8-column weight fragments.
-    // stage_outliers: entries i0 .. i1-1 of the group's first eight, then (at i1 == 8) the rare rest.
+    // Staging of step `step` into buffer `buf`, in pieces that the step function spreads over its
+    // MFMA batches.  stage_x: X rows of passes p0 .. p1-1 go to LDS, and the registers are refilled
+    // with the rows of two steps later.  stage_w: half of this thread's weight fragments.
+    // stage_outliers: this thread's entries, then (one thread per channel) the rare rest.
     auto stage_x = [&](int p0, int p1, int step, int buf, u32x4 a_regs[kAPasses]) {
         _Float16 *A = a_dst + buf * kBufHalves;
         const int k2 = (step + 2 < nk ? step + 2 : nk - 1) * kBK;
 #pragma unroll
         for (int p = p0; p < p1 && p < kAPasses; ++p) {
-            *reinterpret_cast<u32x4 *>(A + p * 32 * kLd) = a_regs[p];
+            *reinterpret_cast<u32x4 *>(A + p * 64 * kLd) = a_regs[p];
             a_regs[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k2);
         }
     };
     auto stage_w = [&](int pair, int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q) {
         _Float16 *brow = b_dst + buf * kBufHalves;
-        const int half = step & 1, g = step >> 1;
+        const int g = step >> 1;
         const uint32_t s2 = meta_scale(Q, g), z = meta_zero(Q, g);
         if constexpr (BITS == 4) {
-#pragma unroll
-            for (int part = 2 * pair; part < 2 * pair + 2; ++part)
-                *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * part) = dequant_frag(G.slot[half], part, z, s2, dc);
+            *reinterpret_cast<u32x4 *>(brow + 16 * b_q + 8 * pair) = dequant_word(G.w[step & 1][pair], z, s2, dc);
         } else {
-            if (pair == 0) {
+            if (pair == 0 && b_r == (step & 1)) {
                 u32x4 f[4];
-                dequant_all(G.slot[half], z, s2, dc, f);
+                dequant_all(G.slot, z, s2, dc, f);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_s + 8 * j) = f[j];
             }
         }
     };
-    // Outliers of this channel inside this thread's 32 columns replace their decoded zeros (the
-    // same thread wrote those, so the order is kept).  Entries 4h .. 4h+3 are in this lane, the
-    // other four in the lane next to it.
-    auto stage_outliers = [&](int i0, int i1, int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q,
-                              int first) {
+    // Outliers of this channel inside the step's 64 columns replace their decoded zeros.  The
+    // writers of those zeros are lanes of the same wave and their stores were issued earlier, so
+    // the order is kept.  4-bit: an entry that is not ours to write goes to the row's padding
+    // (predication would fence the MFMAs off).
+    auto stage_outliers = [&](int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q, int first) {
         _Float16 *brow = b_dst + buf * kBufHalves;
         const int g = step >> 1;
         const int cnt = step < nk ? meta_count(Q, g) : 0;       // nothing to patch behind the last step
-        const uint32_t k_lo = (uint32_t)(step * kBK + 32 * b_h);
-        const uint32_t own_c[2] = {G.col_lo, G.col_hi}, own_v[2] = {G.val_lo, G.val_hi};
+        const uint32_t k_lo = (uint32_t)(step * kBK);
+        bool rest;                                              // this thread takes the entries past the eighth
+        if constexpr (BITS == 4) {
 #pragma unroll
-        for (int e = i0; e < i1; ++e) {
-            const bool mine = (e >> 2) == 0;                    // entries 0..3: own registers; 4..7: the neighbour's
-            const int i = e & 3;
-            uint32_t c = own_c[i >> 1], v = own_v[i >> 1];
-            if (!mine) {
-                c = __builtin_amdgcn_mov_dpp(c, 0xB1, 0xF, 0xF, true);          // quad_perm [1,0,3,2]
-                v = __builtin_amdgcn_mov_dpp(v, 0xB1, 0xF, 0xF, true);
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t col = ((G.col >> (16 * i)) & 0xFFFFu) - k_lo;
+                const uint32_t dst = (2 * b_q + i < cnt && col < (uint32_t)kBK) ? col : kBK + b_q;
+                brow[dst] = __builtin_bit_cast(_Float16, (uint16_t)(G.val >> (16 * i)));
             }
-            // this lane's registers hold entries 4h + i, the neighbour's 4(1-h) + i
-            const int idx = (mine ? 4 * b_h : 4 * (1 - b_h)) + i;
-            const uint32_t col = ((c >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
-            // No predication (it would fence the MFMAs off): an entry that is not ours to write goes
-            // to this thread's share of the row's padding instead.
-            const uint32_t dst = (idx < cnt && col < 32u) ? 32 * b_h + col : kBK + 4 * b_h;
-            brow[dst] = __builtin_bit_cast(_Float16, (uint16_t)(v >> (16 * (i & 1))));
+            rest = b_q == 0;
+        } else {
+            const bool mine = b_r == (step & 1);
+            if (mine) {
+                const uint32_t cs[2] = {G.col_lo, G.col_hi}, vs[2] = {G.val_lo, G.val_hi};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t col = ((cs[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
+                    if (4 * b_s + i < cnt && col < (uint32_t)kBK)
+                        brow[col] = __builtin_bit_cast(_Float16, (uint16_t)(vs[i >> 1] >> (16 * (i & 1))));
+                }
+            }
+            rest = mine && b_s == 0;
         }
-        if (i1 == 8)
-            for (int i = kAhead; i < cnt; ++i) {                // rare: more than kAhead outliers in one group
+        if (rest)
+            for (int i = kAhead; i < cnt; ++i) {        // rare: more than kAhead outliers in one group
                 const uint32_t c = (uint32_t)col_idx[first + i] - k_lo;
-                if (c < 32u) brow[32 * b_h + c] = __builtin_bit_cast(_Float16, out_val[first + i]);
+                if (c < (uint32_t)kBK) brow[c] = __builtin_bit_cast(_Float16, out_val[first + i]);
             }
     };
 
-    float16v acc[MS][2];
+    float16v acc[MSW][2];
 #pragma unroll
-    for (int i = 0; i < MS; ++i)
+    for (int i = 0; i < MSW; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int fi = lane & 31, fk = lane >> 5;           // fragment row and k-block of this lane
-    const _Float16 *a_frag = lds + (wm * (BM / 2) + fi) * kLd + 8 * fk;
+    const _Float16 *a_frag = lds + (wm * (BM / 4) + fi) * kLd + 8 * fk;
     const _Float16 *b_frag = lds + (BM + wn * 64 + fi) * kLd + 8 * fk;
 
     // Fragments of the k-batch being multiplied and of the one after it (16 columns each).
-    u32x4 fa[2][MS], fb[2][2];
-    auto read_frags = [&](int buf, int s, u32x4 a[MS], u32x4 b[2]) {
+    u32x4 fa[2][MSW], fb[2][2];
+    auto read_frags = [&](int buf, int s, u32x4 a[MSW], u32x4 b[2]) {
         const _Float16 *A = a_frag + buf * kBufHalves, *B = b_frag + buf * kBufHalves;
 #pragma unroll
-        for (int i = 0; i < MS; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kLd + 16 * s);
+        for (int i = 0; i < MSW; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kLd + 16 * s);
 #pragma unroll
         for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
     };
@@ -295,9 +322,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
     // Scheduling pattern for the region since the last fence: `count` times one MFMA followed by
-    // `others` of the staging instructions (vector ALU, scalar ALU, global loads, LDS writes).  An
-    // MFMA keeps the matrix pipe busy for 32 cycles, 8 issue slots; a wave that issued its MFMAs in
-    // a row and the staging after them would leave one of the two pipes idle all the time.
+    // `others` of the staging instructions (vector ALU, scalar ALU, global loads, LDS writes).
     auto interleave = [](auto count, auto others) {
 #pragma unroll
         for (int k = 0; k < decltype(count)::value; ++k) {
@@ -310,42 +335,43 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     // One step.  On entry the fragments of its first k-batch are in fa[0], fb[0].  Each k-batch
     // first requests the fragments of the batch after it, then multiplies with a piece of the
     // staging of step + 1 (into the other buffer, from a_regs, G, Q) scheduled among its MFMAs:
-    // the weights in batch 0, the outliers and the X rows in batches 1 and 2.  The block's barrier
+    // the weights in batches 0 and 1, the outliers and the X rows in batch 2.  The block's barrier
     // sits in the middle of the last batch: behind it the first fragments of step + 1 are requested
     // while the rest of the batch still multiplies.
     auto step_fn = [&](int step, int buf, u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
                        int first) {
-        constexpr int half_passes = kAPasses >= 2 ? kAPasses / 2 : 1;
-        constexpr int h = MS >= 2 ? MS / 2 : 1;                 // rows of the last batch ahead of the barrier
-        constexpr int kMfma = 2 * MS;                           // MFMAs of one batch
+        constexpr int kMfma = 2 * MSW;                          // MFMAs of one batch
+        constexpr int h = MSW >= 2 ? MSW / 2 : 1;               // rows of the last batch ahead of the barrier
+        // LDS stores are the slow kind of LDS traffic (a 16-byte store per lane keeps the unit busy
+        // four times as long as a load), so they are spread evenly: fragment loads queued behind a
+        // burst of stores would come back late.
         read_frags(buf, 1, fa[1], fb[1]);
         fence();
-        mfma_rows(0, 0, MS);
+        mfma_rows(0, 0, MSW);
         stage_w(0, step + 1, buf ^ 1, G, Q);
-        stage_w(1, step + 1, buf ^ 1, G, Q);
-        interleave(integral_constant<int, kMfma>{}, integral_constant<int, 72 / kMfma>{});
+        stage_x(0, 1, step + 1, buf ^ 1, a_regs);
+        interleave(integral_constant<int, kMfma>{}, integral_constant<int, 32 / kMfma>{});
         fence();
         read_frags(buf, 2, fa[0], fb[0]);
         fence();
-        mfma_rows(1, 0, MS);
-        stage_outliers(0, 4, step + 1, buf ^ 1, G, Q, first);
-        stage_x(0, half_passes, step + 1, buf ^ 1, a_regs);
-        interleave(integral_constant<int, kMfma>{}, integral_constant<int, (40 + 4 * half_passes) / kMfma>{});
+        mfma_rows(1, 0, MSW);
+        stage_w(1, step + 1, buf ^ 1, G, Q);
+        stage_x(1, 2, step + 1, buf ^ 1, a_regs);
+        interleave(integral_constant<int, kMfma>{}, integral_constant<int, 32 / kMfma>{});
         fence();
         read_frags(buf, 3, fa[1], fb[1]);
         fence();
-        mfma_rows(2, 0, MS);
-        stage_outliers(4, 7, step + 1, buf ^ 1, G, Q, first);
-        stage_x(half_passes, kAPasses, step + 1, buf ^ 1, a_regs);
-        interleave(integral_constant<int, kMfma>{}, integral_constant<int, (40 + 4 * half_passes) / kMfma>{});
+        mfma_rows(2, 0, MSW);
+        stage_outliers(step + 1, buf ^ 1, G, Q, first);
+        stage_x(2, 3, step + 1, buf ^ 1, a_regs);
         fence();
         mfma_rows(3, 0, h);
-        stage_outliers(7, 8, step + 1, buf ^ 1, G, Q, first);  // the last entry and the rare overflow loop
+        stage_x(3, kAPasses, step + 1, buf ^ 1, a_regs);
         fence();
         __syncthreads();
         read_frags(buf ^ 1, 0, fa[0], fb[0]);
         fence();
-        mfma_rows(3, h, MS);
+        mfma_rows(3, h, MSW);
     };
 
     // Prologue: metadata of groups 0..7, codes and outliers of groups 0 and 1, the X rows of
@@ -363,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     issue_group(1, first_n, Gn);
     stage_w(0, 0, 0, Gc, Qc);
     stage_w(1, 0, 0, Gc, Qc);
-    stage_outliers(0, 8, 0, 0, Gc, Qc, first_c);
+    stage_outliers(0, 0, Gc, Qc, first_c);
     stage_x(0, kAPasses, 0, 0, a0);                     // refills a0 with the rows of step 2
     __syncthreads();
     read_frags(0, 0, fa[0], fb[0]);
@@ -391,32 +417,32 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
 #pragma unroll
-    for (int i = 0; i < MS; ++i)
+    for (int i = 0; i < MSW; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int n = n0 + wn * 64 + j * 32 + fi;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+                const int m = m0 + wm * (BM / 4) + i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
                 if (m < M && n < N) Y[(size_t)m * N + n] = (_Float16)acc[i][j][v];
             }
         }
 }
 
-template <int BITS, int MS>
+template <int BITS, int MSW>
 hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, uint8_t *grp_cnt, hipStream_t st)
 {
-    constexpr int BM = 64 * MS;
+    constexpr int BM = 128 * MSW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
     const size_t lds = (size_t)2 * (BM + kBN) * kLd * sizeof(_Float16);
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_kernel<BITS, MS><<<tiles_m * tiles_n, kThreads, lds, st>>>(
+    gemm_kernel<BITS, MSW><<<tiles_m * tiles_n, kThreads, lds, st>>>(
         P.qweight, P.scales, P.zeros, P.row_ptr, P.col_idx, P.out_val, grp_cnt, static_cast<const _Float16 *>(X),
         static_cast<_Float16 *>(Y), P.N, P.K, M, tiles_m, tiles_n, P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
     return hipGetLastError();
@@ -433,12 +459,10 @@ hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void 
     group_count_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.N, P.K / kGroup, cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int ms = ms_override ? ms_override : M <= 64 ? 1 : M <= 128 ? 2 : 4;
-    if (P.bits == 4)
-        return ms == 1 ? launch_ms<4, 1>(P, X, M, Y, cnt, st) : ms == 2 ? launch_ms<4, 2>(P, X, M, Y, cnt, st)
-                                                                         : launch_ms<4, 4>(P, X, M, Y, cnt, st);
-    return ms == 1 ? launch_ms<3, 1>(P, X, M, Y, cnt, st) : ms == 2 ? launch_ms<3, 2>(P, X, M, Y, cnt, st)
-                                                                     : launch_ms<3, 4>(P, X, M, Y, cnt, st);
+    // Rows per tile: 256 unless M is small (the override is in rows: 64 and 128 both mean 128).
+    const int msw = ms_override ? (ms_override >= 4 ? 2 : 1) : M <= 128 ? 1 : 2;
+    if (P.bits == 4) return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, cnt, st) : launch_ms<4, 2>(P, X, M, Y, cnt, st);
+    return msw == 1 ? launch_ms<3, 1>(P, X, M, Y, cnt, st) : launch_ms<3, 2>(P, X, M, Y, cnt, st);
 }
 
 }  // namespace gwq
