@@ -354,6 +354,210 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     }
 }
 
+// ---- any M <= 16, X staged through LDS in chunks of K: the wide kernel ---------------------------
+//
+// For the batches the lean kernel does not take.  The block walks K in phases of `chunk` columns
+// (waves * U groups): per phase every wave stages the X columns of its own U groups (all M rows,
+// zeros beyond K) and requests their codes, multiplies, and then adds the outliers of its channels
+// that fall into the chunk, with X gathered from LDS.  A lane keeps the four result rows
+// 4b .. 4b+3 of its MFMA tiles; the outliers of a channel are split over the waves, every lane
+// walking its share of the (column-sorted) row once with a cursor.  Nothing in the multiply is
+// predicated: groups at or beyond gpr meet zeros in X, their codes are whatever follows in memory
+// (the address is kept inside qweight), their scales and zero points whatever follows in LDS,
+// which a zeroed guard behind the zero points keeps finite.  At most 8 waves, so that the staging
+// registers of X (MR * U / 4 vectors per lane) fit.
+//
+// MR = 8 or 16: rows of X staged (M <= MR; rows M .. MR-1 are loaded as copies of the last row and
+// dropped).  Dynamic LDS: X [M][chunk] halves | scales [16][gpr] halves | zero points [16][gpr]
+// bytes | 96 guard bytes | CSR columns, blockDim * 8 entries | CSR values, same | partial sums
+// [waves][4][64] floats.
+constexpr int kWideGuard = 96;
+
+template <int BITS, int U, int MR>
+__global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batch)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const DecodeProblem &pr = batch.p[blockIdx.y];
+    const int N = pr.N, K = pr.K;
+    const uint32_t *__restrict__ qweight = pr.qweight;
+    const uint16_t *__restrict__ scales = pr.scales;
+    const uint8_t *__restrict__ zeros = pr.zeros;
+    const int32_t *__restrict__ row_ptr = pr.row_ptr;
+    const uint16_t *__restrict__ col_idx = pr.col_idx;
+    const uint16_t *__restrict__ out_val = pr.out_val;
+    const _Float16 *__restrict__ X = pr.X;
+    _Float16 *__restrict__ Y = pr.Y;
+    const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+    // The whole descriptor is requested in one go and only then looked at.
+    asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
+                 "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec));
+    if ((int)blockIdx.x * 16 >= N) return;              // the grid is as wide as the largest layer needs
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int M = batch.M, nwaves = batch.nwaves, nthreads = nwaves * 64;
+    const int r = lane & 15, b = lane >> 4;
+    const int gpr = K / kGroup;
+    const int chunk_groups = nwaves * U;                // groups per phase
+    const int chunk = chunk_groups * kGroup;            // columns per phase: row length of the LDS copy of X
+    const int phases = (gpr + chunk_groups - 1) / chunk_groups;
+
+    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
+    const uint32_t sc_off = (uint32_t)M * chunk * 2;
+    const uint32_t zp_off = sc_off + 32 * gpr;
+    const uint32_t guard_off = zp_off + 16 * gpr;
+    const uint32_t col_off = guard_off + kWideGuard;
+    const uint32_t val_off = col_off + 16 * nthreads;
+    const uint32_t red_off = val_off + 16 * nthreads;
+    float *red = reinterpret_cast<float *>(lds_raw + red_off);
+
+    const DecodeConsts dc(BITS);
+    constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
+    const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
+    constexpr int kQ = U / 4;                           // 64-vector rounds covering U groups
+    const int x_row = r < M ? r : 0;
+    const _Float16 *x_lane = xs + (uint32_t)x_row * chunk + wave * (U * kGroup) + 32 * b;
+    const _Float16 *x_out[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(4 * b + e < M ? 4 * b + e : 0) * chunk;   // rows m >= M are not stored
+    const uint16_t *col_lds = reinterpret_cast<const uint16_t *>(lds_raw + col_off);
+    const uint16_t *val_lds = reinterpret_cast<const uint16_t *>(lds_raw + val_off);
+
+    // A block takes the 16-channel tiles blockIdx.x, blockIdx.x + gridDim.x, ...: when all of K is
+    // one phase, the copy of X staged for the first tile serves the others too.
+    for (int block = blockIdx.x; block * 16 < N; block += gridDim.x) {
+    const bool stage_x = phases > 1 || block == (int)blockIdx.x;
+    const int row0 = block * 16;
+    const int n = row0 + r;
+    const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
+
+    // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
+    const int last_row = row0 + 16 < N ? row0 + 16 : N;
+    const int e_begin = row_ptr[row0], e_end = row_ptr[last_row];
+    const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
+
+    // The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for 16
+    // consecutive channels and adjacent in LDS: vector t of that range, t < 2 gpr a scales vector.
+    for (int t = tid; t < 3 * gpr; t += nthreads) {
+        const bool is_sc = t < 2 * gpr;
+        const int v_sc = block * 2 * gpr + t < sc_last_vec ? block * 2 * gpr + t : sc_last_vec;
+        const int v_zp = block * gpr + (t - 2 * gpr) < zp_last_vec ? block * gpr + (t - 2 * gpr) : zp_last_vec;
+        const u32x4 *src = is_sc ? reinterpret_cast<const u32x4 *>(scales) : reinterpret_cast<const u32x4 *>(zeros);
+        *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = src[is_sc ? v_sc : v_zp];
+    }
+    if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
+
+    // The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin: thread t
+    // brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
+    const int e0 = e_begin & ~7;
+    {
+        const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
+        int v = e0 / 8 + tid;
+        v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
+        v = v < csr_last_vec ? v : csr_last_vec;
+        const u32x4 seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
+        const u32x4 seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
+        reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
+        reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+    }
+    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+    const bool o_live = n < N && 4 * b < M;
+    int j = rp0 + wave;                                 // cursor into this lane's share of the channel's outliers
+    const int j_end = o_live ? rp1 : 0;
+    float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
+
+    for (int ph = 0; ph < phases; ++ph) {
+        const int g_begin = (ph * nwaves + wave) * U;
+        // X columns of this wave's groups, all rows at once (16-byte coalesced loads; vectors
+        // beyond K are loaded from column 0 and stored as zeros), then the codes.
+        u32x4 xstage[MR * kQ];
+        if (stage_x)
+#pragma unroll
+        for (int e = 0; e < MR; ++e)
+#pragma unroll
+            for (int i = 0; i < kQ; ++i) {
+                const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+                const int row = e < M ? e : M - 1;
+                xstage[e * kQ + i] = reinterpret_cast<const u32x4 *>(X)[row * (K / 8) + (kv < K / 8 ? kv : 0)];
+            }
+        const uint32_t code_off = ((uint32_t)n_c * gpr + g_begin) * group_bytes;
+        Slot<BITS> slot[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
+        __builtin_amdgcn_sched_barrier(0);
+        if (stage_x)
+#pragma unroll
+        for (int e = 0; e < MR; ++e)
+            if (e < M) {
+#pragma unroll
+                for (int i = 0; i < kQ; ++i) {
+                    const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+                    reinterpret_cast<u32x4 *>(xs)[e * (chunk / 8) + wave * (U * kGroup / 8) + lane + 64 * i] =
+                        kv < K / 8 ? xstage[e * kQ + i] : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+        __syncthreads();                                // X of the phase (and, first time, everything staged above)
+
+        {
+            const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
+            const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                u32x4 xa[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
+                const _Float16 s = __builtin_bit_cast(_Float16, sc_lane[u]);
+                const uint32_t z = zp_lane[u];
+                u32x4 wb[4];
+                slot[u].decode(z, b, dc, wb);
+                float4v part = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[jj]),
+                                                                  __builtin_bit_cast(half8, wb[jj]), part, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
+            }
+        }
+
+        // Outliers of the chunk's columns [c0, c1): the lane's entries are sorted by column, so it
+        // takes them while they are below c1.  Entries past the staged window come from memory
+        // (two loops: one address space each).
+        const int c0 = ph * chunk, c1 = c0 + chunk;
+        const int j_staged = j_end < staged_end ? j_end : staged_end;
+        while (j < j_staged) {
+            const int col = col_lds[j - e0];
+            if (col >= c1) break;
+            const float v = (float)__builtin_bit_cast(_Float16, val_lds[j - e0]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)x_out[e][col - c0], acc[e]);
+            j += nwaves;
+        }
+        while (j >= staged_end && j < j_end) {          // very long rows only
+            const int col = col_idx[j];
+            if (col >= c1) break;
+            const float v = (float)__builtin_bit_cast(_Float16, out_val[j]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)x_out[e][col - c0], acc[e]);
+            j += nwaves;
+        }
+        if (ph + 1 < phases) __syncthreads();           // everybody is done with this X chunk
+    }
+
+    // Fixed-order reduction over the waves, then FP16 store.
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[(wave * 4 + e) * 64 + lane] = acc[e];
+    __syncthreads();
+    for (int idx = tid; idx < 256; idx += nthreads) {
+        float sum = 0.f;
+        for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
+        const int e = idx >> 6, l = idx & 63;
+        const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
+        if (nn < N && m < M) Y[(size_t)m * N + nn] = (_Float16)sum;
+    }
+    }   // tiles
+}
+
 // ---- any M <= 16, X read from global memory: the general kernel --------------------------------
 //
 // BITS: 3 or 4.  U: groups per chunk (4 or 8).  PIPE: a wave owns more than U groups and
@@ -565,7 +769,8 @@ __global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
     }
 }
 
-constexpr size_t kXLdsBudget = 64 * 1024;               // X[M][k_pad] is staged in LDS up to this size
+constexpr size_t kMaxLds = 160 * 1024;                  // LDS a block may use on gfx950
+constexpr size_t kXLdsBudget = 128 * 1024;              // X[M][k_pad] is staged in LDS up to this size
 
 template <auto Kernel>
 hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nwaves, size_t lds, hipStream_t st)
@@ -573,7 +778,7 @@ hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nw
     static bool attr_set = false;                       // per kernel; the HIP call is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -645,11 +850,44 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         while (u < 16 && (max_gpr + u - 1) / u > 16) u *= 2;
         const int nwaves = (max_gpr + u - 1) / u;
         const size_t x_bytes = (size_t)M * nwaves * u * kGroup * 2;
-        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget) {
+        const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256;
+        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds) {
             batch.nwaves = nwaves;
-            const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256;
             return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, st)
                              : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, st);
+        }
+    }
+
+    // The wide kernel.  Among the shapes (U, waves <= 8) whose LDS footprint fits, the one with the
+    // fewest phases, then the most waves, then the shorter waves.
+    if (waves_override == 0) {
+        int best_u = 0, best_w = 0, best_ph = 1 << 30;
+        size_t best_lds = 0;
+        for (int u = 4; u <= 8; u *= 2)
+            for (int w = 1; w <= 8; ++w) {
+                const size_t lds = (size_t)M * w * u * kGroup * 2 + (size_t)48 * max_gpr + kWideGuard +
+                                   2 * 16 * (size_t)w * 64 + (size_t)w * 1024;
+                if (lds > kMaxLds) continue;
+                const int ph = (max_gpr + w * u - 1) / (w * u);
+                if (ph < best_ph || (ph == best_ph && w > best_w)) { best_ph = ph; best_u = u; best_w = w; best_lds = lds; }
+            }
+        if (best_u) {
+            batch.nwaves = best_w;
+            const int mr = M <= 8 ? 8 : 16;
+            // One resident block per CU (X fills most of the LDS): with a single phase, fewer blocks
+            // that loop over tiles stage X once each.
+            if (best_ph == 1) {
+                static int cus = 0;
+                if (!cus && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess) cus = 256;
+                const int cap = cus / count > 0 ? cus / count : 1;
+                if (blocks > cap) blocks = cap;
+            }
+#define GWQ_WIDE(B, UU, RR) \
+    if (bits == B && best_u == UU && mr == RR) \
+        return launch_kernel<&decode_wide_kernel<B, UU, RR>>(batch, count, blocks, best_w, best_lds, st)
+            GWQ_WIDE(4, 4, 8); GWQ_WIDE(4, 4, 16); GWQ_WIDE(4, 8, 8); GWQ_WIDE(4, 8, 16);
+            GWQ_WIDE(3, 4, 8); GWQ_WIDE(3, 4, 16); GWQ_WIDE(3, 8, 8); GWQ_WIDE(3, 8, 16);
+#undef GWQ_WIDE
         }
     }
 
