@@ -13,16 +13,19 @@
 // partial sums meet in LDS in a fixed order, and one thread per output rounds to FP16 and stores.
 // No atomics, no second pass: results are run-to-run identical.
 //
-// What bounds it.  A matrix is only a few microseconds of HBM time, and at that scale two things
-// matter more than arithmetic:
-//   * every byte must be requested at once: all loads are unconditional (clamped indices), issued
+// What bounds it.  A matrix is only a few microseconds of HBM time, and at that scale these matter
+// more than arithmetic:
+//   * every byte must be requested early: loads are unconditional (clamped addresses), issued
 //     before anything consumes them, and nothing is converted or combined right behind a load
 //     (loads retire in order, so waiting for a young one waits for all older ones);
 //   * the address unit of a CU handles a scattered or sub-dword load lane by lane (about 64 cycles
 //     per instruction against 16 for a coalesced 16-byte load), so everything except the code
 //     stream is fetched with block-wide coalesced 16-byte loads into LDS: the block's scales and
-//     zero points (contiguous for 16 consecutive channels), X (when it fits) and the block's
-//     contiguous CSR segment, whose bounds come in through the scalar cache.
+//     zero points (contiguous for 16 consecutive channels), X, and the block's contiguous CSR
+//     segment, whose bounds come in through the scalar cache;
+//   * the instructions a wave issues: wave-uniform values are kept in scalar registers, offsets
+//     are compile-time constants, and nothing in the multiply is predicated.
+// Two kernels: the lean one for M <= 4 with all of X in LDS, the wide one for everything else.
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -77,22 +80,8 @@ template <> struct Slot<3> {
     }
 };
 
-// Codes of one chunk of U groups of one channel.
-template <int BITS, int U> struct Chunk {
-    Slot<BITS> slot[U];
-    // row_group = index of (channel, group 0); groups past g_last repeat g_last (always valid).
-    __device__ inline void load(const uint32_t *qweight, uint32_t row_group, int g0, int g_last, int b)
-    {
-        constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int g = g0 + u < g_last ? g0 + u : g_last;
-            slot[u].load(qweight, (row_group + g) * group_bytes, b);
-        }
-    }
-};
-
 constexpr int kPre = 4;        // outlier entries a lane handles without a loop
+constexpr int kXPad = 8;       // halves between the rows of X in LDS: the 16 rows of an MFMA operand hit different banks
 
 // One layer of a launch, and the launch: up to kMaxBatch layers, layer i = blockIdx.y.  Passed by
 // value (kernel argument segment) and read through the scalar cache: the descriptor's offset follows
@@ -106,7 +95,7 @@ struct DecodeProblem {
     const uint16_t *out_val;
     const _Float16 *X;
     _Float16 *Y;
-    int N, K, groups_per_wave, sc_last_vec, zp_last_vec, csr_last_vec;
+    int N, K, sc_last_vec, zp_last_vec, csr_last_vec, reserved;
 };
 struct DecodeBatch {
     int M, nwaves;
@@ -160,7 +149,7 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     const int my_waves = (gpr + U - 1) / U;             // waves of this layer that own groups
     const bool active = wave < my_waves;
     const int g_begin = active ? wave * U : 0;
-    const int k_pad = my_waves * U * kGroup;            // row length of the LDS copy of X
+    const int k_pad = my_waves * U * kGroup + kXPad;    // row stride of the LDS copy of X
     const int row0 = block * 16;
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
@@ -399,11 +388,12 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int r = lane & 15, b = lane >> 4;
     const int gpr = K / kGroup;
     const int chunk_groups = nwaves * U;                // groups per phase
-    const int chunk = chunk_groups * kGroup;            // columns per phase: row length of the LDS copy of X
+    const int chunk = chunk_groups * kGroup;            // columns per phase
+    const int x_stride = chunk + kXPad;                 // row stride of the LDS copy of X
     const int phases = (gpr + chunk_groups - 1) / chunk_groups;
 
     _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
-    const uint32_t sc_off = (uint32_t)M * chunk * 2;
+    const uint32_t sc_off = (uint32_t)M * x_stride * 2;
     const uint32_t zp_off = sc_off + 32 * gpr;
     const uint32_t guard_off = zp_off + 16 * gpr;
     const uint32_t col_off = guard_off + kWideGuard;
@@ -416,15 +406,26 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
     constexpr int kQ = U / 4;                           // 64-vector rounds covering U groups
     const int x_row = r < M ? r : 0;
-    const _Float16 *x_lane = xs + (uint32_t)x_row * chunk + wave * (U * kGroup) + 32 * b;
+    const _Float16 *x_lane = xs + (uint32_t)x_row * x_stride + wave * (U * kGroup) + 32 * b;
     const _Float16 *x_out[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(4 * b + e < M ? 4 * b + e : 0) * chunk;   // rows m >= M are not stored
+    for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(4 * b + e < M ? 4 * b + e : 0) * x_stride;   // rows m >= M are not stored
     const uint16_t *col_lds = reinterpret_cast<const uint16_t *>(lds_raw + col_off);
     const uint16_t *val_lds = reinterpret_cast<const uint16_t *>(lds_raw + val_off);
 
     // A block takes the 16-channel tiles blockIdx.x, blockIdx.x + gridDim.x, ...: when all of K is
-    // one phase, the copy of X staged for the first tile serves the others too.
+    // one phase, the copy of X staged for the first tile serves the others too.  The codes of a
+    // phase are requested before the outliers of the phase (or tile) before it are added: by then
+    // the registers that take them are free.
+    Slot<BITS> slot[U];
+    auto load_codes = [&](int tile, int ph) {
+        int nn = tile * 16 + r;
+        nn = nn < N ? nn : N - 1;
+        const uint32_t code_off = ((uint32_t)nn * gpr + (ph * nwaves + wave) * U) * group_bytes;
+#pragma unroll
+        for (int u = 0; u < U; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
+    };
+    load_codes(blockIdx.x, 0);
     for (int block = blockIdx.x; block * 16 < N; block += gridDim.x) {
     const bool stage_x = phases > 1 || block == (int)blockIdx.x;
     const int row0 = block * 16;
@@ -438,29 +439,28 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 
     // The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for 16
     // consecutive channels and adjacent in LDS: vector t of that range, t < 2 gpr a scales vector.
-    for (int t = tid; t < 3 * gpr; t += nthreads) {
+    auto meta_vec = [&](int t) -> u32x4 {
         const bool is_sc = t < 2 * gpr;
         const int v_sc = block * 2 * gpr + t < sc_last_vec ? block * 2 * gpr + t : sc_last_vec;
         const int v_zp = block * gpr + (t - 2 * gpr) < zp_last_vec ? block * gpr + (t - 2 * gpr) : zp_last_vec;
         const u32x4 *src = is_sc ? reinterpret_cast<const u32x4 *>(scales) : reinterpret_cast<const u32x4 *>(zeros);
-        *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = src[is_sc ? v_sc : v_zp];
-    }
-    if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
-
+        return src[is_sc ? v_sc : (t < 3 * gpr ? v_zp : 0)];
+    };
+    const u32x4 meta0 = meta_vec(tid);
     // The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin: thread t
     // brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
     const int e0 = e_begin & ~7;
+    u32x4 seg_col, seg_val;
     {
         const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
         int v = e0 / 8 + tid;
         v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
         v = v < csr_last_vec ? v : csr_last_vec;
-        const u32x4 seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
-        const u32x4 seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
-        reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
-        reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+        seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
+        seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
     }
     const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+
     const bool o_live = n < N && 4 * b < M;
     int j = rp0 + wave;                                 // cursor into this lane's share of the channel's outliers
     const int j_end = o_live ? rp1 : 0;
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     for (int ph = 0; ph < phases; ++ph) {
         const int g_begin = (ph * nwaves + wave) * U;
         // X columns of this wave's groups, all rows at once (16-byte coalesced loads; vectors
-        // beyond K are loaded from column 0 and stored as zeros), then the codes.
+        // beyond K are loaded from column 0 and stored as zeros).
         u32x4 xstage[MR * kQ];
         if (stage_x)
 #pragma unroll
@@ -480,11 +480,15 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 const int row = e < M ? e : M - 1;
                 xstage[e * kQ + i] = reinterpret_cast<const u32x4 *>(X)[row * (K / 8) + (kv < K / 8 ? kv : 0)];
             }
-        const uint32_t code_off = ((uint32_t)n_c * gpr + g_begin) * group_bytes;
-        Slot<BITS> slot[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
         __builtin_amdgcn_sched_barrier(0);
+        if (ph == 0) {                                  // what was requested above for the whole tile
+            if (tid < 3 * gpr) *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * tid) = meta0;
+            for (int t = tid + nthreads; t < 3 * gpr; t += nthreads)
+                *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = meta_vec(t);
+            if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
+            reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
+            reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+        }
         if (stage_x)
 #pragma unroll
         for (int e = 0; e < MR; ++e)
@@ -492,11 +496,11 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 #pragma unroll
                 for (int i = 0; i < kQ; ++i) {
                     const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
-                    reinterpret_cast<u32x4 *>(xs)[e * (chunk / 8) + wave * (U * kGroup / 8) + lane + 64 * i] =
+                    reinterpret_cast<u32x4 *>(xs)[e * (x_stride / 8) + wave * (U * kGroup / 8) + lane + 64 * i] =
                         kv < K / 8 ? xstage[e * kQ + i] : u32x4{0u, 0u, 0u, 0u};
                 }
             }
-        __syncthreads();                                // X of the phase (and, first time, everything staged above)
+        __syncthreads();                                // X of the phase and, first time, the tile's metadata
 
         {
             const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
@@ -519,6 +523,10 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (ph + 1 < phases) load_codes(block, ph + 1);
+        else if ((block + (int)gridDim.x) * 16 < N) load_codes(block + gridDim.x, 0);
+        __builtin_amdgcn_sched_barrier(0);
 
         // Outliers of the chunk's columns [c0, c1): the lane's entries are sorted by column, so it
         // takes them while they are below c1.  Entries past the staged window come from memory
@@ -558,217 +566,6 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     }   // tiles
 }
 
-// ---- any M <= 16, X read from global memory: the general kernel --------------------------------
-//
-// BITS: 3 or 4.  U: groups per chunk (4 or 8).  PIPE: a wave owns more than U groups and
-// double-buffers chunks of U = 4.  Waves split K by groups_per_wave; indices past a wave's last
-// group are clamped and the repeated data dropped by a zero scale, so no branch sits between the
-// loads and their use.
-//
-// Rows m >= M of the X operand are never zeroed: lanes r >= M re-read row 0, which only produces
-// result rows m >= M, and those are not stored.
-//
-// Dynamic LDS, in this order: scales [16][gpr] halves | zero points [16][gpr] bytes | 16 spare bytes
-// | CSR columns, blockDim * 8 entries + 8 zero entries | CSR values, same | partial sums
-// [waves][4][64] floats.  The launcher guarantees kMetaRounds * blockDim >= 3 * gpr.
-constexpr int kMetaRounds = 2; // 16-byte vectors of scales / zero points a thread stages
-
-template <int BITS, int U, bool PIPE>
-__global__ __launch_bounds__(1024) void decode_kernel(const DecodeBatch batch)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const DecodeProblem &pr = batch.p[blockIdx.y];
-    const int N = pr.N, K = pr.K;
-    const int block = blockIdx.x;
-    const uint32_t *__restrict__ qweight = pr.qweight;
-    const uint16_t *__restrict__ scales = pr.scales;
-    const uint8_t *__restrict__ zeros = pr.zeros;
-    const int32_t *__restrict__ row_ptr = pr.row_ptr;
-    const uint16_t *__restrict__ col_idx = pr.col_idx;
-    const uint16_t *__restrict__ out_val = pr.out_val;
-    const _Float16 *__restrict__ X = pr.X;
-    _Float16 *__restrict__ Y = pr.Y;
-    const int M = batch.M, groups_per_wave = pr.groups_per_wave;
-    const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
-    // The whole descriptor is requested in one go and only then looked at.
-    asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
-                 "s"(K), "s"(groups_per_wave), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec));
-    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nwaves = batch.nwaves, nthreads = nwaves * 64;
-    const int r = lane & 15, b = lane >> 4;
-    const int gpr = K / kGroup;
-    const int row0 = block * 16;
-    const int n = row0 + r;
-    const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
-
-    const uint32_t sc_off = 0;
-    const uint32_t zp_off = sc_off + 32 * gpr;
-    const uint32_t spare_off = zp_off + 16 * gpr;
-    const uint32_t col_off = spare_off + 16;
-    const uint32_t val_off = col_off + 16 * nthreads + 16;
-    const uint32_t red_off = val_off + 16 * nthreads + 16;
-    float *red = reinterpret_cast<float *>(lds_raw + red_off);
-
-    // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
-    const int last_row = row0 + 16 < N ? row0 + 16 : N;
-    const int e_begin = row_ptr[row0], e_end = row_ptr[last_row];
-    const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
-
-    // This wave's groups [g_begin, g_last]; a wave past the end of K (has_groups false) walks the
-    // last group with a zero scale.
-    const bool has_groups = wave * groups_per_wave < gpr;
-    const int g_begin = has_groups ? wave * groups_per_wave : gpr - 1;
-    const int g_end = g_begin + groups_per_wave < gpr ? g_begin + groups_per_wave : gpr;
-    const int g_last = g_end - 1;
-
-    // The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for 16
-    // consecutive channels, staged with coalesced 16-byte loads: vector t < 2 gpr is a scales
-    // vector, the next gpr are zero-point vectors, any further thread re-reads vector 0 into the
-    // spare slot.
-    uint32_t meta_dst[kMetaRounds];
-    u32x4 meta[kMetaRounds];
-#pragma unroll
-    for (int i = 0; i < kMetaRounds; ++i) {
-        const int t = tid + i * nthreads;
-        const bool is_sc = t < 2 * gpr, is_zp = !is_sc && t < 3 * gpr;
-        int v = is_sc ? block * 2 * gpr + t : block * gpr + (t - 2 * gpr);
-        const int last = is_sc ? sc_last_vec : zp_last_vec;
-        v = (is_sc || is_zp) ? (v < last ? v : last) : 0;
-        const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
-        meta[i] = src[v];
-        meta_dst[i] = is_sc ? sc_off + 16 * t : is_zp ? zp_off + 16 * (t - 2 * gpr) : spare_off;
-    }
-
-    // The code stream: everything else overlaps its HBM latency.
-    const uint32_t row_group = (uint32_t)n_c * gpr;
-    Chunk<BITS, U> cur;
-    cur.load(qweight, row_group, g_begin, g_last, b);
-
-    // The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin: thread t
-    // brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
-    const int e0 = e_begin & ~7;
-    u32x4 seg_col, seg_val;
-    {
-        const int v_end = e_end > e0 ? (e_end - 1) / 8 : e0 / 8;     // last vector the block needs
-        int v = e0 / 8 + tid;
-        v = v < v_end ? v : v_end;                      // idle threads repeat it: no extra traffic
-        v = v < csr_last_vec ? v : csr_last_vec;
-        seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
-        seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
-    }
-    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
-
-    // Nothing that consumes a load may be scheduled above this point.
-    __builtin_amdgcn_sched_barrier(0);
-    const DecodeConsts dc(BITS);
-#pragma unroll
-    for (int i = 0; i < kMetaRounds; ++i) *reinterpret_cast<u32x4 *>(lds_raw + meta_dst[i]) = meta[i];
-    __syncthreads();
-
-    float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
-    const int x_row = r < M ? r : 0;
-    const _Float16 *xsrc = X + (uint32_t)x_row * K + 32 * b;
-    const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr;
-    const uint8_t *zp_lane = lds_raw + zp_off + r * gpr;
-    auto compute = [&](const Chunk<BITS, U> &c, int g0) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool valid = has_groups && g0 + u <= g_last;      // wave-uniform
-            const int g = valid ? g0 + u : g_last;
-            u32x4 xa[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                xa[j] = *reinterpret_cast<const u32x4 *>(xsrc + (uint32_t)g * kGroup + 8 * j);
-            const _Float16 s_raw = __builtin_bit_cast(_Float16, sc_lane[g]);
-            const float s = valid ? (float)s_raw : 0.f;
-            const uint32_t z = zp_lane[g];
-            u32x4 wb[4];
-            c.slot[u].decode(z, b, dc, wb);
-            float4v part = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[j]),
-                                                              __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(s, part[e], acc[e]);
-        }
-    };
-
-    if (PIPE) {
-        for (int g0 = g_begin; g0 <= g_last; g0 += U) {
-            Chunk<BITS, U> nxt;
-            const bool more = g0 + U <= g_last;
-            if (more) nxt.load(qweight, row_group, g0 + U, g_last, b);
-            compute(cur, g0);
-            if (more) cur = nxt;
-        }
-    } else {
-        compute(cur, g_begin);
-    }
-
-    // The CSR segment has arrived by now: publish it, followed by one vector of zero entries that
-    // lanes without an entry read instead.
-    reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
-    reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
-    if (tid == 0) {
-        reinterpret_cast<u32x4 *>(lds_raw + col_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
-        reinterpret_cast<u32x4 *>(lds_raw + val_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
-    }
-    __syncthreads();
-
-    // Outliers: lane (r, b) of every wave takes a share of its channel's entries for rows
-    // m = 4b .. 4b+3, the rows of its MFMA results.  Entry j sits at LDS index j - e0 when
-    // j < staged_end.
-    const int o_stride = nwaves;
-    const bool o_live = n < N && 4 * b < M;
-    const int o_end = o_live ? (rp1 < staged_end ? rp1 : staged_end) : 0;   // end of the lane's staged entries
-    const unsigned char *col_base = lds_raw + col_off;
-    const uint32_t val_delta = val_off - col_off;
-    float4v oacc = float4v{0.f, 0.f, 0.f, 0.f};
-    auto add_outlier = [&](uint32_t col, uint16_t val_bits) {
-        const float v = (float)__builtin_bit_cast(_Float16, val_bits);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int m = 4 * b + e < M ? 4 * b + e : 0;             // rows m >= M are not stored
-            oacc[e] = __builtin_fmaf(v, (float)X[(uint32_t)m * K + col], oacc[e]);
-        }
-    };
-    auto staged = [&](int idx) {
-        const unsigned char *p = col_base + 2 * idx;
-        add_outlier(*reinterpret_cast<const uint16_t *>(p), *reinterpret_cast<const uint16_t *>(p + val_delta));
-    };
-    const int j_first = rp0 + wave;
-#pragma unroll
-    for (int i = 0; i < kPre; ++i) {
-        const int j = j_first + i * o_stride;
-        staged(j < o_end ? j - e0 : 8 * nthreads);      // the zero entry when the lane has none
-    }
-    if (j_first + kPre * o_stride < o_end || (o_live && rp1 > staged_end)) {
-        int j = j_first + kPre * o_stride;
-        for (; j < o_end; j += o_stride) staged(j - e0);
-        // Entries that did not fit the staged window (very long rows) come straight from memory.
-        j = j_first;
-        if (j < staged_end) j += ((staged_end - j + o_stride - 1) / o_stride) * o_stride;
-        if (o_live)
-            for (; j < rp1; j += o_stride) add_outlier(col_idx[j], out_val[j]);
-    }
-
-    // Fixed-order reduction over the waves, then FP16 store.
-#pragma unroll
-    for (int e = 0; e < 4; ++e) red[(wave * 4 + e) * 64 + lane] = acc[e] + oacc[e];
-    __syncthreads();
-    for (int idx = tid; idx < 256; idx += nthreads) {
-        float sum = 0.f;
-        for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
-        const int e = idx >> 6, l = idx & 63;
-        const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
-        if (nn < N && m < M) Y[(size_t)m * N + nn] = (_Float16)sum;
-    }
-}
-
 constexpr size_t kMaxLds = 160 * 1024;                  // LDS a block may use on gfx950
 constexpr size_t kXLdsBudget = 128 * 1024;              // X[M][k_pad] is staged in LDS up to this size
 
@@ -799,15 +596,6 @@ hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwa
     return hipErrorInvalidValue;
 }
 
-template <int BITS>
-hipError_t launch_general(const DecodeBatch &batch, int count, int blocks, int nwaves, int max_gpw, size_t lds,
-                          hipStream_t st)
-{
-    if (max_gpw <= 4) return launch_kernel<&decode_kernel<BITS, 4, false>>(batch, count, blocks, nwaves, lds, st);
-    if (max_gpw <= 8) return launch_kernel<&decode_kernel<BITS, 8, false>>(batch, count, blocks, nwaves, lds, st);
-    return launch_kernel<&decode_kernel<BITS, 4, true>>(batch, count, blocks, nwaves, lds, st);
-}
-
 }  // namespace
 
 // Decode launch over `count` layers (same bits, same M): grid row i works on layer i; the grid is as
@@ -827,7 +615,6 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         d.X = static_cast<const _Float16 *>(X[i]);
         d.Y = static_cast<_Float16 *>(Y[i]);
         d.N = L.N; d.K = L.K;
-        d.groups_per_wave = 0;
         // Last 16-byte vector of each staged array (the buffers are padded, so clamped reads stay inside).
         const int64_t groups = (int64_t)L.N * gpr;
         d.sc_last_vec = (int)((groups * 2 + 15) / 16) - 1;
@@ -849,7 +636,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         }
         while (u < 16 && (max_gpr + u - 1) / u > 16) u *= 2;
         const int nwaves = (max_gpr + u - 1) / u;
-        const size_t x_bytes = (size_t)M * nwaves * u * kGroup * 2;
+        const size_t x_bytes = (size_t)M * (nwaves * u * kGroup + kXPad) * 2;
         const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256;
         if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds) {
             batch.nwaves = nwaves;
@@ -860,12 +647,12 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 
     // The wide kernel.  Among the shapes (U, waves <= 8) whose LDS footprint fits, the one with the
     // fewest phases, then the most waves, then the shorter waves.
-    if (waves_override == 0) {
+    {
         int best_u = 0, best_w = 0, best_ph = 1 << 30;
         size_t best_lds = 0;
-        for (int u = 4; u <= 8; u *= 2)
+        for (int u = 4; u <= (M <= 8 ? 8 : 4); u *= 2)   // 16 rows of 8 groups would not fit the registers
             for (int w = 1; w <= 8; ++w) {
-                const size_t lds = (size_t)M * w * u * kGroup * 2 + (size_t)48 * max_gpr + kWideGuard +
+                const size_t lds = (size_t)M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_gpr + kWideGuard +
                                    2 * 16 * (size_t)w * 64 + (size_t)w * 1024;
                 if (lds > kMaxLds) continue;
                 const int ph = (max_gpr + w * u - 1) / (w * u);
@@ -885,40 +672,13 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 #define GWQ_WIDE(B, UU, RR) \
     if (bits == B && best_u == UU && mr == RR) \
         return launch_kernel<&decode_wide_kernel<B, UU, RR>>(batch, count, blocks, best_w, best_lds, st)
-            GWQ_WIDE(4, 4, 8); GWQ_WIDE(4, 4, 16); GWQ_WIDE(4, 8, 8); GWQ_WIDE(4, 8, 16);
-            GWQ_WIDE(3, 4, 8); GWQ_WIDE(3, 4, 16); GWQ_WIDE(3, 8, 8); GWQ_WIDE(3, 8, 16);
+            GWQ_WIDE(4, 4, 8); GWQ_WIDE(4, 4, 16); GWQ_WIDE(4, 8, 8);
+            GWQ_WIDE(3, 4, 8); GWQ_WIDE(3, 4, 16); GWQ_WIDE(3, 8, 8);
 #undef GWQ_WIDE
         }
     }
 
-    // The general kernel.  Waves per block: one chunk of eight groups per wave where the rows are
-    // long enough, at most 16, and enough threads to stage every layer's 3 gpr vectors of scales
-    // and zero points.
-    int nwaves = 1;
-    for (int i = 0; i < count; ++i) {
-        const int gpr = P[i]->K / kGroup;
-        int w = waves_override ? waves_override : (gpr + 7) / 8;
-        const int min_waves = (3 * gpr + 64 * kMetaRounds - 1) / (64 * kMetaRounds);
-        if (w < min_waves) w = min_waves;
-        if (w > 16) w = 16;
-        if (w > gpr && gpr >= min_waves) w = gpr;
-        if (count == 1) {                               // a single layer drops waves that would own no group
-            const int gpw = (gpr + w - 1) / w, needed = (gpr + gpw - 1) / gpw;
-            if (needed >= min_waves) w = needed;
-        }
-        if (w > nwaves) nwaves = w;
-    }
-    int max_gpw = 1;
-    for (int i = 0; i < count; ++i) {
-        const int gpr = P[i]->K / kGroup;
-        if (nwaves * 64 * kMetaRounds < 3 * gpr) return hipErrorInvalidValue;      // K <= 65536 keeps this false
-        batch.p[i].groups_per_wave = (gpr + nwaves - 1) / nwaves;
-        if (batch.p[i].groups_per_wave > max_gpw) max_gpw = batch.p[i].groups_per_wave;
-    }
-    batch.nwaves = nwaves;
-    const size_t lds = meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * 1024;
-    return bits == 4 ? launch_general<4>(batch, count, blocks, nwaves, max_gpw, lds, st)
-                     : launch_general<3>(batch, count, blocks, nwaves, max_gpw, lds, st);
+    return hipErrorInvalidValue;                        // unreachable: one wave of four groups always fits
 }
 
 }  // namespace gwq
