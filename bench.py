@@ -197,7 +197,7 @@ def main():
                                                                "all": "one launch over the 7 matrices"}[args.group],
                    "copies_rotated": args.copies, "bytes_per_step": bytes_step, "launch": args.launch},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
-        "roofline": {"bound": "hbm", "kernel": "decode_kernel (4-bit, M=1)", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_small_kernel<4,8,1> (4-bit, M=1, 8 groups per wave)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(), "bytes_per_launch": round(bytes_launch),
                      "avg_launch_us": round(launch_ms * 1e3, 3)},

@@ -44,8 +44,9 @@ def test_decode_small_all_M(bits, N, K):
 @pytest.mark.parametrize("waves", [1, 2, 3, 6, 12, 16])
 @pytest.mark.parametrize("M", [1, 3, 5])
 def test_decode_launch_shapes(bits, waves, M):
-    """Every split of K over the waves of a block (one chunk, eight groups, double-buffered chunks)
-    gives the same answer within tolerance."""
+    """Every split of K over the waves of a block that the tuning knob can ask for (4, 8 or 16 groups
+    per wave in the kernel for M <= 4; the kernel for larger M picks its own) gives the same answer
+    within tolerance."""
     import paper_2411_00850_amd as gwq
     from gpu_helpers import assert_close
     P, rng = _problem(77, 150, 1536, bits)
@@ -194,8 +195,9 @@ def _layer70b(mid, N, K):
 @pytest.mark.parametrize("mid,N,K", [(0, 8192, 8192), (1, 28672, 8192), (2, 8192, 28672)])
 def test_config5_70b_shapes(mid, N, K, bits):
     """Full-size 70B-shaped matrices with column-clustered outliers: gwq_pack byte-exact against the
-    oracle's encoding of the known outlier set, gwq_linear at M in {1, 64, 2048} on 64 sampled
-    channels (all rows) against the oracle."""
+    oracle's encoding of the known outlier set, gwq_linear at M in {1, 4, 16, 64, 2048} on 64 sampled
+    channels (all rows) against the oracle (K = 28672 takes several chunks of K in the kernel for
+    5 <= M <= 16)."""
     import torch
     import paper_2411_00850_amd as gwq
     from gpu_helpers import assert_close, assert_packed_equal, to_gpu
@@ -204,7 +206,7 @@ def test_config5_70b_shapes(mid, N, K, bits):
     D = gwq.pack(to_gpu(W), to_gpu(S), bits, 10000)
     assert_packed_equal(D, P)
     rows = np.sort(gs.rng_for(5, mid, 3).choice(N, 64, replace=False)).astype(np.int32)
-    for M in (1, 64, 2048):
+    for M in (1, 4, 16, 64, 2048):
         X = gs.activations(M, K, gs.rng_for(5, mid, 10 + M))
         Y = gwq.linear(D, to_gpu(X)).cpu().numpy()
         assert np.isfinite(Y.astype(np.float32)).all()
