@@ -221,6 +221,41 @@ def main():
                 s, _, b, nl = decode_leg(1, max(args.steps // 3, 12), 12, args.launch, grouping)
                 extra[f"decode_M1_group_{grouping}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
                                                         "launches_per_step": nl}
+        # decode M = 1 on 70B-shaped matrices (one launch each; weights drawn on the device, three
+        # rotating copies of each so that they stream from HBM): how the same kernel does when the
+        # fixed cost of a launch is spread over 4-14 times the bytes
+        big = {}
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(70)
+        for name, N, K in gs.SHAPES_70B:
+            Wd = (torch.randn((N, K), device=dev, generator=gen) * 0.02).half()
+            Sd = torch.rand((N, K), device=dev, generator=gen)
+            P0 = gwq.pack(Wd, Sd, 4, 10000)
+            del Wd, Sd
+            Ps = [P0, clone_layer(P0), clone_layer(P0)]
+            x = torch.randn((1, K), device=dev, generator=gen).half()
+            y = torch.empty((1, N), dtype=torch.float16, device=dev)
+            calls = [gwq.prepare_linear(P, x, y) for P in Ps]
+            for call in calls:
+                call()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for call in calls:
+                    call()
+            graph.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(8):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (8 * len(calls))
+            big[f"{name}_{N}x{K}"] = {"us": round(us, 2), "GB/s": round(algorithmic_bytes(P0, 1) / us / 1e3, 1)}
+            del Ps, P0, calls, graph
+            torch.cuda.empty_cache()
+        extra["decode_M1_70b_shapes"] = big
         # prefill: M = 2048 over the 7 matrices, one copy (compute-bound)
         M = 2048
         xs, ys = make_xy(M)
