@@ -41,6 +41,18 @@ def test_decode_small_all_M(bits, N, K):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+def test_decode_longest_rows(bits):
+    """K = 65536, the largest the format allows (16-bit column indices): 512 groups per channel, more
+    than one block's waves can hold at once, so every M goes through several chunks of K."""
+    from gpu_helpers import assert_close
+    N, K = 24, 65536
+    P, rng = _problem(900 + bits, N, K, bits)
+    for M in (1, 3, 9, 16):
+        X = gs.activations(M, K, rng)
+        assert_close(_run(P, X), orc.linear_f64(P, X), f"decode N={N} K={K} M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("waves", [1, 2, 3, 6, 12, 16])
 @pytest.mark.parametrize("M", [1, 3, 5])
 def test_decode_launch_shapes(bits, waves, M):
@@ -119,6 +131,16 @@ def test_gemm_small(bits, N, K, M):
     from gpu_helpers import assert_close
     P, rng = _problem(N + K + M + bits, N, K, bits)
     X = gs.activations(M, K, rng, hot_frac=0.01)
+    assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm N={N} K={K} M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_gemm_longest_rows(bits):
+    """The GEMM at K = 65536 (512 groups: the most its per-group outlier counts are laid out for)."""
+    from gpu_helpers import assert_close
+    N, K, M = 40, 65536, 33
+    P, rng = _problem(950 + bits, N, K, bits)
+    X = gs.activations(M, K, rng)
     assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm N={N} K={K} M={M} bits={bits}")
 
 
