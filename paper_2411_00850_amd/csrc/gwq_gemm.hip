@@ -3,29 +3,27 @@
 //   Y[m][n] = sum_k X[m][k] * What[n][k],  What = s*(q - z) (Sec. 3.2, Eq. 10) with the FP16
 //   outliers written over their (zero-decoding) codes.
 //
-// A block of 8 waves owns a BM x 128 tile of Y (BM = 256, or 128 for small M) and walks K in steps
-// of 64 (half a group).  Per step the block stages X[BM][64] and the dequantised weights
-// What[128][64] as FP16 in LDS (double-buffered): a thread turns its codes into FP16 (exact q - z,
-// one multiply by the scale), stores them, and then overwrites the positions of the channel's
-// outliers.  The waves (4 along m, 2 along n) multiply 32x32x16 FP16 MFMA tiles with FP32
-// accumulators and store FP16.
+// A block owns a BM x 128 tile of Y (BM = 256, or 128 for small M) and walks K in steps of 64 (half
+// a group).  Per step X[BM][64] and the dequantised weights What[128][64] are staged as FP16 in LDS
+// (double-buffered) and multiplied with 32x32x16 FP16 MFMA tiles, FP32 accumulators, FP16 store.
 //
-// Two waves share a SIMD because a wave can issue next to nothing while one of its own MFMAs runs
-// (measured: about a quarter of the MFMA's 32 cycles): the staging work of one wave hides behind
-// the MFMAs of the other.  LDS stores are the scarcest resource (about 64 bytes per clock and CU,
-// a quarter of the load rate), so no lane ever stores data that is not needed.
+// The 12 waves of a block have two roles, three waves per SIMD:
+//   * 8 consumers (4 along m, 2 along n) do nothing but read fragments from LDS and issue MFMAs;
+//   * 4 producers stage the next step: X rows from memory to LDS, codes to FP16 (exact q - z, one
+//     multiply by the scale) to LDS, then the channel's outliers over their decoded zeros.
+// A wave can issue next to nothing while one of its own MFMAs runs (measured: about a quarter of
+// the MFMA's 32 cycles are free), so staging done by the multiplying waves themselves is time added
+// to theirs; done by other waves of the SIMD it is hidden.  LDS stores are the scarcest resource
+// (about 64 bytes per clock and CU, a quarter of the load rate), so nothing is stored twice.
 //
 // Everything a step needs from memory is requested two steps (X) or one group (codes, scale, zero
-// point, outliers) ahead, with addresses that do not depend on loaded data, so no wave waits for
-// memory inside the loop.  For the outliers this needs to know, per channel and group, how many
+// point, outliers) ahead, with addresses that do not depend on loaded data, so no producer waits
+// for memory inside the loop.  For the outliers this needs to know, per channel and group, how many
 // CSR entries fall into the group: a small kernel counts them into the workspace first (one byte
 // per channel and group); the running sum is the index of the group's first entry, and its first
-// eight entries are fetched ahead by the channel's threads with unaligned loads (longer runs take a
-// slow path).  Scales, zero points and counts are fetched four groups at a time, again with one
-// unaligned load each.  The staging work of the next step is cut into pieces issued between the
-// MFMA batches of the current one.
-#include <type_traits>
-
+// eight entries are fetched ahead by the channel's two threads with unaligned loads (longer runs
+// take a slow path).  Scales, zero points and counts are fetched four groups at a time, again with
+// one unaligned load each.
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -34,7 +32,8 @@ namespace {
 
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 512;
+constexpr int kConsumers = 8, kProducers = 4;          // waves
+constexpr int kThreads = 64 * (kConsumers + kProducers);
 constexpr int kBN = 128;
 constexpr int kBK = 64;
 constexpr int kLd = kBK + 8;            // LDS row stride in halves: 144 bytes, conflict-free b128 reads
@@ -78,24 +77,26 @@ template <> __device__ inline void load_slot<3>(SlotRegs<3> &r, const uint32_t *
     r.tail = group[12] >> (3 * slot);
 }
 
+// A 16-bit load that is complete when it returns, invisible to the compiler's bookkeeping of
+// outstanding loads: for the rare path inside the staging loop, whose loads would otherwise make
+// the compiler wait for every prefetch in flight at each trip of the loop.
+__device__ inline uint32_t load_u16_now(const uint16_t *p)
+{
+    uint32_t v;
+    asm volatile("global_load_ushort %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+
 // Loads of 8 / 4 bytes at 2-byte / 1-byte alignment (gfx950 global memory takes unaligned addresses).
 struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
 struct __attribute__((packed, aligned(2))) U32a2 { uint32_t v; };
 struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
 
-// What a thread fetches for one group of its channel.
-//   4-bit: thread q of the channel's four owns columns 16q .. 16q+15 of every step: two words per
-//   half of the group, and entries 2q, 2q+1 of the group's first eight outliers.
-//   3-bit (words do not end on 16-column boundaries): thread (s, r) owns slot 2r + s of the group,
-//   i.e. columns 32s .. 32s+31 of the steps of parity r, and entries 4s .. 4s+3; it idles in the
-//   steps of the other parity.
-template <int BITS> struct GroupRegs;
-template <> struct GroupRegs<4> {
-    uint32_t w[2][2];
-    uint32_t col, val;
-};
-template <> struct GroupRegs<3> {
-    SlotRegs<3> slot;
+// What producer thread (n, h) fetches for one group of channel n: its two slots (h and 2 + h: columns
+// 32h .. 32h+31 of the group's two steps) and entries 4h .. 4h+3 of the group's first eight outliers,
+// as packed 16-bit pairs.
+template <int BITS> struct GroupRegs {
+    SlotRegs<BITS> slot[2];
     uint32_t col_lo, col_hi, val_lo, val_hi;
 };
 // Scales, zero points and outlier counts of four consecutive groups of channel n.  (Plain words:
@@ -106,10 +107,10 @@ struct MetaRegs {
 };
 
 // Fragment j (8 codes -> 8 FP16 values s*(q - z)) of a slot.
-__device__ inline u32x4 dequant_word(uint32_t w, uint32_t z, uint32_t s2, const DecodeConsts &d)
+__device__ inline u32x4 dequant_frag(const SlotRegs<4> &r, int j, uint32_t z, uint32_t s2, const DecodeConsts &d)
 {
     const ZeroConsts<4> c(z);
-    u32x4 f = decode_word4(w, c, d);
+    u32x4 f = decode_word4(r.w[j], c, d);
     f.x = pk_mul(f.x, s2); f.y = pk_mul(f.y, s2); f.z = pk_mul(f.z, s2); f.w = pk_mul(f.w, s2);
     return f;
 }
@@ -123,10 +124,8 @@ __device__ inline void dequant_all(const SlotRegs<3> &r, uint32_t z, uint32_t s2
     }
 }
 
-// MSW = 32-row sub-tiles per wave along m; the block tile is BM = 128 * MSW rows by 128 channels,
-// worked on by 8 waves (4 along m, 2 along n), two per SIMD: a wave cannot issue anything else for
-// most of the time one of its MFMAs runs, so the staging work of one wave overlaps the MFMAs of
-// the other wave on its SIMD, not its own.
+// MSW = 32-row sub-tiles per consumer wave along m; the block tile is BM = 128 * MSW rows by 128
+// channels.
 template <int BITS, int MSW>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
                                                         const uint16_t *__restrict__ scales,
@@ -140,7 +139,6 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 {
     constexpr int BM = 128 * MSW;
     constexpr int wpg = words_per_group(BITS);
-    constexpr int kAPasses = BM / 64;                   // 512 threads move 64 rows x 128 bytes per pass
     extern __shared__ _Float16 lds[];                   // [2][BM + 128][kLd]
     constexpr int kBufHalves = (BM + kBN) * kLd;        // one buffer: X rows, then weight rows
 
@@ -160,136 +158,163 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     }
     const int m0 = mt * BM, n0 = nt * kBN;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int gpr = K / kGroup;
     const int nk = K / kBK;                             // steps; two per group
 
-    // Staging roles.  X: 8 threads cover one 128-byte row of a step.  Weights: the four threads of
-    // channel n are neighbours in a wave (see GroupRegs for what each owns).
-    const int a_row = tid >> 3, a_chunk = tid & 7;
-    const int b_n_local = tid >> 2, b_q = tid & 3, b_s = (tid >> 1) & 1, b_r = tid & 1;
-    int b_n = n0 + b_n_local;
-    const bool b_valid = b_n < N;
-    b_n = b_valid ? b_n : N - 1;                        // clamped: loads stay in bounds, tile row unused
-    const DecodeConsts dc(BITS);
+    // Both roles pass the block's barrier exactly 1 + nk times: once when step 0 is staged, then
+    // once per step (the consumers in the middle of the step's last k-batch).
+    if (wave >= kConsumers) {
+        // ======================================= producers =====================================
+        constexpr int kAPasses = BM / 32;               // 256 threads move 32 rows x 128 bytes per pass
+        const int ptid = tid - 64 * kConsumers;
+        const int a_row = ptid >> 3, a_chunk = ptid & 7;   // 8 threads cover one 128-byte row of a step
+        const int b_n_local = ptid >> 1, b_h = ptid & 1;
+        int b_n = n0 + b_n_local;
+        const bool b_valid = b_n < N;
+        b_n = b_valid ? b_n : N - 1;                    // clamped: loads stay in bounds, tile row unused
+        const DecodeConsts dc(BITS);
 
-    const _Float16 *a_src[kAPasses];
+        const _Float16 *a_src[kAPasses];
 #pragma unroll
-    for (int p = 0; p < kAPasses; ++p) {
-        int m = m0 + p * 64 + a_row;
-        m = m < M ? m : M - 1;
-        a_src[p] = X + (size_t)m * K + 8 * a_chunk;
-    }
-    const uint32_t row_group = (uint32_t)b_n * gpr;
-    const uint32_t *q_row = qweight + (size_t)row_group * wpg;
-    _Float16 *const a_dst = lds + a_row * kLd + 8 * a_chunk;            // + buffer, + pass * 64 rows
-    _Float16 *const b_dst = lds + (BM + b_n_local) * kLd;               // + buffer
+        for (int p = 0; p < kAPasses; ++p) {
+            int m = m0 + p * 32 + a_row;
+            m = m < M ? m : M - 1;
+            a_src[p] = X + (size_t)m * K + 8 * a_chunk;
+        }
+        const uint32_t row_group = (uint32_t)b_n * gpr;
+        const uint32_t *q_row = qweight + (size_t)row_group * wpg;
+        _Float16 *const a_dst = lds + a_row * kLd + 8 * a_chunk;            // + buffer, + pass * 32 rows
+        _Float16 *const b_dst = lds + (BM + b_n_local) * kLd;               // + buffer
 
-    auto issue_a = [&](int step, u32x4 dst[kAPasses]) {
-        const int k0 = (step < nk ? step : nk - 1) * kBK;
+        auto issue_a = [&](int step, u32x4 dst[kAPasses]) {
+            const int k0 = (step < nk ? step : nk - 1) * kBK;
 #pragma unroll
-        for (int p = 0; p < kAPasses; ++p) dst[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k0);
-    };
-    // first = CSR index of the group's first entry (it depends on counts fetched long before).
-    auto issue_group = [&](int g, int first, GroupRegs<BITS> &G) {
-        g = g < gpr ? g : gpr - 1;
-        const uint32_t *grp = q_row + (uint32_t)g * wpg;
-        if constexpr (BITS == 4) {
-            const uint2 v0 = *reinterpret_cast<const uint2 *>(grp + 4 * (b_q >> 1) + 2 * (b_q & 1));
-            const uint2 v1 = *reinterpret_cast<const uint2 *>(grp + 8 + 4 * (b_q >> 1) + 2 * (b_q & 1));
-            G.w[0][0] = v0.x; G.w[0][1] = v0.y; G.w[1][0] = v1.x; G.w[1][1] = v1.y;
-            const int j = first + 2 * b_q < last_entry ? first + 2 * b_q : last_entry;   // arrays carry 16 spare bytes
-            G.col = reinterpret_cast<const U32a2 *>(col_idx + j)->v;
-            G.val = reinterpret_cast<const U32a2 *>(out_val + j)->v;
-        } else {
-            load_slot<3>(G.slot, grp, 2 * b_r + b_s);
-            const int j = first + 4 * b_s < last_entry ? first + 4 * b_s : last_entry;
+            for (int p = 0; p < kAPasses; ++p) dst[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k0);
+        };
+        // first = CSR index of the group's first entry (it depends on counts fetched long before).
+        auto issue_group = [&](int g, int first, GroupRegs<BITS> &G) {
+            g = g < gpr ? g : gpr - 1;
+            const uint32_t *grp = q_row + (uint32_t)g * wpg;
+            load_slot<BITS>(G.slot[0], grp, b_h);
+            load_slot<BITS>(G.slot[1], grp, 2 + b_h);
+            const int j = first + 4 * b_h < last_entry ? first + 4 * b_h : last_entry;   // arrays carry 16 spare bytes
             const U64a2 c = *reinterpret_cast<const U64a2 *>(col_idx + j), v = *reinterpret_cast<const U64a2 *>(out_val + j);
             G.col_lo = c.lo; G.col_hi = c.hi; G.val_lo = v.lo; G.val_hi = v.hi;
-        }
-    };
-    // Groups 4q .. 4q+3 (reads past the row or the array stay inside the padded buffers).
-    auto issue_meta = [&](int q, MetaRegs &Q) {
-        const int g = 4 * q < gpr ? 4 * q : 0;
-        const U64a2 sc = *reinterpret_cast<const U64a2 *>(scales + row_group + g);
-        Q.sc = (uint64_t)sc.hi << 32 | sc.lo;
-        Q.zp = reinterpret_cast<const U32a1 *>(zeros + row_group + g)->v;
-        Q.cnt = reinterpret_cast<const U32a1 *>(grp_cnt + row_group + g)->v;
-    };
-    auto meta_scale = [](const MetaRegs &Q, int g) -> uint32_t {
-        const uint32_t h = (uint32_t)(Q.sc >> (16 * (g & 3))) & 0xFFFFu;      // a shift, not a choice of fields
-        return h | h << 16;
-    };
-    auto meta_zero = [](const MetaRegs &Q, int g) -> uint32_t { return (Q.zp >> (8 * (g & 3))) & 0xFFu; };
-    auto meta_count = [&](const MetaRegs &Q, int g) -> int { return b_valid ? (int)((Q.cnt >> (8 * (g & 3))) & 0xFFu) : 0; };
+        };
+        // Groups 4q .. 4q+3 (reads past the row or the array stay inside the padded buffers).
+        auto issue_meta = [&](int q, MetaRegs &Q) {
+            const int g = 4 * q < gpr ? 4 * q : 0;
+            const U64a2 sc = *reinterpret_cast<const U64a2 *>(scales + row_group + g);
+            Q.sc = (uint64_t)sc.hi << 32 | sc.lo;
+            Q.zp = reinterpret_cast<const U32a1 *>(zeros + row_group + g)->v;
+            Q.cnt = reinterpret_cast<const U32a1 *>(grp_cnt + row_group + g)->v;
+        };
+        auto meta_scale = [](const MetaRegs &Q, int g) -> uint32_t {
+            const uint32_t h = (uint32_t)(Q.sc >> (16 * (g & 3))) & 0xFFFFu;      // a shift, not a choice of fields
+            return h | h << 16;
+        };
+        auto meta_zero = [](const MetaRegs &Q, int g) -> uint32_t { return (Q.zp >> (8 * (g & 3))) & 0xFFu; };
+        auto meta_count = [&](const MetaRegs &Q, int g) -> int { return b_valid ? (int)((Q.cnt >> (8 * (g & 3))) & 0xFFu) : 0; };
 
-    // Staging of step `step` into buffer `buf`, in pieces that the step function spreads over its
-    // MFMA batches.  stage_x: X rows of passes p0 .. p1-1 go to LDS, and the registers are refilled
-    // with the rows of two steps later.  stage_w: half of this thread's weight fragments.
-    // stage_outliers: this thread's entries, then (one thread per channel) the rare rest.
-    auto stage_x = [&](int p0, int p1, int step, int buf, u32x4 a_regs[kAPasses]) {
-        _Float16 *A = a_dst + buf * kBufHalves;
-        const int k2 = (step + 2 < nk ? step + 2 : nk - 1) * kBK;
+        // Staging of step `step` into buffer `buf`: this thread's 32 columns of weights, then its four
+        // outlier entries (anywhere in the step's 64 columns: the thread that decoded those columns
+        // is the lane next to this one and its stores were issued before), then the X rows, whose
+        // registers are refilled with the rows of two steps later.
+        auto stage = [&](int step, int buf, u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
+                         int first) {
+            _Float16 *A = a_dst + buf * kBufHalves, *brow = b_dst + buf * kBufHalves;
+            const int half = step & 1, g = step >> 1;
+            const uint32_t s2 = meta_scale(Q, g), z = meta_zero(Q, g);
+            if constexpr (BITS == 4) {
 #pragma unroll
-        for (int p = p0; p < p1 && p < kAPasses; ++p) {
-            *reinterpret_cast<u32x4 *>(A + p * 64 * kLd) = a_regs[p];
-            a_regs[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k2);
-        }
-    };
-    auto stage_w = [&](int pair, int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q) {
-        _Float16 *brow = b_dst + buf * kBufHalves;
-        const int g = step >> 1;
-        const uint32_t s2 = meta_scale(Q, g), z = meta_zero(Q, g);
-        if constexpr (BITS == 4) {
-            *reinterpret_cast<u32x4 *>(brow + 16 * b_q + 8 * pair) = dequant_word(G.w[step & 1][pair], z, s2, dc);
-        } else {
-            if (pair == 0 && b_r == (step & 1)) {
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = dequant_frag(G.slot[half], j, z, s2, dc);
+            } else {
                 u32x4 f[4];
-                dequant_all(G.slot, z, s2, dc, f);
+                dequant_all(G.slot[half], z, s2, dc, f);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_s + 8 * j) = f[j];
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
             }
-        }
-    };
-    // Outliers of this channel inside the step's 64 columns replace their decoded zeros.  The
-    // writers of those zeros are lanes of the same wave and their stores were issued earlier, so
-    // the order is kept.  4-bit: an entry that is not ours to write goes to the row's padding
-    // (predication would fence the MFMAs off).
-    auto stage_outliers = [&](int step, int buf, const GroupRegs<BITS> &G, const MetaRegs &Q, int first) {
-        _Float16 *brow = b_dst + buf * kBufHalves;
-        const int g = step >> 1;
-        const int cnt = step < nk ? meta_count(Q, g) : 0;       // nothing to patch behind the last step
-        const uint32_t k_lo = (uint32_t)(step * kBK);
-        bool rest;                                              // this thread takes the entries past the eighth
-        if constexpr (BITS == 4) {
+            const int cnt = meta_count(Q, g);
+            const uint32_t k_lo = (uint32_t)(step * kBK);
+            const uint32_t cs[2] = {G.col_lo, G.col_hi}, vs[2] = {G.val_lo, G.val_hi};
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const uint32_t col = ((G.col >> (16 * i)) & 0xFFFFu) - k_lo;
-                const uint32_t dst = (2 * b_q + i < cnt && col < (uint32_t)kBK) ? col : kBK + b_q;
-                brow[dst] = __builtin_bit_cast(_Float16, (uint16_t)(G.val >> (16 * i)));
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t col = ((cs[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
+                if (4 * b_h + i < cnt && col < (uint32_t)kBK)
+                    brow[col] = __builtin_bit_cast(_Float16, (uint16_t)(vs[i >> 1] >> (16 * (i & 1))));
             }
-            rest = b_q == 0;
-        } else {
-            const bool mine = b_r == (step & 1);
-            if (mine) {
-                const uint32_t cs[2] = {G.col_lo, G.col_hi}, vs[2] = {G.val_lo, G.val_hi};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t col = ((cs[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
-                    if (4 * b_s + i < cnt && col < (uint32_t)kBK)
-                        brow[col] = __builtin_bit_cast(_Float16, (uint16_t)(vs[i >> 1] >> (16 * (i & 1))));
+            if (b_h == 0)
+                for (int i = kAhead; i < cnt; ++i) {    // rare: more than kAhead outliers in one group
+                    const uint32_t c = load_u16_now(col_idx + first + i) - k_lo;
+                    if (c < (uint32_t)kBK) brow[c] = __builtin_bit_cast(_Float16, (uint16_t)load_u16_now(out_val + first + i));
                 }
+            const int k2 = (step + 2 < nk ? step + 2 : nk - 1) * kBK;
+#pragma unroll
+            for (int p = 0; p < kAPasses; ++p) {
+                *reinterpret_cast<u32x4 *>(A + p * 32 * kLd) = a_regs[p];
+                a_regs[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k2);
             }
-            rest = mine && b_s == 0;
-        }
-        if (rest)
-            for (int i = kAhead; i < cnt; ++i) {        // rare: more than kAhead outliers in one group
-                const uint32_t c = (uint32_t)col_idx[first + i] - k_lo;
-                if (c < (uint32_t)kBK) brow[c] = __builtin_bit_cast(_Float16, out_val[first + i]);
-            }
-    };
+        };
 
+        // Prologue: metadata of groups 0..7, codes and outliers of groups 0 and 1, the X rows of
+        // steps 0 and 1; step 0 staged.
+        MetaRegs Qc, Qn;                                // groups 4q .. 4q+3 and the four after them
+        GroupRegs<BITS> G0, G1;                         // even groups, odd groups
+        u32x4 a0[kAPasses], a1[kAPasses];               // X rows of the even / odd step being staged
+        int first_c = b_valid ? row_ptr[b_n] : 0;       // CSR index of the current group's first entry
+        issue_meta(0, Qc);
+        issue_meta(1, Qn);
+        issue_a(0, a0);
+        issue_a(1, a1);
+        issue_group(0, first_c, G0);
+        int first_n = first_c + meta_count(Qc, 0);
+        issue_group(1, first_n, G1);
+        stage(0, 0, a0, G0, Qc, first_c);               // refills a0 with the rows of step 2
+        __syncthreads();
+
+        // One group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, a1 holds the X
+        // rows of step 2g + 1, a0 those of step 2g + 2 (in flight), Gcur is group g, Gnxt is group
+        // g + 1 (in flight), Qc covers group g, Qn the four groups after Qc's.  Gcur is refilled with
+        // group g + 2 at the end, so the two register sets swap roles from trip to trip and a set
+        // is never copied (a copy would have to wait for loads that were only just issued).
+        // (The scheduling fences keep every request where it is written: left alone, the compiler moves
+        // loads down towards their use, and then waits for them.)
+        auto trip = [&](int g, GroupRegs<BITS> &Gcur, GroupRegs<BITS> &Gnxt) {
+            stage(2 * g + 1, 1, a1, Gcur, Qc, first_c); // second half of group g, while step 2g multiplies
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            const bool roll = (g & 3) == 3;             // group g + 1 starts the next four
+            if (g + 1 < gpr) {
+                MetaRegs Qs;                            // selected by value: a reference would pin both in memory
+                Qs.sc = roll ? Qn.sc : Qc.sc;
+                Qs.zp = roll ? Qn.zp : Qc.zp; Qs.cnt = roll ? Qn.cnt : Qc.cnt;
+                stage(2 * g + 2, 0, a0, Gnxt, Qs, first_n);   // first half of group g + 1, while step 2g + 1 multiplies
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            if (roll) {
+                Qc = Qn;
+                issue_meta((g + 1) / 4 + 1, Qn);
+            }
+            first_c = first_n;
+            first_n = first_c + meta_count(Qc, g + 1);
+            issue_group(g + 2, first_n, Gcur);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        int g = 0;
+        for (; g + 1 < gpr; g += 2) {                   // no path skips half of the body: the compiler's count of
+            trip(g, G0, G1);                            // loads in flight at the top of the loop stays exact
+            trip(g + 1, G1, G0);
+        }
+        if (g < gpr) trip(g, G0, G1);
+        return;
+    }
+
+    // ========================================= consumers =======================================
+    const int wm = wave >> 1, wn = wave & 1;            // 4 x 2 waves, each (BM / 4) x 64
     float16v acc[MSW][2];
 #pragma unroll
     for (int i = 0; i < MSW; ++i)
@@ -321,98 +346,33 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                                                                    acc[i][j], 0, 0, 0);
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-    // Scheduling pattern for the region since the last fence: `count` times one MFMA followed by
-    // `others` of the staging instructions (vector ALU, scalar ALU, global loads, LDS writes).
-    auto interleave = [](auto count, auto others) {
-#pragma unroll
-        for (int k = 0; k < decltype(count)::value; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002 | 0x004 | 0x020 | 0x200, decltype(others)::value, 0);
-        }
-    };
-    using std::integral_constant;
 
-    // One step.  On entry the fragments of its first k-batch are in fa[0], fb[0].  Each k-batch
-    // first requests the fragments of the batch after it, then multiplies with a piece of the
-    // staging of step + 1 (into the other buffer, from a_regs, G, Q) scheduled among its MFMAs:
-    // the weights in batches 0 and 1, the outliers and the X rows in batch 2.  The block's barrier
-    // sits in the middle of the last batch: behind it the first fragments of step + 1 are requested
-    // while the rest of the batch still multiplies.
-    auto step_fn = [&](int step, int buf, u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
-                       int first) {
-        constexpr int kMfma = 2 * MSW;                          // MFMAs of one batch
-        constexpr int h = MSW >= 2 ? MSW / 2 : 1;               // rows of the last batch ahead of the barrier
-        // LDS stores are the slow kind of LDS traffic (a 16-byte store per lane keeps the unit busy
-        // four times as long as a load), so they are spread evenly: fragment loads queued behind a
-        // burst of stores would come back late.
+    __syncthreads();                                    // step 0 is staged
+    read_frags(0, 0, fa[0], fb[0]);
+    // One step: each k-batch first requests the fragments of the batch after it, then multiplies.
+    // The barrier sits in the middle of the last batch: behind it the first fragments of the next
+    // step are requested while the rest of the batch still multiplies.
+    constexpr int h = MSW >= 2 ? MSW / 2 : 1;           // rows of the last batch ahead of the barrier
+    for (int step = 0; step < nk; ++step) {
+        const int buf = step & 1;
         read_frags(buf, 1, fa[1], fb[1]);
         fence();
         mfma_rows(0, 0, MSW);
-        stage_w(0, step + 1, buf ^ 1, G, Q);
-        stage_x(0, 1, step + 1, buf ^ 1, a_regs);
-        interleave(integral_constant<int, kMfma>{}, integral_constant<int, 32 / kMfma>{});
         fence();
         read_frags(buf, 2, fa[0], fb[0]);
         fence();
         mfma_rows(1, 0, MSW);
-        stage_w(1, step + 1, buf ^ 1, G, Q);
-        stage_x(1, 2, step + 1, buf ^ 1, a_regs);
-        interleave(integral_constant<int, kMfma>{}, integral_constant<int, 32 / kMfma>{});
         fence();
         read_frags(buf, 3, fa[1], fb[1]);
         fence();
         mfma_rows(2, 0, MSW);
-        stage_outliers(step + 1, buf ^ 1, G, Q, first);
-        stage_x(2, 3, step + 1, buf ^ 1, a_regs);
         fence();
         mfma_rows(3, 0, h);
-        stage_x(3, kAPasses, step + 1, buf ^ 1, a_regs);
         fence();
         __syncthreads();
         read_frags(buf ^ 1, 0, fa[0], fb[0]);
         fence();
         mfma_rows(3, h, MSW);
-    };
-
-    // Prologue: metadata of groups 0..7, codes and outliers of groups 0 and 1, the X rows of
-    // steps 0 and 1; step 0 staged.
-    MetaRegs Qc, Qn;                                    // groups 4q .. 4q+3 and the four after them
-    GroupRegs<BITS> Gc, Gn;                             // current group, next group
-    u32x4 a0[kAPasses], a1[kAPasses];                   // X rows of the even / odd step being staged
-    int first_c = b_valid ? row_ptr[b_n] : 0;           // CSR index of the current group's first entry
-    issue_meta(0, Qc);
-    issue_meta(1, Qn);
-    issue_a(0, a0);
-    issue_a(1, a1);
-    issue_group(0, first_c, Gc);
-    int first_n = first_c + meta_count(Qc, 0);
-    issue_group(1, first_n, Gn);
-    stage_w(0, 0, 0, Gc, Qc);
-    stage_w(1, 0, 0, Gc, Qc);
-    stage_outliers(0, 0, Gc, Qc, first_c);
-    stage_x(0, kAPasses, 0, 0, a0);                     // refills a0 with the rows of step 2
-    __syncthreads();
-    read_frags(0, 0, fa[0], fb[0]);
-
-    // Main loop, one group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, a1
-    // holds the X rows of step 2g + 1, a0 those of step 2g + 2 (in flight), Gc is group g, Gn is
-    // group g + 1 (in flight), Qc covers group g, Qn the four groups after Qc's.
-    for (int g = 0; g < gpr; ++g) {
-        step_fn(2 * g, 0, a1, Gc, Qc, first_c);         // stages step 2g + 1 (second half of group g)
-        // Second half: stage step 2g + 2 = first half of group g + 1, then move on to it.
-        const bool roll = (g & 3) == 3;                 // group g + 1 starts the next four
-        MetaRegs Qs;                                    // selected by value: a reference would pin both in memory
-        Qs.sc = roll ? Qn.sc : Qc.sc;
-        Qs.zp = roll ? Qn.zp : Qc.zp; Qs.cnt = roll ? Qn.cnt : Qc.cnt;
-        step_fn(2 * g + 1, 1, a0, Gn, Qs, first_n);
-        Gc = Gn;
-        if (roll) {
-            Qc = Qn;
-            issue_meta((g + 1) / 4 + 1, Qn);
-        }
-        first_c = first_n;
-        first_n = first_c + meta_count(Qc, g + 1);
-        issue_group(g + 2, first_n, Gn);
     }
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
