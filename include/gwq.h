@@ -104,8 +104,9 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
  * FP16 output.  M <= 16 takes the bandwidth-bound decode kernel, larger M the MFMA GEMM.
  *   P  host struct with device pointers   X_f16 device [M][K]   Y_f16 device [M][N]
  * X and Y must not overlap; Y is fully overwritten.  M > 16 needs `workspace`: device scratch of
- * at least the linear_workspace bytes gwq_layout reports for an M_max > 16 (it is rewritten by
- * every call; concurrent calls need separate workspaces); for M <= 16 it may be NULL.
+ * at least the linear_workspace bytes gwq_layout reports for an M_max > 16, 16-byte aligned (it
+ * is rewritten by every call; concurrent calls need separate workspaces); for M <= 16 it may be
+ * NULL.
  * Results are deterministic (no floating-point atomics). */
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);

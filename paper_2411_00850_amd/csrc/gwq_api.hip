@@ -86,6 +86,7 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
          (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
         return GWQ_ERR_SHAPE;
     if (M > 16 && (!workspace || workspace_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
+    if (M > 16 && ((uintptr_t)workspace & 15)) return GWQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st)
                            : gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, g_gemm_ms, st);

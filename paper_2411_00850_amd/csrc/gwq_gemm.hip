@@ -5,25 +5,27 @@
 //
 // A block owns a BM x 128 tile of Y (BM = 256, or 128 for small M) and walks K in steps of 64 (half
 // a group).  Per step X[BM][64] and the dequantised weights What[128][64] are staged as FP16 in LDS
-// (double-buffered) and multiplied with 32x32x16 FP16 MFMA tiles, FP32 accumulators, FP16 store.
+// (X in three buffers, the weights in two) and multiplied with 32x32x16 FP16 MFMA tiles, FP32
+// accumulators, FP16 store.
 //
-// The 12 waves of a block have two roles, three waves per SIMD:
+// The 16 waves of a block have three roles, four waves per SIMD:
 //   * 8 consumers (4 along m, 2 along n) do nothing but read fragments from LDS and issue MFMAs;
-//   * 4 producers stage the next step: X rows from memory to LDS, codes to FP16 (exact q - z, one
-//     multiply by the scale) to LDS, then the channel's outliers over their decoded zeros.
+//   * 4 producers stage the weights of the next step: codes to FP16 (exact q - z, one multiply by
+//     the scale) to LDS, then the channel's outliers over their decoded zeros;
+//   * 4 loaders copy the X rows of the step after next from memory straight into LDS (loads with
+//     an LDS destination: no registers, no LDS store instructions).
 // A wave can issue next to nothing while one of its own MFMAs runs (measured: about a quarter of
 // the MFMA's 32 cycles are free), so staging done by the multiplying waves themselves is time added
-// to theirs; done by other waves of the SIMD it is hidden.  LDS stores are the scarcest resource
-// (about 64 bytes per clock and CU, a quarter of the load rate), so nothing is stored twice.
+// to theirs; done by other waves of the SIMD it is hidden.  What the roles share is the LDS: per
+// step 128 KB of fragment reads, 32 KB of X and 16 KB of weights written, which together keep it
+// busy about as long as the step's MFMAs take.
 //
-// Everything a step needs from memory is requested two steps (X) or one group (codes, scale, zero
-// point, outliers) ahead, with addresses that do not depend on loaded data, so no producer waits
-// for memory inside the loop.  For the outliers this needs to know, per channel and group, how many
-// CSR entries fall into the group: a small kernel counts them into the workspace first (one byte
-// per channel and group); the running sum is the index of the group's first entry, and its first
-// eight entries are fetched ahead by the channel's two threads with unaligned loads (longer runs
-// take a slow path).  Scales, zero points and counts are fetched four groups at a time, again with
-// one unaligned load each.
+// Everything a step needs from memory is requested two steps ahead, with addresses that do not
+// depend on data requested in the same trip, so nobody waits for memory inside the loop.  For the
+// outliers this needs to know, per channel and group, where the group's CSR entries start: a small
+// kernel writes that index, with the group's scale and zero point, into the workspace first (one
+// 8-byte record per channel and group); a group's first eight entries are fetched ahead by the
+// channel's two threads with unaligned loads (longer runs take a slow path).
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -32,18 +34,28 @@ namespace {
 
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-constexpr int kConsumers = 8, kProducers = 4;          // waves
-constexpr int kThreads = 64 * (kConsumers + kProducers);
+constexpr int kConsumers = 8, kProducers = 4, kLoaders = 4;     // waves
+constexpr int kThreads = 64 * (kConsumers + kProducers + kLoaders);
 constexpr int kBN = 128;
 constexpr int kBK = 64;
 constexpr int kLd = kBK + 8;            // LDS row stride in halves: 144 bytes, conflict-free b128 reads
 constexpr int kAhead = 8;               // outlier entries per (channel, group) fetched ahead
 
 // ------------------------------------------------------------------------------------------------
-// Outlier counts per (channel, group), saturating at 255.  One wave per channel.
-__global__ __launch_bounds__(256) void group_count_kernel(const int32_t *__restrict__ row_ptr,
-                                                          const uint16_t *__restrict__ col_idx, int N, int gpr,
-                                                          uint8_t *__restrict__ cnt)
+// Per (channel, group) record for the GEMM's producers: the CSR index of the group's first outlier
+// and the group's scale and zero point, so that one 8-byte load fetches everything a group needs
+// besides its codes.  gpr + 1 records per channel; the last one holds the channel's end index.
+// One wave per channel.
+struct GroupRecord {
+    int32_t first;
+    uint32_t scale_zero;                                // scale bits | zero point << 16
+};
+
+__global__ __launch_bounds__(256) void group_index_kernel(const int32_t *__restrict__ row_ptr,
+                                                          const uint16_t *__restrict__ col_idx,
+                                                          const uint16_t *__restrict__ scales,
+                                                          const uint8_t *__restrict__ zeros, int N, int gpr,
+                                                          GroupRecord *__restrict__ rec)
 {
     __shared__ uint32_t c[4][512];                      // gpr <= 512 (K <= 65536)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -55,8 +67,31 @@ __global__ __launch_bounds__(256) void group_count_kernel(const int32_t *__restr
         for (int j = row_ptr[n] + lane; j < j1; j += 64) atomicAdd(&c[wave][col_idx[j] >> 7], 1u);
     }
     __syncthreads();
-    if (n < N)
-        for (int g = lane; g < gpr; g += 64) cnt[(size_t)n * gpr + g] = (uint8_t)(c[wave][g] < 255u ? c[wave][g] : 255u);
+    if (n >= N) return;
+    // Exclusive prefix over the groups: lane l owns groups 8l .. 8l+7.
+    uint32_t mine[8], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int g = 8 * lane + i;
+        mine[i] = g < gpr ? c[wave][g] : 0u;
+        sum += mine[i];
+    }
+    uint32_t incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    uint32_t first = (uint32_t)row_ptr[n] + incl - sum;
+    GroupRecord *out = rec + (size_t)n * (gpr + 1);
+    const size_t row_group = (size_t)n * gpr;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int g = 8 * lane + i;
+        if (g < gpr) out[g] = GroupRecord{(int32_t)first, (uint32_t)scales[row_group + g] | (uint32_t)zeros[row_group + g] << 16};
+        first += mine[i];
+    }
+    if (lane == 0) out[gpr] = GroupRecord{row_ptr[n + 1], 0u};
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -87,23 +122,17 @@ __device__ inline uint32_t load_u16_now(const uint16_t *p)
     return v;
 }
 
-// Loads of 8 / 4 bytes at 2-byte / 1-byte alignment (gfx950 global memory takes unaligned addresses).
+// A load of 8 bytes at 2-byte alignment (gfx950 global memory takes unaligned addresses).
 struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
-struct __attribute__((packed, aligned(2))) U32a2 { uint32_t v; };
-struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
 
 // What producer thread (n, h) fetches for one group of channel n: its two slots (h and 2 + h: columns
-// 32h .. 32h+31 of the group's two steps) and entries 4h .. 4h+3 of the group's first eight outliers,
-// as packed 16-bit pairs.
+// 32h .. 32h+31 of the group's two steps), entries 4h .. 4h+3 of the group's first eight outliers
+// as packed 16-bit pairs, and the record of the group after it.
 template <int BITS> struct GroupRegs {
     SlotRegs<BITS> slot[2];
     uint32_t col_lo, col_hi, val_lo, val_hi;
-};
-// Scales, zero points and outlier counts of four consecutive groups of channel n.  (Plain words:
-// the unaligned loads go through temporaries, so these stay in registers.)
-struct MetaRegs {
-    uint64_t sc;
-    uint32_t zp, cnt;
+    int32_t next_first;
+    uint32_t next_scale_zero;
 };
 
 // Fragment j (8 codes -> 8 FP16 values s*(q - z)) of a slot.
@@ -124,23 +153,35 @@ __device__ inline void dequant_all(const SlotRegs<3> &r, uint32_t z, uint32_t s2
     }
 }
 
+// X rows lie in LDS 128 bytes apart, so the 16-byte chunk c of row r is kept at position
+// c ^ x_swizzle(r): the 16 rows a fragment read touches per cycle then hit 16 different bank groups,
+// whichever of the two plausible lane groupings the hardware uses.
+__device__ inline int x_swizzle(int r)
+{
+    const int t = (r >> 1) & 7;
+    return (t & 3) << 1 | t >> 2;
+}
+template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
 // MSW = 32-row sub-tiles per consumer wave along m; the block tile is BM = 128 * MSW rows by 128
 // channels.
 template <int BITS, int MSW>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
-                                                        const uint16_t *__restrict__ scales,
-                                                        const uint8_t *__restrict__ zeros,
-                                                        const int32_t *__restrict__ row_ptr,
                                                         const uint16_t *__restrict__ col_idx,
                                                         const uint16_t *__restrict__ out_val,
-                                                        const uint8_t *__restrict__ grp_cnt,
+                                                        const GroupRecord *__restrict__ rec,
                                                         const _Float16 *__restrict__ X, _Float16 *__restrict__ Y,
                                                         int N, int K, int M, int tiles_m, int tiles_n, int last_entry)
 {
     constexpr int BM = 128 * MSW;
     constexpr int wpg = words_per_group(BITS);
-    extern __shared__ _Float16 lds[];                   // [2][BM + 128][kLd]
-    constexpr int kBufHalves = (BM + kBN) * kLd;        // one buffer: X rows, then weight rows
+    // LDS: three X buffers of BM rows x 128 bytes (unpadded: the loads that fill them write whole
+    // kilobytes; the 16-byte chunks of a row are permuted instead, see x_swizzle), then two weight
+    // buffers of 128 rows x kLd halves.
+    extern __shared__ _Float16 lds[];
+    constexpr int kXBufHalves = BM * kBK;
+    constexpr int kWBufHalves = kBN * kLd;
+    _Float16 *const lds_w = lds + 3 * kXBufHalves;
 
     // Tile order: bands of two m-tiles, n fastest inside a band; when the tile count divides by 8
     // every XCD (blocks go round-robin over the 8 XCDs) gets one contiguous run of that order.
@@ -165,35 +206,21 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
     // Both roles pass the block's barrier exactly 1 + nk times: once when step 0 is staged, then
     // once per step (the consumers in the middle of the step's last k-batch).
-    if (wave >= kConsumers) {
+    if (wave >= kConsumers && wave < kConsumers + kProducers) {
         // ======================================= producers =====================================
-        constexpr int kAPasses = BM / 32;               // 256 threads move 32 rows x 128 bytes per pass
         const int ptid = tid - 64 * kConsumers;
-        const int a_row = ptid >> 3, a_chunk = ptid & 7;   // 8 threads cover one 128-byte row of a step
         const int b_n_local = ptid >> 1, b_h = ptid & 1;
         int b_n = n0 + b_n_local;
         const bool b_valid = b_n < N;
         b_n = b_valid ? b_n : N - 1;                    // clamped: loads stay in bounds, tile row unused
         const DecodeConsts dc(BITS);
 
-        const _Float16 *a_src[kAPasses];
-#pragma unroll
-        for (int p = 0; p < kAPasses; ++p) {
-            int m = m0 + p * 32 + a_row;
-            m = m < M ? m : M - 1;
-            a_src[p] = X + (size_t)m * K + 8 * a_chunk;
-        }
-        const uint32_t row_group = (uint32_t)b_n * gpr;
-        const uint32_t *q_row = qweight + (size_t)row_group * wpg;
-        _Float16 *const a_dst = lds + a_row * kLd + 8 * a_chunk;            // + buffer, + pass * 32 rows
-        _Float16 *const b_dst = lds + (BM + b_n_local) * kLd;               // + buffer
+        const uint32_t *q_row = qweight + (size_t)b_n * gpr * wpg;
+        const GroupRecord *r_row = rec + (size_t)b_n * (gpr + 1);
+        _Float16 *const b_dst = lds_w + b_n_local * kLd;                    // + buffer
 
-        auto issue_a = [&](int step, u32x4 dst[kAPasses]) {
-            const int k0 = (step < nk ? step : nk - 1) * kBK;
-#pragma unroll
-            for (int p = 0; p < kAPasses; ++p) dst[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k0);
-        };
-        // first = CSR index of the group's first entry (it depends on counts fetched long before).
+        // Requests for group g (clamped: the last trips ask for groups past the row's end and use
+        // none of it); first = CSR index of its first entry.
         auto issue_group = [&](int g, int first, GroupRegs<BITS> &G) {
             g = g < gpr ? g : gpr - 1;
             const uint32_t *grp = q_row + (uint32_t)g * wpg;
@@ -202,31 +229,22 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             const int j = first + 4 * b_h < last_entry ? first + 4 * b_h : last_entry;   // arrays carry 16 spare bytes
             const U64a2 c = *reinterpret_cast<const U64a2 *>(col_idx + j), v = *reinterpret_cast<const U64a2 *>(out_val + j);
             G.col_lo = c.lo; G.col_hi = c.hi; G.val_lo = v.lo; G.val_hi = v.hi;
+            const GroupRecord r = r_row[g + 1];
+            G.next_first = r.first; G.next_scale_zero = r.scale_zero;
         };
-        // Groups 4q .. 4q+3 (reads past the row or the array stay inside the padded buffers).
-        auto issue_meta = [&](int q, MetaRegs &Q) {
-            const int g = 4 * q < gpr ? 4 * q : 0;
-            const U64a2 sc = *reinterpret_cast<const U64a2 *>(scales + row_group + g);
-            Q.sc = (uint64_t)sc.hi << 32 | sc.lo;
-            Q.zp = reinterpret_cast<const U32a1 *>(zeros + row_group + g)->v;
-            Q.cnt = reinterpret_cast<const U32a1 *>(grp_cnt + row_group + g)->v;
-        };
-        auto meta_scale = [](const MetaRegs &Q, int g) -> uint32_t {
-            const uint32_t h = (uint32_t)(Q.sc >> (16 * (g & 3))) & 0xFFFFu;      // a shift, not a choice of fields
-            return h | h << 16;
-        };
-        auto meta_zero = [](const MetaRegs &Q, int g) -> uint32_t { return (Q.zp >> (8 * (g & 3))) & 0xFFu; };
-        auto meta_count = [&](const MetaRegs &Q, int g) -> int { return b_valid ? (int)((Q.cnt >> (8 * (g & 3))) & 0xFFu) : 0; };
 
-        // Staging of step `step` into buffer `buf`: this thread's 32 columns of weights, then its four
+        // Staging of step `step` (of a group with scale and zero point sz, `cnt` outliers from CSR
+        // index `first`) into buffer `buf`: this thread's 32 columns of weights, then its four
         // outlier entries (anywhere in the step's 64 columns: the thread that decoded those columns
-        // is the lane next to this one and its stores were issued before), then the X rows, whose
-        // registers are refilled with the rows of two steps later.
-        auto stage = [&](int step, int buf, u32x4 a_regs[kAPasses], const GroupRegs<BITS> &G, const MetaRegs &Q,
-                         int first) {
-            _Float16 *A = a_dst + buf * kBufHalves, *brow = b_dst + buf * kBufHalves;
-            const int half = step & 1, g = step >> 1;
-            const uint32_t s2 = meta_scale(Q, g), z = meta_zero(Q, g);
+        // is the lane next to this one and its stores were issued before).  The outlier stores are
+        // unconditional: an entry that is absent or outside this step goes to column 64, the row's
+        // padding.  (Stores under a condition would sit in branches, and there the compiler waits
+        // for every load in flight before it touches a loaded value.)
+        uint32_t out_col[4];                            // columns of the group's entries; 0x10000 = no entry
+        auto stage = [&](int step, int buf, const GroupRegs<BITS> &G, uint32_t sz, int first, int cnt) {
+            _Float16 *brow = b_dst + buf * kWBufHalves;
+            const int half = step & 1;
+            const uint32_t s2 = (sz & 0xFFFFu) * 0x10001u, z = sz >> 16;
             if constexpr (BITS == 4) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -237,79 +255,114 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 #pragma unroll
                 for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
             }
-            const int cnt = meta_count(Q, g);
+            cnt = step < nk ? cnt : 0;
             const uint32_t k_lo = (uint32_t)(step * kBK);
             const uint32_t cs[2] = {G.col_lo, G.col_hi}, vs[2] = {G.val_lo, G.val_hi};
+            if (half == 0) {                            // the group's first step: keep the columns for its second
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    out_col[i] = 4 * b_h + i < cnt ? (cs[i >> 1] >> (16 * (i & 1))) & 0xFFFFu : 0x10000u;
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const uint32_t col = ((cs[i >> 1] >> (16 * (i & 1))) & 0xFFFFu) - k_lo;
-                if (4 * b_h + i < cnt && col < (uint32_t)kBK)
-                    brow[col] = __builtin_bit_cast(_Float16, (uint16_t)(vs[i >> 1] >> (16 * (i & 1))));
+                const uint32_t t = out_col[i] - k_lo;   // >= 64 for 0x10000 (k_lo <= 65536 - 64) and for other steps' columns
+                brow[t < (uint32_t)kBK ? t : (uint32_t)kBK] = __builtin_bit_cast(_Float16, (uint16_t)(vs[i >> 1] >> (16 * (i & 1))));
             }
             if (b_h == 0)
                 for (int i = kAhead; i < cnt; ++i) {    // rare: more than kAhead outliers in one group
                     const uint32_t c = load_u16_now(col_idx + first + i) - k_lo;
                     if (c < (uint32_t)kBK) brow[c] = __builtin_bit_cast(_Float16, (uint16_t)load_u16_now(out_val + first + i));
                 }
-            const int k2 = (step + 2 < nk ? step + 2 : nk - 1) * kBK;
-#pragma unroll
-            for (int p = 0; p < kAPasses; ++p) {
-                *reinterpret_cast<u32x4 *>(A + p * 32 * kLd) = a_regs[p];
-                a_regs[p] = *reinterpret_cast<const u32x4 *>(a_src[p] + k2);
-            }
         };
 
-        // Prologue: metadata of groups 0..7, codes and outliers of groups 0 and 1, the X rows of
-        // steps 0 and 1; step 0 staged.
-        MetaRegs Qc, Qn;                                // groups 4q .. 4q+3 and the four after them
+        // Prologue: records of groups 0 and 1, codes and outliers of groups 0 and 1; step 0 staged.
         GroupRegs<BITS> G0, G1;                         // even groups, odd groups
-        u32x4 a0[kAPasses], a1[kAPasses];               // X rows of the even / odd step being staged
-        int first_c = b_valid ? row_ptr[b_n] : 0;       // CSR index of the current group's first entry
-        issue_meta(0, Qc);
-        issue_meta(1, Qn);
-        issue_a(0, a0);
-        issue_a(1, a1);
+        const GroupRecord r0 = r_row[0], r1 = r_row[1];
+        int first_c = r0.first, first_n = r1.first;     // current group, next group
+        uint32_t sz_c = r0.scale_zero, sz_n = r1.scale_zero;
         issue_group(0, first_c, G0);
-        int first_n = first_c + meta_count(Qc, 0);
         issue_group(1, first_n, G1);
-        stage(0, 0, a0, G0, Qc, first_c);               // refills a0 with the rows of step 2
+        stage(0, 0, G0, sz_c, first_c, first_n - first_c);
         __syncthreads();
 
-        // One group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, a1 holds the X
-        // rows of step 2g + 1, a0 those of step 2g + 2 (in flight), Gcur is group g, Gnxt is group
-        // g + 1 (in flight), Qc covers group g, Qn the four groups after Qc's.  Gcur is refilled with
-        // group g + 2 at the end, so the two register sets swap roles from trip to trip and a set
-        // is never copied (a copy would have to wait for loads that were only just issued).
+        // One group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, Gcur is group g
+        // and Gnxt group g + 1 (in flight, with the record of group g + 2).  As soon as Gcur's second
+        // half is staged its registers are refilled with group g + 2, two steps before its first
+        // use, so the two register sets swap roles from trip to trip and a set is never copied (a
+        // copy would have to wait for loads that were only just issued).  The body has no branch
+        // around a request: the compiler's count of loads in flight stays exact.
         // (The scheduling fences keep every request where it is written: left alone, the compiler moves
         // loads down towards their use, and then waits for them.)
         auto trip = [&](int g, GroupRegs<BITS> &Gcur, GroupRegs<BITS> &Gnxt) {
-            stage(2 * g + 1, 1, a1, Gcur, Qc, first_c); // second half of group g, while step 2g multiplies
+            stage(2 * g + 1, 1, Gcur, sz_c, first_c, first_n - first_c);      // second half of group g, while step 2g multiplies
+            __builtin_amdgcn_sched_barrier(0);
+            const int first_nn = Gnxt.next_first;       // group g + 2
+            const uint32_t sz_nn = Gnxt.next_scale_zero;
+            issue_group(g + 2, first_nn, Gcur);
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
-            const bool roll = (g & 3) == 3;             // group g + 1 starts the next four
-            if (g + 1 < gpr) {
-                MetaRegs Qs;                            // selected by value: a reference would pin both in memory
-                Qs.sc = roll ? Qn.sc : Qc.sc;
-                Qs.zp = roll ? Qn.zp : Qc.zp; Qs.cnt = roll ? Qn.cnt : Qc.cnt;
-                stage(2 * g + 2, 0, a0, Gnxt, Qs, first_n);   // first half of group g + 1, while step 2g + 1 multiplies
-            }
+            stage(2 * g + 2, 0, Gnxt, sz_n, first_n, first_nn - first_n);     // first half of group g + 1 (past the end: unused)
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
-            if (roll) {
-                Qc = Qn;
-                issue_meta((g + 1) / 4 + 1, Qn);
-            }
-            first_c = first_n;
-            first_n = first_c + meta_count(Qc, g + 1);
-            issue_group(g + 2, first_n, Gcur);
-            __builtin_amdgcn_sched_barrier(0);
+            first_c = first_n; sz_c = sz_n;
+            first_n = first_nn; sz_n = sz_nn;
         };
         int g = 0;
-        for (; g + 1 < gpr; g += 2) {                   // no path skips half of the body: the compiler's count of
-            trip(g, G0, G1);                            // loads in flight at the top of the loop stays exact
+        for (; g + 1 < gpr; g += 2) {
+            trip(g, G0, G1);
             trip(g + 1, G1, G0);
         }
         if (g < gpr) trip(g, G0, G1);
+        return;
+    }
+
+    if (wave >= kConsumers) {
+        // ========================================= loaders =====================================
+        // Four waves copy the X rows of every step from memory straight into LDS: a load with an
+        // LDS destination writes lane l's 16 bytes at (wave-uniform base) + 16 l, so one instruction
+        // fills eight consecutive 128-byte rows, lane l fetching the chunk that belongs at position
+        // l % 8 of its row.  Step t + 2 is requested when the barrier of step t - 1 has released its
+        // buffer; before the barrier of step t everything but those newest requests has arrived.
+        // Address form: 64-bit scalar base (advanced per step by scalar adds) + 32-bit lane offset,
+        // so a request costs no vector instruction besides the load itself.
+        constexpr int kInstr = BM / 8 / kLoaders;       // per wave and step
+        const int lw = wave - kConsumers - kProducers, lr = lane >> 3;
+        uint32_t row_off[kInstr];                       // bytes from the tile's first row and the step's first column
+#pragma unroll
+        for (int j = 0; j < kInstr; ++j) {
+            const int r = 8 * (lw * kInstr + j) + lr;
+            const int rc = m0 + r < M ? r : M - 1 - m0;
+            row_off[j] = (uint32_t)rc * (uint32_t)K * 2u + 16u * (uint32_t)((lane & 7) ^ x_swizzle(r));
+        }
+        const char *tile = reinterpret_cast<const char *>(X + (size_t)m0 * K);
+        const uint32_t lds_x = (uint32_t)(uintptr_t)lds + (uint32_t)(lw * kInstr) * 1024u;
+        auto issue_x = [&](int step, int buf) {
+            const char *src = tile + (size_t)step * (kBK * 2);
+            const uint32_t dst = lds_x + (uint32_t)buf * (uint32_t)(kXBufHalves * 2);
+#pragma unroll
+            for (int j = 0; j < kInstr; ++j)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :: "s"(dst + j * 1024u), "v"(row_off[j]), "s"(src) : "memory");   // nothing else in this kernel uses m0
+        };
+        issue_x(0, 0);
+        if (nk > 1) {
+            issue_x(1, 1);
+            wait_vm<kInstr>();
+        } else {
+            wait_vm<0>();
+        }
+        __builtin_amdgcn_s_barrier();              // no fence: the explicit waits above are the ordering
+        int buf = 2;                                    // buffer of step t + 2
+        for (int t = 0; t < nk; ++t) {
+            if (t + 2 < nk) {
+                issue_x(t + 2, buf);
+                wait_vm<kInstr>();
+            } else {
+                wait_vm<0>();
+            }
+            __builtin_amdgcn_s_barrier();              // no fence: the explicit waits above are the ordering
+            buf = buf == 2 ? 0 : buf + 1;
+        }
         return;
     }
 
@@ -324,15 +377,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int fi = lane & 31, fk = lane >> 5;           // fragment row and k-block of this lane
-    const _Float16 *a_frag = lds + (wm * (BM / 4) + fi) * kLd + 8 * fk;
-    const _Float16 *b_frag = lds + (BM + wn * 64 + fi) * kLd + 8 * fk;
+    const _Float16 *b_frag = lds_w + (wn * 64 + fi) * kLd + 8 * fk;
+    const _Float16 *a_frag[4];                          // per k-batch: the row's chunk 2s + fk, where the permutation puts it
+#pragma unroll
+    for (int s = 0; s < 4; ++s) a_frag[s] = lds + (wm * (BM / 4) + fi) * kBK + 8 * ((2 * s + fk) ^ x_swizzle(fi));
 
     // Fragments of the k-batch being multiplied and of the one after it (16 columns each).
     u32x4 fa[2][MSW], fb[2][2];
-    auto read_frags = [&](int buf, int s, u32x4 a[MSW], u32x4 b[2]) {
-        const _Float16 *A = a_frag + buf * kBufHalves, *B = b_frag + buf * kBufHalves;
+    auto read_frags = [&](int xbuf, int buf, int s, u32x4 a[MSW], u32x4 b[2]) {
+        const _Float16 *A = a_frag[s] + xbuf, *B = b_frag + buf * kWBufHalves;
 #pragma unroll
-        for (int i = 0; i < MSW; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kLd + 16 * s);
+        for (int i = 0; i < MSW; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kBK);
 #pragma unroll
         for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
     };
@@ -348,31 +403,34 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
 
     __syncthreads();                                    // step 0 is staged
-    read_frags(0, 0, fa[0], fb[0]);
+    read_frags(0, 0, 0, fa[0], fb[0]);
+    int xbuf = 0;                                       // halves from the first X buffer to the step's
     // One step: each k-batch first requests the fragments of the batch after it, then multiplies.
     // The barrier sits in the middle of the last batch: behind it the first fragments of the next
     // step are requested while the rest of the batch still multiplies.
     constexpr int h = MSW >= 2 ? MSW / 2 : 1;           // rows of the last batch ahead of the barrier
     for (int step = 0; step < nk; ++step) {
         const int buf = step & 1;
-        read_frags(buf, 1, fa[1], fb[1]);
+        const int xnext = xbuf == 2 * kXBufHalves ? 0 : xbuf + kXBufHalves;
+        read_frags(xbuf, buf, 1, fa[1], fb[1]);
         fence();
         mfma_rows(0, 0, MSW);
         fence();
-        read_frags(buf, 2, fa[0], fb[0]);
+        read_frags(xbuf, buf, 2, fa[0], fb[0]);
         fence();
         mfma_rows(1, 0, MSW);
         fence();
-        read_frags(buf, 3, fa[1], fb[1]);
+        read_frags(xbuf, buf, 3, fa[1], fb[1]);
         fence();
         mfma_rows(2, 0, MSW);
         fence();
         mfma_rows(3, 0, h);
         fence();
         __syncthreads();
-        read_frags(buf ^ 1, 0, fa[0], fb[0]);
+        read_frags(xnext, buf ^ 1, 0, fa[0], fb[0]);
         fence();
         mfma_rows(3, h, MSW);
+        xbuf = xnext;
     }
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
@@ -390,11 +448,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 }
 
 template <int BITS, int MSW>
-hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, uint8_t *grp_cnt, hipStream_t st)
+hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, hipStream_t st)
 {
     constexpr int BM = 128 * MSW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
-    const size_t lds = (size_t)2 * (BM + kBN) * kLd * sizeof(_Float16);
+    const size_t lds = ((size_t)3 * BM * kBK + (size_t)2 * kBN * kLd) * sizeof(_Float16);
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW>),
@@ -403,26 +461,26 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, uint8_t
         attr_set = true;
     }
     gemm_kernel<BITS, MSW><<<tiles_m * tiles_n, kThreads, lds, st>>>(
-        P.qweight, P.scales, P.zeros, P.row_ptr, P.col_idx, P.out_val, grp_cnt, static_cast<const _Float16 *>(X),
+        P.qweight, P.col_idx, P.out_val, rec, static_cast<const _Float16 *>(X),
         static_cast<_Float16 *>(Y), P.N, P.K, M, tiles_m, tiles_n, P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
     return hipGetLastError();
 }
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t N, int64_t K) { return (size_t)(N * (K / kGroup) + 255) / 256 * 256 + 256; }
+size_t gemm_workspace_bytes(int64_t N, int64_t K) { return (size_t)(N * (K / kGroup + 1)) * sizeof(GroupRecord); }
 
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,
                        hipStream_t st)
 {
-    uint8_t *cnt = static_cast<uint8_t *>(workspace);
-    group_count_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.N, P.K / kGroup, cnt);
+    GroupRecord *rec = static_cast<GroupRecord *>(workspace);
+    group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.scales, P.zeros, P.N, P.K / kGroup, rec);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // Rows per tile: 256 unless M is small (the override is in rows: 64 and 128 both mean 128).
     const int msw = ms_override ? (ms_override >= 4 ? 2 : 1) : M <= 128 ? 1 : 2;
-    if (P.bits == 4) return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, cnt, st) : launch_ms<4, 2>(P, X, M, Y, cnt, st);
-    return msw == 1 ? launch_ms<3, 1>(P, X, M, Y, cnt, st) : launch_ms<3, 2>(P, X, M, Y, cnt, st);
+    if (P.bits == 4) return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, rec, st) : launch_ms<4, 2>(P, X, M, Y, rec, st);
+    return msw == 1 ? launch_ms<3, 1>(P, X, M, Y, rec, st) : launch_ms<3, 2>(P, X, M, Y, rec, st);
 }
 
 }  // namespace gwq

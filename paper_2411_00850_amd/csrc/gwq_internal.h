@@ -31,7 +31,8 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
                        uint32_t *ws, hipStream_t stream);
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
                          int waves_override, hipStream_t stream);
-// workspace: gemm_workspace_bytes(N, K) bytes of device scratch (outlier counts per channel and group).
+// workspace: gemm_workspace_bytes(N, K) bytes of device scratch, 8-byte aligned (one record per channel
+// and group: index of the group's first outlier, scale, zero point).
 size_t gemm_workspace_bytes(int64_t N, int64_t K);
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,
                        hipStream_t stream);

@@ -39,7 +39,7 @@ def test_layout_sizes_7b_shapes():
     total = sum(s[k] for k in ("qweight", "scales", "zeros", "row_ptr", "col_idx", "out_val"))
     assert abs(total / 4096 ** 2 - 0.5644) < 1e-3
     assert gwq.layout(8, 128, 4, ppm=0)["col_idx"] == 16          # never a zero-size buffer
-    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4, M_max=2048)["linear_workspace"] == 4096 * 32 + 256
+    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4, M_max=2048)["linear_workspace"] == 4096 * 33 * 8     # one 8-byte record per channel and group, plus one
     small = gwq.layout(3, 128, 4)                                  # 3 groups: padded to one vector
     assert small["scales"] == 32 and small["zeros"] == 32
 
