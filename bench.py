@@ -11,7 +11,8 @@ from HBM rather than from the 256 MB last-level cache, as a decode pass over a w
 One JSON line is printed.  `value` is the algorithmic GB/s of the timed steps (packed bytes + X + Y
 per step over wall time, inputs resident in HBM).  `roofline` is the decode kernel alone: algorithmic
 bytes per launch over the average launch duration measured with HIP events on the launch stream.
-Further objects report the same pass at M = 4 and 16, the prefill GEMM (M = 2048) in TFLOP/s, gwq_pack,
+Further objects report the same pass at M = 4 and 16, the prefill GEMM (M = 2048) in TFLOP/s (through
+gwq_linear, and through gwq_linear_indexed with the per-layer index built beforehand), gwq_pack,
 and the CPU oracle timed on a bounded sample (`cpu_baseline`).
 """
 import argparse
@@ -256,26 +257,35 @@ def main():
             del Ps, P0, calls, graph
             torch.cuda.empty_cache()
         extra["decode_M1_70b_shapes"] = big
-        # prefill: M = 2048 over the 7 matrices, one copy (compute-bound)
+        # prefill: M = 2048 over the 7 matrices, one copy (compute-bound).  Two ways: gwq_linear, which
+        # rebuilds its per-layer index in the workspace on every call, and gwq_linear_indexed with the
+        # index built once per layer beforehand (it depends on the weights only).
         M = 2048
         xs, ys = make_xy(M)
-        for _ in range(3):
-            for j, P in enumerate(layers):
-                gwq.linear(P, xs[P.K], out=ys[j])
-        torch.cuda.synchronize()
-        reps = 10
-        t = time.perf_counter()
-        for _ in range(reps):
-            for j, P in enumerate(layers):
-                gwq.linear(P, xs[P.K], out=ys[j])
-        torch.cuda.synchronize()
-        s = (time.perf_counter() - t) / reps
         fl = sum(flops(P, M) for P in layers)
-        extra["prefill_M2048"] = {"TFLOP/s": round(fl / s / 1e12, 1), "ms_per_pass": round(s * 1e3, 4),
-                                  "pct_mfma_f16_peak": round(100 * fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 2),
-                                  "roofline": {"bound": "mfma", "achieved": round(fl / s / 1e12, 1),
-                                               "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                               "frac": round(fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
+
+        def time_prefill(calls, reps=10):
+            for _ in range(3):
+                for c in calls:
+                    c()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                for c in calls:
+                    c()
+            torch.cuda.synchronize()
+            s = (time.perf_counter() - t) / reps
+            return {"TFLOP/s": round(fl / s / 1e12, 1), "ms_per_pass": round(s * 1e3, 4),
+                    "pct_mfma_f16_peak": round(100 * fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 2),
+                    "roofline": {"bound": "mfma", "achieved": round(fl / s / 1e12, 1),
+                                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                 "frac": round(fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
+
+        extra["prefill_M2048"] = time_prefill([gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(layers)])
+        indexes = [gwq.linear_index(P) for P in layers]
+        extra["prefill_M2048_indexed"] = time_prefill(
+            [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(layers)])
+        del indexes
         del xs, ys
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
         pk = {}

@@ -111,6 +111,20 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* gwq_linear in two parts, for weights that stay while activations change.  What gwq_linear writes
+ * into its workspace for M > 16 depends on the packed layer alone (per channel and group: where the
+ * group's outliers start, its scale and zero point), so it can be built once, when the layer is
+ * loaded:
+ *   gwq_linear_index   fills `index` (device, >= linear_workspace bytes as reported by gwq_layout
+ *                      for an M_max > 16, 16-byte aligned) from P;
+ *   gwq_linear_indexed is gwq_linear with that index in place of the workspace; it only reads it,
+ *                      so concurrent calls may share one index.  For M <= 16 the index is not
+ *                      used and may be NULL.
+ * The index is valid until P's buffers change.  Same results, bit for bit, as gwq_linear. */
+gwq_status gwq_linear_index(const gwq_packed *P, void *index, size_t index_bytes, void *stream);
+gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
+                              const void *index, size_t index_bytes, void *stream);
+
 /* Several layers in ONE decode launch (M <= 16): Y_f16[i] = gwq_linear(P[i], X_f16[i]) for
  * i < count <= GWQ_MAX_BATCH.  For layers with no data dependence between them, such as the q, k
  * and v or the gate and up projections of a decoder layer (which may share one X): at decode sizes a

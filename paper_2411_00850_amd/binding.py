@@ -56,6 +56,10 @@ def lib():
         L.gwq_pack.argtypes = [vp, vp, ctypes.c_int, ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
         L.gwq_linear.restype = ctypes.c_int
         L.gwq_linear.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.gwq_linear_index.restype = ctypes.c_int
+        L.gwq_linear_index.argtypes = [ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
+        L.gwq_linear_indexed.restype = ctypes.c_int
+        L.gwq_linear_indexed.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
         L.gwq_linear_batch.restype = ctypes.c_int
         L.gwq_linear_batch.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), ctypes.POINTER(vp), i32,
                                        ctypes.POINTER(vp), vp]
@@ -163,13 +167,33 @@ def linear_workspace(P, M, device="cuda"):
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
 
 
-def linear(P, X, out=None, stream=None, workspace=None):
-    """gwq_linear: X FP16 [M, K] on the GPU -> Y FP16 [M, N]."""
+def linear_index(P, stream=None):
+    """gwq_linear_index: the per-layer index gwq_linear_indexed reads for M > 16 (a uint8 tensor).  Build it
+    once per packed layer; it stays valid until the layer's buffers change."""
+    import torch
+    index = linear_workspace(P, 17, P.qweight.device)
+    cs = P.c_struct()
+    rc = lib().gwq_linear_index(ctypes.byref(cs), index.data_ptr(), index.numel(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_linear_index")
+    return index
+
+
+def linear(P, X, out=None, stream=None, workspace=None, index=None):
+    """gwq_linear: X FP16 [M, K] on the GPU -> Y FP16 [M, N].  With `index` (from linear_index) the call
+    is gwq_linear_indexed and needs no workspace."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
     M = X.shape[0]
     if out is None:
         out = torch.empty((M, P.N), dtype=torch.float16, device=X.device)
+    if index is not None:
+        cs = P.c_struct()
+        rc = lib().gwq_linear_indexed(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), index.data_ptr(),
+                                      index.numel(), _stream_ptr(stream))
+        if rc != GWQ_OK:
+            raise GwqError(rc, "gwq_linear_indexed")
+        return out
     if workspace is None:
         workspace = linear_workspace(P, M, X.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
@@ -181,18 +205,19 @@ def linear(P, X, out=None, stream=None, workspace=None):
     return out
 
 
-def prepare_linear(P, X, out):
+def prepare_linear(P, X, out, index=None):
     """Pre-marshalled gwq_linear call for launch-bound loops: returns a zero-argument callable that
     enqueues the same call on whatever torch stream is current when it is invoked (so it can be
-    captured into a HIP graph).  P, X and out must stay alive while the callable is used."""
+    captured into a HIP graph).  P, X and out must stay alive while the callable is used.  With
+    `index` (from linear_index) the call is gwq_linear_indexed."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
     assert out.shape == (X.shape[0], P.N) and out.dtype == torch.float16 and out.is_contiguous()
     cs = P.c_struct()
     ref = ctypes.byref(cs)
-    fn = lib().gwq_linear
+    fn = lib().gwq_linear if index is None else lib().gwq_linear_indexed
     xp, yp, M = ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(out.data_ptr()), X.shape[0]
-    ws = linear_workspace(P, M, X.device)
+    ws = linear_workspace(P, M, X.device) if index is None else index
     wp = ctypes.c_void_p(ws.data_ptr()) if ws is not None else None
     wl = ws.numel() if ws is not None else 0
     current_stream = torch.cuda.current_stream
@@ -200,7 +225,7 @@ def prepare_linear(P, X, out):
     def call(_keep=(cs, P, X, out, ws)):
         rc = fn(ref, xp, M, yp, wp, wl, ctypes.c_void_p(current_stream().cuda_stream))
         if rc != GWQ_OK:
-            raise GwqError(rc, "gwq_linear")
+            raise GwqError(rc, "gwq_linear" if index is None else "gwq_linear_indexed")
     return call
 
 

@@ -34,6 +34,22 @@ gwq_status check_packed(const gwq_packed *P)
     return GWQ_OK;
 }
 
+// Shared argument checks of the gwq_linear variants; `index` is the workspace or the prebuilt index.
+gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const void *Y_f16, const void *index,
+                        size_t index_bytes)
+{
+    gwq_status s = check_packed(P);
+    if (s != GWQ_OK) return s;
+    if (!X_f16 || !Y_f16) return GWQ_ERR_NULL;
+    if (M < 1 || (int64_t)M * P->N >= ((int64_t)1 << 40)) return GWQ_ERR_SHAPE;
+    if (((uintptr_t)X_f16 | (uintptr_t)P->qweight | (uintptr_t)P->scales | (uintptr_t)P->zeros |
+         (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
+        return GWQ_ERR_SHAPE;
+    if (M > 16 && (!index || index_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
+    if (M > 16 && ((uintptr_t)index & 15)) return GWQ_ERR_SHAPE;
+    return GWQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -78,18 +94,37 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
+    gwq_status s = check_linear(P, X_f16, M, Y_f16, workspace, workspace_bytes);
+    if (s != GWQ_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (M <= 16) {
+        e = gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st);
+    } else {
+        e = gwq::launch_gemm_index(*P, workspace, st);
+        if (e == hipSuccess) e = gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, g_gemm_ms, st);
+    }
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_linear_index(const gwq_packed *P, void *index, size_t index_bytes, void *stream)
+{
     gwq_status s = check_packed(P);
     if (s != GWQ_OK) return s;
-    if (!X_f16 || !Y_f16) return GWQ_ERR_NULL;
-    if (M < 1 || (int64_t)M * P->N >= ((int64_t)1 << 40)) return GWQ_ERR_SHAPE;
-    if (((uintptr_t)X_f16 | (uintptr_t)P->qweight | (uintptr_t)P->scales | (uintptr_t)P->zeros |
-         (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
-        return GWQ_ERR_SHAPE;
-    if (M > 16 && (!workspace || workspace_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
-    if (M > 16 && ((uintptr_t)workspace & 15)) return GWQ_ERR_SHAPE;
+    if (!index || index_bytes < gwq::gemm_workspace_bytes(P->N, P->K)) return GWQ_ERR_WORKSPACE;
+    if ((uintptr_t)index & 15) return GWQ_ERR_SHAPE;
+    hipError_t e = gwq::launch_gemm_index(*P, index, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, const void *index,
+                              size_t index_bytes, void *stream)
+{
+    gwq_status s = check_linear(P, X_f16, M, Y_f16, index, index_bytes);
+    if (s != GWQ_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st)
-                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, g_gemm_ms, st);
+                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, index, g_gemm_ms, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 

@@ -470,13 +470,17 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
 
 size_t gemm_workspace_bytes(int64_t N, int64_t K) { return (size_t)(N * (K / kGroup + 1)) * sizeof(GroupRecord); }
 
-hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,
+hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t st)
+{
+    group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.scales, P.zeros, P.N, P.K / kGroup,
+                                                     static_cast<GroupRecord *>(workspace));
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *workspace, int ms_override,
                        hipStream_t st)
 {
-    GroupRecord *rec = static_cast<GroupRecord *>(workspace);
-    group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.scales, P.zeros, P.N, P.K / kGroup, rec);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const GroupRecord *rec = static_cast<const GroupRecord *>(workspace);
     // Rows per tile: 256 unless M is small (the override is in rows: 64 and 128 both mean 128).
     const int msw = ms_override ? (ms_override >= 4 ? 2 : 1) : M <= 128 ? 1 : 2;
     if (P.bits == 4) return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, rec, st) : launch_ms<4, 2>(P, X, M, Y, rec, st);

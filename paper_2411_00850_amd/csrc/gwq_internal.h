@@ -34,7 +34,8 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 // workspace: gemm_workspace_bytes(N, K) bytes of device scratch, 8-byte aligned (one record per channel
 // and group: index of the group's first outlier, scale, zero point).
 size_t gemm_workspace_bytes(int64_t N, int64_t K);
-hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, void *workspace, int ms_override,
-                       hipStream_t stream);
+hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t stream);    // fills the records
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *workspace, int ms_override,
+                       hipStream_t stream);                                                // reads them
 
 }  // namespace gwq

@@ -18,7 +18,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_calls():
-    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_pack",
+    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_index",
+                                    "gwq_linear_indexed", "gwq_pack",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
 
@@ -90,6 +91,25 @@ def test_pack_and_linear_validate_before_touching_the_device():
     assert L.gwq_linear(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4       # M > 16 needs scratch
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, fake, 8, None) == -4
+
+
+def test_linear_index_validates_before_touching_the_device():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ok = _packed()
+    need = gwq.layout(4, 128, 4, M_max=17)["linear_workspace"]
+    assert need == 4 * 2 * 8
+    assert L.gwq_linear_index(None, fake, need, None) == -1
+    assert L.gwq_linear_index(ctypes.byref(ok), None, need, None) == -4
+    assert L.gwq_linear_index(ctypes.byref(ok), fake, need - 1, None) == -4
+    assert L.gwq_linear_index(ctypes.byref(ok), ctypes.c_void_p(0x1008), need, None) == -2
+    assert L.gwq_linear_index(ctypes.byref(_packed(bits=5)), fake, need, None) == -3
+    assert L.gwq_linear_indexed(None, fake, 17, fake, fake, need, None) == -1
+    assert L.gwq_linear_indexed(ctypes.byref(ok), None, 17, fake, fake, need, None) == -1
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 0, fake, fake, need, None) == -2
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4      # M > 16 needs the index
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need - 1, None) == -4
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, ctypes.c_void_p(0x1004), need, None) == -2
 
 
 def test_linear_batch_validates_before_touching_the_device():

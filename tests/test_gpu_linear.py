@@ -152,6 +152,40 @@ def test_gemm_outlier_extremes(ppm):
     assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm ppm={ppm}")
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,ppm", [(200, 1024, 10000), (72, 11008, 10000), (160, 512, 1000000), (50, 384, 0)])
+def test_linear_index_contents(bits, N, K, ppm):
+    """gwq_linear_index: one 8-byte record per channel and group (plus one that closes the row) holding
+    where the group's CSR entries start, its scale and its zero point -- recomputed here from the
+    packed arrays with a sorted search."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import upload_packed
+    P, _ = _problem(77 + bits, N, K, bits, ppm=ppm)
+    rec = gwq.linear_index(upload_packed(P)).cpu().numpy().view(np.uint32).reshape(N, K // 128 + 1, 2)
+    gpr = K // 128
+    for n in range(N):
+        lo, hi = int(P.row_ptr[n]), int(P.row_ptr[n + 1])
+        want = lo + np.searchsorted(P.col_idx[lo:hi].astype(np.int64), 128 * np.arange(gpr + 1))
+        assert np.array_equal(rec[n, :, 0], want), f"first-entry indices of channel {n}"
+        sz = P.scales.reshape(N, gpr)[n].view(np.uint16).astype(np.uint32) | P.zeros.reshape(N, gpr)[n].astype(np.uint32) << 16
+        assert np.array_equal(rec[n, :gpr, 1], sz), f"scale / zero point of channel {n}"
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,M", [(200, 1024, 130), (300, 384, 17), (72, 11008, 300), (128, 256, 5)])
+def test_linear_indexed_equals_linear(bits, N, K, M):
+    """gwq_linear_indexed with a prebuilt index gives gwq_linear's result bit for bit (M <= 16 ignores it),
+    also when one index serves several calls."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu, upload_packed
+    P, rng = _problem(31 + N + bits, N, K, bits)
+    D = upload_packed(P)
+    index = gwq.linear_index(D)
+    for _ in range(2):
+        X = to_gpu(gs.activations(M, K, rng))
+        assert np.array_equal(gwq.linear(D, X, index=index).cpu().numpy(), gwq.linear(D, X).cpu().numpy())
+
+
 # ----------------------------------------------------------------------------- full-size configurations
 
 def test_config1_decode_full():
