@@ -26,6 +26,8 @@
 // kernel writes that index, with the group's scale and zero point, into the workspace first (one
 // 8-byte record per channel and group); a group's first eight entries are fetched ahead by the
 // channel's two threads with unaligned loads (longer runs take a slow path).
+#include <type_traits>
+
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -176,8 +178,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     constexpr int BM = 128 * MSW;
     constexpr int wpg = words_per_group(BITS);
     // LDS: three X buffers of BM rows x 128 bytes (unpadded: the loads that fill them write whole
-    // kilobytes; the 16-byte chunks of a row are permuted instead, see x_swizzle), then two weight
-    // buffers of 128 rows x kLd halves.
+    // kilobytes; the 16-byte chunks of a row are permuted instead, see x_swizzle), then three weight
+    // buffers of 128 rows x kLd halves.  Step t uses buffers t % 3.
     extern __shared__ _Float16 lds[];
     constexpr int kXBufHalves = BM * kBK;
     constexpr int kWBufHalves = kBN * kLd;
@@ -284,8 +286,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         issue_group(1, first_n, G1);
         stage(0, 0, G0, sz_c, first_c, first_n - first_c);
         __syncthreads();
+        int wbuf = 1;                                   // weight buffer of step 2g + 1: (2g + 1) % 3
 
-        // One group (two steps) per trip.  Entering trip g: buffer 0 holds step 2g, Gcur is group g
+        // One group (two steps) per trip.  Entering trip g: step 2g is staged, Gcur is group g
         // and Gnxt group g + 1 (in flight, with the record of group g + 2).  As soon as Gcur's second
         // half is staged its registers are refilled with group g + 2, two steps before its first
         // use, so the two register sets swap roles from trip to trip and a set is never copied (a
@@ -294,14 +297,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         // (The scheduling fences keep every request where it is written: left alone, the compiler moves
         // loads down towards their use, and then waits for them.)
         auto trip = [&](int g, GroupRegs<BITS> &Gcur, GroupRegs<BITS> &Gnxt) {
-            stage(2 * g + 1, 1, Gcur, sz_c, first_c, first_n - first_c);      // second half of group g, while step 2g multiplies
+            stage(2 * g + 1, wbuf, Gcur, sz_c, first_c, first_n - first_c);   // second half of group g
+            wbuf = wbuf == 2 ? 0 : wbuf + 1;
             __builtin_amdgcn_sched_barrier(0);
             const int first_nn = Gnxt.next_first;       // group g + 2
             const uint32_t sz_nn = Gnxt.next_scale_zero;
             issue_group(g + 2, first_nn, Gcur);
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
-            stage(2 * g + 2, 0, Gnxt, sz_n, first_n, first_nn - first_n);     // first half of group g + 1 (past the end: unused)
+            stage(2 * g + 2, wbuf, Gnxt, sz_n, first_n, first_nn - first_n);  // first half of group g + 1 (past the end: unused)
+            wbuf = wbuf == 2 ? 0 : wbuf + 1;
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
             first_c = first_n; sz_c = sz_n;
@@ -321,8 +326,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         // Four waves copy the X rows of every step from memory straight into LDS: a load with an
         // LDS destination writes lane l's 16 bytes at (wave-uniform base) + 16 l, so one instruction
         // fills eight consecutive 128-byte rows, lane l fetching the chunk that belongs at position
-        // l % 8 of its row.  Step t + 2 is requested when the barrier of step t - 1 has released its
-        // buffer; before the barrier of step t everything but those newest requests has arrived.
+        // l % 8 of its row.  Step t + 2 is requested when barrier t - 1 has released its buffer;
+        // before barrier t everything but those newest requests has arrived.
         // Address form: 64-bit scalar base (advanced per step by scalar adds) + 32-bit lane offset,
         // so a request costs no vector instruction besides the load itself.
         constexpr int kInstr = BM / 8 / kLoaders;       // per wave and step
@@ -345,24 +350,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                              :: "s"(dst + j * 1024u), "v"(row_off[j]), "s"(src) : "memory");   // nothing else in this kernel uses m0
         };
         issue_x(0, 0);
-        if (nk > 1) {
-            issue_x(1, 1);
-            wait_vm<kInstr>();
-        } else {
-            wait_vm<0>();
-        }
-        __builtin_amdgcn_s_barrier();              // no fence: the explicit waits above are the ordering
+        issue_x(1, 1);                                  // nk >= 2
+        wait_vm<kInstr>();
+        __builtin_amdgcn_s_barrier();                   // no fence: the explicit waits are the ordering
         int buf = 2;                                    // buffer of step t + 2
         for (int t = 0; t < nk; ++t) {
-            if (t + 2 < nk) {
-                issue_x(t + 2, buf);
-                wait_vm<kInstr>();
-            } else {
-                wait_vm<0>();
-            }
-            __builtin_amdgcn_s_barrier();              // no fence: the explicit waits above are the ordering
+            issue_x(t + 2 < nk ? t + 2 : nk - 1, buf);  // past the end: the last step again, unused
+            wait_vm<kInstr>();
+            __builtin_amdgcn_s_barrier();
             buf = buf == 2 ? 0 : buf + 1;
         }
+        wait_vm<0>();                                   // nothing may still be writing this block's LDS when it ends
         return;
     }
 
@@ -382,56 +380,63 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 #pragma unroll
     for (int s = 0; s < 4; ++s) a_frag[s] = lds + (wm * (BM / 4) + fi) * kBK + 8 * ((2 * s + fk) ^ x_swizzle(fi));
 
-    // Fragments of the k-batch being multiplied and of the one after it (16 columns each).
-    u32x4 fa[2][MSW], fb[2][2];
-    auto read_frags = [&](int xbuf, int buf, int s, u32x4 a[MSW], u32x4 b[2]) {
-        const _Float16 *A = a_frag[s] + xbuf, *B = b_frag + buf * kWBufHalves;
+    // Fragments of three k-batches (16 columns each): the one being multiplied and the two after
+    // it.  With every wave of the block reading, a fragment takes longer to arrive than one batch
+    // of MFMAs lasts, so it is requested two batches ahead.  Batch s of step t uses register set
+    // (t + s) % 3 and LDS buffers t % 3: the loop is unrolled over three steps and all of that is
+    // static.  Barrier t (step t + 1 is staged; steps up to t - 1 are read) comes after batch 1 of
+    // step t, just in time for the request of step t + 1's first fragments.
+    u32x4 fa[3][MSW], fb[3][2];
+    auto read_frags = [&](int buf, int s, int set) {
+        const _Float16 *A = a_frag[s] + buf * kXBufHalves, *B = b_frag + buf * kWBufHalves;
 #pragma unroll
-        for (int i = 0; i < MSW; ++i) a[i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kBK);
+        for (int i = 0; i < MSW; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kBK);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
+        for (int j = 0; j < 2; ++j) fb[set][j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
     };
-    auto mfma_rows = [&](int s, int i0, int i1) {
+    auto mfma_batch = [&](int set) {
 #pragma unroll
-        for (int i = i0; i < i1; ++i)
+        for (int i = 0; i < MSW; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[s & 1][i]),
-                                                                   __builtin_bit_cast(half8, fb[s & 1][j]),
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[set][i]),
+                                                                   __builtin_bit_cast(half8, fb[set][j]),
                                                                    acc[i][j], 0, 0, 0);
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-
-    __syncthreads();                                    // step 0 is staged
-    read_frags(0, 0, 0, fa[0], fb[0]);
-    int xbuf = 0;                                       // halves from the first X buffer to the step's
-    // One step: each k-batch first requests the fragments of the batch after it, then multiplies.
-    // The barrier sits in the middle of the last batch: behind it the first fragments of the next
-    // step are requested while the rest of the batch still multiplies.
-    constexpr int h = MSW >= 2 ? MSW / 2 : 1;           // rows of the last batch ahead of the barrier
-    for (int step = 0; step < nk; ++step) {
-        const int buf = step & 1;
-        const int xnext = xbuf == 2 * kXBufHalves ? 0 : xbuf + kXBufHalves;
-        read_frags(xbuf, buf, 1, fa[1], fb[1]);
+    // One step whose number is p modulo 3.
+    auto one_step = [&](auto phase) {
+        constexpr int p = decltype(phase)::value, q = (p + 1) % 3;
+        read_frags(p, 2, (p + 2) % 3);
         fence();
-        mfma_rows(0, 0, MSW);
+        mfma_batch(p);
         fence();
-        read_frags(xbuf, buf, 2, fa[0], fb[0]);
+        read_frags(p, 3, p);                            // set (p + 3) % 3, free again
         fence();
-        mfma_rows(1, 0, MSW);
-        fence();
-        read_frags(xbuf, buf, 3, fa[1], fb[1]);
-        fence();
-        mfma_rows(2, 0, MSW);
-        fence();
-        mfma_rows(3, 0, h);
+        mfma_batch((p + 1) % 3);
         fence();
         __syncthreads();
-        read_frags(xnext, buf ^ 1, 0, fa[0], fb[0]);
+        read_frags(q, 0, (p + 1) % 3);                  // batch 0 of the next step: set (q + 0) % 3
         fence();
-        mfma_rows(3, h, MSW);
-        xbuf = xnext;
+        mfma_batch((p + 2) % 3);
+        fence();
+        read_frags(q, 1, (p + 2) % 3);
+        fence();
+        mfma_batch(p);
+        fence();
+    };
+
+    __syncthreads();                                    // barrier -1: step 0 is staged
+    read_frags(0, 0, 0);
+    read_frags(0, 1, 1);
+    int step = 0;
+    for (; step + 3 <= nk; step += 3) {
+        one_step(std::integral_constant<int, 0>{});
+        one_step(std::integral_constant<int, 1>{});
+        one_step(std::integral_constant<int, 2>{});
     }
+    if (step < nk) one_step(std::integral_constant<int, 0>{});
+    if (step + 1 < nk) one_step(std::integral_constant<int, 1>{});
 
     // D layout of the 32x32 tile: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
 #pragma unroll
@@ -452,7 +457,7 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
 {
     constexpr int BM = 128 * MSW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
-    const size_t lds = ((size_t)3 * BM * kBK + (size_t)2 * kBN * kLd) * sizeof(_Float16);
+    const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW>),
