@@ -257,6 +257,46 @@ def main():
             del Ps, P0, calls, graph
             torch.cuda.empty_cache()
         extra["decode_M1_70b_shapes"] = big
+        # The same decode pass with FP16 weights through the vendor library (torch's F.linear), as the
+        # paper's efficiency table does (Sec. 4.2: speed and memory against FP16): 7 products per pass,
+        # two rotated copies of the FP16 layer (809 MB), graph replay.  Comparison only, not a product path.
+        try:
+            g16 = torch.Generator(device=dev)
+            g16.manual_seed(7)
+            w16 = [[(torch.randn((P.N, P.K), device=dev, generator=g16, dtype=torch.float32) * 0.02).half()
+                    for P in layers] for _ in range(2)]
+            xs, _ = make_xy(1)
+            outs = [torch.empty((1, P.N), dtype=torch.float16, device=dev) for P in layers]
+
+            def fp16_pass(ws):
+                for j, P in enumerate(layers):
+                    torch.matmul(xs[P.K], ws[j].t(), out=outs[j])
+            for _ in range(3):
+                fp16_pass(w16[0]); fp16_pass(w16[1])
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                fp16_pass(w16[0]); fp16_pass(w16[1])
+            graph.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 50
+            e0.record()
+            for _ in range(reps):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            fp16_ms = e0.elapsed_time(e1) / (2 * reps)
+            fp16_bytes = sum(2 * P.N * P.K for P in layers)
+            packed_bytes = sum(P.nbytes() for P in layers)
+            extra["fp16_library_decode_M1"] = {"ms_per_step": round(fp16_ms, 5), "GB/s": round(fp16_bytes / fp16_ms / 1e6, 1),
+                                               "speedup_of_gwq_int4": round(fp16_ms / (step_s * 1e3), 2),
+                                               "weight_bytes_fp16": fp16_bytes, "weight_bytes_gwq_int4": packed_bytes,
+                                               "memory_ratio": round(fp16_bytes / packed_bytes, 2)}
+            del w16, graph, outs
+            torch.cuda.empty_cache()
+        except Exception as ex:                            # the comparison must not take the benchmark down
+            extra["fp16_library_decode_M1"] = {"error": str(ex)[:200]}
         # prefill: M = 2048 over the 7 matrices, one copy (compute-bound).  Two ways: gwq_linear, which
         # rebuilds its per-layer index in the workspace on every call, and gwq_linear_indexed with the
         # index built once per layer beforehand (it depends on the weights only).
