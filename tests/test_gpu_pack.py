@@ -33,6 +33,24 @@ def test_pack_small_shapes(bits, N, K, ppm):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("ppm", [1000, 5000])
+def test_pack_outlier_fractions_of_the_ablation(bits, ppm):
+    """0.1 % and 0.5 % of the weights kept as outliers (the other fractions of the paper's outlier-ratio
+    table, the one that compares gradient and Hessian localisation), packed and multiplied (decode
+    and GEMM)."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, assert_packed_equal, to_gpu
+    N, K = 160, 2048
+    W, S = _small(40 + ppm, N, K)
+    D, P = _gpu_pack(W, S, bits, ppm), orc.pack(W, S, bits, ppm)
+    assert_packed_equal(D, P)
+    rng = np.random.default_rng(ppm)
+    for M in (1, 40):
+        X = gs.activations(M, K, rng)
+        assert_close(gwq.linear(D, to_gpu(X)).cpu().numpy(), orc.linear_f64(P, X), f"ppm={ppm} M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("kind", ["ties_f32", "f16_scores", "all_equal", "signed_zero_nan_inf"])
 def test_pack_tie_and_special_scores(bits, kind):
     from gpu_helpers import assert_packed_equal
