@@ -79,7 +79,10 @@ typedef struct {
 typedef struct {
     size_t qweight, scales, zeros, row_ptr, col_idx, out_val;
     size_t pack_workspace;    /* for gwq_pack                                             */
-    size_t linear_workspace;  /* for gwq_linear with M <= M_max (0 when M_max <= 16)      */
+    size_t linear_workspace;  /* for gwq_linear with M <= M_max (0 when M_max <= 16):     */
+                              /*   linear_index + linear_scratch                          */
+    size_t linear_index;      /* the per-layer index of gwq_linear_index                  */
+    size_t linear_scratch;    /* for gwq_linear_indexed with M <= M_max (0 when <= 16)    */
     int64_t n_outliers;
 } gwq_sizes;
 
@@ -103,10 +106,13 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
 /* Y[M][N] = X[M][K] * (Q(W) + outliers)^T with Q(W) = s*(q-z) (Eq. 10), FP32 accumulation,
  * FP16 output.  M <= 16 takes the bandwidth-bound decode kernel, larger M the MFMA GEMM.
  *   P  host struct with device pointers   X_f16 device [M][K]   Y_f16 device [M][N]
- * X and Y must not overlap; Y is fully overwritten.  M > 16 needs `workspace`: device scratch of
- * at least the linear_workspace bytes gwq_layout reports for an M_max > 16, 16-byte aligned (it
- * is rewritten by every call; concurrent calls need separate workspaces); for M <= 16 it may be
- * NULL.
+ * X and Y must not overlap; Y is fully overwritten.  M > 16 needs `workspace`: device scratch,
+ * 16-byte aligned, of the linear_workspace bytes gwq_layout reports for an M_max >= M (it is
+ * rewritten by every call; concurrent calls need separate workspaces); for M <= 16 it may be
+ * NULL.  The first linear_index bytes are indispensable (less: GWQ_ERR_WORKSPACE).  The rest
+ * holds FP32 partial sums when a launch also splits K, which it does where rows and channels
+ * alone give too few tiles to fill the chip; with less than that the call still works, without
+ * the split.
  * Results are deterministic (no floating-point atomics). */
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);
@@ -115,15 +121,19 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
  * into its workspace for M > 16 depends on the packed layer alone (per channel and group: where the
  * group's outliers start, its scale and zero point), so it can be built once, when the layer is
  * loaded:
- *   gwq_linear_index   fills `index` (device, >= linear_workspace bytes as reported by gwq_layout
- *                      for an M_max > 16, 16-byte aligned) from P;
- *   gwq_linear_indexed is gwq_linear with that index in place of the workspace; it only reads it,
- *                      so concurrent calls may share one index.  For M <= 16 the index is not
- *                      used and may be NULL.
- * The index is valid until P's buffers change.  Same results, bit for bit, as gwq_linear. */
+ *   gwq_linear_index   fills `index` (device, >= linear_index bytes as reported by gwq_layout,
+ *                      16-byte aligned) from P;
+ *   gwq_linear_indexed is gwq_linear with that index, which it only reads, so concurrent calls
+ *                      may share one.  `scratch` (device, linear_scratch bytes for an M_max >= M,
+ *                      16-byte aligned, one per concurrent call) is the room for the partial
+ *                      sums of a K-split launch; it may be NULL or smaller: then K is not split.
+ *                      For M <= 16 neither is used and both may be NULL.
+ * The index is valid until P's buffers change.  Given the same scratch size as gwq_linear has
+ * left after its index, the results are the same bit for bit. */
 gwq_status gwq_linear_index(const gwq_packed *P, void *index, size_t index_bytes, void *stream);
 gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
-                              const void *index, size_t index_bytes, void *stream);
+                              const void *index, size_t index_bytes, void *scratch,
+                              size_t scratch_bytes, void *stream);
 
 /* Several layers in ONE decode launch (M <= 16): Y_f16[i] = gwq_linear(P[i], X_f16[i]) for
  * i < count <= GWQ_MAX_BATCH.  For layers with no data dependence between them, such as the q, k

@@ -30,7 +30,8 @@ class _Packed(ctypes.Structure):
 
 class _Sizes(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in ("qweight", "scales", "zeros", "row_ptr", "col_idx",
-                                                "out_val", "pack_workspace", "linear_workspace")]
+                                                "out_val", "pack_workspace", "linear_workspace", "linear_index",
+                                                "linear_scratch")]
     _fields_.append(("n_outliers", ctypes.c_int64))
 
 
@@ -59,7 +60,8 @@ def lib():
         L.gwq_linear_index.restype = ctypes.c_int
         L.gwq_linear_index.argtypes = [ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
         L.gwq_linear_indexed.restype = ctypes.c_int
-        L.gwq_linear_indexed.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.gwq_linear_indexed.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp,
+                                         ctypes.c_size_t, vp]
         L.gwq_linear_batch.restype = ctypes.c_int
         L.gwq_linear_batch.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), ctypes.POINTER(vp), i32,
                                        ctypes.POINTER(vp), vp]
@@ -167,11 +169,19 @@ def linear_workspace(P, M, device="cuda"):
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
 
 
+def linear_scratch(P, M, device="cuda"):
+    """Scratch tensor gwq_linear_indexed may use for this layer at M rows (None for the decode path)."""
+    import torch
+    nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, M)["linear_scratch"]
+    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
 def linear_index(P, stream=None):
     """gwq_linear_index: the per-layer index gwq_linear_indexed reads for M > 16 (a uint8 tensor).  Build it
     once per packed layer; it stays valid until the layer's buffers change."""
     import torch
-    index = linear_workspace(P, 17, P.qweight.device)
+    nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, 0)["linear_index"]
+    index = torch.empty(nbytes, dtype=torch.uint8, device=P.qweight.device)
     cs = P.c_struct()
     rc = lib().gwq_linear_index(ctypes.byref(cs), index.data_ptr(), index.numel(), _stream_ptr(stream))
     if rc != GWQ_OK:
@@ -179,9 +189,9 @@ def linear_index(P, stream=None):
     return index
 
 
-def linear(P, X, out=None, stream=None, workspace=None, index=None):
+def linear(P, X, out=None, stream=None, workspace=None, index=None, scratch="auto"):
     """gwq_linear: X FP16 [M, K] on the GPU -> Y FP16 [M, N].  With `index` (from linear_index) the call
-    is gwq_linear_indexed and needs no workspace."""
+    is gwq_linear_indexed; its scratch is allocated here unless one (or None) is passed."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
     M = X.shape[0]
@@ -189,8 +199,11 @@ def linear(P, X, out=None, stream=None, workspace=None, index=None):
         out = torch.empty((M, P.N), dtype=torch.float16, device=X.device)
     if index is not None:
         cs = P.c_struct()
+        if isinstance(scratch, str):
+            scratch = linear_scratch(P, M, X.device)
         rc = lib().gwq_linear_indexed(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), index.data_ptr(),
-                                      index.numel(), _stream_ptr(stream))
+                                      index.numel(), scratch.data_ptr() if scratch is not None else None,
+                                      scratch.numel() if scratch is not None else 0, _stream_ptr(stream))
         if rc != GWQ_OK:
             raise GwqError(rc, "gwq_linear_indexed")
         return out
@@ -215,18 +228,31 @@ def prepare_linear(P, X, out, index=None):
     assert out.shape == (X.shape[0], P.N) and out.dtype == torch.float16 and out.is_contiguous()
     cs = P.c_struct()
     ref = ctypes.byref(cs)
-    fn = lib().gwq_linear if index is None else lib().gwq_linear_indexed
     xp, yp, M = ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(out.data_ptr()), X.shape[0]
-    ws = linear_workspace(P, M, X.device) if index is None else index
-    wp = ctypes.c_void_p(ws.data_ptr()) if ws is not None else None
-    wl = ws.numel() if ws is not None else 0
     current_stream = torch.cuda.current_stream
 
-    def call(_keep=(cs, P, X, out, ws)):
-        rc = fn(ref, xp, M, yp, wp, wl, ctypes.c_void_p(current_stream().cuda_stream))
+    def ptr_len(t):
+        return (ctypes.c_void_p(t.data_ptr()), t.numel()) if t is not None else (None, 0)
+
+    if index is None:
+        fn = lib().gwq_linear
+        ws = linear_workspace(P, M, X.device)
+        wp, wl = ptr_len(ws)
+
+        def call(_keep=(cs, P, X, out, ws)):
+            rc = fn(ref, xp, M, yp, wp, wl, ctypes.c_void_p(current_stream().cuda_stream))
+            if rc != GWQ_OK:
+                raise GwqError(rc, "gwq_linear")
+        return call
+    fn = lib().gwq_linear_indexed
+    sc = linear_scratch(P, M, X.device)
+    (ip, il), (sp, sl) = ptr_len(index), ptr_len(sc)
+
+    def call_indexed(_keep=(cs, P, X, out, index, sc)):
+        rc = fn(ref, xp, M, yp, ip, il, sp, sl, ctypes.c_void_p(current_stream().cuda_stream))
         if rc != GWQ_OK:
-            raise GwqError(rc, "gwq_linear" if index is None else "gwq_linear_indexed")
-    return call
+            raise GwqError(rc, "gwq_linear_indexed")
+    return call_indexed
 
 
 def prepare_linear_batch(layers, Xs, outs):

@@ -34,7 +34,8 @@ gwq_status check_packed(const gwq_packed *P)
     return GWQ_OK;
 }
 
-// Shared argument checks of the gwq_linear variants; `index` is the workspace or the prebuilt index.
+// Shared argument checks of the gwq_linear variants; `index` is the workspace (whose head becomes
+// the index) or the prebuilt index.
 gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const void *Y_f16, const void *index,
                         size_t index_bytes)
 {
@@ -45,7 +46,7 @@ gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const
     if (((uintptr_t)X_f16 | (uintptr_t)P->qweight | (uintptr_t)P->scales | (uintptr_t)P->zeros |
          (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
         return GWQ_ERR_SHAPE;
-    if (M > 16 && (!index || index_bytes < gwq::gemm_workspace_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
+    if (M > 16 && (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
     if (M > 16 && ((uintptr_t)index & 15)) return GWQ_ERR_SHAPE;
     return GWQ_OK;
 }
@@ -72,7 +73,9 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     out->col_idx = ((size_t)k_out * 2 + 15) / 16 * 16 + 16;
     out->out_val = out->col_idx;
     out->pack_workspace = gwq::pack_workspace_bytes(N);
-    out->linear_workspace = M_max > 16 ? gwq::gemm_workspace_bytes(N, K) : 0;
+    out->linear_index = gwq::gemm_index_bytes(N, K);
+    out->linear_scratch = gwq::gemm_scratch_bytes(N, M_max);
+    out->linear_workspace = M_max > 16 ? out->linear_index + out->linear_scratch : 0;
     out->n_outliers = k_out;
     return GWQ_OK;
 }
@@ -101,8 +104,12 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     if (M <= 16) {
         e = gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st);
     } else {
+        // The workspace holds the index, then (whatever is left) the partial sums of a K-split launch.
+        const size_t ib = gwq::gemm_index_bytes(P->N, P->K);
         e = gwq::launch_gemm_index(*P, workspace, st);
-        if (e == hipSuccess) e = gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, g_gemm_ms, st);
+        if (e == hipSuccess)
+            e = gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, static_cast<char *>(workspace) + ib,
+                                 workspace_bytes - ib, g_gemm_ms, st);
     }
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
@@ -111,20 +118,22 @@ gwq_status gwq_linear_index(const gwq_packed *P, void *index, size_t index_bytes
 {
     gwq_status s = check_packed(P);
     if (s != GWQ_OK) return s;
-    if (!index || index_bytes < gwq::gemm_workspace_bytes(P->N, P->K)) return GWQ_ERR_WORKSPACE;
+    if (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K)) return GWQ_ERR_WORKSPACE;
     if ((uintptr_t)index & 15) return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_gemm_index(*P, index, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 
 gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, const void *index,
-                              size_t index_bytes, void *stream)
+                              size_t index_bytes, void *scratch, size_t scratch_bytes, void *stream)
 {
     gwq_status s = check_linear(P, X_f16, M, Y_f16, index, index_bytes);
     if (s != GWQ_OK) return s;
+    if (scratch && ((uintptr_t)scratch & 15)) return GWQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st)
-                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, index, g_gemm_ms, st);
+                           : gwq::launch_gemm(*P, X_f16, M, Y_f16, index, scratch, scratch ? scratch_bytes : 0,
+                                              g_gemm_ms, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 

@@ -166,13 +166,17 @@ __device__ inline int x_swizzle(int r)
 template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 // MSW = 32-row sub-tiles per consumer wave along m; the block tile is BM = 128 * MSW rows by 128
-// channels.
+// channels.  When the tiles alone would leave most of the chip idle (few rows, few channels), K is
+// split as well: `splits` blocks share a tile, block s of them takes groups s * split_groups onwards
+// and writes its FP32 sums to partial[s][M][N] instead of Y; splitk_reduce_kernel adds them up in
+// the order of s.
 template <int BITS, int MSW>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
                                                         const uint16_t *__restrict__ col_idx,
                                                         const uint16_t *__restrict__ out_val,
                                                         const GroupRecord *__restrict__ rec,
                                                         const _Float16 *__restrict__ X, _Float16 *__restrict__ Y,
+                                                        float *__restrict__ partial, int split_groups,
                                                         int N, int K, int M, int tiles_m, int tiles_n, int last_entry)
 {
     constexpr int BM = 128 * MSW;
@@ -187,8 +191,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
     // Tile order: bands of two m-tiles, n fastest inside a band; when the tile count divides by 8
     // every XCD (blocks go round-robin over the 8 XCDs) gets one contiguous run of that order.
-    int id = blockIdx.x;
     const int total = tiles_m * tiles_n;
+    const int split = blockIdx.x / total;
+    int id = blockIdx.x % total;
     if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
     const int band_m = tiles_m >= 2 ? 2 : 1;
     const int per_band = band_m * tiles_n;
@@ -203,8 +208,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int gpr = K / kGroup;
-    const int nk = K / kBK;                             // steps; two per group
+    const int gpr = K / kGroup;                         // groups per row of the matrix
+    const int g_first = split * split_groups;           // this block's groups: g_first .. g_first + gl - 1
+    const int gl = gpr - g_first < split_groups ? gpr - g_first : split_groups;
+    const int nk = 2 * gl;                              // steps; two per group
+    const int k_first = g_first * kGroup;
 
     // Both roles pass the block's barrier exactly 1 + nk times: once when step 0 is staged, then
     // once per step (the consumers in the middle of the step's last k-batch).
@@ -217,14 +225,14 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         b_n = b_valid ? b_n : N - 1;                    // clamped: loads stay in bounds, tile row unused
         const DecodeConsts dc(BITS);
 
-        const uint32_t *q_row = qweight + (size_t)b_n * gpr * wpg;
-        const GroupRecord *r_row = rec + (size_t)b_n * (gpr + 1);
+        const uint32_t *q_row = qweight + ((size_t)b_n * gpr + g_first) * wpg;       // group numbers below are local
+        const GroupRecord *r_row = rec + (size_t)b_n * (gpr + 1) + g_first;
         _Float16 *const b_dst = lds_w + b_n_local * kLd;                    // + buffer
 
         // Requests for group g (clamped: the last trips ask for groups past the row's end and use
         // none of it); first = CSR index of its first entry.
         auto issue_group = [&](int g, int first, GroupRegs<BITS> &G) {
-            g = g < gpr ? g : gpr - 1;
+            g = g < gl ? g : gl - 1;
             const uint32_t *grp = q_row + (uint32_t)g * wpg;
             load_slot<BITS>(G.slot[0], grp, b_h);
             load_slot<BITS>(G.slot[1], grp, 2 + b_h);
@@ -258,7 +266,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                 for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
             }
             cnt = step < nk ? cnt : 0;
-            const uint32_t k_lo = (uint32_t)(step * kBK);
+            const uint32_t k_lo = (uint32_t)(k_first + step * kBK);
             const uint32_t cs[2] = {G.col_lo, G.col_hi}, vs[2] = {G.val_lo, G.val_hi};
             if (half == 0) {                            // the group's first step: keep the columns for its second
 #pragma unroll
@@ -313,11 +321,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             first_n = first_nn; sz_n = sz_nn;
         };
         int g = 0;
-        for (; g + 1 < gpr; g += 2) {
+        for (; g + 1 < gl; g += 2) {
             trip(g, G0, G1);
             trip(g + 1, G1, G0);
         }
-        if (g < gpr) trip(g, G0, G1);
+        if (g < gl) trip(g, G0, G1);
         return;
     }
 
@@ -339,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             const int rc = m0 + r < M ? r : M - 1 - m0;
             row_off[j] = (uint32_t)rc * (uint32_t)K * 2u + 16u * (uint32_t)((lane & 7) ^ x_swizzle(r));
         }
-        const char *tile = reinterpret_cast<const char *>(X + (size_t)m0 * K);
+        const char *tile = reinterpret_cast<const char *>(X + (size_t)m0 * K + k_first);
         const uint32_t lds_x = (uint32_t)(uintptr_t)lds + (uint32_t)(lw * kInstr) * 1024u;
         auto issue_x = [&](int step, int buf) {
             const char *src = tile + (size_t)step * (kBK * 2);
@@ -447,16 +455,50 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + wm * (BM / 4) + i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
-                if (m < M && n < N) Y[(size_t)m * N + n] = (_Float16)acc[i][j][v];
+                if (m < M && n < N) {
+                    if (partial) partial[((size_t)split * M + m) * N + n] = acc[i][j][v];
+                    else Y[(size_t)m * N + n] = (_Float16)acc[i][j][v];
+                }
             }
         }
 }
 
+// Y = sum over the splits of partial[s], added in the order of s (so the result does not depend on
+// which block finished first), rounded to FP16 once.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, _Float16 *__restrict__ Y,
+                                                            size_t count, int splits)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float sum = partial[i];
+    for (int s = 1; s < splits; ++s) sum += partial[(size_t)s * count + i];
+    Y[i] = (_Float16)sum;
+}
+
+// How many ways K is split for a launch of `tiles` tiles over rows of `gpr` groups: as many as keep
+// the block count within the CU count, at least two groups each, at most kMaxSplits.
+constexpr int kMaxSplits = 8, kSplitBelowTiles = 160, kCUs = 256;
+int choose_splits(int tiles, int gpr)
+{
+    if (tiles >= kSplitBelowTiles) return 1;
+    int s = kCUs / tiles;
+    s = s < kMaxSplits ? s : kMaxSplits;
+    s = s < gpr / 2 ? s : gpr / 2;
+    return s < 1 ? 1 : s;
+}
+
 template <int BITS, int MSW>
-hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, hipStream_t st)
+hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, float *partial,
+                     size_t partial_bytes, hipStream_t st)
 {
     constexpr int BM = 128 * MSW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
+    const int gpr = P.K / kGroup;
+    int splits = partial ? choose_splits(tiles_m * tiles_n, gpr) : 1;
+    int split_groups = (gpr + splits - 1) / splits;
+    splits = (gpr + split_groups - 1) / split_groups;   // no empty split
+    if (splits > 1 && (size_t)splits * M * P.N * sizeof(float) > partial_bytes) splits = 1, split_groups = gpr;
+    if (splits == 1) partial = nullptr;
     const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
     if (!attr_set) {
@@ -465,15 +507,30 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_kernel<BITS, MSW><<<tiles_m * tiles_n, kThreads, lds, st>>>(
+    gemm_kernel<BITS, MSW><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
         P.qweight, P.col_idx, P.out_val, rec, static_cast<const _Float16 *>(X),
-        static_cast<_Float16 *>(Y), P.N, P.K, M, tiles_m, tiles_n, P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
+        static_cast<_Float16 *>(Y), partial, split_groups, P.N, P.K, M, tiles_m, tiles_n,
+        P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    const size_t count = (size_t)M * P.N;
+    splitk_reduce_kernel<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(partial, static_cast<_Float16 *>(Y), count, splits);
     return hipGetLastError();
 }
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t N, int64_t K) { return (size_t)(N * (K / kGroup + 1)) * sizeof(GroupRecord); }
+size_t gemm_index_bytes(int64_t N, int64_t K) { return ((size_t)(N * (K / kGroup + 1)) * sizeof(GroupRecord) + 255) / 256 * 256; }
+
+// Scratch for the FP32 partial sums of a K-split launch with up to M_max rows.  Splitting stops
+// where splits x tiles reaches the CU count, so splits * M * N never exceeds that many tiles' worth.
+size_t gemm_scratch_bytes(int64_t N, int64_t M_max)
+{
+    if (M_max <= 16) return 0;
+    const size_t by_rows = (size_t)kMaxSplits * (size_t)M_max * (size_t)N * sizeof(float);
+    const size_t by_tiles = (size_t)kCUs * 256 * kBN * sizeof(float);
+    return by_rows < by_tiles ? by_rows : by_tiles;
+}
 
 hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t st)
 {
@@ -482,14 +539,18 @@ hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t s
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *workspace, int ms_override,
-                       hipStream_t st)
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
+                       size_t scratch_bytes, int ms_override, hipStream_t st)
 {
-    const GroupRecord *rec = static_cast<const GroupRecord *>(workspace);
+    const GroupRecord *rec = static_cast<const GroupRecord *>(index);
+    float *part = static_cast<float *>(scratch);
     // Rows per tile: 256 unless M is small (the override is in rows: 64 and 128 both mean 128).
     const int msw = ms_override ? (ms_override >= 4 ? 2 : 1) : M <= 128 ? 1 : 2;
-    if (P.bits == 4) return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, rec, st) : launch_ms<4, 2>(P, X, M, Y, rec, st);
-    return msw == 1 ? launch_ms<3, 1>(P, X, M, Y, rec, st) : launch_ms<3, 2>(P, X, M, Y, rec, st);
+    if (P.bits == 4)
+        return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, rec, part, scratch_bytes, st)
+                        : launch_ms<4, 2>(P, X, M, Y, rec, part, scratch_bytes, st);
+    return msw == 1 ? launch_ms<3, 1>(P, X, M, Y, rec, part, scratch_bytes, st)
+                    : launch_ms<3, 2>(P, X, M, Y, rec, part, scratch_bytes, st);
 }
 
 }  // namespace gwq

@@ -31,11 +31,13 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
                        uint32_t *ws, hipStream_t stream);
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
                          int waves_override, hipStream_t stream);
-// workspace: gemm_workspace_bytes(N, K) bytes of device scratch, 8-byte aligned (one record per channel
-// and group: index of the group's first outlier, scale, zero point).
-size_t gemm_workspace_bytes(int64_t N, int64_t K);
-hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t stream);    // fills the records
-hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *workspace, int ms_override,
-                       hipStream_t stream);                                                // reads them
+// index: gemm_index_bytes(N, K) bytes, 16-byte aligned (one record per channel and group: index of the
+// group's first outlier, scale, zero point; a multiple of 256 bytes).  scratch: gemm_scratch_bytes(N, M_max)
+// bytes for the partial sums of launches that also split K (may be NULL: then K is never split).
+size_t gemm_index_bytes(int64_t N, int64_t K);
+size_t gemm_scratch_bytes(int64_t N, int64_t M_max);
+hipError_t launch_gemm_index(const gwq_packed &P, void *index, hipStream_t stream);        // fills the records
+hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
+                       size_t scratch_bytes, int ms_override, hipStream_t stream);         // reads them
 
 }  // namespace gwq

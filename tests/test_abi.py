@@ -40,7 +40,10 @@ def test_layout_sizes_7b_shapes():
     total = sum(s[k] for k in ("qweight", "scales", "zeros", "row_ptr", "col_idx", "out_val"))
     assert abs(total / 4096 ** 2 - 0.5644) < 1e-3
     assert gwq.layout(8, 128, 4, ppm=0)["col_idx"] == 16          # never a zero-size buffer
-    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4, M_max=2048)["linear_workspace"] == 4096 * 33 * 8     # one 8-byte record per channel and group, plus one
+    assert s["linear_workspace"] == 0 and gwq.layout(4096, 4096, 4)["linear_index"] == 4096 * 33 * 8     # one 8-byte record per channel and group, plus one
+    big = gwq.layout(4096, 4096, 4, M_max=2048)
+    assert big["linear_scratch"] == 256 * 256 * 128 * 4 and big["linear_workspace"] == big["linear_index"] + big["linear_scratch"]
+    assert gwq.layout(4096, 4096, 4, M_max=64)["linear_scratch"] == 8 * 64 * 4096 * 4      # eight FP32 copies of Y at most
     small = gwq.layout(3, 128, 4)                                  # 3 groups: padded to one vector
     assert small["scales"] == 32 and small["zeros"] == 32
 
@@ -97,19 +100,20 @@ def test_linear_index_validates_before_touching_the_device():
     L = binding.lib()
     fake = ctypes.c_void_p(0x1000)
     ok = _packed()
-    need = gwq.layout(4, 128, 4, M_max=17)["linear_workspace"]
-    assert need == 4 * 2 * 8
+    need = gwq.layout(4, 128, 4, M_max=17)["linear_index"]
+    assert need == 256                                                          # 4 * 2 records of 8 bytes, in 256-byte units
     assert L.gwq_linear_index(None, fake, need, None) == -1
     assert L.gwq_linear_index(ctypes.byref(ok), None, need, None) == -4
     assert L.gwq_linear_index(ctypes.byref(ok), fake, need - 1, None) == -4
     assert L.gwq_linear_index(ctypes.byref(ok), ctypes.c_void_p(0x1008), need, None) == -2
     assert L.gwq_linear_index(ctypes.byref(_packed(bits=5)), fake, need, None) == -3
-    assert L.gwq_linear_indexed(None, fake, 17, fake, fake, need, None) == -1
-    assert L.gwq_linear_indexed(ctypes.byref(ok), None, 17, fake, fake, need, None) == -1
-    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 0, fake, fake, need, None) == -2
-    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4      # M > 16 needs the index
-    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need - 1, None) == -4
-    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, ctypes.c_void_p(0x1004), need, None) == -2
+    assert L.gwq_linear_indexed(None, fake, 17, fake, fake, need, None, 0, None) == -1
+    assert L.gwq_linear_indexed(ctypes.byref(ok), None, 17, fake, fake, need, None, 0, None) == -1
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 0, fake, fake, need, None, 0, None) == -2
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, None, 0, None, 0, None) == -4      # M > 16 needs the index
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need - 1, None, 0, None) == -4
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, ctypes.c_void_p(0x1004), need, None, 0, None) == -2
+    assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need, ctypes.c_void_p(0x1004), 64, None) == -2
 
 
 def test_linear_batch_validates_before_touching_the_device():

@@ -161,8 +161,8 @@ def test_linear_index_contents(bits, N, K, ppm):
     import paper_2411_00850_amd as gwq
     from gpu_helpers import upload_packed
     P, _ = _problem(77 + bits, N, K, bits, ppm=ppm)
-    rec = gwq.linear_index(upload_packed(P)).cpu().numpy().view(np.uint32).reshape(N, K // 128 + 1, 2)
     gpr = K // 128
+    rec = gwq.linear_index(upload_packed(P)).cpu().numpy().view(np.uint32)[:N * (gpr + 1) * 2].reshape(N, gpr + 1, 2)
     for n in range(N):
         lo, hi = int(P.row_ptr[n]), int(P.row_ptr[n + 1])
         want = lo + np.searchsorted(P.col_idx[lo:hi].astype(np.int64), 128 * np.arange(gpr + 1))
@@ -184,6 +184,27 @@ def test_linear_indexed_equals_linear(bits, N, K, M):
     for _ in range(2):
         X = to_gpu(gs.activations(M, K, rng))
         assert np.array_equal(gwq.linear(D, X, index=index).cpu().numpy(), gwq.linear(D, X).cpu().numpy())
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,M", [(200, 1408, 40), (128, 4096, 17), (300, 2048, 200), (1500, 1024, 300), (72, 11008, 64)])
+def test_gemm_split_k(bits, N, K, M):
+    """Few tiles: the launch also splits K (here 2 to 8 ways, also unevenly: 11 groups in 3 + 3 + 3 + 2) and
+    a second kernel adds the FP32 partial sums in a fixed order.  Checked against the oracle, against
+    itself (deterministic) and against the same call without scratch, which does not split."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    P, rng = _problem(500 + N + bits, N, K, bits)
+    X = gs.activations(M, K, rng, hot_frac=0.01)
+    D, Xd = upload_packed(P), to_gpu(X)
+    index = gwq.linear_index(D)
+    split = gwq.linear(D, Xd, index=index).cpu().numpy()
+    whole = gwq.linear(D, Xd, index=index, scratch=None).cpu().numpy()
+    ref = orc.linear_f64(P, X)
+    assert_close(split, ref, f"split-K N={N} K={K} M={M} bits={bits}")
+    assert_close(whole, ref, f"no split N={N} K={K} M={M} bits={bits}")
+    assert np.array_equal(split, gwq.linear(D, Xd, index=index).cpu().numpy())
+    assert np.array_equal(split, gwq.linear(D, Xd).cpu().numpy())          # gwq_linear splits the same way
 
 
 # ----------------------------------------------------------------------------- full-size configurations
