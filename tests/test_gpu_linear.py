@@ -135,6 +135,16 @@ def test_gemm_small(bits, N, K, M):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,M", [(16, 17), (130, 40), (257, 129)])
+def test_gemm_shortest_rows(bits, N, M):
+    """The GEMM at K = 128: one group, two steps, the shortest loop every role of the kernel can run."""
+    from gpu_helpers import assert_close
+    P, rng = _problem(700 + N + bits, N, 128, bits)
+    X = gs.activations(M, 128, rng)
+    assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm N={N} K=128 M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 def test_gemm_longest_rows(bits):
     """The GEMM at K = 65536 (512 groups: the most its per-group outlier counts are laid out for)."""
     from gpu_helpers import assert_close
