@@ -79,6 +79,8 @@ def main():
                     help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
+    ap.add_argument("--extras", default="all", metavar="LIST",
+                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,pack (default: all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are out of scope.")
@@ -212,12 +214,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    legs = set("m,groups,big,fp16,prefill,pack".split(",")) if args.extras == "all" else set(args.extras.split(","))
     if not args.no_extras:
         extra = {}
-        for M in (4, 16):
+        for M in (4, 16) if "m" in legs else ():
             s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), 12, args.launch, args.group)
             extra[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5)}
-        for grouping in ("none", "all"):                # the same M = 1 pass with 7 launches / 1 launch per step
+        for grouping in ("none", "all") if "groups" in legs else ():   # the same M = 1 pass with 7 launches / 1 launch per step
             if grouping != args.group:
                 s, _, b, nl = decode_leg(1, max(args.steps // 3, 12), 12, args.launch, grouping)
                 extra[f"decode_M1_group_{grouping}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
@@ -228,7 +231,7 @@ def main():
         big = {}
         gen = torch.Generator(device=dev)
         gen.manual_seed(70)
-        for name, N, K in gs.SHAPES_70B:
+        for name, N, K in gs.SHAPES_70B if "big" in legs else ():
             Wd = (torch.randn((N, K), device=dev, generator=gen) * 0.02).half()
             Sd = torch.rand((N, K), device=dev, generator=gen)
             P0 = gwq.pack(Wd, Sd, 4, 10000)
@@ -256,11 +259,14 @@ def main():
             big[f"{name}_{N}x{K}"] = {"us": round(us, 2), "GB/s": round(algorithmic_bytes(P0, 1) / us / 1e3, 1)}
             del Ps, P0, calls, graph
             torch.cuda.empty_cache()
-        extra["decode_M1_70b_shapes"] = big
+        if big:
+            extra["decode_M1_70b_shapes"] = big
         # The same decode pass with FP16 weights through the vendor library (torch's F.linear), as the
         # paper's efficiency table does (Sec. 4.2: speed and memory against FP16): 7 products per pass,
         # two rotated copies of the FP16 layer (809 MB), graph replay.  Comparison only, not a product path.
         try:
+            if "fp16" not in legs:
+                raise KeyError("skipped")
             g16 = torch.Generator(device=dev)
             g16.manual_seed(7)
             w16 = [[(torch.randn((P.N, P.K), device=dev, generator=g16, dtype=torch.float32) * 0.02).half()
@@ -295,41 +301,44 @@ def main():
                                                "memory_ratio": round(fp16_bytes / packed_bytes, 2)}
             del w16, graph, outs
             torch.cuda.empty_cache()
+        except KeyError:
+            pass
         except Exception as ex:                            # the comparison must not take the benchmark down
             extra["fp16_library_decode_M1"] = {"error": str(ex)[:200]}
         # prefill: M = 2048 over the 7 matrices, one copy (compute-bound).  Two ways: gwq_linear, which
         # rebuilds its per-layer index in the workspace on every call, and gwq_linear_indexed with the
         # index built once per layer beforehand (it depends on the weights only).
-        M = 2048
-        xs, ys = make_xy(M)
-        fl = sum(flops(P, M) for P in layers)
+        if "prefill" in legs:
+            M = 2048
+            xs, ys = make_xy(M)
+            fl = sum(flops(P, M) for P in layers)
 
-        def time_prefill(calls, reps=10):
-            for _ in range(3):
-                for c in calls:
-                    c()
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            for _ in range(reps):
-                for c in calls:
-                    c()
-            torch.cuda.synchronize()
-            s = (time.perf_counter() - t) / reps
-            return {"TFLOP/s": round(fl / s / 1e12, 1), "ms_per_pass": round(s * 1e3, 4),
-                    "pct_mfma_f16_peak": round(100 * fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 2),
-                    "roofline": {"bound": "mfma", "achieved": round(fl / s / 1e12, 1),
-                                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                 "frac": round(fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
+            def time_prefill(calls, reps=10):
+                for _ in range(3):
+                    for c in calls:
+                        c()
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                for _ in range(reps):
+                    for c in calls:
+                        c()
+                torch.cuda.synchronize()
+                s = (time.perf_counter() - t) / reps
+                return {"TFLOP/s": round(fl / s / 1e12, 1), "ms_per_pass": round(s * 1e3, 4),
+                        "pct_mfma_f16_peak": round(100 * fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 2),
+                        "roofline": {"bound": "mfma", "achieved": round(fl / s / 1e12, 1),
+                                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": round(fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
 
-        extra["prefill_M2048"] = time_prefill([gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(layers)])
-        indexes = [gwq.linear_index(P) for P in layers]
-        extra["prefill_M2048_indexed"] = time_prefill(
-            [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(layers)])
-        del indexes
-        del xs, ys
+            extra["prefill_M2048"] = time_prefill([gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(layers)])
+            indexes = [gwq.linear_index(P) for P in layers]
+            extra["prefill_M2048_indexed"] = time_prefill(
+                [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(layers)])
+            del indexes
+            del xs, ys
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
         pk = {}
-        for name, Wd, Sd in pack_inputs:
+        for name, Wd, Sd in pack_inputs if "pack" in legs else ():
             gwq.pack(Wd, Sd, 4, 10000)
             torch.cuda.synchronize()
             t = time.perf_counter()
@@ -339,7 +348,8 @@ def main():
             s = (time.perf_counter() - t) / 3
             b = Wd.numel() * 6 + P.nbytes()
             pk[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1)}
-        extra["pack_int4"] = pk
+        if pk:
+            extra["pack_int4"] = pk
         out["extras"] = extra
 
     if not args.no_cpu_baseline:
