@@ -5,11 +5,11 @@
 //
 // A block owns a BM x 128 tile of Y (BM = 256, or 128 for small M) and walks K in steps of 64 (half
 // a group).  Per step X[BM][64] and the dequantised weights What[128][64] are staged as FP16 in LDS
-// (X in three buffers, the weights in two) and multiplied with 32x32x16 FP16 MFMA tiles, FP32
-// accumulators, FP16 store.
+// (three buffers each) and multiplied with 32x32x16 FP16 MFMA tiles, FP32 accumulators, FP16 store.
 //
 // The 16 waves of a block have three roles, four waves per SIMD:
-//   * 8 consumers (4 along m, 2 along n) do nothing but read fragments from LDS and issue MFMAs;
+//   * 8 consumers (4 along m, 2 along n) do nothing but read fragments from LDS, two k-batches
+//     ahead, and issue MFMAs;
 //   * 4 producers stage the weights of the next step: codes to FP16 (exact q - z, one multiply by
 //     the scale) to LDS, then the channel's outliers over their decoded zeros;
 //   * 4 loaders copy the X rows of the step after next from memory straight into LDS (loads with
@@ -23,9 +23,13 @@
 // Everything a step needs from memory is requested two steps ahead, with addresses that do not
 // depend on data requested in the same trip, so nobody waits for memory inside the loop.  For the
 // outliers this needs to know, per channel and group, where the group's CSR entries start: a small
-// kernel writes that index, with the group's scale and zero point, into the workspace first (one
-// 8-byte record per channel and group); a group's first eight entries are fetched ahead by the
-// channel's two threads with unaligned loads (longer runs take a slow path).
+// kernel writes that index, with the group's scale and zero point, one 8-byte record per channel
+// and group (per call into the workspace, or once per layer: gwq_linear_index); a group's first
+// eight entries are fetched ahead by the channel's two threads with unaligned loads (longer runs
+// take a slow path).
+//
+// Launches with fewer tiles than CUs also split K over up to eight blocks per tile; their FP32
+// partial sums go to scratch and splitk_reduce_kernel adds them in a fixed order.
 #include <type_traits>
 
 #include "gwq_dequant.h"
@@ -214,8 +218,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     const int nk = 2 * gl;                              // steps; two per group
     const int k_first = g_first * kGroup;
 
-    // Both roles pass the block's barrier exactly 1 + nk times: once when step 0 is staged, then
-    // once per step (the consumers in the middle of the step's last k-batch).
+    // Every wave passes the block's barrier exactly 1 + nk times: once when step 0 is staged, then
+    // once per step (the consumers between the step's second and third k-batch).  Barrier t, the one
+    // of step t, says: step t + 1 is staged, and nobody reads step t - 1 any more.
     if (wave >= kConsumers && wave < kConsumers + kProducers) {
         // ======================================= producers =====================================
         const int ptid = tid - 64 * kConsumers;
