@@ -220,7 +220,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
     // Every wave passes the block's barrier exactly 1 + nk times: once when step 0 is staged, then
     // once per step (the consumers between the step's second and third k-batch).  Barrier t, the one
-    // of step t, says: step t + 1 is staged, and nobody reads step t - 1 any more.
+    // of step t, says: step t + 1 is staged, and nobody reads the buffers of step t any more (its
+    // last fragments are in registers).
     if (wave >= kConsumers && wave < kConsumers + kProducers) {
         // ======================================= producers =====================================
         const int ptid = tid - 64 * kConsumers;
