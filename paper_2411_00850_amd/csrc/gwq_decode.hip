@@ -529,17 +529,40 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
         __builtin_amdgcn_sched_barrier(0);
 
         // Outliers of the chunk's columns [c0, c1): the lane's entries are sorted by column, so it
-        // takes them while they are below c1.  Entries past the staged window come from memory
-        // (two loops: one address space each).
+        // takes them while they are below c1, four at a time (their columns, values and the X
+        // values they select are independent LDS reads; one entry per trip would wait for two
+        // dependent reads each time).  An entry that is not taken reads index 0 and adds zero; as the
+        // entries are sorted, the taken ones are a prefix of the four.  Entries past the staged
+        // window come from memory (two loops: one address space each).
         const int c0 = ph * chunk, c1 = c0 + chunk;
         const int j_staged = j_end < staged_end ? j_end : staged_end;
-        while (j < j_staged) {
-            const int col = col_lds[j - e0];
-            if (col >= c1) break;
-            const float v = (float)__builtin_bit_cast(_Float16, val_lds[j - e0]);
+        for (;;) {
+            int col[4];
+            float val[4];
+            bool ok[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)x_out[e][col - c0], acc[e]);
-            j += nwaves;
+            for (int i = 0; i < 4; ++i) {
+                const int idx = j + i * nwaves;
+                const bool in = idx < j_staged;
+                const int li = in ? idx - e0 : 0;
+                const int c = col_lds[li];
+                ok[i] = in && c < c1;
+                val[i] = ok[i] ? (float)__builtin_bit_cast(_Float16, val_lds[li]) : 0.f;
+                col[i] = ok[i] ? c - c0 : 0;
+            }
+            __builtin_amdgcn_sched_barrier(0);          // all eight reads above are in flight together, ...
+            _Float16 xv[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xv[i][e] = x_out[e][col[i]];
+            __builtin_amdgcn_sched_barrier(0);          // ... and so are these sixteen
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(val[i], (float)xv[i][e], acc[e]);
+            j += ((int)ok[0] + (int)ok[1] + (int)ok[2] + (int)ok[3]) * nwaves;
+            if (!ok[3]) break;
         }
         while (j >= staged_end && j < j_end) {          // very long rows only
             const int col = col_idx[j];
