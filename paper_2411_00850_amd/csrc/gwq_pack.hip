@@ -70,7 +70,10 @@ __global__ void init_ws_kernel(uint32_t *ws, uint32_t k_out)
 }
 
 // One radix-select pass: histogram of this pass's digit over the keys that match the prefix.
-// `total` is a multiple of 8 (K is a multiple of 128).
+// `total` is a multiple of 8 (K is a multiple of 128).  The grid is kept small (two blocks per CU):
+// every block flushes its non-empty bins with global atomics, in the first pass a few hundred bins
+// per block and all blocks on the same addresses, which with 2048 blocks took longer than the pass
+// over the keys.
 template <int PASS, bool F16>
 __global__ __launch_bounds__(kThreads) void hist_kernel(const void *score, size_t total, uint32_t *ws)
 {
@@ -186,22 +189,40 @@ __global__ __launch_bounds__(kThreads) void row_count_kernel(const void *score, 
 }
 
 // Ties at the threshold are kept in flat-index order until `remaining` of them are taken;
-// row_ptr is the running count of kept entries.  One block, rows in chunks of kThreads.
+// row_ptr is the running count of kept entries.  One block; a thread takes kRowsPerThread
+// consecutive rows per round, so that a round of two block scans covers 1024 rows.
+constexpr int kRowsPerThread = 4;
 __global__ __launch_bounds__(kThreads) void row_scan_kernel(uint32_t *ws, int N, int32_t *row_ptr)
 {
     __shared__ uint32_t smem[kWaves];
     const uint32_t need = ws[kWsRemaining];
     uint32_t eq_before = 0, kept_before = 0;
-    for (int n0 = 0; n0 < N; n0 += kThreads) {
-        const int n = n0 + threadIdx.x;
-        const uint32_t gt = n < N ? ws[kWsRows + n] : 0u;
-        const uint32_t eq = n < N ? ws[kWsRows + N + n] : 0u;
+    for (int n0 = 0; n0 < N; n0 += kThreads * kRowsPerThread) {
+        const int base = n0 + threadIdx.x * kRowsPerThread;
+        uint32_t gt[kRowsPerThread], eq[kRowsPerThread], eq_sum = 0;
+#pragma unroll
+        for (int i = 0; i < kRowsPerThread; ++i) {
+            const int n = base + i;
+            gt[i] = n < N ? ws[kWsRows + n] : 0u;
+            eq[i] = n < N ? ws[kWsRows + N + n] : 0u;
+            eq_sum += eq[i];
+        }
         uint32_t eq_total, kept_total;
-        const uint32_t eq_rank = eq_before + block_exclusive_scan(eq, smem, eq_total);
-        const uint32_t take = eq_rank >= need ? 0u : (need - eq_rank < eq ? need - eq_rank : eq);
-        const uint32_t kept = gt + take;
-        const uint32_t pos = kept_before + block_exclusive_scan(kept, smem, kept_total);
-        if (n < N) { ws[kWsRows + 2 * N + n] = take; row_ptr[n] = (int32_t)pos; }
+        uint32_t eq_rank = eq_before + block_exclusive_scan(eq_sum, smem, eq_total);
+        uint32_t take[kRowsPerThread], kept_sum = 0;
+#pragma unroll
+        for (int i = 0; i < kRowsPerThread; ++i) {
+            take[i] = eq_rank >= need ? 0u : (need - eq_rank < eq[i] ? need - eq_rank : eq[i]);
+            eq_rank += eq[i];
+            kept_sum += gt[i] + take[i];
+        }
+        uint32_t pos = kept_before + block_exclusive_scan(kept_sum, smem, kept_total);
+#pragma unroll
+        for (int i = 0; i < kRowsPerThread; ++i) {
+            const int n = base + i;
+            if (n < N) { ws[kWsRows + 2 * N + n] = take[i]; row_ptr[n] = (int32_t)pos; }
+            pos += gt[i] + take[i];
+        }
         eq_before += eq_total;
         kept_before += kept_total;
     }
@@ -363,7 +384,7 @@ hipError_t run_select(const void *score, int N, int K, uint32_t *ws, int32_t *ro
 {
     const size_t total = (size_t)N * K;
     const size_t want = (total / 8 + kThreads - 1) / kThreads;
-    const int blocks = (int)(want < 2048 ? (want ? want : 1) : 2048);
+    const int blocks = (int)(want < 512 ? (want ? want : 1) : 512);
     if (any) {
         // With nothing to keep the threshold set by init_ws_kernel already sits above every key.
         hist_kernel<0, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
