@@ -108,10 +108,16 @@ struct DecodeBatch {
 // so this one is straight-line code with compile-time offsets:
 //   * wave w owns exactly the U groups [wU, wU + U) of the block's 16 channels (the launcher starts
 //     ceil(gpr / U) waves); its index and everything derived from it live in scalar registers;
-//   * groups at or beyond gpr exist only in the last wave.  Nothing is predicated for them: their
-//     codes are whatever follows in memory (the next channel; the address is only kept from
-//     passing the end of qweight), their scales whatever follows in LDS (finite numbers), and they
-//     meet zeros in the LDS copy of X, whose rows are padded to waves * U groups;
+//   * groups at or beyond gpr exist only in the last wave.  Their codes are whatever follows in
+//     memory (the next channel; the address is only kept from passing the end of qweight) and
+//     they meet zeros in the LDS copy of X, whose rows are padded to waves * U groups.  Their
+//     scale and zero point are whatever follows in LDS, at most U - 1 places on, and that must
+//     be a finite scale and a zero point below 2^bits: a NaN scale, or a byte from 192 to 207 as
+//     a 3-bit zero point (it carries the decoder's constant -(16 + z) into the NaN patterns),
+//     would turn the exact zero of such a group into a NaN.  What follows is the next channel's
+//     (fine), for channel 15 the zero points read as scales (tiny finite numbers) or the spare
+//     slot, and for the last channel of a ragged N the padding of the caller's buffers; the
+//     spare slot and that padding are replaced by zeros when the arrays are staged;
 //   * a launch over several layers has as many waves as its longest rows need; the surplus waves of
 //     a shorter layer repeat wave 0's work and drop the result.
 //
@@ -181,17 +187,20 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
         }
     // (2) The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for
     // 16 consecutive channels: thread t < 2 gpr takes a scales vector, the next gpr threads a
-    // zero-point vector, any further thread re-reads vector 0 into the spare slot.
+    // zero-point vector, any further thread re-reads vector 0 (and stores zeros into the spare slot).
     // The LDS copies of the two arrays are adjacent, so thread t stores to vector t of that range
     // (the spare slot follows at vector 3 gpr).
     u32x4 meta;
+    int meta_valid;                                     // bytes of `meta` that lie inside the array
     {
         const bool is_sc = tid < 2 * gpr, is_zp = !is_sc && tid < 3 * gpr;
-        const int v_sc = block * 2 * gpr + tid < sc_last_vec ? block * 2 * gpr + tid : sc_last_vec;
-        const int v_zp = block * gpr + (tid - 2 * gpr) < zp_last_vec ? block * gpr + (tid - 2 * gpr) : zp_last_vec;
+        const int u_sc = block * 2 * gpr + tid, u_zp = block * gpr + (tid - 2 * gpr);
+        const int v_sc = u_sc < sc_last_vec ? u_sc : sc_last_vec;
+        const int v_zp = u_zp < zp_last_vec ? u_zp : zp_last_vec;
         const int v = is_sc ? v_sc : is_zp ? v_zp : 0;
         const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
         meta = src[v];
+        meta_valid = is_sc ? 2 * N * gpr - 16 * u_sc : is_zp ? N * gpr - 16 * u_zp : 0;
     }
     const uint32_t meta_dst = sc_off + 16 * (tid < 3 * gpr ? tid : 3 * gpr);
 
@@ -223,6 +232,16 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
             reinterpret_cast<u32x4 *>(xs)[e * (k_pad / 8) + kv] =
                 kv < K / 8 ? xstage[e * kQ + i] : u32x4{0u, 0u, 0u, 0u};
         }
+    // Bytes beyond the end of scales or zeros (the last block of a ragged N, and the spare slot) are
+    // stored as zeros: the groups at or beyond gpr of the last channel and of channel 15 read them.
+    if (meta_valid < 16) {
+        uint32_t *m = reinterpret_cast<uint32_t *>(&meta);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int nb = meta_valid - 4 * i;
+            m[i] &= nb >= 4 ? ~0u : nb <= 0 ? 0u : (1u << (8 * nb)) - 1u;
+        }
+    }
     *reinterpret_cast<u32x4 *>(lds_raw + meta_dst) = meta;
     __syncthreads();
 
@@ -352,8 +371,12 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
 // 4b .. 4b+3 of its MFMA tiles; the outliers of a channel are split over the waves, every lane
 // walking its share of the (column-sorted) row once with a cursor.  Nothing in the multiply is
 // predicated: groups at or beyond gpr meet zeros in X, their codes are whatever follows in memory
-// (the address is kept inside qweight), their scales and zero points whatever follows in LDS,
-// which a zeroed guard behind the zero points keeps finite.  At most 8 waves, so that the staging
+// (the address is kept inside qweight), and their scale and zero point are replaced by 0 (ANDed
+// with a wave-uniform mask; a select would make the compiler branch around the LDS reads): in the
+// last phase such a group can lie up to a whole chunk beyond gpr, so what it finds in LDS may be
+// anything, and a NaN scale, or a 3-bit zero point that carries the decoder's constants into the
+// NaN patterns, would turn its exact zero into a NaN.  (The 4-bit decoder's constants are finite
+// for every byte, so there the scale alone is masked.)  At most 8 waves, so that the staging
 // registers of X (MR * U / 4 vectors per lane) fit.
 //
 // MR = 8 or 16: rows of X staged (M <= MR; rows M .. MR-1 are loaded as copies of the last row and
@@ -510,8 +533,9 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 u32x4 xa[4];
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
-                const _Float16 s = __builtin_bit_cast(_Float16, sc_lane[u]);
-                const uint32_t z = zp_lane[u];
+                const uint32_t keep = g_begin + u < gpr ? ~0u : 0u; // uniform over the wave: a scalar mask
+                const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc_lane[u] & keep));
+                const uint32_t z = BITS == 3 ? zp_lane[u] & keep : zp_lane[u];
                 u32x4 wb[4];
                 slot[u].decode(z, b, dc, wb);
                 float4v part = float4v{0.f, 0.f, 0.f, 0.f};

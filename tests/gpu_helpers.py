@@ -13,8 +13,10 @@ def to_gpu(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def upload_packed(P):
-    """Oracle-packed host arrays -> device PackedLayer (so gwq_linear is tested on its own)."""
+def upload_packed(P, pad_byte=0x5A):
+    """Oracle-packed host arrays -> device PackedLayer (so gwq_linear is tested on its own).
+    The padding that gwq_layout prescribes behind scales, zeros, col_idx and out_val is filled with
+    `pad_byte`: the library promises never to interpret it."""
     import torch
 
     n_out = int(P.row_ptr[-1])
@@ -23,7 +25,7 @@ def upload_packed(P):
     def dev(a, dt, nbytes=None):
         a = np.ascontiguousarray(a).ravel()
         if nbytes is not None:                       # pad to the size gwq_layout prescribes
-            buf = np.full(nbytes // a.itemsize, 0x5A5A & (2 ** (8 * a.itemsize) - 1), a.dtype)
+            buf = np.full(nbytes // a.itemsize, (pad_byte * 0x0101) & (2 ** (8 * a.itemsize) - 1), a.dtype)
             buf[:a.size] = a
             a = buf
         return torch.from_numpy(a.view(dt)).cuda()

@@ -217,6 +217,67 @@ def test_gemm_split_k(bits, N, K, M):
     assert np.array_equal(split, gwq.linear(D, Xd).cpu().numpy())          # gwq_linear splits the same way
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("pad_byte", [0xFF, 0xC5, 0x7C])
+@pytest.mark.parametrize("N,K", [(396, 640), (27, 384), (45, 2688), (16, 640)])
+def test_padding_and_neighbours_are_never_interpreted(bits, pad_byte, N, K):
+    """The decode kernels run whole waves of 4, 8 or 16 groups, so with K / 128 not a multiple of that
+    the last wave of a channel also multiplies groups that do not exist (against zeros of X).  What
+    such a group finds as its scale and zero point must not matter: for the last channel it is the
+    padding of the caller's buffers (here bytes 0xFF and 0x7C: NaN scales with zero points 255 and 124;
+    and 0xC5: a zero point that carries the 3-bit magic-number decode into a NaN), for channel 15 of a
+    tile the bytes of another array.  N * K / 128 is not a multiple of 8 in the first three shapes, so the last 16-byte vector
+    of scales and zeros ends in padding."""
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    import paper_2411_00850_amd as gwq
+    P, rng = _problem(N + K + bits + pad_byte, N, K, bits, ppm=200000)
+    D = upload_packed(P, pad_byte=pad_byte)
+    for M in (1, 2, 4, 5, 16, 40):
+        X = gs.activations(M, K, rng)
+        Y = gwq.linear(D, to_gpu(X)).cpu().numpy()
+        assert np.isfinite(Y).all(), f"N={N} K={K} bits={bits} M={M} pad={pad_byte:#x}"
+        assert_close(Y, orc.linear_f64(P, X), f"padding N={N} K={K} M={M} bits={bits} pad={pad_byte:#x}")
+
+
+def _sweep_cases():
+    """40 seeded cases: ragged N, K in whole groups, both bit widths, outlier fractions from none to
+    half, outliers spread by weight-scaled scores or clustered in a few columns or a few rows (many
+    entries per group: the kernels' long-run paths), and M from 1 to 300 (decode, GEMM, split-K)."""
+    rng = np.random.default_rng(20241127)
+    cases = []
+    for i in range(40):
+        N = int(rng.integers(1, 400))
+        K = 128 * int(rng.integers(1, 17))
+        bits = (4, 3)[i % 2]
+        ppm = int(rng.choice([0, 1000, 10000, 10000, 50000, 200000, 500000]))
+        kind = ("spread", "cols", "rows")[int(rng.integers(0, 3))]
+        M = int(rng.choice([1, 2, 3, 4, 5, 8, 13, 16, 17, 31, 64, 100, 129, 300]))
+        cases.append((i, N, K, bits, ppm, kind, M))
+    return cases
+
+
+@pytest.mark.parametrize("case,N,K,bits,ppm,kind,M", _sweep_cases())
+def test_linear_random_sweep(case, N, K, bits, ppm, kind, M):
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    rng = np.random.default_rng(1000 + case)
+    W = gs.weight(N, K, rng, planted_cols=2)
+    k_out = orc.outlier_count(N, K, ppm)
+    if kind == "spread" or k_out == 0:
+        S = gs.score_from_weight(W, rng)
+    else:
+        S, _, _ = gs.score_clustered(N, K, k_out, rng, axis="col" if kind == "cols" else "row", frac_hot=0.6,
+                                     hot_share=0.02)
+    P = orc.pack(W, S, bits, ppm)
+    X = gs.activations(M, K, rng, hot_frac=0.01)
+    D, Xd = upload_packed(P), to_gpu(X)
+    ref = orc.linear_f64(P, X)
+    tag = f"sweep {case}: N={N} K={K} bits={bits} ppm={ppm} {kind} M={M}"
+    assert_close(gwq.linear(D, Xd).cpu().numpy(), ref, tag)
+    if M > 16:
+        assert_close(gwq.linear(D, Xd, index=gwq.linear_index(D), scratch=None).cpu().numpy(), ref, tag + " (no split)")
+
+
 # ----------------------------------------------------------------------------- full-size configurations
 
 def test_config1_decode_full():
