@@ -335,6 +335,25 @@ def main():
             extra["prefill_M2048_indexed"] = time_prefill(
                 [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(layers)])
             del indexes
+            # The same seven products with FP16 weights through the vendor library (torch.matmul), for
+            # scale: what a plain GEMM of these shapes reaches on this chip without any dequantisation.
+            if "fp16" in legs:
+                try:
+                    g16 = torch.Generator(device=dev)
+                    g16.manual_seed(8)
+                    w16 = [(torch.randn((P.N, P.K), device=dev, generator=g16, dtype=torch.float32) * 0.02).half()
+                           for P in layers]
+                    lib = time_prefill([(lambda j=j, P=P: torch.matmul(xs[P.K], w16[j].t(), out=ys[j]))
+                                        for j, P in enumerate(layers)])
+                    fl_dense = sum(2 * M * P.N * P.K for P in layers)
+                    lib["TFLOP/s"] = round(fl_dense / (lib["ms_per_pass"] * 1e-3) / 1e12, 1)
+                    lib.pop("roofline"), lib.pop("pct_mfma_f16_peak")
+                    lib["gwq_int4_indexed_relative_speed"] = round(
+                        lib["ms_per_pass"] / extra["prefill_M2048_indexed"]["ms_per_pass"], 3)
+                    extra["fp16_library_prefill_M2048"] = lib
+                    del w16
+                except Exception as ex:                    # the comparison must not take the benchmark down
+                    extra["fp16_library_prefill_M2048"] = {"error": str(ex)[:200]}
             del xs, ys
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
         pk = {}
