@@ -93,6 +93,52 @@ def test_pack_extreme_weights(bits):
     assert_packed_equal(_gpu_pack(W, S, bits, 10000), orc.pack(W, S, bits, 10000))
 
 
+def _sweep_cases():
+    """40 seeded cases: ragged N, K in whole groups, both bit widths, outlier fractions from a single
+    entry to nearly everything, and five kinds of score: weight-scaled FP32 or FP16, FP32 rounded to a
+    few distinct values (ties at the cut), and top sets clustered in a few columns or a few rows."""
+    rng = np.random.default_rng(20241128)
+    cases = []
+    for i in range(40):
+        N = int(rng.integers(1, 600))
+        K = 128 * int(rng.integers(1, 25))
+        bits = (4, 3)[i % 2]
+        ppm = int(rng.choice([1, 7, 1000, 5000, 10000, 10000, 12345, 100000, 500000, 999999]))
+        kind = ("f32", "f16", "ties", "cols", "rows")[int(rng.integers(0, 5))]
+        cases.append((i, N, K, bits, ppm, kind))
+    return cases
+
+
+@pytest.mark.parametrize("case,N,K,bits,ppm,kind", _sweep_cases())
+def test_pack_random_sweep(case, N, K, bits, ppm, kind):
+    from gpu_helpers import assert_packed_equal
+    rng = np.random.default_rng(2000 + case)
+    W = gs.weight(N, K, rng, planted_cols=min(2, K // 64))
+    if case % 4 == 0:                                   # a few rows that stress the scale search
+        W[0] = (rng.integers(-40, 40, K) * 2.0 ** -24).astype(np.float16)
+        W[N // 2] = (rng.standard_normal(K) * 9000).astype(np.float16)
+        W[N - 1, : K // 2] = 0
+    k_out = orc.outlier_count(N, K, ppm)
+    if kind in ("cols", "rows") and 0 < k_out < N * K // 2:
+        S, _, _ = gs.score_clustered(N, K, k_out, rng, axis="col" if kind == "cols" else "row", frac_hot=0.6,
+                                     hot_share=0.05)
+    else:
+        S = gs.score_from_weight(W, rng)
+        if kind == "ties":
+            S = (np.round(S * 32) / 32).astype(np.float32)
+        elif kind == "f16":
+            with np.errstate(over="ignore"):            # scores of the huge rows overflow to inf: wanted
+                S = S.astype(np.float16)
+    if case % 5 == 0:                                   # special values at random places
+        idx = rng.choice(N * K, min(64, N * K), replace=False)
+        flat = S.reshape(-1)
+        flat[idx[:16]] = np.nan
+        flat[idx[16:32]] = np.inf
+        flat[idx[32:48]] = -0.0
+        flat[idx[48:]] = -np.inf
+    assert_packed_equal(_gpu_pack(W, S, bits, ppm), orc.pack(W, S, bits, ppm))
+
+
 def test_pack_is_deterministic():
     import paper_2411_00850_amd as gwq
     from gpu_helpers import to_gpu, download_packed
