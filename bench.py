@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
     ap.add_argument("--extras", default="all", metavar="LIST",
-                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,pack (default: all)")
+                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,pack (default: all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are out of scope.")
@@ -99,11 +99,14 @@ def main():
 
     # ---- inputs: generate on the host (seeded), pack on the GPU with gwq_pack -------------------
     t0 = time.time()
-    layers, pack_inputs = [], []
+    want_int3 = not args.no_extras and (args.extras == "all" or "int3" in args.extras.split(","))
+    layers, layers3, pack_inputs = [], [], []
     for mid, (name, N, K) in enumerate(gs.SHAPES_7B):
         W, S = gs.layer_matrix(2, mid, N, K)
         Wd, Sd = torch.from_numpy(W).to(dev), torch.from_numpy(S).to(dev)
         layers.append(gwq.pack(Wd, Sd, 4, 10000))
+        if want_int3:
+            layers3.append(gwq.pack(Wd, Sd, 3, 10000))
         if name in ("q", "gate", "down"):
             pack_inputs.append((name, Wd, Sd))
         else:
@@ -121,13 +124,14 @@ def main():
 
     GROUPS = {"deps": [[0, 1, 2], [3], [4, 5], [6]], "none": [[i] for i in range(7)], "all": [list(range(7))]}
 
-    def decode_leg(M, steps, warmup, mode, grouping="deps"):
+    def decode_leg(M, steps, warmup, mode, grouping="deps", copies=copies):
         """mode "graph": all copies x 7 launches captured once into a HIP graph and replayed (the
         launch-bound loop of a serving engine), bracketed by two HIP events on the launch stream whose
         elapsed time over the number of launches is the per-launch duration; "eager": plain launches;
         "events": eager with one HIP event between consecutive launches."""
         xs, ys = make_xy(M)
         groups = GROUPS[grouping]
+        layers = copies[0]
         n_launch, n_copies = len(groups), len(copies)
         calls = [[gwq.prepare_linear_batch([c[j] for j in g], [xs[c[j].K] for j in g], [ys[j] for j in g])
                   if len(g) > 1 else gwq.prepare_linear(c[g[0]], xs[c[g[0]].K], ys[g[0]]) for g in groups]
@@ -214,7 +218,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    legs = set("m,groups,big,fp16,prefill,pack".split(",")) if args.extras == "all" else set(args.extras.split(","))
+    legs = set("m,groups,big,fp16,prefill,int3,pack".split(",")) if args.extras == "all" else set(args.extras.split(","))
     if not args.no_extras:
         extra = {}
         for M in (4, 16) if "m" in legs else ():
@@ -228,7 +232,7 @@ def main():
         # decode M = 1 on 70B-shaped matrices (one launch each; weights drawn on the device, three
         # rotating copies of each so that they stream from HBM): how the same kernel does when the
         # fixed cost of a launch is spread over 4-14 times the bytes
-        big = {}
+        big, big_m = {}, {}
         gen = torch.Generator(device=dev)
         gen.manual_seed(70)
         for name, N, K in gs.SHAPES_70B if "big" in legs else ():
@@ -257,10 +261,33 @@ def main():
             torch.cuda.synchronize()
             us = e0.elapsed_time(e1) * 1e3 / (8 * len(calls))
             big[f"{name}_{N}x{K}"] = {"us": round(us, 2), "GB/s": round(algorithmic_bytes(P0, 1) / us / 1e3, 1)}
-            del Ps, P0, calls, graph
+            del calls, graph
+            # the same matrices at M = 64 and M = 2048 (prebuilt index; eager launches, rotating copies)
+            indexes = [gwq.linear_index(P) for P in Ps]
+            for M in (64, 2048):
+                x = torch.randn((M, K), device=dev, generator=gen).half()
+                y = torch.empty((M, N), dtype=torch.float16, device=dev)
+                calls = [gwq.prepare_linear(P, x, y, index=ix) for P, ix in zip(Ps, indexes)]
+                for call in calls:
+                    call()
+                torch.cuda.synchronize()
+                reps = 4 if M == 2048 else 10
+                e0.record()
+                for _ in range(reps):
+                    for call in calls:
+                        call()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / (reps * len(calls))
+                big_m.setdefault(f"M{M}", {})[f"{name}_{N}x{K}"] = {
+                    "us": round(us, 1), "TFLOP/s": round(flops(P0, M) / us / 1e6, 1),
+                    "GB/s": round(algorithmic_bytes(P0, M) / us / 1e3, 1)}
+                del calls, x, y
+            del Ps, P0, indexes
             torch.cuda.empty_cache()
         if big:
             extra["decode_M1_70b_shapes"] = big
+            extra["linear_70b_shapes"] = big_m
         # The same decode pass with FP16 weights through the vendor library (torch's F.linear), as the
         # paper's efficiency table does (Sec. 4.2: speed and memory against FP16): 7 products per pass,
         # two rotated copies of the FP16 layer (809 MB), graph replay.  Comparison only, not a product path.
@@ -355,6 +382,37 @@ def main():
                 except Exception as ex:                    # the comparison must not take the benchmark down
                     extra["fp16_library_prefill_M2048"] = {"error": str(ex)[:200]}
             del xs, ys
+        # The same layer packed at 3 bits (13 words per group): decode M = 1 and M = 8 the way the headline
+        # is timed (grouped launches, six rotating copies, graph replay), and the prefill pass.
+        if "int3" in legs and layers3:
+            copies3 = [layers3] + [[clone_layer(P) for P in layers3] for _ in range(args.copies - 1)]
+            int3 = {}
+            for M in (1, 8):
+                s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), 12, args.launch, args.group, copies=copies3)
+                int3[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
+                                        "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 2)}
+            del copies3
+            M = 2048
+            xs, ys = make_xy(M)
+            fl3 = sum(flops(P, M) for P in layers3)
+            indexes = [gwq.linear_index(P) for P in layers3]
+            calls = [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(layers3)]
+            for _ in range(3):
+                for c in calls:
+                    c()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(10):
+                for c in calls:
+                    c()
+            torch.cuda.synchronize()
+            s3 = (time.perf_counter() - t) / 10
+            int3["prefill_M2048_indexed"] = {"TFLOP/s": round(fl3 / s3 / 1e12, 1), "ms_per_pass": round(s3 * 1e3, 4),
+                                             "pct_mfma_f16_peak": round(100 * fl3 / s3 / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)}
+            int3["weight_bytes"] = sum(P.nbytes() for P in layers3)
+            extra["int3"] = int3
+            del indexes, calls, xs, ys
+            torch.cuda.empty_cache()
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
         pk = {}
         for name, Wd, Sd in pack_inputs if "pack" in legs else ():

@@ -53,29 +53,33 @@ template <> struct Slot<4> {
         const uint32_t off = group_off + 16 * b;
         w = *reinterpret_cast<const uint4 *>(at_byte(q, off < end - 16 ? off : end - 16));
     }
-    __device__ inline void decode(uint32_t z, int /*b*/, const DecodeConsts &d, u32x4 f[4]) const
+    __device__ inline void decode(uint32_t z, int /*b*/, const DecodeConsts &d, u32x4 f[4], int /*tail_lane4*/) const
     {
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
         decode_slot4(ww, z, d, f);
     }
 };
+// 3-bit: a group is 13 words, slot b owns words 3b .. 3b+2 and two codes of word 12 (the tail).  One
+// 16-byte load at byte 12b (4-byte aligned; gfx950 global memory takes that) brings a lane its three
+// words and one more: for slot 3 that fourth word is the tail, which the other three lanes of the
+// channel then fetch from it with a cross-lane read - one memory instruction per group instead of two.
 template <> struct Slot<3> {
-    uint32_t w[3], tail;
+    uint32_t w[3], fourth;
     __device__ inline void load(const uint32_t *q, uint32_t group_off, int b)
     {
-        const uint32_t *p = at_byte(q, group_off + 12 * b);
-        w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
-        tail = *at_byte(q, group_off + 48);
+        const U128a4 v = *reinterpret_cast<const U128a4 *>(at_byte(q, group_off + 12 * b));
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; fourth = v.w;
     }
     __device__ inline void load_clamped(const uint32_t *q, uint32_t group_off, int b, uint32_t end)
     {
         const uint32_t off = group_off + 12 * b;
-        const uint32_t *p = at_byte(q, off < end - 12 ? off : end - 12);
-        w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
-        tail = *at_byte(q, group_off + 48 < end - 4 ? group_off + 48 : end - 4);
+        const U128a4 v = *reinterpret_cast<const U128a4 *>(at_byte(q, off < end - 16 ? off : end - 16));
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; fourth = v.w;
     }
-    __device__ inline void decode(uint32_t z, int b, const DecodeConsts &d, u32x4 f[4]) const
+    // tail_lane4 = 4 * (lane | 48): the byte index of the lane that holds slot 3 of the same channel.
+    __device__ inline void decode(uint32_t z, int b, const DecodeConsts &d, u32x4 f[4], int tail_lane4) const
     {
+        const uint32_t tail = (uint32_t)__builtin_amdgcn_ds_bpermute(tail_lane4, (int)fourth);
         decode_slot3(w, tail >> (3 * b), z, d, f);
     }
 };
@@ -151,6 +155,7 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwaves = batch.nwaves, nthreads = nwaves * 64;
     const int r = lane & 15, b = lane >> 4;
+    const int tail_lane4 = 4 * (lane | 48);             // where the 3-bit tail word of this lane's channel arrives
     const int gpr = K / kGroup;
     const int my_waves = (gpr + U - 1) / U;             // waves of this layer that own groups
     const bool active = wave < my_waves;
@@ -281,7 +286,7 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
             const _Float16 s = __builtin_bit_cast(_Float16, sc_lane[u]);
             const uint32_t z = zp_lane[u];
             u32x4 wb[4];
-            slot[u].decode(z, b, dc, wb);
+            slot[u].decode(z, b, dc, wb, tail_lane4);
             float4v part = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -409,6 +414,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int M = batch.M, nwaves = batch.nwaves, nthreads = nwaves * 64;
     const int r = lane & 15, b = lane >> 4;
+    const int tail_lane4 = 4 * (lane | 48);             // where the 3-bit tail word of this lane's channel arrives
     const int gpr = K / kGroup;
     const int chunk_groups = nwaves * U;                // groups per phase
     const int chunk = chunk_groups * kGroup;            // columns per phase
@@ -537,7 +543,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc_lane[u] & keep));
                 const uint32_t z = BITS == 3 ? zp_lane[u] & keep : zp_lane[u];
                 u32x4 wb[4];
-                slot[u].decode(z, b, dc, wb);
+                slot[u].decode(z, b, dc, wb, tail_lane4);
                 float4v part = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)

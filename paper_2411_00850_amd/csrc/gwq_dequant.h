@@ -35,6 +35,10 @@ __device__ inline uint32_t opaque_v(uint32_t c)
     return r;
 }
 
+// Sixteen bytes at 4-byte alignment (gfx950 global memory takes unaligned vector loads): the 3-bit
+// slots start every 12 bytes.
+struct __attribute__((packed, aligned(4))) U128a4 { uint32_t x, y, z, w; };
+
 // Masks (SGPR) and magic numbers (VGPR) of the decoders, materialised once per kernel.
 struct DecodeConsts {
     uint32_t m0, m1, m2, k1024, kmid, k16;

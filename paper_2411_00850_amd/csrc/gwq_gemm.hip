@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void group_index_kernel(const int32_t *__restr
 // ------------------------------------------------------------------------------------------------
 template <int BITS> struct SlotRegs;
 template <> struct SlotRegs<4> { uint32_t w[4]; };
-template <> struct SlotRegs<3> { uint32_t w[3], tail; };
+template <> struct SlotRegs<3> { uint32_t w[3], fourth; };    // fourth: the word after the slot's three (slot 3: the tail word)
 
 template <int BITS> __device__ inline void load_slot(SlotRegs<BITS> &r, const uint32_t *group, int slot);
 template <> __device__ inline void load_slot<4>(SlotRegs<4> &r, const uint32_t *group, int slot)
@@ -113,9 +113,9 @@ template <> __device__ inline void load_slot<4>(SlotRegs<4> &r, const uint32_t *
 }
 template <> __device__ inline void load_slot<3>(SlotRegs<3> &r, const uint32_t *group, int slot)
 {
-    const uint32_t *p = group + 3 * slot;
-    r.w[0] = p[0]; r.w[1] = p[1]; r.w[2] = p[2];
-    r.tail = group[12] >> (3 * slot);
+    // one 16-byte load at 4-byte alignment; it stays inside the group's 13 words for every slot
+    const U128a4 v = *reinterpret_cast<const U128a4 *>(group + 3 * slot);
+    r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.fourth = v.w;
 }
 
 // A 16-bit load that is complete when it returns, invisible to the compiler's bookkeeping of
@@ -149,9 +149,10 @@ __device__ inline u32x4 dequant_frag(const SlotRegs<4> &r, int j, uint32_t z, ui
     f.x = pk_mul(f.x, s2); f.y = pk_mul(f.y, s2); f.z = pk_mul(f.z, s2); f.w = pk_mul(f.w, s2);
     return f;
 }
-__device__ inline void dequant_all(const SlotRegs<3> &r, uint32_t z, uint32_t s2, const DecodeConsts &d, u32x4 f[4])
+__device__ inline void dequant_all(const SlotRegs<3> &r, uint32_t tail_pair, uint32_t z, uint32_t s2, const DecodeConsts &d,
+                                   u32x4 f[4])
 {
-    decode_slot3(r.w, r.tail, z, d, f);
+    decode_slot3(r.w, tail_pair, z, d, f);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         f[j].x = pk_mul(f[j].x, s2); f[j].y = pk_mul(f[j].y, s2);
@@ -266,8 +267,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                 for (int j = 0; j < 4; ++j)
                     *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = dequant_frag(G.slot[half], j, z, s2, dc);
             } else {
+                // The group's tail word is the fourth word of slot 3, which the odd thread of the
+                // channel has loaded: both threads of the pair read it from there (quad_perm 1,1,3,3).
+                const uint32_t tail = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)G.slot[1].fourth, 0xF5, 0xF, 0xF, false);
                 u32x4 f[4];
-                dequant_all(G.slot[half], z, s2, dc, f);
+                dequant_all(G.slot[half], tail >> (3 * (2 * half + b_h)), z, s2, dc, f);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
             }
