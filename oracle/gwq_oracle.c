@@ -12,7 +12,10 @@
  *   Eq. 8  outliers    O = 1(|W_grad| >= quantile): the largest 1 % of |gradient| stay FP16
  *   Eq. 9  quantise    q = round(W / s) + z        (non-outliers only)
  *   Eq. 10 dequantise  Q(W) = s * (q - z)
- * and the layer it serves, y = x * (Q(W) + outliers)^T, with no bias (Sec. 3.1 disables it).
+ * and the layer it serves, y = x * (Q(W) + outliers)^T, with no bias (Sec. 3.1 disables it);
+ * and Sec. 3.1 for the two figures of merit of a packed layer:
+ *   Eq. 4  squared error           || W - W_Q ||^2
+ *   Eq. 3, 5  first-order change   g^T (W - W_Q) of the loss (its Taylor expansion around W)
  *
  * Readings taken where the text is silent or garbled (each is also listed in the design
  * notes of the repository):
@@ -31,7 +34,8 @@
  * scale against an exhaustive search over every FP16 value with exact rationals, zero point
  * and codes against exact-rational rounding, the |w - Q(w)| <= s/2 bound, the special cases
  * ppm = 0 (plain group-wise RTN) and ppm = 1e6 (y = x W^T by numpy's fp64 matmul), word
- * layouts against hand-assembled words, and the linear map against numpy on decoded weights.
+ * layouts against hand-assembled words, the linear map against numpy on decoded weights, and
+ * the figures of merit against exact rationals on the hand-worked groups.
  * Parity with the paper's model-level results (perplexity, accuracy, the 1.2x speedup) is
  * parity unpinned: it needs the models and datasets, which are not available.
  *
@@ -418,4 +422,38 @@ int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, const uint32_t *qweigh
     }
     free(Xd);
     return failed ? GWQ_ORACLE_NO_MEM : GWQ_ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- figures of merit -- */
+
+/* Sec. 3.1: with W_Q the decoded layer (Eq. 10 plus the FP16 outliers) and D = W - W_Q,
+ *   out[0] = sum D^2          (Eq. 4: what the quantiser minimises)
+ *   out[1] = sum score * D    (Eq. 3 and 5: g^T (W - W_Q), the first-order change of the loss
+ *                              when `score` is the gradient g)
+ *   out[2] = max |D|
+ * Every D is computed in fp64 from exact operands; the sums run in fp64 over n, then k, ascending. */
+int gwq_oracle_quality(int64_t N, int64_t K, int bits, const uint32_t *qweight,
+                       const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
+                       const uint16_t *col_idx, const uint16_t *out_val,
+                       const uint16_t *W, const void *score, int score_is_f16, double *out)
+{
+    if (!qweight || !scales || !zeros || !row_ptr || !W || !score || !out) return GWQ_ORACLE_BAD_ARG;
+    if (N <= 0 || K <= 0 || K % GWQ_GROUP || (bits != 3 && bits != 4)) return GWQ_ORACLE_BAD_ARG;
+    double *w_hat = (double *)malloc((size_t)K * sizeof(double));
+    if (!w_hat) return GWQ_ORACLE_NO_MEM;
+    double sq = 0.0, first = 0.0, mx = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+        decode_row(n, K, bits, qweight, scales, zeros, row_ptr, col_idx, out_val, w_hat);
+        for (int64_t k = 0; k < K; ++k) {
+            double d = gwq_oracle_half_to_double(W[n * K + k]) - w_hat[k];
+            double g = score_is_f16 ? gwq_oracle_half_to_double(((const uint16_t *)score)[n * K + k])
+                                    : (double)((const float *)score)[n * K + k];
+            sq += d * d;
+            first += g * d;
+            if (fabs(d) > mx) mx = fabs(d);
+        }
+    }
+    free(w_hat);
+    out[0] = sq; out[1] = first; out[2] = mx;
+    return GWQ_ORACLE_OK;
 }

@@ -31,6 +31,7 @@ def _load():
     lib.gwq_oracle_pack.argtypes = [vp, vp, i32, i64, i64, i32, u32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_decode.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    lib.gwq_oracle_quality.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     return lib
 
 
@@ -192,3 +193,14 @@ def linear_f64(P, X, rows=None):
                                     _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(Xb), M,
                                     _p(rows_arr), n_rows, _p(Y)), "linear_f64")
     return Y
+
+
+def quality(P, W, score):
+    """(sum (W - W_Q)^2, sum score * (W - W_Q), max |W - W_Q|) in fp64 (Sec. 3.1, Eq. 3-5)."""
+    Wb = _f16_bits(W)
+    score, is16 = _score(score)
+    assert Wb.shape == (P.N, P.K) and score.shape == (P.N, P.K)
+    out = np.empty(3, np.float64)
+    _chk(_lib.gwq_oracle_quality(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros), _p(P.row_ptr),
+                                 _p(P.col_idx), _p(P.out_val), _p(Wb), _p(score), is16, _p(out)), "quality")
+    return float(out[0]), float(out[1]), float(out[2])

@@ -439,3 +439,62 @@ def test_four_bits_beat_three_bits():
     for bits in (3, 4):
         err[bits] = np.linalg.norm(orc.linear_f64(orc.pack(W, S, bits, 10000), X) - ref)
     assert err[4] < err[3]
+
+
+# ----------------------------------------------------------------------------- Sec. 3.1, Eq. 3-5: figures of merit
+
+@pytest.mark.parametrize("row", [r for r in _golden_groups() if 128 % len(r[1]) == 0 and len(r[1]) >= 2])
+def test_quality_on_hand_worked_groups(row):
+    """|| W - W_Q ||^2 (Eq. 4), g^T (W - W_Q) (Eq. 3, 5) and max |W - W_Q| of a one-channel layer made
+    of one hand-worked group repeated to 128 columns, against exact rationals computed from the
+    fixture's own scale, zero point and codes (not from the oracle's decoder).  The scores ascend
+    with the column and are negative in the second half, so a swapped sign, a dropped outlier or a
+    shifted index all change the expected numbers."""
+    bits, w, mask, s_bits, z, codes = row
+    reps = 128 // len(w)
+    W = np.array(w * reps, np.float16).reshape(1, 128)
+    M = np.array(mask * reps, np.uint8).reshape(1, 128)
+    g = np.where(np.arange(128) < 64, np.arange(128) + 1, -(np.arange(128) + 1)).astype(np.float32).reshape(1, 128)
+    P = orc.encode(W, M, bits)
+    assert int(P.scales[0, 0]) == s_bits and int(P.zeros[0, 0]) == z           # the tiling keeps the group's range
+    s = half_fraction(s_bits)
+    sq = first = mx = Fraction(0)
+    for k in range(128):
+        i = k % len(w)
+        w_q = Fraction(w[i]) if mask[i] else s * (codes[i] - z)
+        d = Fraction(w[i]) - w_q
+        sq += d * d
+        first += Fraction(int(g[0, k])) * d
+        mx = max(mx, abs(d))
+    got = orc.quality(P, W, g)
+    for have, want in zip(got, (sq, first, mx)):
+        assert abs(Fraction(have) - want) <= abs(want) * Fraction(1, 10 ** 13)
+    if any(mask) and not all(mask):
+        # the same layer without its outliers kept: a different (larger) error, so the CSR part matters
+        assert orc.quality(orc.encode(W, np.zeros_like(M), bits), W, g)[0] != got[0]
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_quality_special_cases_and_invariants(bits):
+    W, S = _small_problem(60 + bits, N=24, K=384)
+    # everything kept in FP16: no error at all
+    assert orc.quality(orc.pack(W, S, bits, 1000000), W, S) == (0.0, 0.0, 0.0)
+    P = orc.pack(W, S, bits, 10000)
+    D = W.astype(np.float64) - orc.decode(P)
+    sq, first, mx = orc.quality(P, W, S)
+    # definitions through numpy's own reductions
+    assert np.isclose(sq, np.sum(D * D), rtol=1e-12)
+    assert np.isclose(first, np.sum(S.astype(np.float64) * D), rtol=1e-9, atol=1e-12 * np.sum(np.abs(S * D)))
+    assert mx == np.max(np.abs(D))
+    # with the error itself as the score the two sums coincide (D is exact in FP32 here: few bits)
+    Dg = D.astype(np.float32)
+    assert np.array_equal(Dg.astype(np.float64), D)
+    sq2, first2, _ = orc.quality(P, W, Dg)
+    assert np.isclose(first2, sq2, rtol=1e-12)
+    # half a step bounds the error of every kept weight (the scale never clips), outliers have none
+    s_max = float(P.scales.view(np.float16).astype(np.float64).max())
+    assert mx <= s_max / 2 * (1 + 1e-12)
+    assert mx * mx <= sq <= W.size * mx * mx
+    # FP16 scores give the same numbers as their FP32 widening
+    S16 = S.astype(np.float16)
+    assert orc.quality(P, W, S16) == orc.quality(P, W, S16.astype(np.float32))
