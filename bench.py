@@ -414,7 +414,7 @@ def main():
             del indexes, calls, xs, ys
             torch.cuda.empty_cache()
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
-        pk = {}
+        pk, qual = {}, {}
         for name, Wd, Sd in pack_inputs if "pack" in legs else ():
             gwq.pack(Wd, Sd, 4, 10000)
             torch.cuda.synchronize()
@@ -425,8 +425,20 @@ def main():
             s = (time.perf_counter() - t) / 3
             b = Wd.numel() * 6 + P.nbytes()
             pk[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1)}
+            # gwq_quality on what was just packed: W, score and the packed layer read once
+            out3 = gwq.quality(P, Wd, Sd)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(5):
+                gwq.quality(P, Wd, Sd, out=out3)
+            torch.cuda.synchronize()
+            s = (time.perf_counter() - t) / 5
+            qual[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1),
+                          "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 1),
+                          "rms_error": float((out3[0] / Wd.numel()).sqrt())}
         if pk:
             extra["pack_int4"] = pk
+            extra["quality_int4"] = qual
         out["extras"] = extra
 
     if not args.no_cpu_baseline:

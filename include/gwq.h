@@ -84,6 +84,7 @@ typedef struct {
     size_t linear_index;      /* the per-layer index of gwq_linear_index                  */
     size_t linear_scratch;    /* for gwq_linear_indexed with M <= M_max (0 when <= 16)    */
     int64_t n_outliers;
+    size_t quality_workspace; /* for gwq_quality                                          */
 } gwq_sizes;
 
 /* Sizes for a layer (pure host arithmetic, touches no device).  scales, zeros, col_idx and
@@ -145,6 +146,20 @@ gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M,
 #define GWQ_MAX_BATCH 8
 gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const void *const *X_f16,
                             int32_t M, void *const *Y_f16, void *stream);
+
+/* Figures of merit of a packed layer against the weights W it was packed from (Sec. 3.1).  With W_Q
+ * the decoded layer - s*(q-z) (Eq. 10) where a weight was quantised, the stored FP16 value where it was
+ * kept - and D = W - W_Q:
+ *   out[0] = sum D^2          the squared error the quantiser minimises (Eq. 4)
+ *   out[1] = sum score * D    g^T (W - W_Q): the first-order change of the loss (Eq. 3 and 5) when
+ *                             `score` is the gradient the outliers were ranked by
+ *   out[2] = max |D|
+ *   W_f16 device [N][K], score device [N][K] of `score_dtype`, out_f64 device, 3 doubles, 8-byte aligned;
+ *   workspace device, >= quality_workspace bytes as gwq_layout reports, 8-byte aligned.
+ * Every D is exact (fp64 from FP16 operands); the sums are fp64 in a fixed order, so the results are
+ * identical from run to run.  Inputs are expected to be finite. */
+gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, gwq_score_dtype score_dtype,
+                       double *out_f64, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
  * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 4:

@@ -33,6 +33,7 @@ class _Sizes(ctypes.Structure):
                                                 "out_val", "pack_workspace", "linear_workspace", "linear_index",
                                                 "linear_scratch")]
     _fields_.append(("n_outliers", ctypes.c_int64))
+    _fields_.append(("quality_workspace", ctypes.c_size_t))
 
 
 _lib = None
@@ -55,6 +56,8 @@ def lib():
         L.gwq_layout.argtypes = [i32, i32, i32, i32, u32, i32, ctypes.POINTER(_Sizes)]
         L.gwq_pack.restype = ctypes.c_int
         L.gwq_pack.argtypes = [vp, vp, ctypes.c_int, ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
+        L.gwq_quality.restype = ctypes.c_int
+        L.gwq_quality.argtypes = [ctypes.POINTER(_Packed), vp, vp, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
         L.gwq_linear.restype = ctypes.c_int
         L.gwq_linear.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
         L.gwq_linear_index.restype = ctypes.c_int
@@ -160,6 +163,31 @@ def pack(W, score, bits, ppm=10000, stream=None, workspace=None):
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_pack")
     return P
+
+
+def quality(P, W, score, out=None, stream=None, workspace=None):
+    """gwq_quality: float64 tensor [sum (W - W_Q)^2, sum score * (W - W_Q), max |W - W_Q|] on the GPU for the
+    packed layer P against the weights W (FP16 [N, K]) and scores (FP32/FP16 [N, K]) it was packed from."""
+    import torch
+    assert W.is_cuda and score.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
+    assert tuple(W.shape) == (P.N, P.K) and score.shape == W.shape and score.is_contiguous()
+    if score.dtype == torch.float32:
+        st = SCORE_F32
+    elif score.dtype == torch.float16:
+        st = SCORE_F16
+    else:
+        raise TypeError("score must be float32 or float16")
+    if out is None:
+        out = torch.empty(3, dtype=torch.float64, device=W.device)
+    if workspace is None:
+        nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, 0)["quality_workspace"]
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    cs = P.c_struct()
+    rc = lib().gwq_quality(ctypes.byref(cs), W.data_ptr(), score.data_ptr(), st, out.data_ptr(), workspace.data_ptr(),
+                           workspace.numel(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_quality")
+    return out
 
 
 def linear_workspace(P, M, device="cuda"):

@@ -77,6 +77,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     out->linear_scratch = gwq::gemm_scratch_bytes(N, M_max);
     out->linear_workspace = M_max > 16 ? out->linear_index + out->linear_scratch : 0;
     out->n_outliers = k_out;
+    out->quality_workspace = gwq::quality_workspace_bytes(N);
     return GWQ_OK;
 }
 
@@ -91,6 +92,21 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
     if (((uintptr_t)workspace & 3) || ((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 15)) return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_pack(W_f16, score, score_dtype == GWQ_SCORE_F16, *dst,
                                     static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, gwq_score_dtype score_dtype,
+                       double *out_f64, void *workspace, size_t workspace_bytes, void *stream)
+{
+    gwq_status s = check_packed(P);
+    if (s != GWQ_OK) return s;
+    if (!W_f16 || !score || !out_f64) return GWQ_ERR_NULL;
+    if (score_dtype != GWQ_SCORE_F32 && score_dtype != GWQ_SCORE_F16) return GWQ_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < gwq::quality_workspace_bytes(P->N)) return GWQ_ERR_WORKSPACE;
+    if (((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 3) || ((uintptr_t)workspace & 7) || ((uintptr_t)out_f64 & 7))
+        return GWQ_ERR_SHAPE;
+    hipError_t e = gwq::launch_quality(*P, W_f16, score, score_dtype == GWQ_SCORE_F16, workspace, out_f64,
+                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 

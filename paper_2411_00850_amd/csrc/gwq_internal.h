@@ -40,4 +40,9 @@ hipError_t launch_gemm_index(const gwq_packed &P, void *index, hipStream_t strea
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
                        size_t scratch_bytes, int ms_override, hipStream_t stream);         // reads them
 
+// workspace: quality_workspace_bytes(N) bytes, 8-byte aligned (one partial result per channel); out: 3 doubles.
+size_t quality_workspace_bytes(int64_t N);
+hipError_t launch_quality(const gwq_packed &P, const void *W, const void *score, int score_is_f16, void *workspace,
+                          double *out, hipStream_t stream);
+
 }  // namespace gwq

@@ -19,7 +19,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_calls():
     assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_index",
-                                    "gwq_linear_indexed", "gwq_pack",
+                                    "gwq_linear_indexed", "gwq_pack", "gwq_quality",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
 
@@ -114,6 +114,24 @@ def test_linear_index_validates_before_touching_the_device():
     assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need - 1, None, 0, None) == -4
     assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, ctypes.c_void_p(0x1004), need, None, 0, None) == -2
     assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need, ctypes.c_void_p(0x1004), 64, None) == -2
+
+
+def test_quality_validates_before_touching_the_device():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ok = _packed()
+    need = gwq.layout(4, 128, 4)["quality_workspace"]
+    assert need == 4 * 24                                                       # three doubles per channel
+    assert L.gwq_quality(None, fake, fake, 0, fake, fake, need, None) == -1
+    assert L.gwq_quality(ctypes.byref(ok), None, fake, 0, fake, fake, need, None) == -1
+    assert L.gwq_quality(ctypes.byref(ok), fake, None, 0, fake, fake, need, None) == -1
+    assert L.gwq_quality(ctypes.byref(ok), fake, fake, 0, None, fake, need, None) == -1
+    assert L.gwq_quality(ctypes.byref(ok), fake, fake, 2, fake, fake, need, None) == -3
+    assert L.gwq_quality(ctypes.byref(ok), fake, fake, 0, fake, None, need, None) == -4
+    assert L.gwq_quality(ctypes.byref(ok), fake, fake, 0, fake, fake, need - 1, None) == -4
+    assert L.gwq_quality(ctypes.byref(ok), ctypes.c_void_p(0x1008), fake, 0, fake, fake, need, None) == -2
+    assert L.gwq_quality(ctypes.byref(ok), fake, fake, 0, ctypes.c_void_p(0x1004), fake, need, None) == -2
+    assert L.gwq_quality(ctypes.byref(_packed(bits=5)), fake, fake, 0, fake, fake, need, None) == -3
 
 
 def test_linear_batch_validates_before_touching_the_device():
