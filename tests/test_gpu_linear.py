@@ -135,6 +135,17 @@ def test_gemm_small(bits, N, K, M):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,M", [(256, 256, 512), (260, 384, 300), (384, 128, 256), (130, 256, 256), (128, 512, 128)])
+def test_gemm_whole_and_partial_tiles(bits, N, K, M):
+    """Launches whose tiles all lie wholly inside Y, and launches with a ragged last m- or n-tile or
+    rows of Y that are not a multiple of four long; every element is checked."""
+    from gpu_helpers import assert_close
+    P, rng = _problem(3 * N + K + M + bits, N, K, bits)
+    X = gs.activations(M, K, rng, hot_frac=0.01)
+    assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm tiles N={N} K={K} M={M} bits={bits}")
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("N,M", [(16, 17), (130, 40), (257, 129)])
 def test_gemm_shortest_rows(bits, N, M):
     """The GEMM at K = 128: one group, two steps, the shortest loop every role of the kernel can run."""
