@@ -132,7 +132,7 @@ def main():
         xs, ys = make_xy(M)
         groups = GROUPS[grouping]
         layers = copies[0]
-        n_launch, n_copies = len(groups), len(copies)
+        n_launch, n_copies = sum(len({layers[j].K for j in g}) for g in groups), len(copies)   # a grouped call launches once per distinct K
         calls = [[gwq.prepare_linear_batch([c[j] for j in g], [xs[c[j].K] for j in g], [ys[j] for j in g])
                   if len(g) > 1 else gwq.prepare_linear(c[g[0]], xs[c[g[0]].K], ys[g[0]]) for g in groups]
                  for c in copies]
@@ -201,7 +201,7 @@ def main():
         "config": {"workload": "7B decoder layer (q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008), "
                                "int4 g128 + 1% fp16 CSR outliers, decode M=1",
                    "launches_per_step": n_launch, "grouping": {"deps": "qkv | o | gate,up | down", "none": "one launch per matrix",
-                                                               "all": "one launch over the 7 matrices"}[args.group],
+                                                               "all": "one call over the 7 matrices (one launch per distinct K)"}[args.group],
                    "copies_rotated": args.copies, "bytes_per_step": bytes_step, "launch": args.launch},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "decode_small_kernel<4,8,1> (4-bit, M=1, 8 groups per wave)", "achieved": round(achieved, 1),

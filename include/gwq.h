@@ -136,13 +136,14 @@ gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M,
                               const void *index, size_t index_bytes, void *scratch,
                               size_t scratch_bytes, void *stream);
 
-/* Several layers in ONE decode launch (M <= 16): Y_f16[i] = gwq_linear(P[i], X_f16[i]) for
+/* Several layers in one decode launch (M <= 16): Y_f16[i] = gwq_linear(P[i], X_f16[i]) for
  * i < count <= GWQ_MAX_BATCH.  For layers with no data dependence between them, such as the q, k
  * and v or the gate and up projections of a decoder layer (which may share one X): at decode sizes a
  * launch is dominated by latency rather than bandwidth, and one launch over more bytes hides it
  * (the paper's efficiency table, Sec. 4.2, measures whole-model decode).  All layers must have the same
- * `bits`; N and K may differ.  P, X_f16 and Y_f16 are HOST arrays of `count` pointers (to host
- * structs / device buffers); they are read before the call returns.  Same rules as gwq_linear. */
+ * `bits`; N and K may differ (layers of equal K share a launch, so a batch with two values of K takes two).
+ * P, X_f16 and Y_f16 are HOST arrays of `count` pointers (to host structs / device buffers); they are
+ * read before the call returns.  Same rules as gwq_linear. */
 #define GWQ_MAX_BATCH 8
 gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const void *const *X_f16,
                             int32_t M, void *const *Y_f16, void *stream);

@@ -167,8 +167,25 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
              (uintptr_t)P[i]->col_idx | (uintptr_t)P[i]->out_val) & 15)
             return GWQ_ERR_SHAPE;
     }
-    hipError_t e = gwq::launch_decode(count, P, X_f16, M, Y_f16, g_decode_waves, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+    // One launch per distinct K, in order of first appearance: a launch runs as many waves per block as
+    // its longest rows need, and the surplus waves of a layer with shorter rows would only repeat work.
+    bool done[GWQ_MAX_BATCH] = {};
+    for (int32_t i = 0; i < count; ++i) {
+        if (done[i]) continue;
+        const gwq_packed *p[GWQ_MAX_BATCH];
+        const void *x[GWQ_MAX_BATCH];
+        void *y[GWQ_MAX_BATCH];
+        int n = 0;
+        for (int32_t j = i; j < count; ++j)
+            if (!done[j] && P[j]->K == P[i]->K) {
+                p[n] = P[j]; x[n] = X_f16[j]; y[n] = Y_f16[j];
+                done[j] = true;
+                ++n;
+            }
+        hipError_t e = gwq::launch_decode(n, p, x, M, y, g_decode_waves, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return GWQ_ERR_DEVICE;
+    }
+    return GWQ_OK;
 }
 
 gwq_status gwq_tuning_set(const char *key, int32_t value)
