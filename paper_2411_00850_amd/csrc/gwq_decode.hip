@@ -39,6 +39,16 @@ __device__ inline const uint32_t *at_byte(const uint32_t *base, uint32_t byte_of
     return reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + byte_off);
 }
 
+// Eight CSR entries as staged in LDS: one word per entry, column in the low half and FP16 value in
+// the high half, so that an entry costs its reader one LDS read instead of two.
+__device__ inline void store_entries(u32x4 *dst, u32x4 col, u32x4 val)
+{
+    dst[0] = u32x4{(col.x & 0xFFFFu) | val.x << 16, col.x >> 16 | (val.x & 0xFFFF0000u),
+                   (col.y & 0xFFFFu) | val.y << 16, col.y >> 16 | (val.y & 0xFFFF0000u)};
+    dst[1] = u32x4{(col.z & 0xFFFFu) | val.z << 16, col.z >> 16 | (val.z & 0xFFFF0000u),
+                   (col.w & 0xFFFFu) | val.w << 16, col.w >> 16 | (val.w & 0xFFFF0000u)};
+}
+
 // Registers of one slot (32 codes) as loaded from memory; offsets are bytes from qweight.
 template <int BITS> struct Slot;
 template <> struct Slot<4> {
@@ -126,7 +136,7 @@ struct DecodeBatch {
 //     a shorter layer repeat wave 0's work and drop the result.
 //
 // Dynamic LDS, in this order: X [MS][k_pad] halves | scales [16][gpr] halves | zero points [16][gpr]
-// bytes | 16 spare bytes | CSR columns, blockDim * 8 entries + 8 zero entries | CSR values, same |
+// bytes | 16 spare bytes | CSR entries (column | value << 16), blockDim * 8 + 8 zero entries |
 // partial sums [waves][MS][64] floats.  blockDim >= 3 gpr holds by construction (64 ceil(gpr / U)
 // threads, U <= 16), so one 16-byte vector per thread stages all scales and zero points.
 template <int BITS, int U, int MS>
@@ -169,9 +179,8 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     const uint32_t sc_off = (uint32_t)MS * k_pad * 2;
     const uint32_t zp_off = sc_off + 32 * gpr;
     const uint32_t spare_off = zp_off + 16 * gpr;
-    const uint32_t col_off = spare_off + 16;
-    const uint32_t val_off = col_off + 16 * nthreads + 16;
-    const uint32_t red_off = val_off + 16 * nthreads + 16;
+    const uint32_t ent_off = spare_off + 16;
+    const uint32_t red_off = ent_off + 32 * nthreads + 32;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
 
     // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
@@ -299,11 +308,10 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
 
     // The CSR segment has arrived by now: publish it, followed by one vector of zero entries that
     // lanes without an entry read instead.
-    reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
-    reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+    store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
     if (tid == 0) {
-        reinterpret_cast<u32x4 *>(lds_raw + col_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
-        reinterpret_cast<u32x4 *>(lds_raw + val_off)[nthreads] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4 *>(lds_raw + ent_off)[2 * nthreads] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4 *>(lds_raw + ent_off)[2 * nthreads + 1] = u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
 
@@ -312,8 +320,7 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
     const int o_stride = 4 * nwaves;
     const bool o_live = n < N;
     const int o_end = o_live ? (rp1 < staged_end ? rp1 : staged_end) : 0;   // end of the lane's staged entries
-    const unsigned char *col_base = lds_raw + col_off;
-    const uint32_t val_delta = val_off - col_off;
+    const uint32_t *entries = reinterpret_cast<const uint32_t *>(lds_raw + ent_off);
     float oacc[MS];
 #pragma unroll
     for (int e = 0; e < MS; ++e) oacc[e] = 0.f;
@@ -323,8 +330,8 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
         for (int e = 0; e < MS; ++e) oacc[e] = __builtin_fmaf((float)v, (float)xs[(uint32_t)e * k_pad + col], oacc[e]);
     };
     auto staged = [&](int idx) {
-        const unsigned char *p = col_base + 2 * idx;
-        add_outlier(*reinterpret_cast<const uint16_t *>(p), *reinterpret_cast<const uint16_t *>(p + val_delta));
+        const uint32_t entry = entries[idx];
+        add_outlier(entry & 0xFFFFu, (uint16_t)(entry >> 16));
     };
     const int j_first = rp0 + 4 * wave + b;
 #pragma unroll
@@ -386,7 +393,7 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
 //
 // MR = 8 or 16: rows of X staged (M <= MR; rows M .. MR-1 are loaded as copies of the last row and
 // dropped).  Dynamic LDS: X [M][chunk] halves | scales [16][gpr] halves | zero points [16][gpr]
-// bytes | 96 guard bytes | CSR columns, blockDim * 8 entries | CSR values, same | partial sums
+// bytes | 96 guard bytes | CSR entries (column | value << 16), blockDim * 8 | partial sums
 // [waves][4][64] floats.
 constexpr int kWideGuard = 96;
 
@@ -425,9 +432,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const uint32_t sc_off = (uint32_t)M * x_stride * 2;
     const uint32_t zp_off = sc_off + 32 * gpr;
     const uint32_t guard_off = zp_off + 16 * gpr;
-    const uint32_t col_off = guard_off + kWideGuard;
-    const uint32_t val_off = col_off + 16 * nthreads;
-    const uint32_t red_off = val_off + 16 * nthreads;
+    const uint32_t ent_off = guard_off + kWideGuard;
+    const uint32_t red_off = ent_off + 32 * nthreads;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
 
     const DecodeConsts dc(BITS);
@@ -439,8 +445,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const _Float16 *x_out[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(4 * b + e < M ? 4 * b + e : 0) * x_stride;   // rows m >= M are not stored
-    const uint16_t *col_lds = reinterpret_cast<const uint16_t *>(lds_raw + col_off);
-    const uint16_t *val_lds = reinterpret_cast<const uint16_t *>(lds_raw + val_off);
+    const uint32_t *entries = reinterpret_cast<const uint32_t *>(lds_raw + ent_off);
 
     // A block takes the 16-channel tiles blockIdx.x, blockIdx.x + gridDim.x, ...: when all of K is
     // one phase, the copy of X staged for the first tile serves the others too.  The codes of a
@@ -515,8 +520,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             for (int t = tid + nthreads; t < 3 * gpr; t += nthreads)
                 *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = meta_vec(t);
             if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
-            reinterpret_cast<u32x4 *>(lds_raw + col_off)[tid] = seg_col;
-            reinterpret_cast<u32x4 *>(lds_raw + val_off)[tid] = seg_val;
+            store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
         }
         if (stage_x)
 #pragma unroll
@@ -575,12 +579,13 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 const int idx = j + i * nwaves;
                 const bool in = idx < j_staged;
                 const int li = in ? idx - e0 : 0;
-                const int c = col_lds[li];
+                const uint32_t entry = entries[li];
+                const int c = (int)(entry & 0xFFFFu);
                 ok[i] = in && c < c1;
-                val[i] = ok[i] ? (float)__builtin_bit_cast(_Float16, val_lds[li]) : 0.f;
+                val[i] = ok[i] ? (float)__builtin_bit_cast(_Float16, (uint16_t)(entry >> 16)) : 0.f;
                 col[i] = ok[i] ? c - c0 : 0;
             }
-            __builtin_amdgcn_sched_barrier(0);          // all eight reads above are in flight together, ...
+            __builtin_amdgcn_sched_barrier(0);          // all four reads above are in flight together, ...
             _Float16 xv[4][4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
