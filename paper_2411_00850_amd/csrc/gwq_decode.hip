@@ -6,8 +6,9 @@
 // Mapping.  A block owns 16 output channels; its waves split K by whole groups of 128.  A wave
 // feeds v_mfma_f32_16x16x32_f16 with X as the 16 x 32 operand (rows m) and the dequantised codes
 // as the 32 x 16 operand (columns n): lane (r = lane % 16, b = lane / 16) owns slot b of each
-// group of channel n0 + r, i.e. 32 consecutive codes = one 16-byte load (4-bit) or a 12-byte
-// load plus the shared tail word (3-bit).  Codes become the exact FP16 integers q - z with one
+// group of channel n0 + r, i.e. 32 consecutive codes = one 16-byte load (at 3 bits: the slot's
+// three words plus the word behind them, which for slot 3 is the tail word all four slots share;
+// the other lanes of the channel fetch it from that lane).  Codes become the exact FP16 integers q - z with one
 // AND-OR and one packed add per pair; the group scale is applied to the four FP32 results per
 // lane after the group's four MFMAs.  The lanes then add their channel's outliers, the waves'
 // partial sums meet in LDS in a fixed order, and one thread per output rounds to FP16 and stores.
@@ -22,7 +23,8 @@
 //     per instruction against 16 for a coalesced 16-byte load), so everything except the code
 //     stream is fetched with block-wide coalesced 16-byte loads into LDS: the block's scales and
 //     zero points (contiguous for 16 consecutive channels), X, and the block's contiguous CSR
-//     segment, whose bounds come in through the scalar cache;
+//     segment (kept in LDS as one word per entry, column and value together), whose bounds come
+//     in through the scalar cache;
 //   * the instructions a wave issues: wave-uniform values are kept in scalar registers, offsets
 //     are compile-time constants, and nothing in the multiply is predicated.
 // Two kernels: the lean one for M <= 4 with all of X in LDS, the wide one for everything else.
