@@ -334,14 +334,19 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
         uint16_t s_bits;
         int z;
         scale_and_zero<BITS>(mn, mx, s_bits, z);
-        const double s = half_bits_to_double(s_bits);
 
-        // Eq. 9 per weight; an outlier takes the code z.
+        // Eq. 9 per weight; an outlier takes the code z.  The quotient is taken in FP32 (a correctly
+        // rounded division, as the oracle's is in fp64): for FP16 operands w = mw 2^a and s = ms 2^b with
+        // 11-bit mw, ms the exact quotient is either a half-integer, which FP32 holds exactly, or at
+        // least 1 / (4 ms) >= 2^-13 away from one while below 2^6 in magnitude, far more than the 2^-18
+        // an FP32 rounding can move it: both precisions round to the same integer.  Quotients too large
+        // for that argument are clamped to 0 or maxq either way.
+        const float s32 = (float)__builtin_bit_cast(_Float16, s_bits);
         uint32_t code[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const double qr = rint(half_bits_to_double(w[i]) / s) + (double)z;
-            const int q = !(qr > 0.0) ? 0 : (qr > maxq ? maxq : (int)qr);
+            const float qr = rintf((float)__builtin_bit_cast(_Float16, w[i]) / s32) + (float)z;
+            const int q = !(qr > 0.f) ? 0 : (qr > (float)maxq ? maxq : (int)qr);
             code[i] = (sel_mask >> i & 1) ? (uint32_t)z : (uint32_t)q;
         }
 
