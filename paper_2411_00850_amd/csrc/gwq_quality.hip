@@ -62,12 +62,12 @@ template <int BITS, bool F16> struct Chunk {
 // from the layout of the packed format: even positions in the low half of a word, odd ones in the
 // high half, `bits` bits apiece, ascending; 3-bit words hold ten codes and codes 30 and 31 of a slot
 // sit in the tail word at bits 3*slot and 16 + 3*slot.
-template <int BITS> __device__ inline int code_of(const uint32_t *code, int slot, int c0, int t)
+template <int BITS> __device__ inline int code_of(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t tail, int slot, int c0, int t)
 {
-    if (BITS == 4) return (int)((code[0] >> (16 * (t & 1) + 4 * (t >> 1))) & 15u);
+    if (BITS == 4) return (int)((w0 >> (16 * (t & 1) + 4 * (t >> 1))) & 15u);
     const int c = c0 + t;
-    if (c >= 30) return (int)((code[3] >> (16 * (c & 1) + 3 * slot)) & 7u);
-    const uint32_t word = c < 10 ? code[0] : c < 20 ? code[1] : code[2];
+    if (c >= 30) return (int)((tail >> (16 * (c & 1) + 3 * slot)) & 7u);
+    const uint32_t word = c < 10 ? w0 : c < 20 ? w1 : w2;
     const int p = c < 10 ? c : c < 20 ? c - 10 : c - 20;
     return (int)((word >> (16 * (p & 1) + 3 * (p >> 1))) & 7u);
 }
@@ -126,7 +126,8 @@ __global__ __launch_bounds__(kQThreads) void quality_kernel(const uint32_t *__re
             const double w = (double)(float)__builtin_bit_cast(_Float16, (uint16_t)(w2[t >> 1] >> (16 * (t & 1))));
             const double g = F16 ? (double)(float)__builtin_bit_cast(_Float16, (uint16_t)(g4[t >> 1] >> (16 * (t & 1))))
                                  : (double)__builtin_bit_cast(float, g4[t]);
-            const double d = w - s * (double)(code_of<BITS>(c.code, slot, c0, t) - z);
+            const double d = w - s * (double)(code_of<BITS>(c.code[0], c.code[BITS == 4 ? 0 : 1], c.code[BITS == 4 ? 0 : 2],
+                                                           c.code[BITS == 4 ? 0 : 3], slot, c0, t) - z);
             m.sq += d * d;
             m.first += g * d;
             m.mx = m.mx > fabs(d) ? m.mx : fabs(d);
