@@ -165,8 +165,8 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
  * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 4:
  * it picks 4, 8 or 16 groups per wave accordingly; the kernel for larger M sizes itself by the LDS it
- * needs), "gemm_rows" (rows of Y per block of the GEMM: 128 or 256; 64 is taken as 128).  Unknown
- * keys or out-of-range values return GWQ_ERR_UNSUPPORTED. */
+ * needs), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond M = 512
+ * and below that the shape a cost model of the launch expects to be fastest).  Unknown keys or out-of-range values return GWQ_ERR_UNSUPPORTED. */
 gwq_status gwq_tuning_set(const char *key, int32_t value);
 
 const char *gwq_status_string(gwq_status status);

@@ -7,7 +7,7 @@
 namespace {
 
 int g_decode_waves = 0;   // 0 = heuristic
-int g_gemm_ms = 0;        // 0 = heuristic
+int g_gemm_ms = 0;        // rows of Y per GEMM block; 0 = heuristic
 
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
@@ -197,8 +197,8 @@ gwq_status gwq_tuning_set(const char *key, int32_t value)
         return GWQ_OK;
     }
     if (!strcmp(key, "gemm_rows")) {
-        if (value != 0 && value != 64 && value != 128 && value != 256) return GWQ_ERR_UNSUPPORTED;
-        g_gemm_ms = value / 64;
+        if (value != 0 && value != 32 && value != 64 && value != 128 && value != 256) return GWQ_ERR_UNSUPPORTED;
+        g_gemm_ms = value;
         return GWQ_OK;
     }
     return GWQ_ERR_UNSUPPORTED;

@@ -3,13 +3,13 @@
 //   Y[m][n] = sum_k X[m][k] * What[n][k],  What = s*(q - z) (Sec. 3.2, Eq. 10) with the FP16
 //   outliers written over their (zero-decoding) codes.
 //
-// A block owns a BM x 128 tile of Y (BM = 256, or 128 for small M) and walks K in steps of 64 (half
+// A block owns a BM x 128 tile of Y (BM = 256; 128, 64 or 32 for small M) and walks K in steps of 64 (half
 // a group).  Per step X[BM][64] and the dequantised weights What[128][64] are staged as FP16 in LDS
 // (three buffers each) and multiplied with 32x32x16 FP16 MFMA tiles, FP32 accumulators, FP16 store.
 //
 // The 16 waves of a block have three roles, four waves per SIMD:
-//   * 8 consumers (4 along m, 2 along n) do nothing but read fragments from LDS, two k-batches
-//     ahead, and issue MFMAs;
+//   * 8 consumers (4 along m, 2 along n; 2 x 4 or 1 x 4 in the blocks for small M) do nothing but read
+//     fragments from LDS, two k-batches ahead, and issue MFMAs;
 //   * 4 producers stage the weights of the next step: codes to FP16 (exact q - z, one multiply by
 //     the scale) to LDS, then the channel's outliers over their decoded zeros;
 //   * 4 loaders copy the X rows of the step after next from memory straight into LDS (loads with
@@ -170,12 +170,15 @@ __device__ inline int x_swizzle(int r)
 }
 template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// MSW = 32-row sub-tiles per consumer wave along m; the block tile is BM = 128 * MSW rows by 128
-// channels.  When the tiles alone would leave most of the chip idle (few rows, few channels), K is
+// The consumer waves form a WM x WN grid (WN = 2 or 4 along n), each with MSW 32-row sub-tiles along m
+// and 128 / 32 / WN 32-column sub-tiles along n: the block tile is BM = 32 * MSW * WM rows by 128
+// channels - 256 rows (MSW 2, 4 x 2 waves) for large M, 128 (MSW 1, 4 x 2), 64 (2 x 4) and 32 rows
+// (1 x 4, four consumer waves idle) for small M, where a step is bounded by LDS traffic and the staged
+// weights are then read by fewer rows of waves.  When the tiles alone would leave most of the chip idle (few rows, few channels), K is
 // split as well: `splits` blocks share a tile, block s of them takes groups s * split_groups onwards
 // and writes its FP32 sums to partial[s][M][N] instead of Y; splitk_reduce_kernel adds them up in
 // the order of s.
-template <int BITS, int MSW>
+template <int BITS, int MSW, int WN, int WM>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
                                                         const uint16_t *__restrict__ col_idx,
                                                         const uint16_t *__restrict__ out_val,
@@ -184,7 +187,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                                                         float *__restrict__ partial, int split_groups,
                                                         int N, int K, int M, int tiles_m, int tiles_n, int last_entry)
 {
-    constexpr int BM = 128 * MSW;
+    static_assert(WM * WN <= kConsumers, "consumer waves");
+    constexpr int BM = 32 * MSW * WM;                   // WM x WN consumer waves work; with fewer than eight the rest idle
+    constexpr int NB = kBN / 32 / WN;                   // 32-column sub-tiles per consumer wave
     constexpr int wpg = words_per_group(BITS);
     // LDS: three X buffers of BM rows x 128 bytes (unpadded: the loads that fill them write whole
     // kilobytes; the 16-byte chunks of a row are permuted instead, see x_swizzle), then three weight
@@ -383,20 +388,24 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     }
 
     // ========================================= consumers =======================================
-    const int wm = wave >> 1, wn = wave & 1;            // 4 x 2 waves, each (BM / 4) x 64
-    float16v acc[MSW][2];
+    const int wm = wave / WN, wn = wave % WN;           // WM x WN waves, each 32 MSW rows by 32 NB columns
+    if (wm >= WM) {                                     // a consumer wave without a sub-tile only keeps the barrier count
+        for (int t = 0; t < 1 + nk; ++t) __syncthreads();
+        return;
+    }
+    float16v acc[MSW][NB];
 #pragma unroll
     for (int i = 0; i < MSW; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int fi = lane & 31, fk = lane >> 5;           // fragment row and k-block of this lane
-    const _Float16 *b_frag = lds_w + (wn * 64 + fi) * kLd + 8 * fk;
+    const _Float16 *b_frag = lds_w + (wn * (32 * NB) + fi) * kLd + 8 * fk;
     const _Float16 *a_frag[4];                          // per k-batch: the row's chunk 2s + fk, where the permutation puts it
 #pragma unroll
-    for (int s = 0; s < 4; ++s) a_frag[s] = lds + (wm * (BM / 4) + fi) * kBK + 8 * ((2 * s + fk) ^ x_swizzle(fi));
+    for (int s = 0; s < 4; ++s) a_frag[s] = lds + (wm * (32 * MSW) + fi) * kBK + 8 * ((2 * s + fk) ^ x_swizzle(fi));
 
     // Fragments of three k-batches (16 columns each): the one being multiplied and the two after
     // it.  With every wave of the block reading, a fragment takes longer to arrive than one batch
@@ -404,19 +413,19 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
     // (t + s) % 3 and LDS buffers t % 3: the loop is unrolled over three steps and all of that is
     // static.  Barrier t (step t + 1 is staged; steps up to t - 1 are read) comes after batch 1 of
     // step t, just in time for the request of step t + 1's first fragments.
-    u32x4 fa[3][MSW], fb[3][2];
+    u32x4 fa[3][MSW], fb[3][NB];
     auto read_frags = [&](int buf, int s, int set) {
         const _Float16 *A = a_frag[s] + buf * kXBufHalves, *B = b_frag + buf * kWBufHalves;
 #pragma unroll
         for (int i = 0; i < MSW; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(A + i * 32 * kBK);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) fb[set][j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
+        for (int j = 0; j < NB; ++j) fb[set][j] = *reinterpret_cast<const u32x4 *>(B + j * 32 * kLd + 16 * s);
     };
     auto mfma_batch = [&](int set) {
 #pragma unroll
         for (int i = 0; i < MSW; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NB; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[set][i]),
                                                                    __builtin_bit_cast(half8, fb[set][j]),
                                                                    acc[i][j], 0, 0, 0);
@@ -460,11 +469,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 #pragma unroll
     for (int i = 0; i < MSW; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn * 64 + j * 32 + fi;
+        for (int j = 0; j < NB; ++j) {
+            const int n = n0 + wn * (32 * NB) + j * 32 + fi;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * (BM / 4) + i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+                const int m = m0 + wm * (32 * MSW) + i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
                 if (m < M && n < N) {
                     if (partial) partial[((size_t)split * M + m) * N + n] = acc[i][j][v];
                     else Y[(size_t)m * N + n] = (_Float16)acc[i][j][v];
@@ -497,27 +506,70 @@ int choose_splits(int tiles, int gpr)
     return s < 1 ? 1 : s;
 }
 
-template <int BITS, int MSW>
+struct SplitPlan {
+    int splits, split_groups;
+};
+SplitPlan plan_split(int tiles, int gpr, bool have_scratch)
+{
+    int splits = have_scratch ? choose_splits(tiles, gpr) : 1;
+    const int split_groups = (gpr + splits - 1) / splits;
+    splits = (gpr + split_groups - 1) / split_groups;   // no empty split
+    return SplitPlan{splits, split_groups};
+}
+
+// Rows of Y per block for a launch the caller did not fix the shape of.  Beyond M = 512 the 256-row
+// tile, which has the most MFMA work per staged weight.  Below, the shape with the smallest expected
+// duration under a linear model fitted to measurements (288 launches: 11 matrices from 2048 x 2048 to
+// 8192 x 8192 and 4096 x 11008, M = 17 .. 512, every shape; it picks the measured best or a shape
+// within 3 % of it on all but the 2048 x 2048 matrix): a launch takes, in microseconds,
+//   rounds * (block + steps * step)  +  (K split ? 2.8 + 0.47 per MB of FP32 partial sums : 0)
+// with rounds = ceil(blocks / 256 CUs), steps = K-steps of one block, and per shape the cost of a step
+// (what its LDS traffic takes) and of a block's start and end.  Small tiles win where M leaves the
+// larger ones mostly empty, or where they avoid the split of K and its second pass; large tiles win
+// once the chip is full, since each stages the same weights for more rows.
+struct ShapeCost {
+    int rows;
+    float step_us, block_us;
+};
+constexpr ShapeCost kShapeCost[4] = {{32, 0.42f, 0.9f}, {64, 0.49f, 0.45f}, {128, 0.60f, 1.6f}, {256, 0.87f, 2.2f}};
+int choose_rows(int M, int N, int K, bool have_scratch)
+{
+    if (M > 512) return 256;
+    const int gpr = K / kGroup, tiles_n = (N + kBN - 1) / kBN;
+    int best = 256;
+    float best_us = 0.f;
+    for (const ShapeCost &c : kShapeCost) {
+        if (c.rows > 32 && c.rows >= 2 * M) continue;   // a tile at most half full: the next smaller holds M too
+        const int tiles = (M + c.rows - 1) / c.rows * tiles_n;
+        const SplitPlan sp = plan_split(tiles, gpr, have_scratch);
+        const int rounds = (tiles * sp.splits + kCUs - 1) / kCUs;
+        float us = rounds * (c.block_us + 2 * sp.split_groups * c.step_us);
+        if (sp.splits > 1) us += 2.8f + 0.47f * (4e-6f * sp.splits * M * N);
+        if (best_us == 0.f || us < best_us) best = c.rows, best_us = us;
+    }
+    return best;
+}
+
+template <int BITS, int MSW, int WN, int WM>
 hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, float *partial,
                      size_t partial_bytes, hipStream_t st)
 {
-    constexpr int BM = 128 * MSW;
+    constexpr int BM = 32 * MSW * WM;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
     const int gpr = P.K / kGroup;
-    int splits = partial ? choose_splits(tiles_m * tiles_n, gpr) : 1;
-    int split_groups = (gpr + splits - 1) / splits;
-    splits = (gpr + split_groups - 1) / split_groups;   // no empty split
+    const SplitPlan sp = plan_split(tiles_m * tiles_n, gpr, partial != nullptr);
+    int splits = sp.splits, split_groups = sp.split_groups;
     if (splits > 1 && (size_t)splits * M * P.N * sizeof(float) > partial_bytes) splits = 1, split_groups = gpr;
     if (splits == 1) partial = nullptr;
     const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
     static bool attr_set = false;                       // per instantiation; idempotent HIP call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_kernel<BITS, MSW><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
+    gemm_kernel<BITS, MSW, WN, WM><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
         P.qweight, P.col_idx, P.out_val, rec, static_cast<const _Float16 *>(X),
         static_cast<_Float16 *>(Y), partial, split_groups, P.N, P.K, M, tiles_m, tiles_n,
         P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
@@ -554,13 +606,20 @@ hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const
 {
     const GroupRecord *rec = static_cast<const GroupRecord *>(index);
     float *part = static_cast<float *>(scratch);
-    // Rows per tile: 256 unless M is small (the override is in rows: 64 and 128 both mean 128).
-    const int msw = ms_override ? (ms_override >= 4 ? 2 : 1) : M <= 128 ? 1 : 2;
-    if (P.bits == 4)
-        return msw == 1 ? launch_ms<4, 1>(P, X, M, Y, rec, part, scratch_bytes, st)
-                        : launch_ms<4, 2>(P, X, M, Y, rec, part, scratch_bytes, st);
-    return msw == 1 ? launch_ms<3, 1>(P, X, M, Y, rec, part, scratch_bytes, st)
-                    : launch_ms<3, 2>(P, X, M, Y, rec, part, scratch_bytes, st);
+    // Rows per tile (the override is in rows): 256 (consumer waves 4 x 2, 64 x 64 each), 128 (4 x 2, 32 x 64
+    // each), 64 (2 x 4, 32 x 32 each) or 32 (1 x 4, four consumer waves idle).  In the small shapes the
+    // weights a block stages are read from LDS by two rows of waves, or one, instead of four, and the
+    // LDS is what bounds a step.
+    const int rows = ms_override ? ms_override : choose_rows(M, (int)P.N, (int)P.K, part != nullptr);
+    const int shape = rows == 256 ? 2 : rows == 128 ? 1 : rows == 64 ? 0 : 3;
+#define GWQ_GEMM(B) \
+    return shape == 2   ? launch_ms<B, 2, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st) \
+           : shape == 1 ? launch_ms<B, 1, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st) \
+           : shape == 0 ? launch_ms<B, 1, 4, 2>(P, X, M, Y, rec, part, scratch_bytes, st) \
+                        : launch_ms<B, 1, 4, 1>(P, X, M, Y, rec, part, scratch_bytes, st)
+    if (P.bits == 4) GWQ_GEMM(4);
+    GWQ_GEMM(3);
+#undef GWQ_GEMM
 }
 
 }  // namespace gwq

@@ -158,6 +158,9 @@ def test_tuning_and_strings():
     assert L.gwq_tuning_set(b"nonsense", 1) == -3
     assert L.gwq_tuning_set(None, 1) == -1
     assert L.gwq_tuning_set(b"decode_waves", 2) == 0 and L.gwq_tuning_set(b"decode_waves", 0) == 0
+    assert L.gwq_tuning_set(b"gemm_rows", 48) == -3 and L.gwq_tuning_set(b"gemm_rows", 512) == -3
+    for rows in (32, 64, 128, 256, 0):
+        assert L.gwq_tuning_set(b"gemm_rows", rows) == 0
     assert L.gwq_status_string(0) == b"ok"
     assert b"workspace" in L.gwq_status_string(-4)
     assert gwq.version().startswith("gwq-gfx950")

@@ -146,6 +146,24 @@ def test_gemm_whole_and_partial_tiles(bits, N, K, M):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("rows", [32, 64, 128, 256])
+def test_gemm_block_shapes(bits, rows):
+    """Each of the GEMM's four block shapes (rows of Y per block; the library picks by M) forced on
+    the same problems, so that every shape also sees several tiles along m, a ragged last tile and
+    a K split."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close
+    try:
+        gwq.tuning_set("gemm_rows", rows)
+        for N, K, M in ((200, 1408, 100), (130, 512, 300), (72, 2048, 17)):
+            P, rng = _problem(rows + N + M + bits, N, K, bits)
+            X = gs.activations(M, K, rng, hot_frac=0.01)
+            assert_close(_run(P, X), orc.linear_f64(P, X), f"gemm rows={rows} N={N} K={K} M={M} bits={bits}")
+    finally:
+        gwq.tuning_set("gemm_rows", 0)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("N,M", [(16, 17), (130, 40), (257, 129)])
 def test_gemm_shortest_rows(bits, N, M):
     """The GEMM at K = 128: one group, two steps, the shortest loop every role of the kernel can run."""
