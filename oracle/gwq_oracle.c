@@ -16,6 +16,9 @@
  * and Sec. 3.1 for the two figures of merit of a packed layer:
  *   Eq. 4  squared error           || W - W_Q ||^2
  *   Eq. 3, 5  first-order change   g^T (W - W_Q) of the loss (its Taylor expansion around W)
+ * and for the score itself, Eq. 2: g = grad_W L.  For one linear layer Y = X W^T the chain rule
+ * gives g[n][k] = sum_m (dL/dY)[m][n] * X[m][k]; the mean over calibration samples (Sec. 4.4)
+ * is a scaled accumulation of that.
  *
  * Readings taken where the text is silent or garbled (each is also listed in the design
  * notes of the repository):
@@ -455,5 +458,29 @@ int gwq_oracle_quality(int64_t N, int64_t K, int bits, const uint32_t *qweight,
     }
     free(w_hat);
     out[0] = sq; out[1] = first; out[2] = mx;
+    return GWQ_ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------- score production -- */
+
+/* Eq. 2 for one linear layer Y = X W^T (no bias, Sec. 3.1): the gradient of the loss with respect to
+ * W, given the gradient dY[M][N] of the loss with respect to Y and the layer's input X[M][K], is
+ *   g[n][k] = sum_m dY[m][n] * X[m][k]          (chain rule; m ascending, fp64, products exact)
+ * and out[n][k] = beta * prev[n][k] + alpha * g[n][k]: with alpha = 1 / samples, beta = 0 for the
+ * first sample and 1 afterwards this is the mean gradient over calibration samples (Sec. 4.4).
+ * prev may be NULL when beta == 0. */
+int gwq_oracle_score(const uint16_t *dY, const uint16_t *X, int64_t M, int64_t N, int64_t K,
+                     double alpha, double beta, const float *prev, double *out)
+{
+    if (!dY || !X || !out || (beta != 0.0 && !prev)) return GWQ_ORACLE_BAD_ARG;
+    if (M <= 0 || N <= 0 || K <= 0) return GWQ_ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(static)           /* rows are independent; each sum keeps its order */
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            double g = 0.0;
+            for (int64_t m = 0; m < M; ++m)
+                g += gwq_oracle_half_to_double(dY[m * N + n]) * gwq_oracle_half_to_double(X[m * K + k]);
+            out[n * K + k] = (beta != 0.0 ? beta * (double)prev[n * K + k] : 0.0) + alpha * g;
+        }
     return GWQ_ORACLE_OK;
 }

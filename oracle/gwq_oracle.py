@@ -32,6 +32,7 @@ def _load():
     lib.gwq_oracle_decode.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
     lib.gwq_oracle_quality.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.gwq_oracle_score.argtypes = [vp, vp, i64, i64, i64, ctypes.c_double, ctypes.c_double, vp, vp]
     return lib
 
 
@@ -204,3 +205,19 @@ def quality(P, W, score):
     _chk(_lib.gwq_oracle_quality(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros), _p(P.row_ptr),
                                  _p(P.col_idx), _p(P.out_val), _p(Wb), _p(score), is16, _p(out)), "quality")
     return float(out[0]), float(out[1]), float(out[2])
+
+
+def score(dY, X, alpha=1.0, beta=0.0, prev=None):
+    """out[n][k] = beta * prev[n][k] + alpha * sum_m dY[m][n] X[m][k] in fp64: the weight gradient of a
+    linear layer Y = X W^T from the gradient dY of the loss with respect to Y (Eq. 2, chain rule)."""
+    dYb, Xb = _f16_bits(dY), _f16_bits(X)
+    M, N = dYb.shape
+    K = Xb.shape[1]
+    assert Xb.shape[0] == M
+    if prev is not None:
+        prev = np.ascontiguousarray(prev, np.float32)
+        assert prev.shape == (N, K)
+    out = np.empty((N, K), np.float64)
+    _chk(_lib.gwq_oracle_score(_p(dYb), _p(Xb), M, N, K, ctypes.c_double(alpha), ctypes.c_double(beta),
+                               _p(prev) if prev is not None else None, _p(out)), "score")
+    return out

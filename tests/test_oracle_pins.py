@@ -498,3 +498,75 @@ def test_quality_special_cases_and_invariants(bits):
     # FP16 scores give the same numbers as their FP32 widening
     S16 = S.astype(np.float16)
     assert orc.quality(P, W, S16) == orc.quality(P, W, S16.astype(np.float32))
+
+
+# ----------------------------------------------------------------------------- score of one layer (Eq. 2)
+
+def test_score_hand_worked_case():
+    """Eq. 2 with the chain rule for Y = X W^T, on a case worked by hand (tests/golden/score_hand_worked.txt)."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "score_hand_worked.txt")) if l.strip() and l[0] != "#"]
+    M, N, K = map(int, rows[0])
+    num = lambda rs: np.array([[float(v) for v in r] for r in rs])
+    dY, X, want = num(rows[1:1 + M]), num(rows[1 + M:1 + 2 * M]), num(rows[1 + 2 * M:1 + 2 * M + N])
+    assert dY.shape == (M, N) and X.shape == (M, K) and want.shape == (N, K)
+    got = orc.score(dY.astype(np.float16), X.astype(np.float16))
+    assert np.array_equal(got, want)
+    # asymmetric on purpose: the transposed product, or rows taken for columns, gives other numbers
+    assert not np.array_equal(got, (X.T @ dY).T[:, ::-1])
+
+
+def test_score_is_the_derivative_of_a_loss():
+    """The score is the gradient of the loss with respect to W (Eq. 2).  For the squared-error loss
+    L(W) = 1/2 sum (X W^T - T)^2 the gradient with respect to Y is Y - T, and L is quadratic in each
+    weight, so a central difference of L is its exact derivative: the oracle must agree with it entry by
+    entry.  Values are small dyadic rationals, so every quantity is exact in fp64."""
+    rng = np.random.default_rng(11)
+    M, N, K = 5, 4, 6
+    X = rng.integers(-8, 9, (M, K)) / 4.0
+    W = rng.integers(-8, 9, (N, K)) / 8.0
+    T = rng.integers(-8, 9, (M, N)) / 2.0
+    loss = lambda w: 0.5 * ((X @ w.T - T) ** 2).sum()
+    dY = X @ W.T - T
+    assert np.array_equal(dY.astype(np.float16).astype(np.float64), dY)
+    got = orc.score(dY.astype(np.float16), X.astype(np.float16))
+    for n in range(N):
+        for k in range(K):
+            up, dn = W.copy(), W.copy()
+            up[n, k] += 1.0
+            dn[n, k] -= 1.0
+            assert got[n, k] == (loss(up) - loss(dn)) / 2.0, (n, k)
+
+
+def test_score_special_cases_and_linearity():
+    rng = np.random.default_rng(12)
+    M, N, K = 7, 5, 9
+    dY = rng.standard_normal((M, N)).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    # one sample: the outer product, each entry one exact product of two FP16 numbers
+    one = orc.score(dY[:1], X[:1])
+    for n in range(N):
+        for k in range(K):
+            assert Fraction(float(one[n, k])) == Fraction(float(dY[0, n])) * Fraction(float(X[0, k]))
+    # a sum over samples, in the order of m: exact rationals, rounded by fp64 additions
+    full = orc.score(dY, X)
+    for n, k in ((0, 0), (4, 8), (2, 3)):
+        acc = 0.0
+        for m in range(M):
+            acc += float(dY[m, n]) * float(X[m, k])
+        assert full[n, k] == acc
+        exact = sum(Fraction(float(dY[m, n])) * Fraction(float(X[m, k])) for m in range(M))
+        assert abs(Fraction(full[n, k]) - exact) <= Fraction(1, 2 ** 45)
+    # a unit dY picks a row of X: dY[m][n] = 1 only at (m0, n0) -> g[n0] = X[m0], all other rows 0
+    unit = np.zeros((M, N), np.float16)
+    unit[3, 2] = 1.0
+    g = orc.score(unit, X)
+    assert np.array_equal(g[2], X[3].astype(np.float64)) and not g[[0, 1, 3, 4]].any()
+    # mean over samples (Sec. 4.4) as a scaled accumulation: two halves with alpha = 1/2
+    prev = orc.score(dY[:4], X[:4], alpha=0.5).astype(np.float32)
+    both = orc.score(dY[4:], X[4:], alpha=0.5, beta=1.0, prev=prev)
+    want = prev.astype(np.float64) + 0.5 * orc.score(dY[4:], X[4:])
+    assert np.array_equal(both, want)
+    assert np.allclose(both, 0.5 * full, rtol=0, atol=1e-6)
+    # beta = 0 ignores prev altogether, NaN included
+    nan_prev = np.full((N, K), np.nan, np.float32)
+    assert np.array_equal(orc.score(dY, X, alpha=2.0, beta=0.0, prev=nan_prev), 2.0 * full)
