@@ -162,6 +162,22 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
 gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, gwq_score_dtype score_dtype,
                        double *out_f64, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The score that gwq_pack ranks, for one linear layer (Sec. 3.1, Eq. 2: the gradient of the loss with
+ * respect to the weights).  For Y = X W^T without bias the chain rule gives it from the gradient dY of the
+ * loss with respect to Y:
+ *   g[n][k] = sum over m of dY[m][n] * X[m][k]
+ *   score[n][k] = beta * score[n][k] + alpha * g[n][k]
+ * so the mean over calibration samples (Sec. 4.4) is one call per sample or batch of samples with
+ * alpha = 1 / samples, beta = 0 on the first call (score is then not read: it may be uninitialised)
+ * and 1 afterwards.
+ *   dY_f16  device [M][N] row-major FP16; 16-byte aligned when N is a multiple of 8, else 2-byte
+ *   X_f16   device [M][K] row-major FP16, 16-byte aligned; K a multiple of 128, <= 65536 (as gwq_pack)
+ *   score_f32 device [N][K] row-major FP32, 4-byte aligned: what gwq_pack takes as GWQ_SCORE_F32
+ *   M >= 1, N >= 1
+ * Products are exact, sums FP32 (MFMA); deterministic.  No workspace. */
+gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N, int32_t K, float alpha,
+                     float beta, float *score_f32, void *stream);
+
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
  * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 4:
  * it picks 4, 8 or 16 groups per wave accordingly; the kernel for larger M sizes itself by the LDS it

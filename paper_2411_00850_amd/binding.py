@@ -58,6 +58,8 @@ def lib():
         L.gwq_pack.argtypes = [vp, vp, ctypes.c_int, ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
         L.gwq_quality.restype = ctypes.c_int
         L.gwq_quality.argtypes = [ctypes.POINTER(_Packed), vp, vp, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
+        L.gwq_score.restype = ctypes.c_int
+        L.gwq_score.argtypes = [vp, vp, i32, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp]
         L.gwq_linear.restype = ctypes.c_int
         L.gwq_linear.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
         L.gwq_linear_index.restype = ctypes.c_int
@@ -187,6 +189,24 @@ def quality(P, W, score, out=None, stream=None, workspace=None):
                            workspace.numel(), _stream_ptr(stream))
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_quality")
+    return out
+
+
+def score(dY, X, out=None, alpha=1.0, beta=0.0, stream=None):
+    """gwq_score: out = beta * out + alpha * dY^T X, the weight gradient of a linear layer Y = X W^T from the gradient
+    dY (FP16 [M, N]) of the loss with respect to Y and the layer's input X (FP16 [M, K]); out is FP32 [N, K]."""
+    import torch
+    assert dY.is_cuda and X.is_cuda and dY.dtype == torch.float16 and X.dtype == torch.float16
+    assert dY.is_contiguous() and X.is_contiguous() and dY.dim() == 2 and X.dim() == 2 and dY.shape[0] == X.shape[0]
+    M, N = dY.shape
+    K = X.shape[1]
+    if out is None:
+        assert beta == 0.0, "beta != 0 accumulates into `out`"
+        out = torch.empty((N, K), dtype=torch.float32, device=X.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (N, K)
+    rc = lib().gwq_score(dY.data_ptr(), X.data_ptr(), M, N, K, alpha, beta, out.data_ptr(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_score")
     return out
 
 

@@ -110,6 +110,17 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 
+gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N, int32_t K, float alpha,
+                     float beta, float *score_f32, void *stream)
+{
+    if (!dY_f16 || !X_f16 || !score_f32) return GWQ_ERR_NULL;
+    if (M < 1 || N < 1 || K < gwq::kGroup || K % gwq::kGroup || K > 65536) return GWQ_ERR_SHAPE;
+    if (((uintptr_t)X_f16 & 15) || ((uintptr_t)score_f32 & 3) || ((uintptr_t)dY_f16 & (N % 8 ? 1 : 15)))
+        return GWQ_ERR_SHAPE;
+    hipError_t e = gwq::launch_score(dY_f16, X_f16, M, N, K, alpha, beta, score_f32, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, void *workspace,
                       size_t workspace_bytes, void *stream)
 {

@@ -45,4 +45,8 @@ size_t quality_workspace_bytes(int64_t N);
 hipError_t launch_quality(const gwq_packed &P, const void *W, const void *score, int score_is_f16, void *workspace,
                           double *out, hipStream_t stream);
 
+// score = beta * score + alpha * dY^T X (dY [M][N], X [M][K] FP16; score [N][K] FP32); K a multiple of 128.
+hipError_t launch_score(const void *dY, const void *X, int M, int N, int K, float alpha, float beta, float *score,
+                        hipStream_t stream);
+
 }  // namespace gwq

@@ -19,7 +19,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_calls():
     assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_index",
-                                    "gwq_linear_indexed", "gwq_pack", "gwq_quality",
+                                    "gwq_linear_indexed", "gwq_pack", "gwq_quality", "gwq_score",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
 
@@ -166,3 +166,18 @@ def test_tuning_and_strings():
     assert gwq.version().startswith("gwq-gfx950")
     with pytest.raises(gwq.GwqError):
         gwq.layout(4, 100, 4)
+
+
+def test_score_validates_before_touching_the_device():
+    L = gwq.binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    f = ctypes.c_float
+    assert L.gwq_score(None, fake, 4, 8, 128, f(1), f(0), fake, None) == -1
+    assert L.gwq_score(fake, None, 4, 8, 128, f(1), f(0), fake, None) == -1
+    assert L.gwq_score(fake, fake, 4, 8, 128, f(1), f(0), None, None) == -1
+    for M, N, K in ((0, 8, 128), (4, 0, 128), (4, 8, 0), (4, 8, 64), (4, 8, 192), (4, 8, 65536 + 128)):
+        assert L.gwq_score(fake, fake, M, N, K, f(1), f(0), fake, None) == -2, (M, N, K)
+    assert L.gwq_score(ctypes.c_void_p(0x1008), fake, 4, 8, 128, f(1), f(0), fake, None) == -2   # N % 8 == 0: 16 bytes
+    assert L.gwq_score(ctypes.c_void_p(0x1001), fake, 4, 7, 128, f(1), f(0), fake, None) == -2
+    assert L.gwq_score(fake, ctypes.c_void_p(0x1008), 4, 8, 128, f(1), f(0), fake, None) == -2
+    assert L.gwq_score(fake, fake, 4, 8, 128, f(1), f(0), ctypes.c_void_p(0x1002), None) == -2
