@@ -436,9 +436,30 @@ def main():
             qual[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1),
                           "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 1),
                           "rms_error": float((out3[0] / Wd.numel()).sqrt())}
+        # gwq_score: the weight gradient dY^T X of a layer from M = 2048 samples (what gwq_pack ranks), FP16 MFMA
+        sc = {}
+        for name, Wd, Sd in pack_inputs if "pack" in legs else ():
+            N, K = Wd.shape
+            M = 2048
+            g = torch.Generator(device="cuda")
+            g.manual_seed(N + K)
+            dYd = (0.05 * torch.randn((M, N), device="cuda", generator=g)).half()
+            Xd = torch.randn((M, K), device="cuda", generator=g).half()
+            So = gwq.score(dYd, Xd)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(5):
+                gwq.score(dYd, Xd, out=So)
+            torch.cuda.synchronize()
+            s = (time.perf_counter() - t) / 5
+            fl = 2.0 * M * N * K
+            sc[name] = {"ms": round(s * 1e3, 3), "TFLOP/s": round(fl / s / 1e12, 1),
+                        "pct_mfma_f16_peak": round(100 * fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 2)}
+            del dYd, Xd, So
         if pk:
             extra["pack_int4"] = pk
             extra["quality_int4"] = qual
+            extra["score_M2048"] = sc
         out["extras"] = extra
 
     if not args.no_cpu_baseline:

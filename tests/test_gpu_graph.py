@@ -93,3 +93,43 @@ def test_pack_and_quality_replay_from_a_graph():
         sq, first, mx = orc.quality(P, W2, S2)
         got = out3.cpu().numpy()
         assert abs(got[0] - sq) <= 1e-11 * sq and got[2] == mx
+
+
+def test_score_replays_from_a_graph():
+    """gwq_score, then gwq_pack ranking what it wrote, captured together: the calibration step of one layer."""
+    import ctypes
+    import torch
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu, assert_packed_equal
+    M, N, K, bits = 150, 96, 384, 4
+    W, _, rng = _layer(44, N, K, bits)
+    Wd = to_gpu(W)
+    dYd = to_gpu((0.05 * rng.standard_normal((M, N))).astype(np.float16))
+    Xd = to_gpu(gs.activations(M, K, rng))
+    Sd = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    ws = torch.empty(gwq.layout(N, K, bits, 128, 10000)["pack_workspace"], dtype=torch.uint8, device="cuda")
+    gwq.score(dYd, Xd, out=Sd)
+    D = gwq.pack(Wd, Sd, bits, 10000, workspace=ws)
+    torch.cuda.synchronize()
+
+    def work():
+        gwq.score(dYd, Xd, out=Sd, alpha=0.5)
+        gwq.score(dYd, Xd, out=Sd, alpha=0.5, beta=1.0)
+        cs = D.c_struct()
+        rc = gwq.lib().gwq_pack(Wd.data_ptr(), Sd.data_ptr(), 0, ctypes.byref(cs), ws.data_ptr(), ws.numel(),
+                                torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    for trial in range(3):
+        dYd.copy_(to_gpu((0.05 * rng.standard_normal((M, N))).astype(np.float16)))
+        Xd.copy_(to_gpu(gs.activations(M, K, rng)))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Sd.cpu().numpy().copy()
+        work()                                            # the same work, eager, with the library's other kernels around it
+        torch.cuda.synchronize()
+        assert np.array_equal(got, Sd.cpu().numpy()), trial
+        assert_packed_equal(D, orc.pack(W, got, bits, 10000))
