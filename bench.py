@@ -425,6 +425,18 @@ def main():
             s = (time.perf_counter() - t) / 3
             b = Wd.numel() * 6 + P.nbytes()
             pk[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1)}
+            if name == "gate":                          # the same layer ranked by FP16 scores: two select passes, 2-byte reads
+                Sh = Sd.half()
+                gwq.pack(Wd, Sh, 4, 10000)
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                for _ in range(3):
+                    Ph = gwq.pack(Wd, Sh, 4, 10000)
+                torch.cuda.synchronize()
+                sh = (time.perf_counter() - t) / 3
+                bh = Wd.numel() * 4 + Ph.nbytes()
+                pk["gate_f16_score"] = {"ms": round(sh * 1e3, 3), "GB/s": round(bh / sh / 1e9, 1)}
+                del Sh, Ph
             # gwq_quality on what was just packed: W, score and the packed layer read once
             out3 = gwq.quality(P, Wd, Sd)
             torch.cuda.synchronize()

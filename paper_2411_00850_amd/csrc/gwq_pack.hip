@@ -1,4 +1,4 @@
-// gwq_pack on gfx950: outlier selection (Sec. 3.2, Eq. 8) as a three-pass radix select over the
+// gwq_pack on gfx950: outlier selection (Sec. 3.2, Eq. 8) as a three-pass (FP16 scores: two-pass) radix select over the
 // bit patterns of |score|, CSR build in flat-index order, then per (row, group of 128) the scale,
 // zero point and codes of Eq. 6, 7 and 9 and the word layout documented in gwq.h.
 //
@@ -396,8 +396,13 @@ hipError_t run_select(const void *score, int N, int K, uint32_t *ws, int32_t *ro
         pick_kernel<0><<<1, kSelBins / 2, 0, st>>>(ws);
         hist_kernel<1, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
         pick_kernel<1><<<1, kSelBins / 2, 0, st>>>(ws);
-        hist_kernel<2, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
-        pick_kernel<2><<<1, kSelBins / 2, 0, st>>>(ws);
+        // The key of an FP16 score is its exact binary32 widening, whose low 13 bits are zero (payloads of
+        // NaNs included): the third pass would find every key in bin 0 and change nothing, so FP16 scores
+        // are selected in two passes.
+        if (!F16) {
+            hist_kernel<2, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
+            pick_kernel<2><<<1, kSelBins / 2, 0, st>>>(ws);
+        }
     }
     row_count_kernel<F16><<<N, kThreads, 0, st>>>(score, K, ws, N);
     row_scan_kernel<<<1, kThreads, 0, st>>>(ws, N, row_ptr);
