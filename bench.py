@@ -448,6 +448,38 @@ def main():
             qual[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1),
                           "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 1),
                           "rms_error": float((out3[0] / Wd.numel()).sqrt())}
+        # decode M = 1 against the fraction of weights kept as FP16 outliers (the paper's ablation of that
+        # fraction, Sec. 4.4, measures accuracy; this is what the fraction costs the kernel): q, gate and down,
+        # one launch each, six copies rotated, replayed from a graph
+        if "pack" in legs and pack_inputs:
+            by_ppm = {}
+            for ppm in (0, 1000, 5000, 10000):
+                first = [gwq.pack(Wd, Sd, 4, ppm) for _, Wd, Sd in pack_inputs]
+                sets = [first] + [[clone_layer(P) for P in first] for _ in range(5)]
+                xs1 = {K: torch.from_numpy(gs.activations(1, K, gs.rng_for(2, 100, K))).to(dev) for K in (4096, 11008)}
+                ys1 = [torch.empty((1, P.N), dtype=torch.float16, device=dev) for P in first]
+                calls = [gwq.prepare_linear(P, xs1[P.K], ys1[j]) for c in sets for j, P in enumerate(c)]
+                for c in calls:
+                    c()
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for c in calls:
+                        c()
+                graph.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(20):
+                    graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 20 / 6          # q + gate + down once
+                b = sum(algorithmic_bytes(P, 1) for P in first)
+                by_ppm[str(ppm)] = {"us_q_gate_down": round(us, 2), "GB/s": round(b / us / 1e3, 1), "bytes": b}
+                del first, sets, calls, graph
+                torch.cuda.empty_cache()
+            extra["decode_M1_by_outlier_ppm"] = by_ppm
         # gwq_score: the weight gradient dY^T X of a layer from M = 2048 samples (what gwq_pack ranks), FP16 MFMA
         sc = {}
         for name, Wd, Sd in pack_inputs if "pack" in legs else ():
