@@ -173,7 +173,7 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
  *   dY_f16  device [M][N] row-major FP16; 16-byte aligned when N is a multiple of 8, else 2-byte
  *   X_f16   device [M][K] row-major FP16, 16-byte aligned; K a multiple of 128, <= 65536 (as gwq_pack)
  *   score_f32 device [N][K] row-major FP32, 4-byte aligned: what gwq_pack takes as GWQ_SCORE_F32
- *   M >= 1, N >= 1
+ *   M >= 1, 1 <= N <= 2^24
  * Products are exact, sums FP32 (MFMA); deterministic.  No workspace. */
 gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N, int32_t K, float alpha,
                      float beta, float *score_f32, void *stream);

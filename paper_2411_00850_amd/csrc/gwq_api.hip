@@ -114,7 +114,7 @@ gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N
                      float beta, float *score_f32, void *stream)
 {
     if (!dY_f16 || !X_f16 || !score_f32) return GWQ_ERR_NULL;
-    if (M < 1 || N < 1 || K < gwq::kGroup || K % gwq::kGroup || K > 65536) return GWQ_ERR_SHAPE;
+    if (M < 1 || N < 1 || N > (1 << 24) || K < gwq::kGroup || K % gwq::kGroup || K > 65536) return GWQ_ERR_SHAPE;
     if (((uintptr_t)X_f16 & 15) || ((uintptr_t)score_f32 & 3) || ((uintptr_t)dY_f16 & (N % 8 ? 1 : 15)))
         return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_score(dY_f16, X_f16, M, N, K, alpha, beta, score_f32, static_cast<hipStream_t>(stream));

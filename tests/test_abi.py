@@ -175,7 +175,7 @@ def test_score_validates_before_touching_the_device():
     assert L.gwq_score(None, fake, 4, 8, 128, f(1), f(0), fake, None) == -1
     assert L.gwq_score(fake, None, 4, 8, 128, f(1), f(0), fake, None) == -1
     assert L.gwq_score(fake, fake, 4, 8, 128, f(1), f(0), None, None) == -1
-    for M, N, K in ((0, 8, 128), (4, 0, 128), (4, 8, 0), (4, 8, 64), (4, 8, 192), (4, 8, 65536 + 128)):
+    for M, N, K in ((0, 8, 128), (4, 0, 128), (4, 8, 0), (4, 8, 64), (4, 8, 192), (4, 8, 65536 + 128), (4, (1 << 24) + 8, 128)):
         assert L.gwq_score(fake, fake, M, N, K, f(1), f(0), fake, None) == -2, (M, N, K)
     assert L.gwq_score(ctypes.c_void_p(0x1008), fake, 4, 8, 128, f(1), f(0), fake, None) == -2   # N % 8 == 0: 16 bytes
     assert L.gwq_score(ctypes.c_void_p(0x1001), fake, 4, 7, 128, f(1), f(0), fake, None) == -2
