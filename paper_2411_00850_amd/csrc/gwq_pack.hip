@@ -273,8 +273,8 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
     const int gpr = K / kGroup;
     const uint32_t thr = ws[kWsPrefix];
     const uint32_t take = ws[kWsRows + 2 * N + n];
-    uint32_t ties_seen = 0;
-    uint32_t out_pos = (uint32_t)row_ptr[n];
+    uint32_t ties_seen = 0, gt_seen = 0;                // of the chunks before the current one
+    const uint32_t out_pos = (uint32_t)row_ptr[n];
 
     for (int k0 = 0; k0 < K; k0 += kElemsPerIter) {
         const int k = k0 + tid * 8;
@@ -298,9 +298,13 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
             for (int i = 0; i < 8; ++i) w[i] = 0;
         }
 
-        // Rank of this thread's first threshold tie within the row, in flat-index order.
-        uint32_t ties_total;
-        const uint32_t tie_rank = ties_seen + block_exclusive_scan(__popc(eq_mask), smem, ties_total);
+        // One scan for both counts (each at most 2048 per chunk: 16 bits apiece): the keys above the
+        // threshold and the threshold ties before this thread, in flat-index order.  The first `take`
+        // ties of the row are kept, so of the ties before this thread min(their number, take) are, and
+        // the thread's first kept entry goes behind those and the larger keys before it.
+        uint32_t both_total;
+        const uint32_t both = block_exclusive_scan((uint32_t)__popc(gt_mask) | (uint32_t)__popc(eq_mask) << 16, smem, both_total);
+        const uint32_t tie_rank = ties_seen + (both >> 16);
         uint32_t sel_mask = gt_mask;
         {
             uint32_t r = tie_rank;
@@ -308,13 +312,12 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
             for (int i = 0; i < 8; ++i)
                 if (eq_mask >> i & 1) { if (r < take) sel_mask |= 1u << i; ++r; }
         }
-        uint32_t sel_total;
-        uint32_t pos = out_pos + block_exclusive_scan(__popc(sel_mask), smem, sel_total);
+        uint32_t pos = out_pos + gt_seen + (both & 0xFFFFu) + (tie_rank < take ? tie_rank : take);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             if (sel_mask >> i & 1) { col_idx[pos] = (uint16_t)(k + i); out_val[pos] = w[i]; ++pos; }
-        ties_seen += ties_total;
-        out_pos += sel_total;
+        ties_seen += both_total >> 16;
+        gt_seen += both_total & 0xFFFFu;
 
         // Masked min / max of the group (range always contains 0), reduced over 16 lanes.
         float mn = 0.f, mx = 0.f;
