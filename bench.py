@@ -48,7 +48,8 @@ def flops(P, M):
 def clone_layer(P):
     from paper_2411_00850_amd.binding import PackedLayer
     return PackedLayer(P.N, P.K, P.bits, P.ppm, P.n_outliers, P.qweight.clone(), P.scales.clone(),
-                       P.zeros.clone(), P.row_ptr.clone(), P.col_idx.clone(), P.out_val.clone())
+                       P.zeros.clone(), P.row_ptr.clone(), P.col_idx.clone(), P.out_val.clone(),
+                       P.index.clone() if P.index is not None else None)
 
 
 def read_traffic():
@@ -66,8 +67,9 @@ def read_traffic():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=3000,
+                    help="untimed steps first; a few thousand (0.1 s) let the clocks settle: short warm-ups read 3 %% low")
     ap.add_argument("--copies", type=int, default=6, help="rotating copies of the packed layer")
     ap.add_argument("--group", choices=["deps", "none", "all"], default="deps",
                     help="launches per step: 4 grouped by data dependence (default), 7 single, or 1 over all")
@@ -222,11 +224,11 @@ def main():
     if not args.no_extras:
         extra = {}
         for M in (4, 16) if "m" in legs else ():
-            s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), 12, args.launch, args.group)
+            s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, args.group)
             extra[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5)}
         for grouping in ("none", "all") if "groups" in legs else ():   # the same M = 1 pass with 7 launches / 1 launch per step
             if grouping != args.group:
-                s, _, b, nl = decode_leg(1, max(args.steps // 3, 12), 12, args.launch, grouping)
+                s, _, b, nl = decode_leg(1, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, grouping)
                 extra[f"decode_M1_group_{grouping}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
                                                         "launches_per_step": nl}
         # decode M = 1 on 70B-shaped matrices (one launch each; weights drawn on the device, three
@@ -340,11 +342,14 @@ def main():
             xs, ys = make_xy(M)
             fl = sum(flops(P, M) for P in layers)
 
-            def time_prefill(calls, reps=10):
-                for _ in range(3):
+            def time_prefill(calls, reps=20):
+                # Warm up for a fifth of a second: the first passes after lighter work run up to 10 %
+                # slower than the settled rate, whichever variant comes first.
+                t = time.perf_counter()
+                while time.perf_counter() - t < 0.2:
                     for c in calls:
                         c()
-                torch.cuda.synchronize()
+                    torch.cuda.synchronize()
                 t = time.perf_counter()
                 for _ in range(reps):
                     for c in calls:
@@ -357,11 +362,18 @@ def main():
                                      "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": round(fl / s / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}}
 
+            # gwq_linear on layers as gwq_pack returns them (index filled at pack time), on the same layers
+            # without that index (gwq_linear then builds one in its workspace on every call), and
+            # gwq_linear_indexed with an index built by gwq_linear_index.
+            import dataclasses
             extra["prefill_M2048"] = time_prefill([gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(layers)])
+            bare = [dataclasses.replace(P, index=None) for P in layers]
+            extra["prefill_M2048_index_per_call"] = time_prefill(
+                [gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(bare)])
             indexes = [gwq.linear_index(P) for P in layers]
             extra["prefill_M2048_indexed"] = time_prefill(
-                [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(layers)])
-            del indexes
+                [gwq.prepare_linear(P, xs[P.K], ys[j], index=indexes[j]) for j, P in enumerate(bare)])
+            del indexes, bare
             # The same seven products with FP16 weights through the vendor library (torch.matmul), for
             # scale: what a plain GEMM of these shapes reaches on this chip without any dequantisation.
             if "fp16" in legs:
@@ -388,7 +400,7 @@ def main():
             copies3 = [layers3] + [[clone_layer(P) for P in layers3] for _ in range(args.copies - 1)]
             int3 = {}
             for M in (1, 8):
-                s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), 12, args.launch, args.group, copies=copies3)
+                s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, args.group, copies=copies3)
                 int3[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
                                         "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 2)}
             del copies3

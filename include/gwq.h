@@ -73,6 +73,12 @@ typedef struct {
     int32_t *row_ptr;
     uint16_t *col_idx;
     uint16_t *out_val;
+    void *index;              /* optional (may be NULL): the per-layer index of gwq_linear_index, */
+                              /* >= linear_index bytes, 16-byte aligned.  gwq_pack fills it when  */
+                              /* set; gwq_linear then reads it for M > 16 instead of building one */
+                              /* in its workspace on every call.  It must describe the layer's    */
+                              /* current contents: set it to NULL for a layer packed elsewhere    */
+                              /* (or fill it with gwq_linear_index).                              */
 } gwq_packed;
 
 /* Byte sizes of every buffer of a gwq_packed plus the workspaces of the two device calls. */
@@ -98,7 +104,8 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
 /* Encode one layer (Eq. 8 selection, then Eq. 6, 7, 9 per group, then the word layout).
  *   W_f16   device, FP16 [N][K]          score  device, [N][K] of `score_dtype`
  *   dst     host struct; its scalars describe the layer, its pointers are device buffers of
- *           the sizes gwq_layout reports; all of them are fully overwritten
+ *           the sizes gwq_layout reports; all of them are fully overwritten (dst->index too
+ *           when it is not NULL)
  *   workspace device scratch of >= pack_workspace bytes, 256-byte aligned
  * The result is a function of the inputs only (bit-exact, run-to-run identical). */
 gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_dtype,
@@ -110,10 +117,11 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
  * X and Y must not overlap; Y is fully overwritten.  M > 16 needs `workspace`: device scratch,
  * 16-byte aligned, of the linear_workspace bytes gwq_layout reports for an M_max >= M (it is
  * rewritten by every call; concurrent calls need separate workspaces); for M <= 16 it may be
- * NULL.  The first linear_index bytes are indispensable (less: GWQ_ERR_WORKSPACE).  The rest
- * holds FP32 partial sums when a launch also splits K, which it does where rows and channels
- * alone give too few tiles to fill the chip; with less than that the call still works, without
- * the split.
+ * NULL.  The first linear_index bytes are indispensable (less: GWQ_ERR_WORKSPACE): the call
+ * builds the layer's index there, unless P->index holds it already (then that part stays
+ * untouched).  The rest holds FP32 partial sums when a launch also splits K, which it does where
+ * rows and channels alone give too few tiles to fill the chip; with less than that the call
+ * still works, without the split.
  * Results are deterministic (no floating-point atomics). */
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);

@@ -25,7 +25,8 @@ class _Packed(ctypes.Structure):
                 ("group", ctypes.c_int32), ("outlier_ppm", ctypes.c_uint32),
                 ("n_outliers", ctypes.c_int64),
                 ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
-                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("out_val", ctypes.c_void_p)]
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("out_val", ctypes.c_void_p),
+                ("index", ctypes.c_void_p)]
 
 
 class _Sizes(ctypes.Structure):
@@ -118,18 +119,20 @@ class PackedLayer:
     row_ptr: "torch.Tensor"   # int32 [N+1]
     col_idx: "torch.Tensor"   # int16 view of uint16 [n_outliers + padding]
     out_val: "torch.Tensor"   # int16 view of FP16 bits [n_outliers + padding]
+    index: "torch.Tensor" = None   # optional uint8 [linear_index bytes]: filled by gwq_pack, read by gwq_linear for M > 16
 
     def c_struct(self):
         return _Packed(self.N, self.K, self.bits, 128, self.ppm, self.n_outliers,
                        self.qweight.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(),
-                       self.row_ptr.data_ptr(), self.col_idx.data_ptr(), self.out_val.data_ptr())
+                       self.row_ptr.data_ptr(), self.col_idx.data_ptr(), self.out_val.data_ptr(),
+                       self.index.data_ptr() if self.index is not None else None)
 
     def nbytes(self):
         return sum(t.numel() * t.element_size() for t in
                    (self.qweight, self.scales, self.zeros, self.row_ptr, self.col_idx, self.out_val))
 
 
-def alloc_packed(N, K, bits, ppm=10000, device="cuda"):
+def alloc_packed(N, K, bits, ppm=10000, device="cuda", with_index=True):
     import torch
     sz = layout(N, K, bits, 128, ppm)
     gpr = K // 128
@@ -141,11 +144,14 @@ def alloc_packed(N, K, bits, ppm=10000, device="cuda"):
                        torch.empty(sz["zeros"], dtype=torch.uint8, device=device),
                        torch.empty(N + 1, dtype=torch.int32, device=device),
                        torch.empty(n_slots, dtype=torch.int16, device=device),
-                       torch.empty(n_slots, dtype=torch.int16, device=device)), sz
+                       torch.empty(n_slots, dtype=torch.int16, device=device),
+                       torch.empty(sz["linear_index"], dtype=torch.uint8, device=device) if with_index else None), sz
 
 
-def pack(W, score, bits, ppm=10000, stream=None, workspace=None):
-    """gwq_pack: W FP16 [N, K] and score FP32/FP16 [N, K] on the GPU -> PackedLayer."""
+def pack(W, score, bits, ppm=10000, stream=None, workspace=None, with_index=True):
+    """gwq_pack: W FP16 [N, K] and score FP32/FP16 [N, K] on the GPU -> PackedLayer.  with_index: also fill the
+    layer's index (8 bytes per group, +12 % memory), which gwq_linear then reads for M > 16 instead of building one
+    on every call."""
     import torch
     assert W.is_cuda and score.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
     assert score.shape == W.shape and score.is_contiguous()
@@ -156,7 +162,7 @@ def pack(W, score, bits, ppm=10000, stream=None, workspace=None):
     else:
         raise TypeError("score must be float32 or float16")
     N, K = W.shape
-    P, sz = alloc_packed(N, K, bits, ppm, W.device)
+    P, sz = alloc_packed(N, K, bits, ppm, W.device, with_index)
     if workspace is None:
         workspace = torch.empty(sz["pack_workspace"], dtype=torch.uint8, device=W.device)
     cs = P.c_struct()

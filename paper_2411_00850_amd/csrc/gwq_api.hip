@@ -31,6 +31,7 @@ gwq_status check_packed(const gwq_packed *P)
     if (s != GWQ_OK) return s;
     if (P->n_outliers != outlier_count(P->N, P->K, P->outlier_ppm)) return GWQ_ERR_SHAPE;
     if (!P->qweight || !P->scales || !P->zeros || !P->row_ptr || !P->col_idx || !P->out_val) return GWQ_ERR_NULL;
+    if ((uintptr_t)P->index & 15) return GWQ_ERR_SHAPE;  // optional, but aligned when present
     return GWQ_OK;
 }
 
@@ -92,6 +93,7 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
     if (((uintptr_t)workspace & 3) || ((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 15)) return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_pack(W_f16, score, score_dtype == GWQ_SCORE_F16, *dst,
                                     static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
+    if (e == hipSuccess && dst->index) e = gwq::launch_gemm_index(*dst, dst->index, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 
@@ -132,11 +134,12 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
         e = gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st);
     } else {
         // The workspace holds the index, then (whatever is left) the partial sums of a K-split launch.
+        // A layer that carries its index (filled by gwq_pack) is not indexed again.
         const size_t ib = gwq::gemm_index_bytes(P->N, P->K);
-        e = gwq::launch_gemm_index(*P, workspace, st);
+        e = P->index ? hipSuccess : gwq::launch_gemm_index(*P, workspace, st);
         if (e == hipSuccess)
-            e = gwq::launch_gemm(*P, X_f16, M, Y_f16, workspace, static_cast<char *>(workspace) + ib,
-                                 workspace_bytes - ib, g_gemm_ms, st);
+            e = gwq::launch_gemm(*P, X_f16, M, Y_f16, P->index ? P->index : workspace,
+                                 static_cast<char *>(workspace) + ib, workspace_bytes - ib, g_gemm_ms, st);
     }
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }

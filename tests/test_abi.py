@@ -76,6 +76,9 @@ def test_pack_and_linear_validate_before_touching_the_device():
     L = binding.lib()
     fake = ctypes.c_void_p(0x1000)
     ok = _packed()
+    assert ok.index is None                              # the optional index defaults to NULL
+    assert L.gwq_pack(fake, fake, 0, ctypes.byref(_packed(index=0x1008)), fake, 1 << 20, None) == -2   # present: 16-byte aligned
+    assert L.gwq_linear(ctypes.byref(_packed(index=0x1004)), fake, 1, fake, None, 0, None) == -2
     assert L.gwq_pack(None, fake, 0, ctypes.byref(ok), fake, 1 << 20, None) == -1
     assert L.gwq_pack(fake, None, 0, ctypes.byref(ok), fake, 1 << 20, None) == -1
     assert L.gwq_pack(fake, fake, 0, None, fake, 1 << 20, None) == -1

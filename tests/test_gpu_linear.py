@@ -390,3 +390,32 @@ def test_config5_70b_shapes(mid, N, K, bits):
         assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"70B N={N} K={K} bits={bits} M={M}")
     del D
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_pack_time_index_is_the_index_and_gwq_linear_reads_it(bits):
+    """gwq_pack fills the layer's optional index; it must equal what gwq_linear_index builds, and gwq_linear must give
+    the same bits with it, without it (index built per call) and through gwq_linear_indexed."""
+    import dataclasses
+    import torch
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu, assert_close
+    N, K = 200, 1408
+    rng = np.random.default_rng(90 + bits)
+    W = gs.weight(N, K, rng, planted_cols=2)
+    S = gs.score_from_weight(W, rng)
+    D = gwq.pack(to_gpu(W), to_gpu(S), bits, 10000)
+    assert D.index is not None
+    built = gwq.linear_index(D)
+    assert torch.equal(D.index[:built.numel()], built)
+    bare = dataclasses.replace(D, index=None)
+    assert gwq.pack(to_gpu(W), to_gpu(S), bits, 10000, with_index=False).index is None
+    P = orc.pack(W, S, bits, 10000)
+    for M in (17, 64, 300):
+        X = gs.activations(M, K, rng)
+        Xd = to_gpu(X)
+        y_own = gwq.linear(D, Xd)
+        y_bare = gwq.linear(bare, Xd)
+        y_idx = gwq.linear(bare, Xd, index=built)
+        assert torch.equal(y_own, y_bare) and torch.equal(y_own, y_idx), M
+        assert_close(y_own.cpu().numpy(), orc.linear_f64(P, X), f"bits={bits} M={M}")
