@@ -173,7 +173,16 @@ __global__ __launch_bounds__(kQThreads) void quality_reduce_kernel(const Merit *
 {
     __shared__ Merit wave_part[kQThreads / 64];
     Merit m{0.0, 0.0, 0.0};
-    for (int n = threadIdx.x; n < N; n += kQThreads) merit_add(m, partial[n]);
+    // Eight channels' partial results requested at a time (the additions keep their order).
+    int n = threadIdx.x;
+    for (; n + 7 * kQThreads < N; n += 8 * kQThreads) {
+        Merit p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) p[i] = partial[n + i * kQThreads];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) merit_add(m, p[i]);
+    }
+    for (; n < N; n += kQThreads) merit_add(m, partial[n]);
     m = block_sum(m, wave_part);
     if (threadIdx.x == 0) {
         out[0] = m.sq;
