@@ -93,7 +93,9 @@ typedef struct {
     size_t quality_workspace; /* for gwq_quality                                          */
 } gwq_sizes;
 
-/* Sizes for a layer (pure host arithmetic, touches no device).  scales, zeros, col_idx and
+/* Sizes of the buffers that hold one layer in the format above: the b-bit codes, scale and zero point of
+ * Sec. 3.2 (Eq. 6, 7, 9) per group and the FP16 outliers Eq. 8 selects (pure host arithmetic, touches
+ * no device; sized for the 256 compute units of gfx950).  scales, zeros, col_idx and
  * out_val are rounded up to whole 16-byte vectors plus one spare vector: gwq_linear reads them
  * with wide loads, so buffers must have these sizes and be 16-byte aligned (the padding is
  * never interpreted).
@@ -106,7 +108,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
  *   dst     host struct; its scalars describe the layer, its pointers are device buffers of
  *           the sizes gwq_layout reports; all of them are fully overwritten (dst->index too
  *           when it is not NULL)
- *   workspace device scratch of >= pack_workspace bytes, 256-byte aligned
+ *   workspace device scratch of >= pack_workspace bytes, 4-byte aligned; W_f16 and score 16-byte aligned
  * The result is a function of the inputs only (bit-exact, run-to-run identical). */
 gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_dtype,
                     gwq_packed *dst, void *workspace, size_t workspace_bytes, void *stream);
@@ -122,6 +124,9 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
  * untouched).  The rest holds FP32 partial sums when a launch also splits K, which it does where
  * rows and channels alone give too few tiles to fill the chip; with less than that the call
  * still works, without the split.
+ * For M > 16 the weights enter the MFMA as FP16 numbers s*(q-z), with s capped at the largest FP16 value for
+ * which s*(2^bits-1) is finite (4364 at 4 bits, 9352 at 3; only groups whose range exceeds 65460 reach the
+ * cap, which moves such a weight by < 0.1 %); for M <= 16 the scale multiplies FP32 sums.
  * Results are deterministic (no floating-point atomics). */
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);
@@ -163,7 +168,8 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
  *   out[1] = sum score * D    g^T (W - W_Q): the first-order change of the loss (Eq. 3 and 5) when
  *                             `score` is the gradient the outliers were ranked by
  *   out[2] = max |D|
- *   W_f16 device [N][K], score device [N][K] of `score_dtype`, out_f64 device, 3 doubles, 8-byte aligned;
+ *   W_f16 device [N][K], score device [N][K] of `score_dtype` (both 16-byte aligned), out_f64 device, 3 doubles,
+ *   8-byte aligned;
  *   workspace device, >= quality_workspace bytes as gwq_layout reports, 8-byte aligned.
  * Every D is exact (fp64 from FP16 operands); the sums are fp64 in a fixed order, so the results are
  * identical from run to run.  Inputs are expected to be finite. */
@@ -175,7 +181,7 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
  * loss with respect to Y:
  *   g[n][k] = sum over m of dY[m][n] * X[m][k]
  *   score[n][k] = beta * score[n][k] + alpha * g[n][k]
- * so the mean over calibration samples (Sec. 4.4) is one call per sample or batch of samples with
+ * so the mean over calibration samples (Sec. 4.3, ablation on the number of calibration samples) is one call per sample or batch of samples with
  * alpha = 1 / samples, beta = 0 on the first call (score is then not read: it may be uninitialised)
  * and 1 afterwards.
  *   dY_f16  device [M][N] row-major FP16; 16-byte aligned when N is a multiple of 8, else 2-byte
@@ -186,7 +192,9 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
 gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N, int32_t K, float alpha,
                      float beta, float *score_f32, void *stream);
 
-/* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.
+/* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.  The values are
+ * process-wide (atomic, read once per call by every thread's calls): a hook for benchmarks and tests, not a
+ * per-call option.
  * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 4:
  * it picks 4, 8 or 16 groups per wave accordingly; the kernel for larger M sizes itself by the LDS it
  * needs), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond M = 512

@@ -17,7 +17,7 @@
  *   Eq. 4  squared error           || W - W_Q ||^2
  *   Eq. 3, 5  first-order change   g^T (W - W_Q) of the loss (its Taylor expansion around W)
  * and for the score itself, Eq. 2: g = grad_W L.  For one linear layer Y = X W^T the chain rule
- * gives g[n][k] = sum_m (dL/dY)[m][n] * X[m][k]; the mean over calibration samples (Sec. 4.4)
+ * gives g[n][k] = sum_m (dL/dY)[m][n] * X[m][k]; the mean over calibration samples (Sec. 4.3, ablation on the number of calibration samples)
  * is a scaled accumulation of that.
  *
  * Readings taken where the text is silent or garbled (each is also listed in the design
@@ -467,7 +467,7 @@ int gwq_oracle_quality(int64_t N, int64_t K, int bits, const uint32_t *qweight,
  * W, given the gradient dY[M][N] of the loss with respect to Y and the layer's input X[M][K], is
  *   g[n][k] = sum_m dY[m][n] * X[m][k]          (chain rule; m ascending, fp64, products exact)
  * and out[n][k] = beta * prev[n][k] + alpha * g[n][k]: with alpha = 1 / samples, beta = 0 for the
- * first sample and 1 afterwards this is the mean gradient over calibration samples (Sec. 4.4).
+ * first sample and 1 afterwards this is the mean gradient over calibration samples (Sec. 4.3, ablation on the number of calibration samples).
  * prev may be NULL when beta == 0. */
 int gwq_oracle_score(const uint16_t *dY, const uint16_t *X, int64_t M, int64_t N, int64_t K,
                      double alpha, double beta, const float *prev, double *out)

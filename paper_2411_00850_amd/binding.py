@@ -1,7 +1,10 @@
 """ctypes binding of libgwq.so: the same calls as include/gwq.h, argument marshalling only.
 
-The library is loaded from this directory; if it is missing it is built once with hipcc.
-There is no fallback path: without the library every call raises.
+The library is loaded from this directory.  It is built by `__graft_entry__.build()` (or
+`python -m paper_2411_00850_amd.build`); if it is missing, it is built here once - but only while this
+process has not touched the GPU yet (a compiler run started from a process that holds the GPU, or from
+under a profiler's preload, is not safe), otherwise loading raises.  A library older than its sources
+is loaded with a warning.  There is no fallback path: without the library every call raises.
 """
 import ctypes
 import os
@@ -48,9 +51,17 @@ def lib():
     """The loaded C library (built on first use if the shared object is not there)."""
     global _lib
     if _lib is None:
+        from . import build as _build
         if not os.path.exists(_LIB_PATH):
-            from . import build as _build
+            import sys
+            torch = sys.modules.get("torch")
+            if torch is not None and torch.cuda.is_initialized():
+                raise RuntimeError("libgwq.so is not built and this process already uses the GPU: run "
+                                   "__graft_entry__.build() (or python -m paper_2411_00850_amd.build) first")
             _build.build()
+        elif _build.stale():
+            import warnings
+            warnings.warn("libgwq.so is older than its sources: rebuild with __graft_entry__.build()")
         L = ctypes.CDLL(_LIB_PATH)
         vp, i32, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint32
         L.gwq_layout.restype = ctypes.c_int

@@ -27,5 +27,14 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def stale() -> bool:
+    """True when the built library is older than one of its sources or the public header."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(INCLUDE, "gwq.h")]
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -6,8 +6,9 @@
 
 namespace {
 
-int g_decode_waves = 0;   // 0 = heuristic
-int g_gemm_ms = 0;        // rows of Y per GEMM block; 0 = heuristic
+// Measurement hooks of gwq_tuning_set: process-wide, read once per call.
+std::atomic<int> g_decode_waves{0};   // 0 = heuristic
+std::atomic<int> g_gemm_ms{0};        // rows of Y per GEMM block; 0 = heuristic
 
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
@@ -31,14 +32,13 @@ gwq_status check_packed(const gwq_packed *P)
     if (s != GWQ_OK) return s;
     if (P->n_outliers != outlier_count(P->N, P->K, P->outlier_ppm)) return GWQ_ERR_SHAPE;
     if (!P->qweight || !P->scales || !P->zeros || !P->row_ptr || !P->col_idx || !P->out_val) return GWQ_ERR_NULL;
+    if ((uintptr_t)P->row_ptr & 3) return GWQ_ERR_SHAPE;
     if ((uintptr_t)P->index & 15) return GWQ_ERR_SHAPE;  // optional, but aligned when present
     return GWQ_OK;
 }
 
-// Shared argument checks of the gwq_linear variants; `index` is the workspace (whose head becomes
-// the index) or the prebuilt index.
-gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const void *Y_f16, const void *index,
-                        size_t index_bytes)
+// Shared argument checks of the gwq_linear variants.
+gwq_status check_xy(const gwq_packed *P, const void *X_f16, int32_t M, const void *Y_f16)
 {
     gwq_status s = check_packed(P);
     if (s != GWQ_OK) return s;
@@ -47,12 +47,49 @@ gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const
     if (((uintptr_t)X_f16 | (uintptr_t)P->qweight | (uintptr_t)P->scales | (uintptr_t)P->zeros |
          (uintptr_t)P->col_idx | (uintptr_t)P->out_val) & 15)
         return GWQ_ERR_SHAPE;
+    return GWQ_OK;
+}
+
+// The same plus the index: `index` is the workspace (whose head becomes the index) or the prebuilt index.
+gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const void *Y_f16, const void *index,
+                        size_t index_bytes)
+{
+    gwq_status s = check_xy(P, X_f16, M, Y_f16);
+    if (s != GWQ_OK) return s;
     if (M > 16 && (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
     if (M > 16 && ((uintptr_t)index & 15)) return GWQ_ERR_SHAPE;
     return GWQ_OK;
 }
 
 }  // namespace
+
+namespace gwq {
+
+int device_cus()
+{
+    static std::atomic<int> cus[64];                    // 0 = not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cus[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
+hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<uint32_t> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) dev = -1;
+    const bool tracked = dev >= 0 && dev < 32;
+    if (tracked && (done.load(std::memory_order_acquire) >> dev & 1u)) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && tracked) done.fetch_or(1u << dev, std::memory_order_release);
+    return e;
+}
+
+}  // namespace gwq
 
 extern "C" {
 
@@ -105,7 +142,7 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
     if (!W_f16 || !score || !out_f64) return GWQ_ERR_NULL;
     if (score_dtype != GWQ_SCORE_F32 && score_dtype != GWQ_SCORE_F16) return GWQ_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < gwq::quality_workspace_bytes(P->N)) return GWQ_ERR_WORKSPACE;
-    if (((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 3) || ((uintptr_t)workspace & 7) || ((uintptr_t)out_f64 & 7))
+    if (((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 15) || ((uintptr_t)workspace & 7) || ((uintptr_t)out_f64 & 7))
         return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_quality(*P, W_f16, score, score_dtype == GWQ_SCORE_F16, workspace, out_f64,
                                        static_cast<hipStream_t>(stream));

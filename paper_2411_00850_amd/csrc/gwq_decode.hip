@@ -632,13 +632,9 @@ constexpr size_t kXLdsBudget = 128 * 1024;              // X[M][k_pad] is staged
 template <auto Kernel>
 hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nwaves, size_t lds, hipStream_t st)
 {
-    static bool attr_set = false;                       // per kernel; the HIP call is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint32_t> lds_allowed{0};        // per kernel
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(Kernel), (int)kMaxLds, lds_allowed);
+    if (e != hipSuccess) return e;
     Kernel<<<dim3(blocks, count), nwaves * 64, lds, st>>>(batch);
     return hipGetLastError();
 }
@@ -724,8 +720,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
             // One resident block per CU (X fills most of the LDS): with a single phase, fewer blocks
             // that loop over tiles stage X once each.
             if (best_ph == 1) {
-                static int cus = 0;
-                if (!cus && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess) cus = 256;
+                const int cus = device_cus();
                 const int cap = cus / count > 0 ? cus / count : 1;
                 if (blocks > cap) blocks = cap;
             }

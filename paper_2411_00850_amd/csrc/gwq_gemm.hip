@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void group_index_kernel(const int32_t *__restr
                                                           const uint16_t *__restrict__ col_idx,
                                                           const uint16_t *__restrict__ scales,
                                                           const uint8_t *__restrict__ zeros, int N, int gpr,
-                                                          GroupRecord *__restrict__ rec)
+                                                          uint32_t scale_cap, GroupRecord *__restrict__ rec)
 {
     __shared__ uint32_t c[4][512];                      // gpr <= 512 (K <= 65536)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -94,7 +94,13 @@ __global__ __launch_bounds__(256) void group_index_kernel(const int32_t *__restr
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int g = 8 * lane + i;
-        if (g < gpr) out[g] = GroupRecord{(int32_t)first, (uint32_t)scales[row_group + g] | (uint32_t)zeros[row_group + g] << 16};
+        if (g < gpr) {
+            // The GEMM multiplies FP16 operands s * (q - z): a scale is capped at the largest FP16 value whose
+            // product with 2^bits - 1 is still finite (only ranges beyond 65460 reach it; positive FP16
+            // patterns order like integers).
+            const uint32_t sc = scales[row_group + g];
+            out[g] = GroupRecord{(int32_t)first, (sc < scale_cap ? sc : scale_cap) | (uint32_t)zeros[row_group + g] << 16};
+        }
         first += mine[i];
     }
     if (lane == 0) out[gpr] = GroupRecord{row_ptr[n + 1], 0u};
@@ -351,8 +357,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         // fills eight consecutive 128-byte rows, lane l fetching the chunk that belongs at position
         // l % 8 of its row.  Step t + 2 is requested when barrier t - 1 has released its buffer;
         // before barrier t everything but those newest requests has arrived.
-        // Address form: 64-bit scalar base (advanced per step by scalar adds) + 32-bit lane offset,
-        // so a request costs no vector instruction besides the load itself.
+        // The step's base address is wave-uniform (advanced by scalar adds); a lane adds its row offset.
         constexpr int kInstr = BM / 8 / kLoaders;       // per wave and step
         const int lw = wave - kConsumers - kProducers, lr = lane >> 3;
         uint32_t row_off[kInstr];                       // bytes from the tile's first row and the step's first column
@@ -363,14 +368,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             row_off[j] = (uint32_t)rc * (uint32_t)K * 2u + 16u * (uint32_t)((lane & 7) ^ x_swizzle(r));
         }
         const char *tile = reinterpret_cast<const char *>(X + (size_t)m0 * K + k_first);
-        const uint32_t lds_x = (uint32_t)(uintptr_t)lds + (uint32_t)(lw * kInstr) * 1024u;
+        typedef __attribute__((address_space(3))) unsigned char lds_byte;
+        typedef const __attribute__((address_space(1))) unsigned char global_byte;
+        lds_byte *const lds_x = (lds_byte *)lds + (uint32_t)(lw * kInstr) * 1024u;
         auto issue_x = [&](int step, int buf) {
             const char *src = tile + (size_t)step * (kBK * 2);
-            const uint32_t dst = lds_x + (uint32_t)buf * (uint32_t)(kXBufHalves * 2);
+            lds_byte *dst = lds_x + (uint32_t)buf * (uint32_t)(kXBufHalves * 2);
 #pragma unroll
-            for (int j = 0; j < kInstr; ++j)
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                             :: "s"(dst + j * 1024u), "v"(row_off[j]), "s"(src) : "memory");   // nothing else in this kernel uses m0
+            for (int j = 0; j < kInstr; ++j)    // the builtin sets up m0 (the LDS base of the wave's 1 KB) itself
+                __builtin_amdgcn_global_load_lds((global_byte *)(src + row_off[j]), dst + j * 1024u, 16, 0, 0);
         };
         issue_x(0, 0);
         issue_x(1, 1);                                  // nk >= 2
@@ -496,11 +502,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 
 // How many ways K is split for a launch of `tiles` tiles over rows of `gpr` groups: as many as keep
 // the block count within the CU count, at least two groups each, at most kMaxSplits.
+// kCUs is the compute-unit count of the MI355X, which the scratch size reported by gwq_layout (a pure host
+// call) is based on; a launch plans with the current device's count, never beyond kCUs.
 constexpr int kMaxSplits = 8, kSplitBelowTiles = 160, kCUs = 256;
-int choose_splits(int tiles, int gpr)
+int launch_cus()
+{
+    const int n = device_cus();
+    return n < kCUs ? n : kCUs;
+}
+int choose_splits(int tiles, int gpr, int cus)
 {
     if (tiles >= kSplitBelowTiles) return 1;
-    int s = kCUs / tiles;
+    int s = cus / tiles;
     s = s < kMaxSplits ? s : kMaxSplits;
     s = s < gpr / 2 ? s : gpr / 2;
     return s < 1 ? 1 : s;
@@ -509,9 +522,9 @@ int choose_splits(int tiles, int gpr)
 struct SplitPlan {
     int splits, split_groups;
 };
-SplitPlan plan_split(int tiles, int gpr, bool have_scratch)
+SplitPlan plan_split(int tiles, int gpr, bool have_scratch, int cus)
 {
-    int splits = have_scratch ? choose_splits(tiles, gpr) : 1;
+    int splits = have_scratch ? choose_splits(tiles, gpr, cus) : 1;
     const int split_groups = (gpr + splits - 1) / splits;
     splits = (gpr + split_groups - 1) / split_groups;   // no empty split
     return SplitPlan{splits, split_groups};
@@ -535,14 +548,14 @@ constexpr ShapeCost kShapeCost[4] = {{32, 0.42f, 0.9f}, {64, 0.49f, 0.45f}, {128
 int choose_rows(int M, int N, int K, bool have_scratch)
 {
     if (M > 512) return 256;
-    const int gpr = K / kGroup, tiles_n = (N + kBN - 1) / kBN;
+    const int gpr = K / kGroup, tiles_n = (N + kBN - 1) / kBN, cus = launch_cus();
     int best = 256;
     float best_us = 0.f;
     for (const ShapeCost &c : kShapeCost) {
         if (c.rows > 32 && c.rows >= 2 * M) continue;   // a tile at most half full: the next smaller holds M too
         const int tiles = (M + c.rows - 1) / c.rows * tiles_n;
-        const SplitPlan sp = plan_split(tiles, gpr, have_scratch);
-        const int rounds = (tiles * sp.splits + kCUs - 1) / kCUs;
+        const SplitPlan sp = plan_split(tiles, gpr, have_scratch, cus);
+        const int rounds = (tiles * sp.splits + cus - 1) / cus;
         float us = rounds * (c.block_us + 2 * sp.split_groups * c.step_us);
         if (sp.splits > 1) us += 2.8f + 0.47f * (4e-6f * sp.splits * M * N);
         if (best_us == 0.f || us < best_us) best = c.rows, best_us = us;
@@ -557,17 +570,15 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
     constexpr int BM = 32 * MSW * WM;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
     const int gpr = P.K / kGroup;
-    const SplitPlan sp = plan_split(tiles_m * tiles_n, gpr, partial != nullptr);
+    const SplitPlan sp = plan_split(tiles_m * tiles_n, gpr, partial != nullptr, launch_cus());
     int splits = sp.splits, split_groups = sp.split_groups;
     if (splits > 1 && (size_t)splits * M * P.N * sizeof(float) > partial_bytes) splits = 1, split_groups = gpr;
     if (splits == 1) partial = nullptr;
     const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
-    static bool attr_set = false;                       // per instantiation; idempotent HIP call
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<uint32_t> lds_allowed{0};        // per instantiation
+    {
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM>), (int)lds, lds_allowed);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     gemm_kernel<BITS, MSW, WN, WM><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
         P.qweight, P.col_idx, P.out_val, rec, static_cast<const _Float16 *>(X),
@@ -596,8 +607,10 @@ size_t gemm_scratch_bytes(int64_t N, int64_t M_max)
 
 hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t st)
 {
+    // 4364 * 15 = 65460 and 9352 * 7 = 65464: the last scales on the FP16 grid that keep s * (q - z) finite.
+    const uint32_t scale_cap = P.bits == 4 ? 0x6C43u : 0x7091u;
     group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.scales, P.zeros, P.N, P.K / kGroup,
-                                                     static_cast<GroupRecord *>(workspace));
+                                                     scale_cap, static_cast<GroupRecord *>(workspace));
     return hipGetLastError();
 }
 

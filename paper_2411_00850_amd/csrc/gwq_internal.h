@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "gwq.h"
 
 namespace gwq {
@@ -12,6 +14,13 @@ constexpr int kSelBins = 2048;     // bins of one radix-select pass
 constexpr int kMaxBatch = GWQ_MAX_BATCH;   // layers per grouped decode launch
 
 __host__ __device__ constexpr int words_per_group(int bits) { return bits == 4 ? 16 : 13; }
+
+// Compute units of the current device, asked once per device (256 on MI355X; 256 if the query fails).
+int device_cus();
+
+// Lets `kernel` use up to `bytes` of dynamic LDS on the current device.  `done` is the caller's per-kernel
+// record (bit d: done on device d); the HIP call is idempotent, so a race between threads is harmless.
+hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<uint32_t> &done);
 
 // ---- gwq_pack workspace: uint32 words -------------------------------------------------------
 // [0, 3*kSelBins)        histograms of the three radix-select passes

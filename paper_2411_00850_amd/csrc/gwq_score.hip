@@ -3,7 +3,7 @@
 // without bias the chain rule gives, from the gradient dY of the loss with respect to Y,
 //   g[n][k] = sum_m dY[m][n] * X[m][k]
 // and the entry point writes score = beta * score + alpha * g, so that the mean over calibration
-// samples (Sec. 4.4) is a sequence of calls with alpha = 1 / samples.
+// samples (Sec. 4.3, ablation on the number of calibration samples) is a sequence of calls with alpha = 1 / samples.
 //
 // A dense contraction over the samples m with both operands stored m-major, bound by MFMA.  A block of
 // four waves owns a 128 (n) x 128 (k) tile of the score and walks m in steps of 64; a wave owns 64 x 64
@@ -197,15 +197,12 @@ hipError_t launch_score(const void *dY, const void *X, int M, int N, int K, floa
                         hipStream_t st)
 {
     const int tiles_k = K / kTile, tiles_n = (N + kTile - 1) / kTile;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&score_kernel<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoreLds);
+    static std::atomic<uint32_t> lds_allowed[2];        // per kernel
+    {
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&score_kernel<true>), (int)kScoreLds, lds_allowed[0]);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&score_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoreLds);
+            e = allow_dynamic_lds(reinterpret_cast<const void *>(&score_kernel<false>), (int)kScoreLds, lds_allowed[1]);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     const _Float16 *d = static_cast<const _Float16 *>(dY), *x = static_cast<const _Float16 *>(X);
     const int blocks = (tiles_n * tiles_k + 7) / 8 * 8;

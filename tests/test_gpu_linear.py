@@ -268,6 +268,45 @@ def test_padding_and_neighbours_are_never_interpreted(bits, pad_byte, N, K):
         assert_close(Y, orc.linear_f64(P, X), f"padding N={N} K={K} M={M} bits={bits} pad={pad_byte:#x}")
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+def test_linear_extreme_weight_ranges(bits):
+    """Groups that span the whole FP16 range (scale 4368: s * 15 would round to infinity as an FP16 product),
+    subnormal groups, one-sided and empty ones, through the decode kernels (FP32 scale) and the GEMM (FP16
+    operands s * (q - z), scale capped so that they stay finite: the cap moves such a weight by < 0.1 %).
+    Activations are small so that the FP16 outputs stay finite; every channel is checked on its own."""
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    import paper_2411_00850_amd as gwq
+    rng = np.random.default_rng(8)
+    N, K = 32, 512
+    W = gs.weight(N, K, rng)
+    W[0] = (rng.integers(-40, 40, K) * 2.0 ** -24).astype(np.float16)      # subnormals
+    W[1] = (rng.standard_normal(K) * 9000).astype(np.float16)               # near the FP16 maximum
+    W[2] = np.abs(W[2])
+    W[3] = -np.abs(W[3])
+    W[4] = 0
+    W[6, :128] = np.float16(65504.0)
+    W[6, 128:256] = np.float16(-65504.0)
+    W[7, :128] = (rng.random(128) * 65504).astype(np.float16)               # 0 .. max: scale 4368 (4-bit)
+    W[7, 5] = np.float16(65504.0)
+    W[7, 9] = 0
+    S = gs.score_from_weight(W, rng)
+    S[6:8] = 0                                                              # keep those rows quantised
+    P = orc.pack(W, S, bits, 10000)
+    assert orc.half_to_double(int(P.scales[7, 0])) * ((1 << bits) - 1) >= 65504
+    D = upload_packed(P)
+    wnorm = np.linalg.norm(orc.decode(P), axis=1)
+    live = np.flatnonzero(wnorm > 1e-3)                                    # not the subnormal and the empty channel
+    for M in (1, 5, 16, 17, 40, 300):
+        X = (gs.activations(M, K, rng).astype(np.float32) * 1e-3).astype(np.float16)
+        Y = gwq.linear(D, to_gpu(X)).cpu().numpy().astype(np.float64)
+        ref = orc.linear_f64(P, X)
+        assert np.isfinite(Y).all(), f"M={M}"
+        # channels equalised by the norm of their weights, so the huge ones do not hide the others
+        assert_close(Y[:, live] / wnorm[live], ref[:, live] / wnorm[live], f"extreme ranges bits={bits} M={M}")
+        assert not Y[:, 4].any()
+        assert np.abs(Y[:, 0] - ref[:, 0]).max() <= 2.0 ** -24             # subnormal weights: FP16 output underflows
+
+
 def _sweep_cases():
     """40 seeded cases: ragged N, K in whole groups, both bit widths, outlier fractions from none to
     half, outliers spread by weight-scaled scores or clustered in a few columns or a few rows (many
@@ -338,17 +377,22 @@ def test_config2_and_3_decode_7b_shapes(mid, N, K):
 
 
 @pytest.mark.parametrize("mid,N,K", SHAPES_7B)
-def test_config4_prefill_7b_shapes_sampled(mid, N, K):
-    """Prefill M = 2048 with hot activation channels; the oracle computes 160 sampled output
-    channels (all 2048 rows of each), the GPU computes everything."""
+def test_config4_prefill_7b_shapes_full(mid, N, K):
+    """Prefill M = 2048 with hot activation channels: every one of the 2048 x N outputs against the
+    oracle's fp64 product (the full product, so every tile of the GEMM's grid, its ragged last
+    n-tile at N = 11008 and the tile order over the XCDs are all compared)."""
     from gpu_helpers import assert_close
     W, mask = _layer7b(mid, N, K)
     P = orc.encode(W, mask, 4, 10000)
     X = gs.activations(2048, K, gs.rng_for(4, mid, 2), hot_frac=0.001)
-    rows = np.sort(gs.rng_for(4, mid, 3).choice(N, 160, replace=False)).astype(np.int32)
     Y = _run(P, X)
     assert np.isfinite(Y.astype(np.float32)).all()
-    assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"prefill N={N} K={K}")
+    ref = orc.linear_f64(P, X)
+    assert_close(Y, ref, f"prefill N={N} K={K}")
+    # no tile may hide behind the matrix-wide norms: every 256 x 128 tile of Y meets the tolerance on its own
+    for m0 in range(0, 2048, 256):
+        for n0 in range(0, N, 128):
+            assert_close(Y[m0:m0 + 256, n0:n0 + 128], ref[m0:m0 + 256, n0:n0 + 128], f"prefill N={N} K={K} tile {m0},{n0}")
 
 
 # ----------------------------------------------------------------------------- 70B-shaped layers (config 5)
@@ -368,13 +412,23 @@ def _layer70b(mid, N, K):
     return W, S, mask
 
 
+def _stratified_channels(N, rng):
+    """One channel out of every band of 16 (the decode kernels' tile; eight per 128-wide GEMM tile), plus
+    the first and the last channel."""
+    starts = np.arange(0, N, 16)
+    picks = starts + rng.integers(0, 16, starts.size)
+    picks = np.minimum(picks, N - 1)
+    return np.unique(np.concatenate([[0, N - 1], picks])).astype(np.int32)
+
+
 @pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("mid,N,K", [(0, 8192, 8192), (1, 28672, 8192), (2, 8192, 28672)])
 def test_config5_70b_shapes(mid, N, K, bits):
     """Full-size 70B-shaped matrices with column-clustered outliers: gwq_pack byte-exact against the
-    oracle's encoding of the known outlier set, gwq_linear at M in {1, 4, 16, 64, 2048} on 64 sampled
-    channels (all rows) against the oracle (K = 28672 takes several chunks of K in the kernel for
-    5 <= M <= 16)."""
+    oracle's encoding of the known outlier set; gwq_linear at M in {1, 4, 8, 16, 64} on EVERY output
+    against the oracle's full product, and at M = 2048 on a stratified sample that has a channel in
+    every 16-channel band (so in every tile of both kernels), all 2048 rows of each (K = 28672 takes
+    several chunks of K in the kernel for 5 <= M <= 16)."""
     import torch
     import paper_2411_00850_amd as gwq
     from gpu_helpers import assert_close, assert_packed_equal, to_gpu
@@ -382,12 +436,19 @@ def test_config5_70b_shapes(mid, N, K, bits):
     P = orc.encode(W, mask, bits, 10000)
     D = gwq.pack(to_gpu(W), to_gpu(S), bits, 10000)
     assert_packed_equal(D, P)
-    rows = np.sort(gs.rng_for(5, mid, 3).choice(N, 64, replace=False)).astype(np.int32)
-    for M in (1, 4, 16, 64, 2048):
+    for M in (1, 4, 8, 16, 64):
         X = gs.activations(M, K, gs.rng_for(5, mid, 10 + M))
         Y = gwq.linear(D, to_gpu(X)).cpu().numpy()
         assert np.isfinite(Y.astype(np.float32)).all()
-        assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"70B N={N} K={K} bits={bits} M={M}")
+        ref = orc.linear_f64(P, X)
+        assert_close(Y, ref, f"70B N={N} K={K} bits={bits} M={M}")
+        for n0 in range(0, N, 1024):                      # and band by band, so no part hides behind the whole
+            assert_close(Y[:, n0:n0 + 1024], ref[:, n0:n0 + 1024], f"70B N={N} K={K} bits={bits} M={M} band {n0}")
+    rows = _stratified_channels(N, gs.rng_for(5, mid, 3))
+    X = gs.activations(2048, K, gs.rng_for(5, mid, 10 + 2048))
+    Y = gwq.linear(D, to_gpu(X)).cpu().numpy()
+    assert np.isfinite(Y.astype(np.float32)).all()
+    assert_close(Y[:, rows], orc.linear_f64(P, X, rows), f"70B N={N} K={K} bits={bits} M=2048")
     del D
     torch.cuda.empty_cache()
 

@@ -93,6 +93,56 @@ def test_pack_extreme_weights(bits):
     assert_packed_equal(_gpu_pack(W, S, bits, 10000), orc.pack(W, S, bits, 10000))
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+def test_pack_non_finite_weights(bits):
+    """inf and NaN weights (values unspecified, everything else intact): as outliers they are copied bit
+    for bit and the whole encoding must equal the oracle's; inside the quantised part they may only
+    change their own group - every other group, the CSR arrays and all range invariants must hold, and
+    gwq_linear on the result must leave the channels without such a group within tolerance."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, assert_packed_equal, download_packed, to_gpu
+    rng = np.random.default_rng(700 + bits)
+    N, K = 40, 1024
+    W = gs.weight(N, K, rng, planted_cols=2)
+    S = gs.score_from_weight(W, rng)
+    ppm = 20000
+    specials = np.array([0x7C00, 0xFC00, 0x7E00, 0xFE01, 0x7C01, 0x7FFF], np.uint16)
+    flat = rng.choice(N * K, 36, replace=False)
+    kept, quantised = flat[:18], flat[18:]
+    S.ravel()[kept] = 1e6 + np.arange(18)
+    S.ravel()[quantised] = 0.0
+    Wb = W.view(np.uint16).copy()
+    Wb.ravel()[kept] = np.tile(specials, 3)
+    Wk = Wb.view(np.float16)
+    assert_packed_equal(_gpu_pack(Wk, S, bits, ppm), orc.pack(Wk, S, bits, ppm))
+
+    clean = Wb.copy()
+    clean.ravel()[kept] = 0
+    Wq = clean.copy()
+    Wq.ravel()[quantised] = np.tile(specials, 3)
+    D = _gpu_pack(Wq.view(np.float16), S, bits, ppm)
+    got, C = download_packed(D), orc.pack(clean.view(np.float16), S, bits, ppm)
+    for name in ("row_ptr", "col_idx", "out_val"):
+        assert np.array_equal(got[name], getattr(C, name)), name
+    touched = np.zeros((N, K // 128), bool)
+    touched[quantised // K, (quantised % K) // 128] = True
+    qw = got["qweight"].reshape(C.qweight.shape)
+    assert np.array_equal(qw[~touched], C.qweight[~touched])
+    assert np.array_equal(got["scales"].reshape(N, -1)[~touched], C.scales[~touched])
+    assert np.array_equal(got["zeros"].reshape(N, -1)[~touched], C.zeros[~touched])
+    assert got["zeros"].max() <= (1 << bits) - 1
+    if bits == 3:
+        assert not (qw[:, :, :12] & np.uint32(0x80008000)).any() and not (qw[:, :, 12] & np.uint32(0xF000F000)).any()
+    codes = orc.unpack_codes(qw, N, K, bits)
+    assert np.array_equal(codes[C.mask.astype(bool)], np.repeat(got["zeros"], 128).reshape(N, K)[C.mask.astype(bool)])
+    ok_rows = np.flatnonzero(~touched.any(axis=1))
+    assert ok_rows.size >= 8
+    for M in (1, 16, 40):
+        X = gs.activations(M, K, rng)
+        Y = gwq.linear(D, to_gpu(X)).cpu().numpy()
+        assert_close(Y[:, ok_rows], orc.linear_f64(C, X, ok_rows.astype(np.int32)), f"non-finite W, M={M}")
+
+
 def _sweep_cases():
     """40 seeded cases: ragged N, K in whole groups, both bit widths, outlier fractions from a single
     entry to nearly everything, and five kinds of score: weight-scaled FP32 or FP16, FP32 rounded to a

@@ -69,7 +69,7 @@ def test_score_picks_rows_and_columns_exactly():
 
 
 def test_score_mean_over_samples_and_scaling():
-    """Sec. 4.4: the mean gradient over calibration samples as calls with alpha = 1 / samples, beta = 0 then 1."""
+    """Sec. 4.3 (ablation on the number of calibration samples): the mean gradient over calibration samples as calls with alpha = 1 / samples, beta = 0 then 1."""
     import paper_2411_00850_amd as gwq
     from gpu_helpers import to_gpu
     M, N, K = 96, 72, 256

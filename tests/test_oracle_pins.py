@@ -172,6 +172,29 @@ def test_select_invariants_and_tie_rule():
     assert sel_tie.max() < unsel_tie.min()               # ties go to the lowest flat index
 
 
+@pytest.mark.parametrize("ppm", [1, 10000, 31000, 500000])
+def test_select_fp16_scores_every_pattern_incl_nan_payloads(ppm):
+    """FP16 scores are ranked by the binary32 pattern of their exact widening; a NaN keeps sign and
+    payload (shifted into the binary32 fraction) and so ranks above +inf, larger payloads first.  Pinned
+    to numpy's binary16 -> binary32 conversion on all 65 536 patterns, shuffled: 2046 NaNs, both
+    infinities, both zeros, every subnormal.  31 000 ppm cuts inside the NaN block."""
+    rng = np.random.default_rng(ppm)
+    bits = rng.permutation(np.arange(65536, dtype=np.uint16))
+    S = bits.view(np.float16).reshape(512, 128)
+    wide = S.astype(np.float32).view(np.uint32).ravel()
+    nan = ((bits >> 10) & 31 == 31) & (bits & 1023 != 0)
+    assert nan.sum() == 2046
+    assert np.array_equal(wide[nan] & 0x7FFFFFFF, 0x7F800000 | ((bits[nan].astype(np.uint32) & 1023) << 13))
+    k_out = orc.outlier_count(512, 128, ppm)
+    got = orc.select(S, ppm)
+    assert int(got.sum()) == k_out
+    assert np.array_equal(got, numpy_select(S, k_out))
+    if k_out >= 2046:
+        assert got.ravel()[nan].all()                      # every NaN outranks every number
+    else:
+        assert not got.ravel()[~nan].any()                 # and the cut inside the NaNs takes NaNs only
+
+
 def test_select_rejects_bad_ppm():
     with pytest.raises(RuntimeError):
         orc.select(np.zeros((2, 128), np.float32), 1000001)
@@ -400,6 +423,54 @@ def test_all_outliers_is_dense_fp16_matmul(bits):
     assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
 
 
+@pytest.mark.parametrize("bits", [3, 4])
+def test_non_finite_weights_stay_local_and_keep_the_invariants(bits):
+    """Weights that are inf or NaN: their values are unspecified, but (a) the selection does not look at
+    W, so the count and the positions are those of the finite matrix; (b) a non-finite weight that is an
+    outlier is only copied, bit for bit, so the rest of the encoding equals that of the matrix with the
+    weight replaced by 0; (c) a non-finite weight that is quantised can only change its own group; (d)
+    every stored field stays in range (zero points, the unused bits of 3-bit words, CSR structure)."""
+    rng = np.random.default_rng(400 + bits)
+    N, K = 12, 512
+    W = random_w(rng, (N, K))
+    S = rng.random((N, K)).astype(np.float32)
+    ppm = 20000
+    specials = np.array([0x7C00, 0xFC00, 0x7E00, 0xFE01, 0x7C01, 0x7FFF], np.uint16)   # +-inf, quiet and signalling NaNs
+    flat = rng.choice(N * K, 24, replace=False)
+    kept, quantised = flat[:12], flat[12:]
+    S.ravel()[kept] = 5.0 + np.arange(12)                  # these are certainly selected
+    S.ravel()[quantised] = 0.0                             # these certainly are not
+    Wb = W.view(np.uint16).copy()
+    Wb.ravel()[kept] = np.tile(specials, 2)
+    clean = Wb.copy()
+    clean.ravel()[kept] = 0
+    # (a), (b): non-finite outliers
+    P, C = orc.pack(Wb.view(np.float16), S, bits, ppm), orc.pack(clean.view(np.float16), S, bits, ppm)
+    assert np.array_equal(P.mask, C.mask) and P.mask.ravel()[kept].all()
+    for name in ("qweight", "scales", "zeros", "row_ptr", "col_idx"):
+        assert np.array_equal(getattr(P, name), getattr(C, name)), name
+    pos = {int(f): j for j, f in enumerate(np.flatnonzero(P.mask.ravel()))}
+    for f, pat in zip(kept, np.tile(specials, 2)):
+        assert P.out_val[pos[int(f)]] == pat               # NaN payloads and signs survive
+    # (c), (d): non-finite weights inside the quantised part
+    Wq = clean.copy()
+    Wq.ravel()[quantised] = np.tile(specials, 2)
+    Q = orc.pack(Wq.view(np.float16), S, bits, ppm)
+    assert np.array_equal(Q.mask, C.mask) and np.array_equal(Q.row_ptr, C.row_ptr) and np.array_equal(Q.col_idx, C.col_idx)
+    assert np.array_equal(Q.out_val, C.out_val)
+    touched = np.zeros((N, K // 128), bool)
+    touched[quantised // K, (quantised % K) // 128] = True
+    assert np.array_equal(Q.qweight[~touched], C.qweight[~touched])
+    assert np.array_equal(Q.scales[~touched], C.scales[~touched]) and np.array_equal(Q.zeros[~touched], C.zeros[~touched])
+    assert Q.zeros.max() <= (1 << bits) - 1
+    if bits == 3:
+        assert not (Q.qweight[:, :, :12] & np.uint32(0x80008000)).any()
+        assert not (Q.qweight[:, :, 12] & np.uint32(0xF000F000)).any()
+    assert np.array_equal(py_unpack(Q.qweight, N, K, bits) <= (1 << bits) - 1, np.ones((N, K), bool))
+    assert np.array_equal(orc.unpack_codes(Q.qweight, N, K, bits)[Q.mask.astype(bool)],
+                          np.repeat(Q.zeros, 128).reshape(N, K)[Q.mask.astype(bool)])   # outliers still carry z
+
+
 # ----------------------------------------------------------------------------- Eq. 10 + the layer
 
 @pytest.mark.parametrize("bits", [3, 4])
@@ -561,7 +632,7 @@ def test_score_special_cases_and_linearity():
     unit[3, 2] = 1.0
     g = orc.score(unit, X)
     assert np.array_equal(g[2], X[3].astype(np.float64)) and not g[[0, 1, 3, 4]].any()
-    # mean over samples (Sec. 4.4) as a scaled accumulation: two halves with alpha = 1/2
+    # mean over samples (Sec. 4.3) as a scaled accumulation: two halves with alpha = 1/2
     prev = orc.score(dY[:4], X[:4], alpha=0.5).astype(np.float32)
     both = orc.score(dY[4:], X[4:], alpha=0.5, beta=1.0, prev=prev)
     want = prev.astype(np.float64) + 0.5 * orc.score(dY[4:], X[4:])
