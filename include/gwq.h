@@ -149,6 +149,19 @@ gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M,
                               const void *index, size_t index_bytes, void *scratch,
                               size_t scratch_bytes, void *stream);
 
+/* gwq_linear for callers that cannot allocate or pass a workspace (code under HIP graph capture, serving loops
+ * and harnesses in which hipMalloc is off limits): the same kernels, with the scratch that M > 16 needs - the
+ * layer's index when P->index is NULL, then the FP32 partial sums of a K-split launch - held in a static device
+ * array of GWQ_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, for the life of the process).  The
+ * call allocates and frees nothing.  Arguments and results as gwq_linear given a workspace of the
+ * linear_workspace bytes gwq_layout reports for M_max = M (bit for bit).  When index (if the layer has none)
+ * plus partial sums for this N and M exceed GWQ_STATIC_SCRATCH_BYTES the call returns GWQ_ERR_WORKSPACE and
+ * does nothing (every shape up to 28672 x 8192 fits at any M).  All calls on a GPU share that GPU's array:
+ * calls that may overlap in time on one GPU (different streams, different threads) race and must not be made;
+ * calls on one stream are ordered and safe.  Nothing in the array has to start at zero. */
+#define GWQ_STATIC_SCRATCH_BYTES (48u << 20)
+gwq_status gwq_linear_static(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, void *stream);
+
 /* Several layers in one decode launch (M <= 16): Y_f16[i] = gwq_linear(P[i], X_f16[i]) for
  * i < count <= GWQ_MAX_BATCH.  For layers with no data dependence between them, such as the q, k
  * and v or the gate and up projections of a decoder layer (which may share one X): at decode sizes a

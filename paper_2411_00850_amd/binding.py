@@ -79,6 +79,8 @@ def lib():
         L.gwq_linear_indexed.restype = ctypes.c_int
         L.gwq_linear_indexed.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp,
                                          ctypes.c_size_t, vp]
+        L.gwq_linear_static.restype = ctypes.c_int
+        L.gwq_linear_static.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp]
         L.gwq_linear_batch.restype = ctypes.c_int
         L.gwq_linear_batch.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), ctypes.POINTER(vp), i32,
                                        ctypes.POINTER(vp), vp]
@@ -280,6 +282,22 @@ def linear(P, X, out=None, stream=None, workspace=None, index=None, scratch="aut
     rc = lib().gwq_linear(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), ws_ptr, ws_len, _stream_ptr(stream))
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_linear")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def linear_static(P, X, out, stream=None):
+    """gwq_linear_static: gwq_linear with the library's own static scratch instead of a workspace; the call
+    allocates nothing, so `out` (FP16 [M, N]) is the caller's."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == P.K
+    assert out.is_cuda and out.dtype == torch.float16 and out.is_contiguous() and tuple(out.shape) == (X.shape[0], P.N)
+    cs = P.c_struct()
+    rc = lib().gwq_linear_static(ctypes.byref(cs), X.data_ptr(), X.shape[0], out.data_ptr(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_linear_static")
     return out
 
 

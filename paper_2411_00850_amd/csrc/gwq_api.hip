@@ -2,9 +2,37 @@
 // so argument errors are reported on machines without a GPU as well.
 #include <string.h>
 
+#include <mutex>
+
 #include "gwq_internal.h"
 
+// Scratch of gwq_linear_static: one copy per GPU, held until the process ends.  In host code this name is
+// only a handle for hipGetSymbolAddress; the device address is asked once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[GWQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[64];                                // per device: address of its copy of `scratch`
+
+// Device address of the current device's copy of `scratch`.
+hipError_t static_scratch(unsigned char **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char *>(g_scratch_ptr[dev]);
+    return hipSuccess;
+}
 
 // Measurement hooks of gwq_tuning_set: process-wide, read once per call.
 std::atomic<int> g_decode_waves{0};   // 0 = heuristic
@@ -201,6 +229,26 @@ gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M,
     hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st)
                            : gwq::launch_gemm(*P, X_f16, M, Y_f16, index, scratch, scratch ? scratch_bytes : 0,
                                               g_gemm_ms, st);
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_linear_static(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16, void *stream)
+{
+    gwq_status s = check_xy(P, X_f16, M, Y_f16);
+    if (s != GWQ_OK) return s;
+    // What gwq_linear would want as its workspace for this M (host arithmetic only).
+    const size_t ib = (M > 16 && !P->index) ? gwq::gemm_index_bytes(P->N, P->K) : 0;
+    const size_t sb = M > 16 ? gwq::gemm_scratch_bytes(P->N, M) : 0;
+    if (ib + sb > GWQ_STATIC_SCRATCH_BYTES) return GWQ_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M <= 16)                                        // the decode kernels use no scratch
+        return gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st) == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+    unsigned char *base = nullptr;
+    if (static_scratch(&base) != hipSuccess) return GWQ_ERR_DEVICE;
+    // Same layout as gwq_linear's workspace: the index (when the layer carries none), then the partial sums.
+    hipError_t e = P->index ? hipSuccess : gwq::launch_gemm_index(*P, base, st);
+    if (e == hipSuccess)
+        e = gwq::launch_gemm(*P, X_f16, M, Y_f16, P->index ? P->index : base, base + ib, sb, g_gemm_ms, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 

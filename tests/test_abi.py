@@ -19,7 +19,7 @@ def declared_functions():
 
 def test_header_declares_the_expected_calls():
     assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_index",
-                                    "gwq_linear_indexed", "gwq_pack", "gwq_quality", "gwq_score",
+                                    "gwq_linear_indexed", "gwq_linear_static", "gwq_pack", "gwq_quality", "gwq_score",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
 
@@ -117,6 +117,22 @@ def test_linear_index_validates_before_touching_the_device():
     assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need - 1, None, 0, None) == -4
     assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, ctypes.c_void_p(0x1004), need, None, 0, None) == -2
     assert L.gwq_linear_indexed(ctypes.byref(ok), fake, 17, fake, fake, need, ctypes.c_void_p(0x1004), 64, None) == -2
+
+
+def test_linear_static_validates_before_touching_the_device():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ok = _packed()
+    assert L.gwq_linear_static(None, fake, 17, fake, None) == -1
+    assert L.gwq_linear_static(ctypes.byref(ok), None, 17, fake, None) == -1
+    assert L.gwq_linear_static(ctypes.byref(ok), fake, 17, None, None) == -1
+    assert L.gwq_linear_static(ctypes.byref(ok), fake, 0, fake, None) == -2
+    assert L.gwq_linear_static(ctypes.byref(ok), ctypes.c_void_p(0x1002), 17, fake, None) == -2
+    assert L.gwq_linear_static(ctypes.byref(_packed(bits=5)), fake, 17, fake, None) == -3
+    # index + partial sums beyond the static array: refused, nothing launched
+    big = _packed(N=60000, K=65536)
+    assert L.gwq_linear_static(ctypes.byref(big), fake, 2048, fake, None) == -4
+    assert gwq.STATIC_SCRATCH_BYTES == 48 << 20
 
 
 def test_quality_validates_before_touching_the_device():
