@@ -209,9 +209,12 @@ gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N
  * process-wide (atomic, read once per call by every thread's calls): a hook for benchmarks and tests, not a
  * per-call option.
  * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 4:
- * it picks 4, 8 or 16 groups per wave accordingly; the kernel for larger M sizes itself by the LDS it
- * needs), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond M = 512
- * and below that the shape a cost model of the launch expects to be fastest).  Unknown keys or out-of-range values return GWQ_ERR_UNSUPPORTED. */
+ * it picks 4, 8 or 16 groups per wave accordingly; the kernels for larger M size themselves),
+ * "decode_stream" (1: never the streaming decode kernel; 2: also for M <= 4, wherever K <= 4096 lets it
+ * run; by default it takes 5 <= M <= 16 there), "decode_tiles" (16-channel tiles per block of the streaming
+ * kernel, 1..4096), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
+ * M = 512 and below that the shape a cost model of the launch expects to be fastest).  Unknown keys or
+ * out-of-range values return GWQ_ERR_UNSUPPORTED. */
 gwq_status gwq_tuning_set(const char *key, int32_t value);
 
 const char *gwq_status_string(gwq_status status);

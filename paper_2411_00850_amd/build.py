@@ -13,18 +13,24 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False) -> str:
+STAMP_LIB = os.path.join(HERE, "libgwq_stamp.so")     # measurement build: kernels record device timestamps
+
+
+def build(verbose: bool = False, stamps: bool = False) -> str:
+    """Builds libgwq.so; with `stamps` the separate measurement library libgwq_stamp.so instead, whose
+    decode kernels record the shader clock at their milestones (gwq_debug_read_stamps)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-I", INCLUDE, "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    out = STAMP_LIB if stamps else LIB
+    cmd = [hipcc, *FLAGS, *(["-DGWQ_STAMP"] if stamps else []), "-I", INCLUDE, "-I", CSRC,
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode:
         # the host pass warns that it does not know the packed-fp32 feature; that is harmless
         noise = "is not a recognized feature for this target"
         print("\n".join(l for l in (res.stdout + res.stderr).splitlines() if noise not in l))
     if res.returncode:
-        raise RuntimeError("hipcc failed building libgwq.so")
-    return LIB
+        raise RuntimeError("hipcc failed building " + os.path.basename(out))
+    return out
 
 
 def stale() -> bool:
@@ -37,4 +43,5 @@ def stale() -> bool:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, stamps="--stamps" in sys.argv))

@@ -37,6 +37,10 @@ hipError_t static_scratch(unsigned char **out)
 // Measurement hooks of gwq_tuning_set: process-wide, read once per call.
 std::atomic<int> g_decode_waves{0};   // 0 = heuristic
 std::atomic<int> g_gemm_ms{0};        // rows of Y per GEMM block; 0 = heuristic
+std::atomic<int> g_decode_stream{0};  // 0 = heuristic, 1 = never the streaming kernel, 2 = wherever it can run
+std::atomic<int> g_decode_tiles{0};   // tiles per block of the streaming kernel; 0 = heuristic
+
+gwq::DecodeTuning decode_tuning() { return gwq::DecodeTuning{g_decode_waves, g_decode_stream, g_decode_tiles}; }
 
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
@@ -196,7 +200,7 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (M <= 16) {
-        e = gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st);
+        e = gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, decode_tuning(), st);
     } else {
         // The workspace holds the index, then (whatever is left) the partial sums of a K-split launch.
         // A layer that carries its index (filled by gwq_pack) is not indexed again.
@@ -226,7 +230,7 @@ gwq_status gwq_linear_indexed(const gwq_packed *P, const void *X_f16, int32_t M,
     if (s != GWQ_OK) return s;
     if (scratch && ((uintptr_t)scratch & 15)) return GWQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st)
+    hipError_t e = M <= 16 ? gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, decode_tuning(), st)
                            : gwq::launch_gemm(*P, X_f16, M, Y_f16, index, scratch, scratch ? scratch_bytes : 0,
                                               g_gemm_ms, st);
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
@@ -242,7 +246,7 @@ gwq_status gwq_linear_static(const gwq_packed *P, const void *X_f16, int32_t M, 
     if (ib + sb > GWQ_STATIC_SCRATCH_BYTES) return GWQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (M <= 16)                                        // the decode kernels use no scratch
-        return gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, g_decode_waves, st) == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+        return gwq::launch_decode(1, &P, &X_f16, M, &Y_f16, decode_tuning(), st) == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
     unsigned char *base = nullptr;
     if (static_scratch(&base) != hipSuccess) return GWQ_ERR_DEVICE;
     // Same layout as gwq_linear's workspace: the index (when the layer carries none), then the partial sums.
@@ -281,7 +285,7 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
                 done[j] = true;
                 ++n;
             }
-        hipError_t e = gwq::launch_decode(n, p, x, M, y, g_decode_waves, static_cast<hipStream_t>(stream));
+        hipError_t e = gwq::launch_decode(n, p, x, M, y, decode_tuning(), static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return GWQ_ERR_DEVICE;
     }
     return GWQ_OK;
@@ -293,6 +297,16 @@ gwq_status gwq_tuning_set(const char *key, int32_t value)
     if (!strcmp(key, "decode_waves")) {
         if (value < 0 || value > 16) return GWQ_ERR_UNSUPPORTED;
         g_decode_waves = value;
+        return GWQ_OK;
+    }
+    if (!strcmp(key, "decode_stream")) {
+        if (value < 0 || value > 2) return GWQ_ERR_UNSUPPORTED;
+        g_decode_stream = value;
+        return GWQ_OK;
+    }
+    if (!strcmp(key, "decode_tiles")) {
+        if (value < 0 || value > 4096) return GWQ_ERR_UNSUPPORTED;
+        g_decode_tiles = value;
         return GWQ_OK;
     }
     if (!strcmp(key, "gemm_rows")) {

@@ -28,6 +28,8 @@
 //   * the instructions a wave issues: wave-uniform values are kept in scalar registers, offsets
 //     are compile-time constants, and nothing in the multiply is predicated.
 // Two kernels: the lean one for M <= 4 with all of X in LDS, the wide one for everything else.
+#include <type_traits>
+
 #include "gwq_dequant.h"
 #include "gwq_internal.h"
 
@@ -142,7 +144,7 @@ struct DecodeBatch {
 // partial sums [waves][MS][64] floats.  blockDim >= 3 gpr holds by construction (64 ceil(gpr / U)
 // threads, U <= 16), so one 16-byte vector per thread stages all scales and zero points.
 template <int BITS, int U, int MS>
-__global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
+__device__ __forceinline__ void decode_small_body(const DecodeBatch &batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const DecodeProblem &pr = batch.p[blockIdx.y];
@@ -374,6 +376,12 @@ __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch ba
         sum += __shfl_xor(sum, 32);
         if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (_Float16)sum;
     }
+}
+
+template <int BITS, int U, int MS>
+__global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
+{
+    decode_small_body<BITS, U, MS>(batch);
 }
 
 // ---- any M <= 16, X staged through LDS in chunks of K: the wide kernel ---------------------------
@@ -626,6 +634,384 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     }   // tiles
 }
 
+// ---- any M <= 16 with K <= 4096: the streaming kernel --------------------------------------------
+//
+// The wide kernel above pays for X twice: every group's MFMA operands are read from LDS (4 KB of LDS
+// reads per KB of codes), and every outlier entry gathers its X values with one 2-byte LDS read per
+// row.  It also stages X per tile and stops at several block-wide barriers per tile.  This kernel
+// keeps X where each use wants it:
+//   * wave w owns groups [4w, 4w + 4) of every tile, so the X operands of its MFMAs never change: they
+//     are loaded once per block into registers (64 per lane), in operand layout, straight from memory;
+//   * the outliers read a transposed copy XT[k][MR] in LDS (MR = 4, 8 or 16 rows, staged once per
+//     block): the lanes (r, b) of channel r take one entry each and fetch four rows of its column with
+//     one 8-byte read.  With MR = 16 the four lanes of a channel share an entry (four rows each), with
+//     fewer rows they take different entries;
+//   * a block walks `tiles_per_block` consecutive 16-channel tiles.  Codes, scales, zero points and CSR
+//     bounds of a tile are requested three tiles ahead into one of three register sets (the loop is
+//     unrolled over them), its CSR segment two tiles ahead; one block barrier per tile publishes the
+//     segment in LDS and the previous tile's partial sums, which a quarter or half of the block then
+//     adds in a fixed order while the others go on.
+// XT is written by the waves from their X operands, with the matrix cores doing the transposition: an
+// operand times a 32 x 16 selection matrix (a single 1.0 per column) returns sixteen of the operand's 32
+// columns in the MFMA result layout, where lane (n, q) holds rows 4q .. 4q+3 of column n - the 8 bytes one
+// outlier read fetches.  X is therefore read from memory once per block (every block needs all of it, and
+// at M = 16 the blocks' reads of X are four times the bytes of the codes).  Column k keeps its rows at byte
+// k * 2 MR, with one address bit flipped where bit 5 of k is set, so that the two half-groups of lanes of
+// a store instruction (columns 32 apart) fall into different banks.
+//
+// Dynamic LDS: XT [K][MR] halves | CSR entries (column | value << 16) [2][ent_cap] + 8 zero words |
+// partial sums [2][waves][4][64] floats.
+constexpr int kStreamU = 4;                             // groups per wave
+
+// Optional build (-DGWQ_STAMP, a separate library: see build.py): wave 0 of every block records the
+// shader clock at the kernel's milestones, read back with gwq_debug_read_stamps.  Not part of the product.
+#ifdef GWQ_STAMP
+constexpr int kStampSlots = 16, kStampBlocks = 2048;
+__device__ unsigned long long g_stamps[kStampBlocks * kStampSlots];
+#define GWQ_STAMP_AT(i) \
+    do { \
+        if (tid == 0) { \
+            const unsigned blk = (blockIdx.y * gridDim.x + blockIdx.x) % kStampBlocks; \
+            g_stamps[blk * kStampSlots + (i)] = (i) == 0 ? wall_clock64() : clock64(); \
+        } \
+    } while (0)
+#else
+#define GWQ_STAMP_AT(i) do { } while (0)
+#endif
+
+struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
+struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
+
+// A load that is complete when it returns, invisible to the compiler's bookkeeping of outstanding loads
+// (for the rare path below, whose loads would otherwise make every trip wait for all prefetches).
+__device__ inline uint32_t load_u16_now(const uint16_t *p)
+{
+    uint32_t v;
+    asm volatile("global_load_ushort %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+
+// Byte offset in XT of rows 4q .. 4q+3 of column `col` (MR rows of FP16 per column).
+template <int MR> __device__ inline uint32_t xt_offset(uint32_t col, int q)
+{
+    constexpr uint32_t flip = MR == 16 ? 16u : MR == 8 ? 128u : 64u;
+    return (col * (2 * MR) + 8 * q) ^ ((col & 32u) ? flip : 0u);
+}
+
+// Everything a wave needs from memory for one tile.
+template <int BITS> struct TileRegs {
+    Slot<BITS> slot[kStreamU];
+    U64a2 sc;                                           // four scales
+    uint32_t zp;                                        // four zero points
+    int rp0, rp1;                                       // CSR range of this lane's channel
+    int e_begin, e_end;                                 // CSR range of the tile (wave-uniform)
+    u32x4 seg_col, seg_val;                             // this thread's eight entries of the tile's segment
+};
+
+template <int BITS, int MR>
+__global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch batch, const int tiles_per_block,
+                                                            const int ent_cap)
+{
+    constexpr int U = kStreamU, RB = MR / 4, SPLIT = 4 / RB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const DecodeProblem &pr = batch.p[blockIdx.y];
+    const int N = pr.N, K = pr.K;
+    const uint32_t *__restrict__ qweight = pr.qweight;
+    const uint16_t *__restrict__ scales = pr.scales;
+    const uint8_t *__restrict__ zeros = pr.zeros;
+    const int32_t *__restrict__ row_ptr = pr.row_ptr;
+    const uint16_t *__restrict__ col_idx = pr.col_idx;
+    const uint16_t *__restrict__ out_val = pr.out_val;
+    const _Float16 *__restrict__ X = pr.X;
+    _Float16 *__restrict__ Y = pr.Y;
+    const int csr_last_vec = pr.csr_last_vec;
+    asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
+                 "s"(K), "s"(csr_last_vec));
+    const int tiles = (N + 15) >> 4;
+    const int tile0 = (int)blockIdx.x * tiles_per_block;
+    if (tile0 >= tiles) return;                         // the grid is as wide as the largest layer needs
+    const int nt = tiles - tile0 < tiles_per_block ? tiles - tile0 : tiles_per_block;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int M = batch.M, nwaves = batch.nwaves, nthreads = nwaves * 64;
+    const int r = lane & 15, b = lane >> 4;
+    const int tail_lane4 = 4 * (lane | 48);
+    const int gpr = K / kGroup, K8 = K >> 3;
+    const int g0 = wave * U;
+    GWQ_STAMP_AT(0);                                    // wall clock (100 MHz) at the start
+    GWQ_STAMP_AT(1);
+
+    unsigned char *const xt = lds_raw;
+    uint32_t *const ent = reinterpret_cast<uint32_t *>(lds_raw + (uint32_t)K * (2 * MR));
+    float *const red = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ent) + 8 * (uint32_t)ent_cap + 32);
+    const int zero_entry = 2 * ent_cap;                 // an entry with value 0 in column 0
+
+    const DecodeConsts dc(BITS);
+    constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
+    const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
+
+    // row_ptr again as a pointer to constant memory (nothing in this launch writes it): a load through it with a
+    // wave-uniform index is a scalar load, which does not queue behind the vector loads in flight.
+    const __attribute__((address_space(4))) int32_t *row_ptr_k =
+        (const __attribute__((address_space(4))) int32_t *)(uintptr_t)row_ptr;
+    // Requests for tile number `it` of this block (clamped: past the last one it is the last again): the
+    // CSR bounds of the tile (scalar loads), then everything the lanes need.
+    auto issue_bounds = [&](TileRegs<BITS> &T, int it) {
+        const int row0 = (tile0 + (it < nt ? it : nt - 1)) * 16;
+        const int last_row = row0 + 16 < N ? row0 + 16 : N;
+        T.e_begin = row_ptr_k[row0];                    // uniform addresses in the constant address space: scalar loads
+        T.e_end = row_ptr_k[last_row];
+    };
+    auto issue_tile = [&](TileRegs<BITS> &T, int it) {
+        const int n = (tile0 + (it < nt ? it : nt - 1)) * 16 + r;
+        const int n_c = n < N ? n : N - 1;
+        const uint32_t first_group = (uint32_t)n_c * gpr + g0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) T.slot[u].load_clamped(qweight, (first_group + u) * group_bytes, b, code_end);
+        T.sc = *reinterpret_cast<const U64a2 *>(scales + first_group);       // the arrays carry 16 spare bytes
+        T.zp = reinterpret_cast<const U32a1 *>(zeros + first_group)->v;
+        T.rp0 = row_ptr[n_c];
+        T.rp1 = row_ptr[n_c + 1];
+    };
+    // The tile's CSR segment [e_begin, e_end) from the 16-byte boundary below e_begin: thread t brings
+    // entries e0 + 8t .. e0 + 8t + 7 (idle threads repeat the last vector: no extra traffic).
+    auto issue_seg = [&](TileRegs<BITS> &T) {
+        const int e0 = T.e_begin & ~7;
+        const int v_end = T.e_end > e0 ? (T.e_end - 1) / 8 : e0 / 8;
+        int v = e0 / 8 + tid;
+        v = v < v_end ? v : v_end;
+        v = v < csr_last_vec ? v : csr_last_vec;
+        T.seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
+        T.seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
+    };
+
+    // Order of the first requests: tile 0, X, tiles 1 and 2 - none of which waits for anything - and, once
+    // the CSR bounds of the first two tiles have come in through the scalar cache (requested first of all),
+    // their segments.  X is consumed before the first tile, with everything behind it still in flight.
+    TileRegs<BITS> A, B, C;
+    issue_bounds(A, 0);
+    issue_bounds(B, 1);
+    issue_bounds(C, 2);
+    issue_tile(A, 0);
+
+    // X operands of this wave's MFMAs: lane (r, b) holds row r, columns 32 b + 8 j .. + 7 of each group.
+    u32x4 xa[U][4];
+    const bool x_row_live = r < M;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int g = g0 + u < gpr ? g0 + u : gpr - 1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xa[u][j] = reinterpret_cast<const u32x4 *>(X)[(x_row_live ? r : 0) * K8 + g * (kGroup / 8) + 4 * b + j];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    issue_tile(B, 1);
+    issue_tile(C, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_seg(A);
+    issue_seg(B);
+    __builtin_amdgcn_sched_barrier(0);
+    GWQ_STAMP_AT(2);                                    // everything requested
+
+    if (tid < 8) ent[zero_entry + tid] = 0u;
+    // Rows at or beyond M and groups at or beyond gpr multiply zeros.  Every register is masked, with no
+    // branch, so that X has arrived on every path into the loop.
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t keep = (x_row_live && g0 + u < gpr) ? ~0u : 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xa[u][j] &= u32x4{keep, keep, keep, keep};
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    GWQ_STAMP_AT(3);                                    // X has arrived
+
+    // XT from the operands.  Operand (u, j) holds, as its MFMA column 8 b' + t, the X column
+    // 128 (g0 + u) + 32 b' + 8 j + t; selection matrix s picks MFMA columns 16 s .. 16 s + 15, so lane
+    // (n = r, q = b) receives rows 4q .. 4q+3 of X column 128 (g0 + u) + 64 s + 32 (n / 8) + 8 j + n % 8.
+    {
+        u32x4 sel[2];
+#pragma unroll
+        for (int sq = 0; sq < 2; ++sq) {
+            const int at = b == 2 * sq + (r >> 3) ? (r & 7) : -1;    // position of this lane's 1.0, if it has one
+            sel[sq] = u32x4{at == 0 ? 0x3C00u : at == 1 ? 0x3C000000u : 0u, at == 2 ? 0x3C00u : at == 3 ? 0x3C000000u : 0u,
+                            at == 4 ? 0x3C00u : at == 5 ? 0x3C000000u : 0u, at == 6 ? 0x3C00u : at == 7 ? 0x3C000000u : 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (g0 + u < gpr) {                         // uniform over the wave
+                // eight independent MFMAs back to back, then their results: nothing waits for the one before it
+                float4v t[4][2];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int sq = 0; sq < 2; ++sq)
+                        t[j][sq] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                            __builtin_bit_cast(half8, xa[u][j]), __builtin_bit_cast(half8, sel[sq]),
+                            float4v{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int sq = 0; sq < 2; ++sq) {
+                        const uint32_t col = (uint32_t)(g0 + u) * kGroup + 64 * sq + 32 * (r >> 3) + 8 * j + (r & 7);
+                        const half2v lo = half2v{(_Float16)t[j][sq][0], (_Float16)t[j][sq][1]};
+                        const half2v hi = half2v{(_Float16)t[j][sq][2], (_Float16)t[j][sq][3]};
+                        if (b < RB)
+                            *reinterpret_cast<uint2 *>(xt + xt_offset<MR>(col, b)) =
+                                uint2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
+
+    GWQ_STAMP_AT(4);                                    // XT written
+    const int xq = b % RB;                              // which four rows of XT this lane adds
+    const int sub = wave * SPLIT + b / RB;              // this lane's share of its channel's entries
+    const int stride = nwaves * SPLIT;
+    const int red_groups = nthreads >= 512 ? 2 : 1;     // sets of 256 threads that take turns adding partial sums
+
+    // Adds the partial sums of tile number `it` (written before the last barrier) and stores its outputs.
+    auto reduce_tile = [&](int it) {
+        const float *src = red + (it & 1) * (nwaves * 256);
+        const int row0 = (tile0 + it) * 16;
+        auto one = [&](int idx) {
+            const int e = idx >> 6, l = idx & 63, bq = l >> 4;
+            if (bq >= RB) return;
+            float sum = 0.f;
+            for (int w = 0; w < nwaves; ++w)
+#pragma unroll
+                for (int sp = 0; sp < SPLIT; ++sp) sum += src[(w * 4 + e) * 64 + (l & 15) + 16 * (bq + RB * sp)];
+            const int nn = row0 + (l & 15), m = 4 * bq + e;
+            if (nn < N && m < M) Y[(size_t)m * N + nn] = (_Float16)sum;
+        };
+        if (nthreads >= 256) {
+            const int grp = it % red_groups;
+            if ((tid >> 8) == grp) one(tid & 255);
+        } else {
+            for (int idx = tid; idx < 256; idx += nthreads) one(idx);
+        }
+    };
+
+    // One tile: T holds it, T2 is the set of the tile two further on (its CSR segment is requested here).
+    // Requests are unconditional (past the block's last tile they repeat it): a trip always leaves the same
+    // queue of requests behind, which is what lets the waits inside the loop be exact.
+    auto step = [&](TileRegs<BITS> &T, TileRegs<BITS> &T2, int it) {
+        const int buf = it & 1;
+        const int e0 = T.e_begin & ~7;
+        const int staged_end = e0 + ent_cap < T.e_end ? e0 + ent_cap : T.e_end;
+        // Real copies into other registers: the set is refilled below while these are still needed, and a
+        // refilled value must land in the register the next trip reads it from (otherwise the compiler moves
+        // it there at the end of the trip, and a move of a value still on its way waits for it).
+        int rp0, rp1;
+        uint32_t sc2[2], zp;
+        asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3" : "=&v"(rp0), "=&v"(rp1) : "v"(T.rp0), "v"(T.rp1));
+        asm volatile("v_mov_b32 %0, %3\n\tv_mov_b32 %1, %4\n\tv_mov_b32 %2, %5"
+                     : "=&v"(sc2[0]), "=&v"(sc2[1]), "=&v"(zp) : "v"(T.sc.lo), "v"(T.sc.hi), "v"(T.zp));
+        if (it == 0) GWQ_STAMP_AT(5);                   // tile 0 has arrived
+
+        float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t keep = g0 + u < gpr ? ~0u : 0u;      // uniform over the wave
+            const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)((sc2[u >> 1] >> (16 * (u & 1))) & keep));
+            const uint32_t z = (zp >> (8 * u)) & 0xFFu & (BITS == 3 ? keep : ~0u);
+            u32x4 wb[4];
+            T.slot[u].decode(z, b, dc, wb, tail_lane4);
+            float4v part = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[u][j]),
+                                                              __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (it == 0) GWQ_STAMP_AT(6);                   // multiplied
+        u32x4 seg_col = T.seg_col, seg_val = T.seg_val;
+        issue_seg(T2);
+        issue_bounds(T, it + 3);
+        issue_tile(T, it + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        if (8 * tid < ent_cap) store_entries(reinterpret_cast<u32x4 *>(ent + buf * ent_cap) + 2 * tid, seg_col, seg_val);
+        if (it == 0) GWQ_STAMP_AT(7);                   // its CSR segment has arrived
+        __syncthreads();                                // this tile's entries and the previous tile's sums are in LDS
+        if (it == 0) GWQ_STAMP_AT(8);                   // through the barrier
+        if (it > 0) reduce_tile(it - 1);
+
+        // Outliers: entry j of the channel sits at LDS index j - e0 while j < staged_end.
+        const int n = (tile0 + it) * 16 + r;
+        const int j_end = n < N ? rp1 : rp0;
+        const int j_staged = j_end < staged_end ? j_end : staged_end;
+        for (int j = rp0 + sub; j < j_staged; j += 4 * stride) {
+            uint32_t entry[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = j + i * stride;
+                entry[i] = ent[idx < j_staged ? buf * ent_cap + idx - e0 : zero_entry];
+            }
+            uint2 xv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t col = entry[i] & 0xFFFFu;
+                xv[i] = *reinterpret_cast<const uint2 *>(xt + xt_offset<MR>(col, xq));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v = (float)__builtin_bit_cast(_Float16, (uint16_t)(entry[i] >> 16));
+                const half2v x01 = __builtin_bit_cast(half2v, xv[i].x), x23 = __builtin_bit_cast(half2v, xv[i].y);
+                acc[0] = __builtin_fmaf(v, (float)x01[0], acc[0]);
+                acc[1] = __builtin_fmaf(v, (float)x01[1], acc[1]);
+                acc[2] = __builtin_fmaf(v, (float)x23[0], acc[2]);
+                acc[3] = __builtin_fmaf(v, (float)x23[1], acc[3]);
+            }
+        }
+        if (j_end > staged_end) {                       // rows longer than the staged window: straight from memory
+            int j = rp0 + sub;
+            if (j < staged_end) j += (staged_end - j + stride - 1) / stride * stride;
+            for (; j < j_end; j += stride) {
+                const uint32_t col = load_u16_now(col_idx + j);
+                const float v = (float)__builtin_bit_cast(_Float16, (uint16_t)load_u16_now(out_val + j));
+                const uint2 x = *reinterpret_cast<const uint2 *>(xt + xt_offset<MR>(col, xq));
+                const half2v x01 = __builtin_bit_cast(half2v, x.x), x23 = __builtin_bit_cast(half2v, x.y);
+                acc[0] = __builtin_fmaf(v, (float)x01[0], acc[0]);
+                acc[1] = __builtin_fmaf(v, (float)x01[1], acc[1]);
+                acc[2] = __builtin_fmaf(v, (float)x23[0], acc[2]);
+                acc[3] = __builtin_fmaf(v, (float)x23[1], acc[3]);
+            }
+        }
+        float *dst = red + buf * (nwaves * 256) + wave * 256 + lane;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[e * 64] = acc[e];
+        if (it == 0) GWQ_STAMP_AT(9);                   // outliers added
+    };
+
+    // The first three trips stand outside the loop: after them the requests in flight are those a trip of
+    // the loop leaves behind, in the same order, so the loop's waits hold from its first trip on.
+    step(A, C, 0);
+    if (nt > 1) {
+        step(B, A, 1);
+        if (nt > 2) {
+            step(C, B, 2);
+            int it = 3;
+            for (; it + 3 <= nt; it += 3) {
+                step(A, C, it);
+                step(B, A, it + 1);
+                step(C, B, it + 2);
+            }
+            if (it < nt) {
+                step(A, C, it);
+                if (it + 1 < nt) step(B, A, it + 1);
+            }
+        }
+    }
+    GWQ_STAMP_AT(10);                                   // all tiles done
+    __syncthreads();
+    GWQ_STAMP_AT(11);
+    reduce_tile(nt - 1);
+    GWQ_STAMP_AT(12);                                   // stored
+}
+
 constexpr size_t kMaxLds = 160 * 1024;                  // LDS a block may use on gfx950
 constexpr size_t kXLdsBudget = 128 * 1024;              // X[M][k_pad] is staged in LDS up to this size
 
@@ -657,8 +1043,9 @@ hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwa
 // Decode launch over `count` layers (same bits, same M): grid row i works on layer i; the grid is as
 // wide as the layer with most channels needs and the surplus blocks of smaller layers exit at once.
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
-                         int waves_override, hipStream_t st)
+                         const DecodeTuning &tune, hipStream_t st)
 {
+    const int waves_override = tune.waves;
     DecodeBatch batch;
     batch.M = M;
     int blocks = 0, max_gpr = 1;
@@ -684,7 +1071,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     const size_t meta = (size_t)48 * max_gpr + 16;
 
     // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
-    if (M <= 4) {
+    if (M <= 4 && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
         int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
         if (waves_override > 0) {                       // the most waves that do not exceed the request
             u = 4;
@@ -698,6 +1085,50 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
             batch.nwaves = nwaves;
             return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, st)
                              : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, st);
+        }
+    }
+
+    // The streaming kernel: rows of at most 32 groups (8 waves of 4), XT[K][rows] in LDS.  By default for
+    // the batches the lean kernel does not take.
+    if (tune.stream != 1 && (M > 4 || tune.stream == 2) && max_gpr <= 8 * kStreamU) {
+        const int nwaves = (max_gpr + kStreamU - 1) / kStreamU, nthreads = 64 * nwaves;
+        const int mr = M <= 4 ? 4 : M <= 8 ? 8 : 16;
+        const size_t xt = (size_t)max_gpr * kGroup * 2 * mr, red = (size_t)2 * nwaves * 1024;
+        const size_t avail = kMaxLds - xt - red - 32;
+        int ent_cap = (int)(avail / 8) & ~7;
+        if (ent_cap > 8 * nthreads) ent_cap = 8 * nthreads;
+        if (ent_cap >= 64) {
+            const size_t lds = xt + (size_t)8 * ent_cap + 32 + red;
+            // Blocks a CU holds at once: the kernel's registers allow eight waves.
+            int bpc = (int)(kMaxLds / lds);
+            if (bpc > 8 / nwaves) bpc = 8 / nwaves;
+            if (bpc < 1) bpc = 1;
+            const int slots = device_cus() * bpc;
+            // The fewest tiles per block with which all layers' blocks are resident at once.
+            int tpb = tune.tiles;
+            if (tpb <= 0)
+                for (tpb = 1;; ++tpb) {
+                    int total = 0;
+                    for (int i = 0; i < count; ++i) total += ((P[i]->N + 15) / 16 + tpb - 1) / tpb;
+                    if (total <= slots) break;
+                }
+            // A block that gets a single tile has nothing to pipeline and pays the set-up of XT for it: the wide
+            // kernel is faster there (4096 channels on 256 CUs).
+            const bool take = tune.stream == 2 || tune.tiles > 0 || tpb >= 2;
+            batch.nwaves = nwaves;
+            const int grid = (blocks + tpb - 1) / tpb;
+            hipError_t e = hipErrorInvalidValue;
+#define GWQ_STREAM(B, RR) \
+    if (take && bits == B && mr == RR) { \
+        static std::atomic<uint32_t> lds_allowed{0}; \
+        e = allow_dynamic_lds(reinterpret_cast<const void *>(&decode_stream_kernel<B, RR>), (int)kMaxLds, lds_allowed); \
+        if (e != hipSuccess) return e; \
+        decode_stream_kernel<B, RR><<<dim3(grid, count), nthreads, lds, st>>>(batch, tpb, ent_cap); \
+        return hipGetLastError(); \
+    }
+            GWQ_STREAM(4, 4) GWQ_STREAM(4, 8) GWQ_STREAM(4, 16) GWQ_STREAM(3, 4) GWQ_STREAM(3, 8) GWQ_STREAM(3, 16)
+#undef GWQ_STREAM
+            if (take) return e;
         }
     }
 
@@ -737,3 +1168,13 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 }
 
 }  // namespace gwq
+
+#ifdef GWQ_STAMP
+// Copies the first `count` recorded stamps to the host (waits for the device first).
+extern "C" int gwq_debug_read_stamps(unsigned long long *host, int count)
+{
+    if (count > gwq::kStampBlocks * gwq::kStampSlots) count = gwq::kStampBlocks * gwq::kStampSlots;
+    if (hipDeviceSynchronize() != hipSuccess) return -1;
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(gwq::g_stamps), sizeof(unsigned long long) * count) == hipSuccess ? count : -1;
+}
+#endif

@@ -38,8 +38,13 @@ inline size_t pack_workspace_bytes(int64_t N) { return (size_t)(kWsRows + 3 * N)
 // Launchers (defined in the .hip files).  Each enqueues on `stream` and returns the last HIP error.
 hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
                        uint32_t *ws, hipStream_t stream);
+// Measurement overrides of the decode launch (0 = built-in choice): waves per block of the kernel for M <= 4;
+// streaming kernel 1 = never, 2 = for every M <= 16 it can take; its tiles per block.
+struct DecodeTuning {
+    int waves, stream, tiles;
+};
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
-                         int waves_override, hipStream_t stream);
+                         const DecodeTuning &tune, hipStream_t stream);
 // index: gemm_index_bytes(N, K) bytes, 16-byte aligned (one record per channel and group: index of the
 // group's first outlier, scale, zero point; a multiple of 256 bytes).  scratch: gemm_scratch_bytes(N, M_max)
 // bytes for the partial sums of launches that also split K (may be NULL: then K is never split).

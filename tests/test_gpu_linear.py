@@ -72,6 +72,29 @@ def test_decode_launch_shapes(bits, waves, M):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,ppm", [(16, 128, 10000), (150, 1536, 10000), (333, 4096, 10000), (100, 640, 300000),
+                                     (40, 512, 1000000), (97, 2048, 0)])
+@pytest.mark.parametrize("tiles", [0, 1, 2, 3, 4, 7])
+def test_decode_streaming_kernel(bits, N, K, ppm, tiles):
+    """The streaming decode kernel (X operands in registers, transposed X in LDS, tiles requested three ahead)
+    for every M it takes, forced on for M <= 4 as well, with every number of tiles per block from one
+    (nothing to pipeline) through the three register sets and beyond, ragged N, short rows (one wave),
+    and rows with more outliers than the staged window holds (ppm = 30 % and 100 %)."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close
+    P, rng = _problem(N + K + bits + ppm % 7, N, K, bits, ppm=ppm)
+    gwq.tuning_set("decode_stream", 2)
+    gwq.tuning_set("decode_tiles", tiles)
+    try:
+        for M in (1, 2, 3, 4, 5, 7, 8, 9, 12, 16):
+            X = gs.activations(M, K, rng)
+            assert_close(_run(P, X), orc.linear_f64(P, X), f"stream N={N} K={K} M={M} bits={bits} ppm={ppm} tiles={tiles}")
+    finally:
+        gwq.tuning_set("decode_stream", 0)
+        gwq.tuning_set("decode_tiles", 0)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("ppm", [0, 1000000, 200000])
 def test_decode_outlier_extremes(bits, ppm):
     """No outliers, only outliers (a dense FP16 layer in CSR form), and a heavy 20 %."""
