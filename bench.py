@@ -8,12 +8,19 @@ grouped launch (gwq_linear_batch), o alone, gate and up in one, down alone - 4 l
 layer exists in several copies and the steps rotate over them, so every step streams its weights
 from HBM rather than from the 256 MB last-level cache, as a decode pass over a whole model does.
 
-One JSON line is printed.  `value` is the algorithmic GB/s of the timed steps (packed bytes + X + Y
+One JSON line is printed.  `value` is the algorithmic GB/s of the K timed steps (packed bytes + X + Y
 per step over wall time, inputs resident in HBM).  `roofline` is the decode kernel alone: algorithmic
-bytes per launch over the average launch duration measured with HIP events on the launch stream.
-Further objects report the same pass at M = 4 and 16, the prefill GEMM (M = 2048) in TFLOP/s (through
-gwq_linear, and through gwq_linear_indexed with the per-layer index built beforehand), gwq_pack,
-and the CPU oracle timed on a bounded sample (`cpu_baseline`).
+bytes per launch over the launch duration, from HIP events on the launch stream around each of at least
+200 further steps (median over the replays, whatever --steps says: 20 steps are 0.7 ms, too short to
+settle).  `roofline.kernel` is what the library's dispatcher reports for the launches that ran
+(gwq_linear_plan), `roofline.achievable` a plain streaming read of the same bytes launched the same way
+(gwq_probe_stream: the ceiling a kernel with no arithmetic reaches on this machine), and
+`roofline.traffic` the counter-measured HBM bytes, taken from profiles/ only when that summary was made
+from the decode sources as they are now.  Further objects report the same pass at M = 4 and 16, the
+prefill GEMM (M = 2048) in TFLOP/s against the MFMA peak and against MFMAs issued from registers
+(gwq_probe_mfma), the 3-bit layer, the 70B shapes, gwq_pack / gwq_quality / gwq_score, one row per
+(configuration, shape, bits, M) with the oracle timed beside the kernel (`extras.rows`), a 512-step
+decoder-layer loop against FP16 weights, and the CPU oracle on a bounded sample (`cpu_baseline`).
 """
 import argparse
 import json
@@ -61,16 +68,188 @@ def settle(fn, seconds=0.1):
         torch.cuda.synchronize()
 
 
+def source_hash():
+    """SHA-1 (12 hex digits) of the decode kernels' sources: ties a counter summary to the code it measured."""
+    import hashlib
+    h = hashlib.sha1()
+    for name in ("gwq_decode.hip", "gwq_dequant.h", "gwq_internal.h"):
+        h.update(open(os.path.join(ROOT, "paper_2411_00850_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:12]
+
+
 def read_traffic():
-    """HBM bytes per decode launch from the committed rocprofv3 counter summary, if present."""
+    """HBM bytes per decode launch from the committed rocprofv3 counter summary - only when the summary was
+    made from the decode sources as they are now (its `source_sha1` line), else None."""
     path = os.path.join(ROOT, "profiles", "decode_gemv_7b_int4_m1_pmc.txt")
+    traffic, made_from = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                traffic = float(line.split(":")[1])
+            if line.startswith("source_sha1:"):
+                made_from = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None
+    return traffic if made_from == source_hash() else None
+
+
+def median_replay_ms(graph, min_replays):
+    """Median duration of one replay of `graph`, from a pair of HIP events on the launch stream around each."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min_replays)]
+    torch.cuda.synchronize()
+    for a, b in evs:
+        a.record()
+        graph.replay()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.median([a.elapsed_time(b) for a, b in evs]))
+
+
+def result_rows(gwq, gs, dev, torch):
+    """extras.rows: for configurations 1-4 (the 4096 x 4096 layer and the 7B shapes) the full matrices - the
+    oracle selects, encodes and multiplies on the host, the library packs and multiplies on the GPU, and the
+    two are compared (packing byte for byte, outputs by the two error measures of the tolerance); for
+    configuration 5 (70B shapes) the kernel runs the full matrices and the oracle a slab of 1024 channels,
+    its times scaled by N / 1024 and marked as such.  Oracle times: `all` = the cores of this process
+    (OpenMP over channels in the product; selection and encoding are serial code), `one` = one thread."""
+    import ctypes
+    from oracle import gwq_oracle as orc
+    gomp = ctypes.CDLL("libgomp.so.1")
+    cores = len(os.sched_getaffinity(0))
+
+    def timed(fn, threads):
+        gomp.omp_set_num_threads(threads)
+        t = time.perf_counter()
+        r = fn()
+        dt = time.perf_counter() - t
+        gomp.omp_set_num_threads(cores)
+        return r, dt
+
+    def gpu_us(Ps, M, K, N, index=None):
+        x = torch.from_numpy(gs.activations(M, K, gs.rng_for(9, M, K))).to(dev)
+        y = torch.empty((M, N), dtype=torch.float16, device=dev)
+        calls = [gwq.prepare_linear(P, x, y, index=index[i] if index else None) for i, P in enumerate(Ps)]
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for c in calls:
+                c()
+        settle(graph.replay, 0.05)
+        us = median_replay_ms(graph, max(10, 120 // len(Ps))) * 1e3 / len(Ps)
+        return us, x, y
+
+    def errors(Yg, Yr):
+        Yg = Yg.astype(np.float64)
+        return (float(np.linalg.norm(Yg - Yr) / max(np.linalg.norm(Yr), 1e-300)),
+                float(np.abs(Yg - Yr).max() / max(np.abs(Yr).max(), 1e-300)))
+
+    rows = []
+    plan = [(1, "single 4096x4096", 4096, 4096, lambda: gs.config1()[:2], [(4, (1,))]),
+            (2, "q/k/v/o 4096x4096", 4096, 4096, lambda: gs.layer_matrix(2, 0, 4096, 4096), [(4, (1, 4, 16, 2048)), (3, (1, 8))]),
+            (2, "gate/up 11008x4096", 11008, 4096, lambda: gs.layer_matrix(2, 4, 11008, 4096), [(4, (1, 4, 16, 2048)), (3, (1, 8))]),
+            (2, "down 4096x11008", 4096, 11008, lambda: gs.layer_matrix(2, 6, 4096, 11008), [(4, (1, 4, 16, 2048)), (3, (1, 8))])]
+    for cfg, shape, N, K, make, variants in plan:
+        W, S = make()
+        mask, t_sel = timed(lambda: orc.select(S, 10000), 1)
+        Wd, Sd = torch.from_numpy(W).to(dev), torch.from_numpy(S).to(dev)
+        for bits, Ms in variants:
+            P, t_enc = timed(lambda: orc.encode(W, mask, bits, 10000), 1)
+            D = gwq.pack(Wd, Sd, bits, 10000)
+            settle(lambda: gwq.pack(Wd, Sd, bits, 10000), 0.05)
+            t = time.perf_counter()
+            for _ in range(3):
+                D = gwq.pack(Wd, Sd, bits, 10000)
+            torch.cuda.synchronize()
+            pack_ms = (time.perf_counter() - t) / 3 * 1e3
+            g = N * (K // 128)
+            exact = all(np.array_equal(a.reshape(b.shape), b) for a, b in (
+                (D.qweight.cpu().numpy().view(np.uint32), P.qweight), (D.scales.cpu().numpy().view(np.uint16)[:g], P.scales),
+                (D.zeros.cpu().numpy()[:g], P.zeros), (D.row_ptr.cpu().numpy(), P.row_ptr),
+                (D.col_idx.cpu().numpy().view(np.uint16)[:D.n_outliers], P.col_idx),
+                (D.out_val.cpu().numpy().view(np.uint16)[:D.n_outliers], P.out_val)))
+            pack_bytes = 6 * N * K + D.nbytes()
+            rows.append({"config": cfg, "shape": shape, "bits": bits, "op": "gwq_pack", "bytes": pack_bytes,
+                         "gpu_ms": round(pack_ms, 3), "GB/s": round(pack_bytes / pack_ms / 1e6, 1),
+                         "frac_hbm_peak": round(pack_bytes / pack_ms / 1e6 / HBM_PEAK_GBS, 4),
+                         "oracle_s": {"select": round(t_sel, 2), "encode": round(t_enc, 2), "threads": 1},
+                         "pack_bit_exact": bool(exact)})
+            clones = [D] + [clone_layer(D) for _ in range(5)]
+            for M in Ms:
+                cfg_m = 4 if M == 2048 else (3 if bits == 3 and cfg == 2 else cfg)
+                if M <= 16:
+                    us, x, y = gpu_us(clones, M, K, N)
+                else:
+                    us, x, y = gpu_us(clones[:2], M, K, N)
+                Yg = y.cpu().numpy()
+                X = x.cpu().numpy()
+                b, fl = algorithmic_bytes(D, M), flops(D, M)
+                row = {"config": cfg_m, "shape": shape, "bits": bits, "op": "gwq_linear", "M": M, "bytes": b, "flops": fl,
+                       "gpu_us": round(us, 2), "GB/s": round(b / us / 1e3, 1), "TFLOP/s": round(fl / us / 1e6, 2),
+                       "kernel": gwq.linear_plan(D, M).split(" ")[0]}
+                if M <= 64:
+                    row["bound"], row["frac"] = "hbm", round(b / us / 1e3 / HBM_PEAK_GBS, 4)
+                else:
+                    row["bound"], row["frac"] = "mfma", round(fl / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)
+                if M <= 16:
+                    Yr, t_all = timed(lambda: orc.linear_f64(P, X), cores)
+                    _, t_one = timed(lambda: orc.linear_f64(P, X), 1)
+                    row["oracle_s"] = {"all": round(t_all, 4), "one": round(t_one, 4), "cores": cores}
+                    row["rel_fro"], row["max_abs"] = errors(Yg, Yr)
+                else:                                   # a stated subset of channels, scaled to the matrix
+                    sub = np.arange(0, N, N // 256, dtype=np.int32)[:256]
+                    Yr, t_all = timed(lambda: orc.linear_f64(P, X, sub), cores)
+                    _, t_one = timed(lambda: orc.linear_f64(P, X, sub[:16]), 1)
+                    row["oracle_s"] = {"all": round(t_all * N / sub.size, 2), "one": round(t_one * N / 16, 1), "cores": cores,
+                                       "sample": f"{sub.size} channels (every {N // 256}th) on all cores, 16 on one; scaled to N"}
+                    row["rel_fro"], row["max_abs"] = errors(Yg[:, sub], Yr)
+                row["within_tolerance"] = bool(row["rel_fro"] <= 2e-3 and row["max_abs"] <= 1e-2)
+                rows.append(row)
+                del x, y
+            del clones, D
+            torch.cuda.empty_cache()
+        del Wd, Sd
+    # configuration 5: full-size kernels on device-drawn weights, oracle on a slab of 1024 channels
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(75)
+    for name, N, K in gs.SHAPES_70B:
+        rng = gs.rng_for(5, N % 97, K % 89)
+        Ws = gs.weight(1024, K, rng)
+        Ss = gs.score_from_weight(Ws, rng)
+        Wd = (torch.randn((N, K), device=dev, generator=gen) * 0.02).half()
+        Sd = torch.rand((N, K), device=dev, generator=gen)
+        for bits in (4, 3):
+            Pslab, t_pack = timed(lambda: orc.pack(Ws, Ss, bits, 10000), 1)
+            D = gwq.pack(Wd, Sd, bits, 10000)
+            clones = [D, clone_layer(D), clone_layer(D)]
+            for M in (1, 64, 2048):
+                us, x, y = gpu_us(clones if M == 1 else clones[:2], M, K, N)
+                b, fl = algorithmic_bytes(D, M), flops(D, M)
+                row = {"config": 5, "shape": f"{name} {N}x{K}", "bits": bits, "op": "gwq_linear", "M": M, "bytes": b, "flops": fl,
+                       "gpu_us": round(us, 2), "GB/s": round(b / us / 1e3, 1), "TFLOP/s": round(fl / us / 1e6, 2),
+                       "kernel": gwq.linear_plan(D, M).split(" ")[0]}
+                if M <= 64:
+                    row["bound"], row["frac"] = "hbm", round(b / us / 1e3 / HBM_PEAK_GBS, 4)
+                else:
+                    row["bound"], row["frac"] = "mfma", round(fl / us / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)
+                X = x.cpu().numpy()
+                rows_all = None if M <= 64 else np.arange(0, 1024, 16, dtype=np.int32)
+                n_all = 1024 if M <= 64 else 64
+                _, t_all = timed(lambda: orc.linear_f64(Pslab, X, rows_all), cores)
+                one_rows = np.arange(0, 1024, 1024 // (64 if M == 1 else 8 if M == 64 else 2), dtype=np.int32)
+                _, t_one = timed(lambda: orc.linear_f64(Pslab, X, one_rows), 1)
+                row["oracle_s"] = {"all": round(t_all * N / n_all, 3), "one": round(t_one * N / one_rows.size, 2), "cores": cores,
+                                   "pack_one_thread": round(t_pack * N / 1024, 1),
+                                   "sample": f"a slab of 1024 channels of the same K ({n_all} of them on all cores, "
+                                             f"{one_rows.size} on one), scaled to N; parity of these shapes: tests/test_gpu_linear.py"}
+                rows.append(row)
+                del x, y
+            del clones, D
+            torch.cuda.empty_cache()
+        del Wd, Sd
+    return rows
 
 
 def main():
@@ -91,7 +270,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
     ap.add_argument("--extras", default="all", metavar="LIST",
-                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,pack (default: all)")
+                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,pack,rows,loop (default: all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are out of scope.")
@@ -151,7 +330,7 @@ def main():
             for call in calls[i % n_copies]:
                 call()
         torch.cuda.synchronize()
-        kernel_ms = None
+        kernel_ms, median_step_ms = None, None
         if mode == "graph":
             ref = [y.clone() for y in ys]               # eager result of the last warm-up step
             graph = torch.cuda.CUDAGraph()
@@ -179,6 +358,8 @@ def main():
             torch.cuda.synchronize()
             wall = time.perf_counter() - t
             kernel_ms = e0.elapsed_time(e1) / (steps * n_launch)
+            # at least 200 more steps, one pair of events per replay (n_copies steps), median
+            median_step_ms = median_replay_ms(graph, max(20, -(-200 // n_copies))) / n_copies
         else:
             ev = mode == "events"
             evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_launch + 1)] for _ in range(steps)] if ev else None
@@ -197,7 +378,34 @@ def main():
                 kernel_ms = sum(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(steps) for j in range(n_launch))
                 kernel_ms /= steps * n_launch
         bytes_step = sum(algorithmic_bytes(P, M) for P in layers)
+        decode_leg.median_step_ms = median_step_ms      # of the leg that ran last
+        decode_leg.plans = [gwq.linear_plan([layers[j] for j in g if layers[j].K == k], M)
+                            for g in groups for k in dict.fromkeys(layers[j].K for j in g)]
         return wall / steps, kernel_ms, bytes_step, n_launch
+
+    def stream_read_leg(M, grouping, layer_set):
+        """The ceiling: one plain streaming read (gwq_probe_stream) per launch of the decode pass, over exactly
+        the launch's algorithmic bytes, the same number of rotating copies, replayed from one graph."""
+        groups = GROUPS[grouping]
+        per_launch = [sum(algorithmic_bytes(layer_set[j], M) for j in g if layer_set[j].K == k) // 16 * 16
+                      for g in groups for k in dict.fromkeys(layer_set[j].K for j in g)]
+        bufs = [[torch.empty(b, dtype=torch.uint8, device=dev).random_(0, 255) for b in per_launch] for _ in range(args.copies)]
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        for c in bufs:
+            for t in c:
+                gwq.probe_stream(t, sink)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for c in bufs:
+                for t in c:
+                    gwq.probe_stream(t, sink)
+        settle(graph.replay)
+        ms = median_replay_ms(graph, max(20, -(-200 // args.copies))) / args.copies
+        del graph, bufs
+        torch.cuda.empty_cache()
+        return {"us_per_step": round(ms * 1e3, 2), "GB/s": round(sum(per_launch) / ms / 1e6, 1),
+                "launches_per_step": len(per_launch), "what": "plain streaming read of the same bytes, same launches and rotation"}
 
     # ---- the timed steps: decode M = 1 ---------------------------------------------------------------
     step_s, launch_ms, bytes_step, n_launch = decode_leg(1, args.steps, args.warmup, args.launch, args.group)
@@ -206,7 +414,14 @@ def main():
         # Eager launches are CPU-bound: time the kernels with one HIP event between consecutive launches.
         _, launch_ms, _, _ = decode_leg(1, args.steps, args.warmup, "events", args.group)
     bytes_launch = bytes_step / n_launch
+    achieved_timed = bytes_launch / (launch_ms * 1e-3) / 1e9
+    med_ms = decode_leg.median_step_ms
+    if med_ms is not None:
+        launch_ms = med_ms / n_launch                   # the figure the roofline uses: median over >= 200 steps
     achieved = bytes_launch / (launch_ms * 1e-3) / 1e9
+    plans = decode_leg.plans
+    kernels = sorted({p.split(" ")[0] for p in plans})
+    ceiling = stream_read_leg(1, args.group, layers) if args.launch == "graph" else None
     out = {
         "metric": "gwq_linear decode GB/s (% HBM peak) & prefill TFLOP/s (% MFMA peak), 7B shapes",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -218,11 +433,18 @@ def main():
                                                                "all": "one call over the 7 matrices (one launch per distinct K)"}[args.group],
                    "copies_rotated": args.copies, "bytes_per_step": bytes_step, "launch": args.launch},
         "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
-        "roofline": {"bound": "hbm", "kernel": "decode_small_kernel<4,8,1> (4-bit, M=1, 8 groups per wave)", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": kernels[0] if len(kernels) == 1 else kernels, "launches": plans,
+                     "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": read_traffic(), "bytes_per_launch": round(bytes_launch),
-                     "avg_launch_us": round(launch_ms * 1e3, 3)},
+                     "avg_launch_us": round(launch_ms * 1e3, 3),
+                     "timing": "median over >= 200 steps, HIP events around each graph replay" if med_ms is not None
+                               else "mean over the timed steps",
+                     "achieved_in_timed_steps": round(achieved_timed, 1)},
     }
+    if ceiling:
+        out["roofline"]["achievable"] = ceiling
+        out["roofline"]["frac_of_achievable"] = round(bytes_step / (launch_ms * n_launch * 1e-3) / 1e9 / ceiling["GB/s"], 4)
 
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -232,12 +454,16 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    legs = set("m,groups,big,fp16,prefill,int3,pack".split(",")) if args.extras == "all" else set(args.extras.split(","))
+    legs = set("m,groups,big,fp16,prefill,int3,pack,rows,loop".split(",")) if args.extras == "all" else set(args.extras.split(","))
     if not args.no_extras:
         extra = {}
         for M in (4, 16) if "m" in legs else ():
             s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, args.group)
-            extra[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5)}
+            if decode_leg.median_step_ms:
+                s = decode_leg.median_step_ms * 1e-3
+            extra[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
+                                     "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 2),
+                                     "kernels": sorted({p.split(" ")[0] for p in decode_leg.plans})}
         for grouping in ("none", "all") if "groups" in legs else ():   # the same M = 1 pass with 7 launches / 1 launch per step
             if grouping != args.group:
                 s, _, b, nl = decode_leg(1, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, grouping)
@@ -265,17 +491,29 @@ def main():
             with torch.cuda.graph(graph):
                 for call in calls:
                     call()
-            graph.replay()
+            settle(graph.replay)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(8):
-                graph.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / (8 * len(calls))
-            big[f"{name}_{N}x{K}"] = {"us": round(us, 2), "GB/s": round(algorithmic_bytes(P0, 1) / us / 1e3, 1)}
+            us = median_replay_ms(graph, 70) * 1e3 / len(calls)      # 210 launches
+            bb = algorithmic_bytes(P0, 1)
+            big[f"{name}_{N}x{K}"] = {"us": round(us, 2), "GB/s": round(bb / us / 1e3, 1),
+                                      "pct_hbm_peak": round(100 * bb / us / 1e3 / HBM_PEAK_GBS, 2),
+                                      "kernel": gwq.linear_plan(P0, 1).split(" ")[0]}
             del calls, graph
+            # the same bytes through the plain streaming read, three rotating buffers, one graph
+            sink = torch.zeros(4, dtype=torch.int32, device=dev)
+            pb = [torch.empty(bb // 16 * 16, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(3)]
+            for t in pb:
+                gwq.probe_stream(t, sink)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for t in pb:
+                    gwq.probe_stream(t, sink)
+            settle(graph.replay)
+            us_s = median_replay_ms(graph, 70) * 1e3 / 3
+            big[f"{name}_{N}x{K}"]["achievable_GB/s"] = round(bb / us_s / 1e3, 1)
+            big[f"{name}_{N}x{K}"]["frac_of_achievable"] = round(us_s / us, 4)
+            del graph, pb
             # the same matrices at M = 64 and M = 2048 (prebuilt index; eager launches, rotating copies)
             indexes = [gwq.linear_index(P) for P in Ps]
             for M in (64, 2048):
@@ -379,6 +617,22 @@ def main():
             # gwq_linear_indexed with an index built by gwq_linear_index.
             import dataclasses
             extra["prefill_M2048"] = time_prefill([gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(layers)])
+            # The ceiling beside it: 32x32x16 FP16 MFMAs issued out of registers on every SIMD (two blocks of four
+            # waves per CU), no memory, no LDS - what the matrix cores give at the clock they settle at.
+            sink = torch.zeros(4, dtype=torch.int32, device=dev)
+            pblocks, piters = 2 * torch.cuda.get_device_properties(dev).multi_processor_count, 4000
+            pfl = gwq.probe_mfma(pblocks, piters, sink)
+            settle(lambda: gwq.probe_mfma(pblocks, piters, sink), 0.2)
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(15)]
+            for a, b in evs:
+                a.record(); gwq.probe_mfma(pblocks, piters, sink); b.record()
+            torch.cuda.synchronize()
+            probe_tf = pfl / (float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e-3) / 1e12
+            for key in ("prefill_M2048",):
+                r = extra[key]["roofline"]
+                r["kernel"] = sorted({gwq.linear_plan(P, M).split(" ")[0] for P in layers})
+                r["achievable"] = {"TFLOP/s": round(probe_tf, 1), "what": "register-only 32x32x16 FP16 MFMA loop on all CUs"}
+                r["frac_of_achievable"] = round(r["achieved"] / probe_tf, 4)
             bare = [dataclasses.replace(P, index=None) for P in layers]
             extra["prefill_M2048_index_per_call"] = time_prefill(
                 [gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(bare)])
@@ -413,8 +667,13 @@ def main():
             int3 = {}
             for M in (1, 8):
                 s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, args.group, copies=copies3)
+                if decode_leg.median_step_ms:
+                    s = decode_leg.median_step_ms * 1e-3
                 int3[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
-                                        "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 2)}
+                                        "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 2),
+                                        "kernels": sorted({p.split(" ")[0] for p in decode_leg.plans})}
+            if args.launch == "graph":
+                int3["decode_M1_achievable"] = stream_read_leg(1, args.group, layers3)
             del copies3
             M = 2048
             xs, ys = make_xy(M)
@@ -526,6 +785,10 @@ def main():
             extra["pack_int4"] = pk
             extra["quality_int4"] = qual
             extra["score_M2048"] = sc
+        # One row per (configuration, shape, bits, M): the kernel on rotating copies (median replay) beside the
+        # oracle on the host cores (all cores and one), with the parity errors of exactly that row.
+        if "rows" in legs:
+            extra["rows"] = result_rows(gwq, gs, dev, torch)
         out["extras"] = extra
 
     if not args.no_cpu_baseline:

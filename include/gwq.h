@@ -205,6 +205,24 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
 gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N, int32_t K, float alpha,
                      float beta, float *score_f32, void *stream);
 
+/* Which kernel gwq_linear (count = 1) or gwq_linear_batch (layers of one K) would launch for these layers and M:
+ * kernel name with its template arguments, grid, block, LDS bytes, written as text (NUL-terminated, truncated
+ * to text_bytes).  Pure host call: reads the structs' scalars (and the tuning hooks), launches nothing, so a
+ * benchmark can label its numbers with the kernel that actually ran.  with_scratch: for M > 16, whether the
+ * call has the scratch for a K-split launch.  Errors as gwq_linear_batch; M > 16 needs count = 1. */
+gwq_status gwq_linear_plan(int32_t count, const gwq_packed *const *P, int32_t M, int32_t with_scratch, char *text,
+                           size_t text_bytes);
+
+/* Measurement probes for the ceilings the kernels are compared with (no part of the method: the paper gives no
+ * kernel and no hardware numbers; the benchmark runs these beside the real kernels, launched the same way).
+ *   gwq_probe_stream  one plain streaming read of `bytes` (a multiple of 16, 16-byte aligned) of device memory:
+ *                     what moving the same bytes takes with no arithmetic at all;
+ *   gwq_probe_mfma    `blocks` blocks of four waves, each wave issuing 8 * iters v_mfma_f32_32x32x16_f16 out of
+ *                     registers: 2 * 32*32*16 * 8 * iters * 4 * blocks floating-point operations.
+ * sink: 4 bytes of device memory (practically never written). */
+gwq_status gwq_probe_stream(const void *src, size_t bytes, void *sink, void *stream);
+gwq_status gwq_probe_mfma(int32_t blocks, int32_t iters, void *sink, void *stream);
+
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.  The values are
  * process-wide (atomic, read once per call by every thread's calls): a hook for benchmarks and tests, not a
  * per-call option.

@@ -84,6 +84,12 @@ def lib():
         L.gwq_linear_batch.restype = ctypes.c_int
         L.gwq_linear_batch.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), ctypes.POINTER(vp), i32,
                                        ctypes.POINTER(vp), vp]
+        L.gwq_linear_plan.restype = ctypes.c_int
+        L.gwq_linear_plan.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), i32, i32, ctypes.c_char_p, ctypes.c_size_t]
+        L.gwq_probe_stream.restype = ctypes.c_int
+        L.gwq_probe_stream.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        L.gwq_probe_mfma.restype = ctypes.c_int
+        L.gwq_probe_mfma.argtypes = [i32, i32, vp, vp]
         L.gwq_tuning_set.restype = ctypes.c_int
         L.gwq_tuning_set.argtypes = [ctypes.c_char_p, i32]
         L.gwq_status_string.restype = ctypes.c_char_p
@@ -110,6 +116,35 @@ def tuning_set(key, value):
     rc = lib().gwq_tuning_set(key.encode(), int(value))
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_tuning_set")
+
+
+def linear_plan(layers, M, with_scratch=True):
+    """gwq_linear_plan: the kernel (name, template arguments, launch shape) that gwq_linear / gwq_linear_batch
+    would launch for these layers (one PackedLayer or a list of layers of one K) and M, as text."""
+    if not isinstance(layers, (list, tuple)):
+        layers = [layers]
+    structs = [P.c_struct() for P in layers]
+    parr = (ctypes.POINTER(_Packed) * len(structs))(*[ctypes.pointer(c) for c in structs])
+    buf = ctypes.create_string_buffer(256)
+    rc = lib().gwq_linear_plan(len(structs), parr, int(M), int(bool(with_scratch)), buf, 256)
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_linear_plan")
+    return buf.value.decode()
+
+
+def probe_stream(src, sink, stream=None):
+    """gwq_probe_stream over the bytes of the tensor `src` (a multiple of 16)."""
+    rc = lib().gwq_probe_stream(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_probe_stream")
+
+
+def probe_mfma(blocks, iters, sink, stream=None):
+    """gwq_probe_mfma; returns the floating-point operations the launch performs."""
+    rc = lib().gwq_probe_mfma(int(blocks), int(iters), sink.data_ptr(), _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_probe_mfma")
+    return 2.0 * 32 * 32 * 16 * 8 * iters * 4 * blocks
 
 
 def _stream_ptr(stream):

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libgwq.so")
-SOURCES = ["gwq_api.hip", "gwq_pack.hip", "gwq_decode.hip", "gwq_gemm.hip", "gwq_quality.hip", "gwq_score.hip"]
+SOURCES = ["gwq_api.hip", "gwq_pack.hip", "gwq_decode.hip", "gwq_gemm.hip", "gwq_quality.hip", "gwq_score.hip", "gwq_probe.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -291,6 +291,49 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
     return GWQ_OK;
 }
 
+gwq_status gwq_linear_plan(int32_t count, const gwq_packed *const *P, int32_t M, int32_t with_scratch, char *text,
+                           size_t text_bytes)
+{
+    if (!P || !text) return GWQ_ERR_NULL;
+    if (count < 1 || count > GWQ_MAX_BATCH || M < 1 || text_bytes < 1 || (M > 16 && count != 1)) return GWQ_ERR_SHAPE;
+    for (int32_t i = 0; i < count; ++i) {
+        gwq_status s = check_packed(P[i]);
+        if (s != GWQ_OK) return s;
+        if (P[i]->bits != P[0]->bits) return GWQ_ERR_UNSUPPORTED;
+        if (P[i]->K != P[0]->K) return GWQ_ERR_SHAPE;
+    }
+    gwq::PlanText plan;
+    plan.text[0] = 0;
+    hipError_t e;
+    if (M <= 16) {
+        const void *x[GWQ_MAX_BATCH] = {};
+        void *y[GWQ_MAX_BATCH] = {};
+        e = gwq::launch_decode(count, P, x, M, y, decode_tuning(), nullptr, &plan);
+    } else {
+        // the pointer only says whether partial sums may be used; nothing is launched
+        e = gwq::launch_gemm(*P[0], nullptr, M, nullptr, nullptr, with_scratch ? &plan : nullptr,
+                             with_scratch ? gwq::gemm_scratch_bytes(P[0]->N, M) : 0, g_gemm_ms, nullptr, &plan);
+    }
+    if (e != hipSuccess) return GWQ_ERR_DEVICE;
+    strncpy(text, plan.text, text_bytes - 1);
+    text[text_bytes - 1] = 0;
+    return GWQ_OK;
+}
+
+gwq_status gwq_probe_stream(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink) return GWQ_ERR_NULL;
+    if (bytes < 16 || bytes % 16 || bytes >= ((size_t)1 << 40) || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3)) return GWQ_ERR_SHAPE;
+    return gwq::launch_probe_stream(src, bytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
+gwq_status gwq_probe_mfma(int32_t blocks, int32_t iters, void *sink, void *stream)
+{
+    if (!sink) return GWQ_ERR_NULL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1 || ((uintptr_t)sink & 3)) return GWQ_ERR_SHAPE;
+    return gwq::launch_probe_mfma(blocks, iters, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
 gwq_status gwq_tuning_set(const char *key, int32_t value)
 {
     if (!key) return GWQ_ERR_NULL;

@@ -28,6 +28,8 @@
 //   * the instructions a wave issues: wave-uniform values are kept in scalar registers, offsets
 //     are compile-time constants, and nothing in the multiply is predicated.
 // Two kernels: the lean one for M <= 4 with all of X in LDS, the wide one for everything else.
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "gwq_dequant.h"
@@ -1043,7 +1045,7 @@ hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwa
 // Decode launch over `count` layers (same bits, same M): grid row i works on layer i; the grid is as
 // wide as the layer with most channels needs and the surplus blocks of smaller layers exit at once.
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
-                         const DecodeTuning &tune, hipStream_t st)
+                         const DecodeTuning &tune, hipStream_t st, PlanText *describe)
 {
     const int waves_override = tune.waves;
     DecodeBatch batch;
@@ -1083,6 +1085,11 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256;
         if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds) {
             batch.nwaves = nwaves;
+            if (describe) {
+                snprintf(describe->text, sizeof(describe->text), "decode_small_kernel<%d,%d,%d> grid %dx%d block %d lds %zu",
+                         bits, u, M, blocks, count, 64 * nwaves, lds);
+                return hipSuccess;
+            }
             return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, st)
                              : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, st);
         }
@@ -1117,6 +1124,12 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
             const bool take = tune.stream == 2 || tune.tiles > 0 || tpb >= 2;
             batch.nwaves = nwaves;
             const int grid = (blocks + tpb - 1) / tpb;
+            if (take && describe) {
+                snprintf(describe->text, sizeof(describe->text),
+                         "decode_stream_kernel<%d,%d> grid %dx%d block %d lds %zu tiles_per_block %d", bits, mr, grid,
+                         count, nthreads, lds, tpb);
+                return hipSuccess;
+            }
             hipError_t e = hipErrorInvalidValue;
 #define GWQ_STREAM(B, RR) \
     if (take && bits == B && mr == RR) { \
@@ -1154,6 +1167,11 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
                 const int cus = device_cus();
                 const int cap = cus / count > 0 ? cus / count : 1;
                 if (blocks > cap) blocks = cap;
+            }
+            if (describe) {
+                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d> grid %dx%d block %d lds %zu phases %d",
+                         bits, best_u, mr, blocks, count, 64 * best_w, best_lds, best_ph);
+                return hipSuccess;
             }
 #define GWQ_WIDE(B, UU, RR) \
     if (bits == B && best_u == UU && mr == RR) \

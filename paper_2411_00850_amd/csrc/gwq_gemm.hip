@@ -30,6 +30,8 @@
 //
 // Launches with fewer tiles than CUs also split K over up to eight blocks per tile; their FP32
 // partial sums go to scratch and splitk_reduce_kernel adds them in a fixed order.
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "gwq_dequant.h"
@@ -565,7 +567,7 @@ int choose_rows(int M, int N, int K, bool have_scratch)
 
 template <int BITS, int MSW, int WN, int WM>
 hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, float *partial,
-                     size_t partial_bytes, hipStream_t st)
+                     size_t partial_bytes, hipStream_t st, PlanText *describe)
 {
     constexpr int BM = 32 * MSW * WM;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (P.N + kBN - 1) / kBN;
@@ -575,6 +577,11 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
     if (splits > 1 && (size_t)splits * M * P.N * sizeof(float) > partial_bytes) splits = 1, split_groups = gpr;
     if (splits == 1) partial = nullptr;
     const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
+    if (describe) {
+        snprintf(describe->text, sizeof(describe->text), "gemm_kernel<%d,%d,%d,%d> tile %dx%d grid %d block %d lds %zu k_splits %d",
+                 BITS, MSW, WN, WM, BM, kBN, tiles_m * tiles_n * splits, kThreads, lds, splits);
+        return hipSuccess;
+    }
     static std::atomic<uint32_t> lds_allowed{0};        // per instantiation
     {
         hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM>), (int)lds, lds_allowed);
@@ -615,7 +622,7 @@ hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t s
 }
 
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
-                       size_t scratch_bytes, int ms_override, hipStream_t st)
+                       size_t scratch_bytes, int ms_override, hipStream_t st, PlanText *describe)
 {
     const GroupRecord *rec = static_cast<const GroupRecord *>(index);
     float *part = static_cast<float *>(scratch);
@@ -626,10 +633,10 @@ hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const
     const int rows = ms_override ? ms_override : choose_rows(M, (int)P.N, (int)P.K, part != nullptr);
     const int shape = rows == 256 ? 2 : rows == 128 ? 1 : rows == 64 ? 0 : 3;
 #define GWQ_GEMM(B) \
-    return shape == 2   ? launch_ms<B, 2, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st) \
-           : shape == 1 ? launch_ms<B, 1, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st) \
-           : shape == 0 ? launch_ms<B, 1, 4, 2>(P, X, M, Y, rec, part, scratch_bytes, st) \
-                        : launch_ms<B, 1, 4, 1>(P, X, M, Y, rec, part, scratch_bytes, st)
+    return shape == 2   ? launch_ms<B, 2, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+           : shape == 1 ? launch_ms<B, 1, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+           : shape == 0 ? launch_ms<B, 1, 4, 2>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+                        : launch_ms<B, 1, 4, 1>(P, X, M, Y, rec, part, scratch_bytes, st, describe)
     if (P.bits == 4) GWQ_GEMM(4);
     GWQ_GEMM(3);
 #undef GWQ_GEMM

@@ -43,8 +43,13 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
 struct DecodeTuning {
     int waves, stream, tiles;
 };
+// With `describe` set a launcher only writes there which kernel, template arguments and launch shape it
+// would use for these arguments, and launches nothing.
+struct PlanText {
+    char text[192];
+};
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
-                         const DecodeTuning &tune, hipStream_t stream);
+                         const DecodeTuning &tune, hipStream_t stream, PlanText *describe = nullptr);
 // index: gemm_index_bytes(N, K) bytes, 16-byte aligned (one record per channel and group: index of the
 // group's first outlier, scale, zero point; a multiple of 256 bytes).  scratch: gemm_scratch_bytes(N, M_max)
 // bytes for the partial sums of launches that also split K (may be NULL: then K is never split).
@@ -52,12 +57,18 @@ size_t gemm_index_bytes(int64_t N, int64_t K);
 size_t gemm_scratch_bytes(int64_t N, int64_t M_max);
 hipError_t launch_gemm_index(const gwq_packed &P, void *index, hipStream_t stream);        // fills the records
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
-                       size_t scratch_bytes, int ms_override, hipStream_t stream);         // reads them
+                       size_t scratch_bytes, int ms_override, hipStream_t stream,
+                       PlanText *describe = nullptr);                                      // reads them
 
 // workspace: quality_workspace_bytes(N) bytes, 8-byte aligned (one partial result per channel); out: 3 doubles.
 size_t quality_workspace_bytes(int64_t N);
 hipError_t launch_quality(const gwq_packed &P, const void *W, const void *score, int score_is_f16, void *workspace,
                           double *out, hipStream_t stream);
+
+// Measurement probes (gwq_probe.hip): one plain streaming read of `bytes` (a multiple of 16); `blocks` blocks of
+// four waves that issue 8 * iters 32x32x16 FP16 MFMAs each out of registers.  sink: 4 bytes, practically never written.
+hipError_t launch_probe_stream(const void *src, size_t bytes, void *sink, hipStream_t stream);
+hipError_t launch_probe_mfma(int blocks, int iters, void *sink, hipStream_t stream);
 
 // score = beta * score + alpha * dY^T X (dY [M][N], X [M][K] FP16; score [N][K] FP32); K a multiple of 128.
 hipError_t launch_score(const void *dY, const void *X, int M, int N, int K, float alpha, float beta, float *score,

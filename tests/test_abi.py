@@ -19,7 +19,8 @@ def declared_functions():
 
 def test_header_declares_the_expected_calls():
     assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_index",
-                                    "gwq_linear_indexed", "gwq_linear_static", "gwq_pack", "gwq_quality", "gwq_score",
+                                    "gwq_linear_indexed", "gwq_linear_plan", "gwq_linear_static", "gwq_pack",
+                                    "gwq_probe_mfma", "gwq_probe_stream", "gwq_quality", "gwq_score",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
 
@@ -133,6 +134,35 @@ def test_linear_static_validates_before_touching_the_device():
     big = _packed(N=60000, K=65536)
     assert L.gwq_linear_static(ctypes.byref(big), fake, 2048, fake, None) == -4
     assert gwq.STATIC_SCRATCH_BYTES == 48 << 20
+
+
+def test_linear_plan_names_the_kernel_without_a_device():
+    """gwq_linear_plan is pure host arithmetic: it names the kernel the dispatcher picks for a shape and M."""
+    L = binding.lib()
+    buf = ctypes.create_string_buffer(256)
+
+    def plan(layers, M, scratch=1):
+        arr = (ctypes.POINTER(binding._Packed) * len(layers))(*[ctypes.pointer(p) for p in layers])
+        assert L.gwq_linear_plan(len(layers), arr, M, scratch, buf, 256) == 0
+        return buf.value.decode()
+
+    q = _packed(N=4096, K=4096)
+    gate = _packed(N=11008, K=4096)
+    down = _packed(N=4096, K=11008)
+    assert plan([q], 1).startswith("decode_small_kernel<4,8,1> grid 256x1 block 256")
+    assert plan([q, q, q], 1).startswith("decode_small_kernel<4,8,1> grid 256x3")
+    assert plan([down], 1).startswith("decode_small_kernel<4,8,1> grid 256x1 block 704")
+    assert plan([gate, gate], 16).startswith("decode_stream_kernel<4,16>")          # several tiles per block
+    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16>")                  # one tile per block
+    assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_wide_kernel<3,")
+    assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4> tile 256x128 grid 256 ")
+    assert "k_splits 1" in plan([q], 64, scratch=0) and "k_splits 1" not in plan([q], 64, scratch=1)
+    arr = (ctypes.POINTER(binding._Packed) * 2)(ctypes.pointer(q), ctypes.pointer(down))
+    assert L.gwq_linear_plan(2, arr, 1, 1, buf, 256) == -2                          # one K per launch
+    assert L.gwq_linear_plan(1, arr, 1, 1, None, 256) == -1
+    assert L.gwq_probe_stream(None, 1024, ctypes.c_void_p(0x1000), None) == -1
+    assert L.gwq_probe_stream(ctypes.c_void_p(0x1000), 1000, ctypes.c_void_p(0x1000), None) == -2
+    assert L.gwq_probe_mfma(0, 10, ctypes.c_void_p(0x1000), None) == -2
 
 
 def test_quality_validates_before_touching_the_device():
