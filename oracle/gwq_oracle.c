@@ -461,6 +461,19 @@ int gwq_oracle_quality(int64_t N, int64_t K, int bits, const uint32_t *qweight,
     return GWQ_ORACLE_OK;
 }
 
+/* ---------------------------------------------------------------- gated pair of the MLP -- */
+
+/* The layers the paper quantises sit in decoder blocks whose MLP is down(silu(gate(x)) * up(x)); its
+ * efficiency table (Sec. 4.2) times generation through all of them.  Given the two products G = X Wg^T and
+ * U = X Wu^T (as gwq_oracle_linear_f64 returns them), H[i] = silu(G[i]) * U[i] with
+ * silu(x) = x / (1 + exp(-x)), in fp64, element by element. */
+int gwq_oracle_gate_up(const double *G, const double *U, int64_t count, double *H)
+{
+    if (!G || !U || !H || count < 0) return GWQ_ORACLE_BAD_ARG;
+    for (int64_t i = 0; i < count; ++i) H[i] = G[i] / (1.0 + exp(-G[i])) * U[i];
+    return GWQ_ORACLE_OK;
+}
+
 /* ---------------------------------------------------------------- score production -- */
 
 /* Eq. 2 for one linear layer Y = X W^T (no bias, Sec. 3.1): the gradient of the loss with respect to

@@ -32,6 +32,7 @@ def _load():
     lib.gwq_oracle_decode.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
     lib.gwq_oracle_quality.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.gwq_oracle_gate_up.argtypes = [vp, vp, i64, vp]
     lib.gwq_oracle_score.argtypes = [vp, vp, i64, i64, i64, ctypes.c_double, ctypes.c_double, vp, vp]
     return lib
 
@@ -205,6 +206,16 @@ def quality(P, W, score):
     _chk(_lib.gwq_oracle_quality(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros), _p(P.row_ptr),
                                  _p(P.col_idx), _p(P.out_val), _p(Wb), _p(score), is16, _p(out)), "quality")
     return float(out[0]), float(out[1]), float(out[2])
+
+
+def gate_up(G, U):
+    """silu(G) * U element by element in fp64 (the gated pair of a decoder MLP) for two products of linear_f64."""
+    G = np.ascontiguousarray(G, np.float64)
+    U = np.ascontiguousarray(U, np.float64)
+    assert G.shape == U.shape
+    H = np.empty_like(G)
+    _chk(_lib.gwq_oracle_gate_up(_p(G), _p(U), G.size, _p(H)), "gate_up")
+    return H
 
 
 def score(dY, X, alpha=1.0, beta=0.0, prev=None):

@@ -571,6 +571,32 @@ def test_quality_special_cases_and_invariants(bits):
     assert orc.quality(P, W, S16) == orc.quality(P, W, S16.astype(np.float32))
 
 
+# ----------------------------------------------------------------------------- gated pair (silu(gate) * up)
+
+def test_gate_up_closed_forms_and_identities():
+    """silu(x) = x * sigmoid(x): exact values where the sigmoid is rational (sigmoid(ln 3) = 3/4, sigmoid(ln 7) = 7/8,
+    sigmoid(0) = 1/2), the identity silu(x) - silu(-x) = x, the limits silu(x) -> x and silu(-x) -> 0 for large x,
+    the slope 1/2 at 0 - and the second factor entering linearly."""
+    ln3, ln7 = np.log(3.0), np.log(7.0)
+    G = np.array([0.0, ln3, -ln3, ln7, -ln7, 40.0, -40.0, 745.0, -745.0, 1e-9])
+    one = np.ones_like(G)
+    H = orc.gate_up(G, one)
+    want = [0.0, 0.75 * ln3, -0.25 * ln3, 0.875 * ln7, -0.125 * ln7, 40.0, 0.0, 745.0, 0.0, 0.5e-9]
+    assert np.allclose(H, want, rtol=1e-14, atol=1e-15)
+    assert np.isfinite(H).all() and H[8] <= 0.0 and abs(H[8]) < 1e-300        # no overflow of exp on the way
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(1000) * 5
+    assert np.allclose(orc.gate_up(x, np.ones_like(x)) - orc.gate_up(-x, np.ones_like(x)), x, rtol=1e-13, atol=1e-15)
+    u = rng.standard_normal(1000)
+    assert np.allclose(orc.gate_up(x, 3.0 * u), 3.0 * orc.gate_up(x, u), rtol=1e-15)
+    assert np.array_equal(orc.gate_up(x, np.zeros_like(x)), np.zeros_like(x) * x)
+    # a transposed pair of arguments would fail this: silu acts on the first factor only
+    assert not np.allclose(orc.gate_up(x, u), orc.gate_up(u, x))
+    # shape is kept, elementwise
+    Hm = orc.gate_up(x.reshape(10, 100), u.reshape(10, 100))
+    assert Hm.shape == (10, 100) and np.array_equal(Hm.ravel(), orc.gate_up(x, u))
+
+
 # ----------------------------------------------------------------------------- score of one layer (Eq. 2)
 
 def test_score_hand_worked_case():
