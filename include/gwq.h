@@ -205,6 +205,18 @@ gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score
 gwq_status gwq_score(const void *dY_f16, const void *X_f16, int32_t M, int32_t N, int32_t K, float alpha,
                      float beta, float *score_f32, void *stream);
 
+/* The gated pair of a decoder layer's MLP in decode (M <= 16):
+ *   H[m][n] = silu(G[m][n]) * U[m][n],   G = gwq_linear(P_gate, X),  U = gwq_linear(P_up, X),  silu(x) = x / (1 + e^-x)
+ * What the efficiency table (Sec. 4.2) times is whole-model generation, where every decoder layer runs this pair
+ * and then the down projection on H; at decode sizes a launch is bound by latency, so for M <= 4 both products
+ * and the gate are one launch (the FP32 sums of the gate product never leave the block) and G and U are never
+ * written.  For 5 <= M <= 16 (and rows too long for that kernel) the two products go to `workspace` (device,
+ * >= 4*M*N bytes, 16-byte aligned; may be NULL for M <= 4 with K <= 16384) and a third launch combines them.
+ * P_gate and P_up must agree in N, K and bits.  H_f16 device [M][N], fully overwritten.  For M <= 4 H is
+ * computed from the FP32 sums; otherwise from the FP16-rounded products.  Other rules as gwq_linear. */
+gwq_status gwq_linear_gate_up(const gwq_packed *P_gate, const gwq_packed *P_up, const void *X_f16, int32_t M, void *H_f16,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* Which kernel gwq_linear (count = 1) or gwq_linear_batch (layers of one K) would launch for these layers and M:
  * kernel name with its template arguments, grid, block, LDS bytes, written as text (NUL-terminated, truncated
  * to text_bytes).  Pure host call: reads the structs' scalars (and the tuning hooks), launches nothing, so a

@@ -84,6 +84,8 @@ def lib():
         L.gwq_linear_batch.restype = ctypes.c_int
         L.gwq_linear_batch.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), ctypes.POINTER(vp), i32,
                                        ctypes.POINTER(vp), vp]
+        L.gwq_linear_gate_up.restype = ctypes.c_int
+        L.gwq_linear_gate_up.argtypes = [ctypes.POINTER(_Packed), ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
         L.gwq_linear_plan.restype = ctypes.c_int
         L.gwq_linear_plan.argtypes = [i32, ctypes.POINTER(ctypes.POINTER(_Packed)), i32, i32, ctypes.c_char_p, ctypes.c_size_t]
         L.gwq_probe_stream.restype = ctypes.c_int
@@ -116,6 +118,37 @@ def tuning_set(key, value):
     rc = lib().gwq_tuning_set(key.encode(), int(value))
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_tuning_set")
+
+
+def prepare_linear_gate_up(Pg, Pu, X, out):
+    """Pre-marshalled gwq_linear_gate_up call: out = silu(X Wg^T) * (X Wu^T) (FP16 [M, N]); returns a zero-argument
+    callable that enqueues it on the current torch stream.  The workspace (needed beyond M = 4) is allocated here."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == Pg.K == Pu.K
+    M = X.shape[0]
+    assert out.is_cuda and out.dtype == torch.float16 and out.is_contiguous() and tuple(out.shape) == (M, Pg.N) and Pg.N == Pu.N
+    ws = torch.empty(4 * M * Pg.N, dtype=torch.uint8, device=X.device) if (M > 4 or Pg.K > 16384) else None
+    cg, cu = Pg.c_struct(), Pu.c_struct()
+    rg, ru = ctypes.byref(cg), ctypes.byref(cu)
+    xp, hp = ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(out.data_ptr())
+    wp, wl = (ctypes.c_void_p(ws.data_ptr()), ws.numel()) if ws is not None else (None, 0)
+    fn = lib().gwq_linear_gate_up
+    current_stream = torch.cuda.current_stream
+
+    def call(_keep=(cg, cu, Pg, Pu, X, out, ws)):
+        rc = fn(rg, ru, xp, M, hp, wp, wl, ctypes.c_void_p(current_stream().cuda_stream))
+        if rc != GWQ_OK:
+            raise GwqError(rc, "gwq_linear_gate_up")
+    return call
+
+
+def linear_gate_up(Pg, Pu, X, out=None):
+    """gwq_linear_gate_up: silu(X Wg^T) * (X Wu^T) as FP16 [M, N]."""
+    import torch
+    if out is None:
+        out = torch.empty((X.shape[0], Pg.N), dtype=torch.float16, device=X.device)
+    prepare_linear_gate_up(Pg, Pu, X, out)()
+    return out
 
 
 def linear_plan(layers, M, with_scratch=True):

@@ -291,6 +291,36 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
     return GWQ_OK;
 }
 
+gwq_status gwq_linear_gate_up(const gwq_packed *P_gate, const gwq_packed *P_up, const void *X_f16, int32_t M, void *H_f16,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    gwq_status s = check_xy(P_gate, X_f16, M, H_f16);
+    if (s != GWQ_OK) return s;
+    s = check_xy(P_up, X_f16, M, H_f16);
+    if (s != GWQ_OK) return s;
+    if (M > 16 || P_gate->N != P_up->N || P_gate->K != P_up->K) return GWQ_ERR_SHAPE;
+    if (P_gate->bits != P_up->bits) return GWQ_ERR_UNSUPPORTED;
+    if ((uintptr_t)workspace & 15) return GWQ_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const gwq_packed *p[2] = {P_gate, P_up};
+    const void *x[2] = {X_f16, X_f16};
+    if (M <= 4) {                                       // one launch: the second run of each block writes H
+        void *y[2] = {H_f16, H_f16};
+        gwq::DecodeTuning t = decode_tuning();
+        t.gated_pairs = true;
+        hipError_t e = gwq::launch_decode(2, p, x, M, y, t, st);
+        if (e == hipSuccess) return GWQ_OK;
+        if (e != hipErrorNotSupported) return GWQ_ERR_DEVICE;
+    }
+    // Larger batches (and rows too long for the kernel above): the two products into the workspace, then H.
+    const size_t each = (size_t)M * P_gate->N * 2;
+    if (!workspace || workspace_bytes < 2 * each) return GWQ_ERR_WORKSPACE;
+    void *y[2] = {workspace, static_cast<char *>(workspace) + each};
+    hipError_t e = gwq::launch_decode(2, p, x, M, y, decode_tuning(), st);
+    if (e == hipSuccess) e = gwq::launch_silu_mul(y[0], y[1], H_f16, (size_t)M * P_gate->N, st);
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
 gwq_status gwq_linear_plan(int32_t count, const gwq_packed *const *P, int32_t M, int32_t with_scratch, char *text,
                            size_t text_bytes)
 {

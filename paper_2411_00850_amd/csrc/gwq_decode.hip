@@ -145,11 +145,21 @@ struct DecodeBatch {
 // bytes | 16 spare bytes | CSR entries (column | value << 16), blockDim * 8 + 8 zero entries |
 // partial sums [waves][MS][64] floats.  blockDim >= 3 gpr holds by construction (64 ceil(gpr / U)
 // threads, U <= 16), so one 16-byte vector per thread stages all scales and zero points.
-template <int BITS, int U, int MS>
-__device__ __forceinline__ void decode_small_body(const DecodeBatch &batch)
+//
+// MODE 0 stores Y.  MODE 1 and 2 are the two halves of the gated pair H = silu(X Wg^T) * (X Wu^T): the
+// first run keeps its FP32 sums in LDS (behind the partial sums), the second combines them with its own
+// and stores H, so the pair costs one launch and never writes the two products.
+__device__ inline float silu(float x)
+{
+    // x * sigmoid(x); exp2 and the reciprocal are the hardware's approximations (about 1 ulp each)
+    return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * x));
+}
+
+template <int BITS, int U, int MS, int MODE>
+__device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, const int layer)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    const DecodeProblem &pr = batch.p[blockIdx.y];
+    const DecodeProblem &pr = batch.p[layer];
     const int N = pr.N, K = pr.K;
     const int block = blockIdx.x;
     const uint32_t *__restrict__ qweight = pr.qweight;
@@ -376,14 +386,30 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch)
         float sum = s0 + s1;
         sum += __shfl_xor(sum, 16);
         sum += __shfl_xor(sum, 32);
-        if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (_Float16)sum;
+        float *stash = red + nwaves * MS * 64 + e * 16 + (lane & 15);   // written and read by the same thread
+        if (MODE == 1) {
+            if (lane < 16) *stash = sum;
+        } else {
+            if (MODE == 2) sum = silu(*stash) * sum;
+            if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (_Float16)sum;
+        }
     }
 }
 
 template <int BITS, int U, int MS>
 __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
 {
-    decode_small_body<BITS, U, MS>(batch);
+    decode_small_body<BITS, U, MS, 0>(batch, blockIdx.y);
+}
+
+// Grid row y multiplies layers 2y (gate) and 2y + 1 (up, whose Y receives H) of the batch, one after the other
+// in the same block; the barrier between them keeps the second run's staging out of the first run's LDS reads.
+template <int BITS, int U, int MS>
+__global__ __launch_bounds__(1024) void decode_small_gate_up_kernel(const DecodeBatch batch)
+{
+    decode_small_body<BITS, U, MS, 1>(batch, 2 * blockIdx.y);
+    __syncthreads();
+    decode_small_body<BITS, U, MS, 2>(batch, 2 * blockIdx.y + 1);
 }
 
 // ---- any M <= 16, X staged through LDS in chunks of K: the wide kernel ---------------------------
@@ -1029,10 +1055,12 @@ hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nw
 
 template <int BITS>
 hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwaves, int u, int ms, size_t lds,
-                        hipStream_t st)
+                        bool gated_pairs, hipStream_t st)
 {
 #define GWQ_SMALL(UU, MM) \
-    if (u == UU && ms == MM) return launch_kernel<&decode_small_kernel<BITS, UU, MM>>(batch, count, blocks, nwaves, lds, st)
+    if (u == UU && ms == MM) \
+        return gated_pairs ? launch_kernel<&decode_small_gate_up_kernel<BITS, UU, MM>>(batch, count / 2, blocks, nwaves, lds, st) \
+                           : launch_kernel<&decode_small_kernel<BITS, UU, MM>>(batch, count, blocks, nwaves, lds, st)
     GWQ_SMALL(4, 1); GWQ_SMALL(4, 2); GWQ_SMALL(4, 3); GWQ_SMALL(4, 4);
     GWQ_SMALL(8, 1); GWQ_SMALL(8, 2); GWQ_SMALL(8, 3); GWQ_SMALL(8, 4);
     GWQ_SMALL(16, 1); GWQ_SMALL(16, 2);
@@ -1082,18 +1110,20 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         while (u < 16 && (max_gpr + u - 1) / u > 16) u *= 2;
         const int nwaves = (max_gpr + u - 1) / u;
         const size_t x_bytes = (size_t)M * (nwaves * u * kGroup + kXPad) * 2;
-        const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256;
+        const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256 + 64 * (size_t)M;
         if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds) {
             batch.nwaves = nwaves;
             if (describe) {
-                snprintf(describe->text, sizeof(describe->text), "decode_small_kernel<%d,%d,%d> grid %dx%d block %d lds %zu",
-                         bits, u, M, blocks, count, 64 * nwaves, lds);
+                snprintf(describe->text, sizeof(describe->text), "%s<%d,%d,%d> grid %dx%d block %d lds %zu",
+                         tune.gated_pairs ? "decode_small_gate_up_kernel" : "decode_small_kernel", bits, u, M, blocks,
+                         tune.gated_pairs ? count / 2 : count, 64 * nwaves, lds);
                 return hipSuccess;
             }
-            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, st)
-                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, st);
+            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, st)
+                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, st);
         }
     }
+    if (tune.gated_pairs) return hipErrorNotSupported;  // only the kernel above multiplies gated pairs
 
     // The streaming kernel: rows of at most 32 groups (8 waves of 4), XT[K][rows] in LDS.  By default for
     // the batches the lean kernel does not take.
@@ -1183,6 +1213,22 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     }
 
     return hipErrorInvalidValue;                        // unreachable: one wave of four groups always fits
+}
+
+namespace {
+__global__ __launch_bounds__(256) void silu_mul_kernel(const _Float16 *__restrict__ G, const _Float16 *__restrict__ U,
+                                                       _Float16 *__restrict__ H, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) H[i] = (_Float16)(silu((float)G[i]) * (float)U[i]);
+}
+}  // namespace
+
+hipError_t launch_silu_mul(const void *G, const void *U, void *H, size_t count, hipStream_t st)
+{
+    silu_mul_kernel<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(static_cast<const _Float16 *>(G), static_cast<const _Float16 *>(U),
+                                                                   static_cast<_Float16 *>(H), count);
+    return hipGetLastError();
 }
 
 }  // namespace gwq

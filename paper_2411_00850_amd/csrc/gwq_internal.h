@@ -42,6 +42,7 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
 // streaming kernel 1 = never, 2 = for every M <= 16 it can take; its tiles per block.
 struct DecodeTuning {
     int waves, stream, tiles;
+    bool gated_pairs = false;   // layers (2i, 2i+1) are gate and up of a gated pair: one launch writes silu(gate) * up into Y[2i+1]
 };
 // With `describe` set a launcher only writes there which kernel, template arguments and launch shape it
 // would use for these arguments, and launches nothing.
@@ -69,6 +70,9 @@ hipError_t launch_quality(const gwq_packed &P, const void *W, const void *score,
 // four waves that issue 8 * iters 32x32x16 FP16 MFMAs each out of registers.  sink: 4 bytes, practically never written.
 hipError_t launch_probe_stream(const void *src, size_t bytes, void *sink, hipStream_t stream);
 hipError_t launch_probe_mfma(int blocks, int iters, void *sink, hipStream_t stream);
+
+// H = silu(G) * U elementwise over `count` FP16 values (the unfused form of the gated pair, for M > 4).
+hipError_t launch_silu_mul(const void *G, const void *U, void *H, size_t count, hipStream_t stream);
 
 // score = beta * score + alpha * dY^T X (dY [M][N], X [M][K] FP16; score [N][K] FP32); K a multiple of 128.
 hipError_t launch_score(const void *dY, const void *X, int M, int N, int K, float alpha, float beta, float *score,

@@ -18,8 +18,8 @@ def declared_functions():
 
 
 def test_header_declares_the_expected_calls():
-    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_index",
-                                    "gwq_linear_indexed", "gwq_linear_plan", "gwq_linear_static", "gwq_pack",
+    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_gate_up",
+                                    "gwq_linear_index", "gwq_linear_indexed", "gwq_linear_plan", "gwq_linear_static", "gwq_pack",
                                     "gwq_probe_mfma", "gwq_probe_stream", "gwq_quality", "gwq_score",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
 
@@ -163,6 +163,21 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert L.gwq_probe_stream(None, 1024, ctypes.c_void_p(0x1000), None) == -1
     assert L.gwq_probe_stream(ctypes.c_void_p(0x1000), 1000, ctypes.c_void_p(0x1000), None) == -2
     assert L.gwq_probe_mfma(0, 10, ctypes.c_void_p(0x1000), None) == -2
+
+
+def test_linear_gate_up_validates_before_touching_the_device():
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    ok = _packed()
+    assert L.gwq_linear_gate_up(None, ctypes.byref(ok), fake, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), None, fake, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(ok), None, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(ok), fake, 17, fake, None, 0, None) == -2     # decode sizes only
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(_packed(N=8)), fake, 1, fake, None, 0, None) == -2
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(_packed(bits=3)), fake, 1, fake, None, 0, None) == -3
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(ok), fake, 8, fake, None, 0, None) == -4      # M > 4 needs the workspace
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(ok), fake, 8, fake, fake, 4 * 8 * 4 - 1, None) == -4
+    assert L.gwq_linear_gate_up(ctypes.byref(ok), ctypes.byref(ok), fake, 8, fake, ctypes.c_void_p(0x1008), 1 << 20, None) == -2
 
 
 def test_quality_validates_before_touching_the_device():

@@ -503,3 +503,40 @@ def test_pack_time_index_is_the_index_and_gwq_linear_reads_it(bits):
         y_idx = gwq.linear(bare, Xd, index=built)
         assert torch.equal(y_own, y_bare) and torch.equal(y_own, y_idx), M
         assert_close(y_own.cpu().numpy(), orc.linear_f64(P, X), f"bits={bits} M={M}")
+
+
+# ----------------------------------------------------------------------------- gated pair: silu(gate) * up in one launch
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K", [(16, 128), (200, 1024), (333, 4096), (72, 11008), (40, 24576)])
+def test_gate_up_fused_decode(bits, N, K):
+    """gwq_linear_gate_up against the oracle: silu(X Wg^T) * (X Wu^T) from the oracle's fp64 products.  M <= 4 is
+    one launch (both products in the same block), larger M two products and a combining kernel; K = 24576
+    is past what the one-launch kernel stages, so it takes the workspace path at every M."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    Pg, rng = _problem(500 + N + bits, N, K, bits)
+    Pu, _ = _problem(900 + N + bits, N, K, bits)
+    Dg, Du = upload_packed(Pg), upload_packed(Pu)
+    for M in (1, 2, 3, 4, 5, 9, 16):
+        X = gs.activations(M, K, rng)
+        H = gwq.linear_gate_up(Dg, Du, to_gpu(X)).cpu().numpy()
+        ref = orc.gate_up(orc.linear_f64(Pg, X), orc.linear_f64(Pu, X))
+        assert_close(H, ref, f"gate_up N={N} K={K} M={M} bits={bits}")
+    if K <= 4096:
+        assert gwq.linear_plan([Dg, Du], 1).startswith("decode_small_kernel")     # the plain batch, for comparison
+
+
+def test_gate_up_7b_shape_full():
+    """The 7B gate/up pair (11008 x 4096) at M = 1 and 4, every output."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    Wg, mg = _layer7b(4, 11008, 4096)
+    Pg = orc.encode(Wg, mg, 4, 10000)
+    Wu, Su = gs.layer_matrix(2, 5, 11008, 4096)
+    Pu = orc.pack(Wu, Su, 4, 10000)
+    Dg, Du = upload_packed(Pg), upload_packed(Pu)
+    for M in (1, 4):
+        X = gs.activations(M, 4096, gs.rng_for(2, 5, 20 + M))
+        H = gwq.linear_gate_up(Dg, Du, to_gpu(X)).cpu().numpy()
+        assert_close(H, orc.gate_up(orc.linear_f64(Pg, X), orc.linear_f64(Pu, X)), f"gate/up 7B M={M}")
