@@ -40,6 +40,38 @@ namespace {
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
+// Optional build (-DGWQ_STAMP, a separate library: see build.py): wave 0 of every block records the
+// shader clock at the kernel's milestones, read back with gwq_debug_read_stamps.  Not part of the product.
+#ifdef GWQ_STAMP
+constexpr int kStampSlots = 16, kStampBlocks = 2048;
+__device__ unsigned long long g_stamps[kStampBlocks * kStampSlots];
+#define GWQ_STAMP_AT(i) \
+    do { \
+        if (tid == 0) { \
+            const unsigned blk = (blockIdx.y * gridDim.x + blockIdx.x) % kStampBlocks; \
+            g_stamps[blk * kStampSlots + (i)] = (i) == 0 ? wall_clock64() : clock64(); \
+        } \
+    } while (0)
+// The same for the lean kernel, held in scalar registers until the end so that no store disturbs the run:
+// slot 0 of a block's record is the wall clock, slots 1 .. from its first wave, 8 + those of its last wave.
+#define GWQ_TS_DECL unsigned long long ts_[8] = {}; const unsigned long long ts_wall_ = wall_clock64()
+#define GWQ_TS(i) ts_[i] = clock64()
+#define GWQ_TS_FLUSH(first, last) \
+    do { \
+        if ((tid & 63) == 0 && ((first) || (last))) { \
+            const unsigned blk = (blockIdx.y * gridDim.x + blockIdx.x) % kStampBlocks; \
+            if (first) g_stamps[blk * kStampSlots] = ts_wall_; \
+            for (int i_ = 0; i_ < 7; ++i_) g_stamps[blk * kStampSlots + ((last) && !(first) ? 8 : 1) + i_] = ts_[i_]; \
+        } \
+    } while (0)
+#else
+#define GWQ_STAMP_AT(i) do { } while (0)
+#define GWQ_TS_DECL do { } while (0)
+#define GWQ_TS(i) do { } while (0)
+#define GWQ_TS_FLUSH(first, last) do { } while (0)
+#endif
+
+
 __device__ inline const uint32_t *at_byte(const uint32_t *base, uint32_t byte_off)
 {
     return reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + byte_off);
@@ -180,6 +212,8 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwaves = batch.nwaves, nthreads = nwaves * 64;
+    GWQ_TS_DECL;
+    GWQ_TS(0);                                          // descriptor has arrived
     const int r = lane & 15, b = lane >> 4;
     const int tail_lane4 = 4 * (lane | 48);             // where the 3-bit tail word of this lane's channel arrives
     const int gpr = K / kGroup;
@@ -199,9 +233,15 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const uint32_t red_off = ent_off + 32 * nthreads + 32;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
 
-    // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
+    // CSR bounds of the block and of this lane's channel.  The block's bounds are read through a pointer to
+    // constant memory (nothing in the launch writes row_ptr): with a wave-uniform index that is a scalar
+    // load, which nobody waits for until the segment is requested, behind the code stream.  (Through the plain
+    // pointer the compiler issues a vector load and waits for it on the spot to make the value uniform -
+    // a whole memory round trip before the first code is requested.)
     const int last_row = row0 + 16 < N ? row0 + 16 : N;
-    const int e_begin = row_ptr[row0], e_end = row_ptr[last_row];
+    const __attribute__((address_space(4))) int32_t *row_ptr_k =
+        (const __attribute__((address_space(4))) int32_t *)(uintptr_t)row_ptr;
+    const int e_begin = row_ptr_k[row0], e_end = row_ptr_k[last_row];
     const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
 
     // Staging loads, all 16-byte and coalesced.  (1) X: each wave brings the columns of its own
@@ -253,6 +293,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
 
     // Nothing that consumes a load may be scheduled above this point.
     __builtin_amdgcn_sched_barrier(0);
+    GWQ_TS(1);                                          // staging and the first codes requested
     const DecodeConsts dc(BITS);
 #pragma unroll
     for (int e = 0; e < MS; ++e)
@@ -274,6 +315,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     }
     *reinterpret_cast<u32x4 *>(lds_raw + meta_dst) = meta;
     __syncthreads();
+    GWQ_TS(2);                                          // X, scales and zero points are in LDS
 
     // (3) The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin:
     // thread t brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
@@ -322,6 +364,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
         }
     }
 
+    GWQ_TS(3);                                          // all codes multiplied
     // The CSR segment has arrived by now: publish it, followed by one vector of zero entries that
     // lanes without an entry read instead.
     store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
@@ -367,12 +410,14 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
 
     // Fixed-order reduction over the waves and the four lanes of a channel, then FP16 store.
     // Only lanes b = 0 of a wave that owns groups hold dense results (rows m < 4).
+    GWQ_TS(4);                                          // outliers added
 #pragma unroll
     for (int e = 0; e < MS; ++e) {
         const float dense = (active && b == 0) ? acc[e] : 0.f;
         red[(wave * MS + e) * 64 + lane] = dense + oacc[e];
     }
     __syncthreads();
+    GWQ_TS(5);                                          // partial sums of all waves are in LDS
     // Wave e (or the wave that reaches it by striding) sums row e: every lane adds its column of
     // partial sums over the waves, then the four lanes of a channel meet.
     for (int e = wave; e < MS; e += nwaves) {
@@ -394,6 +439,8 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
             if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (_Float16)sum;
         }
     }
+    GWQ_TS(6);                                          // stored
+    GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
 }
 
 template <int BITS, int U, int MS>
@@ -504,9 +551,11 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
 
-    // CSR bounds of the block (uniform: scalar loads) and of this lane's channel.
+    // CSR bounds of the block (scalar loads through the constant address space) and of this lane's channel.
     const int last_row = row0 + 16 < N ? row0 + 16 : N;
-    const int e_begin = row_ptr[row0], e_end = row_ptr[last_row];
+    const __attribute__((address_space(4))) int32_t *row_ptr_k =
+        (const __attribute__((address_space(4))) int32_t *)(uintptr_t)row_ptr;
+    const int e_begin = row_ptr_k[row0], e_end = row_ptr_k[last_row];
     const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
 
     // The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for 16
@@ -691,21 +740,6 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 // partial sums [2][waves][4][64] floats.
 constexpr int kStreamU = 4;                             // groups per wave
 
-// Optional build (-DGWQ_STAMP, a separate library: see build.py): wave 0 of every block records the
-// shader clock at the kernel's milestones, read back with gwq_debug_read_stamps.  Not part of the product.
-#ifdef GWQ_STAMP
-constexpr int kStampSlots = 16, kStampBlocks = 2048;
-__device__ unsigned long long g_stamps[kStampBlocks * kStampSlots];
-#define GWQ_STAMP_AT(i) \
-    do { \
-        if (tid == 0) { \
-            const unsigned blk = (blockIdx.y * gridDim.x + blockIdx.x) % kStampBlocks; \
-            g_stamps[blk * kStampSlots + (i)] = (i) == 0 ? wall_clock64() : clock64(); \
-        } \
-    } while (0)
-#else
-#define GWQ_STAMP_AT(i) do { } while (0)
-#endif
 
 struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
 struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
