@@ -236,7 +236,12 @@ int gwq_oracle_quant_group(const uint16_t *w, const uint8_t *mask, int len, int 
  *        Word 12 (the tail) holds the last two codes of every slot:
  *        code 32b+30 -> bit 3b, code 32b+31 -> bit 16 + 3b; all other bits are zero.
  */
-#define GWQ_GROUP 128
+#define GWQ_GROUP 128   /* codes per block of the word layout */
+
+/* The quantisation group (Sec. 3.2, first paragraph: scale and zero point are per group of beta weights of an
+ * output channel along the input dimension; the paper sets beta = 16) is 16, 32, 64 or 128: a whole number of
+ * groups per 128-code block of the word layout, which does not depend on it. */
+static int group_ok(int group) { return group == 16 || group == 32 || group == 64 || group == 128; }
 
 static int words_per_group(int bits) { return bits == 4 ? 16 : 13; }
 
@@ -307,36 +312,38 @@ int gwq_oracle_unpack_codes(const uint32_t *qweight, int64_t N, int64_t K, int b
 
 /* ---------------------------------------------------------------- gwq_pack twin ---- */
 
-/* Everything after the selection: CSR of the marked entries, then per (row, group of 128
- * along K) scale, zero, codes (Eq. 6, 7, 9) and the word layout above.  `mask` is the outlier
- * indicator [N*K]; col_idx/out_val must hold as many entries as the mask marks. */
-int gwq_oracle_encode(const uint16_t *W, const uint8_t *mask, int64_t N, int64_t K, int bits,
+/* Everything after the selection: CSR of the marked entries, then per (row, group of `group`
+ * consecutive weights along K) scale, zero, codes (Eq. 6, 7, 9), and the word layout above per
+ * block of 128 codes.  `mask` is the outlier indicator [N*K]; col_idx/out_val must hold as many
+ * entries as the mask marks; scales/zeros are [N][K/group]. */
+int gwq_oracle_encode(const uint16_t *W, const uint8_t *mask, int64_t N, int64_t K, int bits, int group,
                       uint32_t *qweight, uint16_t *scales, uint8_t *zeros,
                       int32_t *row_ptr, uint16_t *col_idx, uint16_t *out_val)
 {
     if (!W || !mask || !qweight || !scales || !zeros || !row_ptr) return GWQ_ORACLE_BAD_ARG;
-    if (N <= 0 || K <= 0 || K % GWQ_GROUP || K > 65536 || (bits != 3 && bits != 4))
+    if (N <= 0 || K <= 0 || K % GWQ_GROUP || K > 65536 || (bits != 3 && bits != 4) || !group_ok(group))
         return GWQ_ORACLE_BAD_ARG;
     int rc = gwq_oracle_csr(W, mask, N, K, row_ptr, col_idx, out_val);
     int nw = words_per_group(bits);
-    int64_t gpr = K / GWQ_GROUP;
+    int64_t bpr = K / GWQ_GROUP, gpr = K / group;       /* blocks and groups per row */
     uint8_t codes[GWQ_GROUP];
     for (int64_t n = 0; n < N && rc == GWQ_ORACLE_OK; ++n)
-        for (int64_t g = 0; g < gpr && rc == GWQ_ORACLE_OK; ++g) {
-            int64_t off = n * K + g * GWQ_GROUP;
-            rc = gwq_oracle_quant_group(W + off, mask + off, GWQ_GROUP, bits,
-                                        &scales[n * gpr + g], &zeros[n * gpr + g], codes);
-            pack_group(codes, bits, qweight + (n * gpr + g) * nw);
+        for (int64_t blk = 0; blk < bpr && rc == GWQ_ORACLE_OK; ++blk) {
+            for (int64_t k = blk * GWQ_GROUP; k < (blk + 1) * GWQ_GROUP && rc == GWQ_ORACLE_OK; k += group)
+                rc = gwq_oracle_quant_group(W + n * K + k, mask + n * K + k, group, bits,
+                                            &scales[n * gpr + k / group], &zeros[n * gpr + k / group],
+                                            codes + (k - blk * GWQ_GROUP));
+            pack_group(codes, bits, qweight + (n * bpr + blk) * nw);
         }
     return rc;
 }
 
 /* Whole encoding: selection (Eq. 8) followed by gwq_oracle_encode.
- * Output sizes: qweight N*(K/128)*wpg words, scales/zeros N*(K/128), row_ptr N+1,
+ * Output sizes: qweight N*(K/128)*wpg words, scales/zeros N*(K/group), row_ptr N+1,
  * col_idx/out_val k_out = gwq_oracle_outlier_count(N, K, ppm).
  * mask_out (optional, N*K bytes) receives the outlier indicator. */
 int gwq_oracle_pack(const uint16_t *W, const void *score, int score_is_f16,
-                    int64_t N, int64_t K, int bits, uint32_t ppm,
+                    int64_t N, int64_t K, int bits, int group, uint32_t ppm,
                     uint32_t *qweight, uint16_t *scales, uint8_t *zeros,
                     int32_t *row_ptr, uint16_t *col_idx, uint16_t *out_val, uint8_t *mask_out)
 {
@@ -345,7 +352,7 @@ int gwq_oracle_pack(const uint16_t *W, const void *score, int score_is_f16,
     if (!mask) return GWQ_ORACLE_NO_MEM;
     int rc = gwq_oracle_select(score, score_is_f16, N, K, ppm, mask);
     if (rc == GWQ_ORACLE_OK)
-        rc = gwq_oracle_encode(W, mask, N, K, bits, qweight, scales, zeros, row_ptr, col_idx, out_val);
+        rc = gwq_oracle_encode(W, mask, N, K, bits, group, qweight, scales, zeros, row_ptr, col_idx, out_val);
     if (!mask_out) free(mask);
     return rc;
 }
@@ -354,44 +361,47 @@ int gwq_oracle_pack(const uint16_t *W, const void *score, int score_is_f16,
 
 /* Decoded row n of the layer's weight in fp64: Eq. 10 for the codes, plus the FP16
  * outliers of that row (the code under an outlier decodes to 0). */
-static void decode_row(int64_t n, int64_t K, int bits, const uint32_t *qweight,
+static void decode_row(int64_t n, int64_t K, int bits, int group, const uint32_t *qweight,
                        const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
                        const uint16_t *col_idx, const uint16_t *out_val, double *w_hat)
 {
     int nw = words_per_group(bits);
-    int64_t gpr = K / GWQ_GROUP;
+    int64_t bpr = K / GWQ_GROUP, gpr = K / group;
     uint8_t codes[GWQ_GROUP];
-    for (int64_t g = 0; g < gpr; ++g) {
-        unpack_group(qweight + (n * gpr + g) * nw, bits, codes);
-        double s = gwq_oracle_half_to_double(scales[n * gpr + g]);
-        int z = zeros[n * gpr + g];
-        for (int i = 0; i < GWQ_GROUP; ++i) w_hat[g * GWQ_GROUP + i] = s * (double)(codes[i] - z);
+    for (int64_t blk = 0; blk < bpr; ++blk) {
+        unpack_group(qweight + (n * bpr + blk) * nw, bits, codes);
+        for (int i = 0; i < GWQ_GROUP; ++i) {
+            int64_t k = blk * GWQ_GROUP + i;
+            double s = gwq_oracle_half_to_double(scales[n * gpr + k / group]);
+            int z = zeros[n * gpr + k / group];
+            w_hat[k] = s * (double)(codes[i] - z);
+        }
     }
     for (int32_t j = row_ptr[n]; j < row_ptr[n + 1]; ++j)
         w_hat[col_idx[j]] += gwq_oracle_half_to_double(out_val[j]);
 }
 
-int gwq_oracle_decode(int64_t N, int64_t K, int bits, const uint32_t *qweight,
+int gwq_oracle_decode(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
                       const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
                       const uint16_t *col_idx, const uint16_t *out_val, double *W_hat)
 {
     if (!qweight || !scales || !zeros || !row_ptr || !W_hat) return GWQ_ORACLE_BAD_ARG;
-    if (N <= 0 || K <= 0 || K % GWQ_GROUP || (bits != 3 && bits != 4)) return GWQ_ORACLE_BAD_ARG;
+    if (N <= 0 || K <= 0 || K % GWQ_GROUP || (bits != 3 && bits != 4) || !group_ok(group)) return GWQ_ORACLE_BAD_ARG;
     for (int64_t n = 0; n < N; ++n)
-        decode_row(n, K, bits, qweight, scales, zeros, row_ptr, col_idx, out_val, W_hat + n * K);
+        decode_row(n, K, bits, group, qweight, scales, zeros, row_ptr, col_idx, out_val, W_hat + n * K);
     return GWQ_ORACLE_OK;
 }
 
 /* Y[m, j] = sum_k X[m, k] * W_hat[rows[j], k] in fp64, k ascending; Y is [M][n_rows].
  * rows == NULL means rows 0..n_rows-1 (n_rows = N gives the full product Y[M][N]). */
-int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, const uint32_t *qweight,
+int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
                           const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
                           const uint16_t *col_idx, const uint16_t *out_val,
                           const uint16_t *X, int64_t M, const int32_t *rows, int64_t n_rows,
                           double *Y)
 {
     if (!qweight || !scales || !zeros || !row_ptr || !X || !Y) return GWQ_ORACLE_BAD_ARG;
-    if (N <= 0 || K <= 0 || K % GWQ_GROUP || M <= 0 || n_rows < 0 || (bits != 3 && bits != 4))
+    if (N <= 0 || K <= 0 || K % GWQ_GROUP || M <= 0 || n_rows < 0 || (bits != 3 && bits != 4) || !group_ok(group))
         return GWQ_ORACLE_BAD_ARG;
     if (rows)
         for (int64_t j = 0; j < n_rows; ++j)
@@ -413,7 +423,7 @@ int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, const uint32_t *qweigh
 #pragma omp for schedule(static)
             for (int64_t j = 0; j < n_rows; ++j) {
                 int64_t n = rows ? rows[j] : j;
-                decode_row(n, K, bits, qweight, scales, zeros, row_ptr, col_idx, out_val, w_hat);
+                decode_row(n, K, bits, group, qweight, scales, zeros, row_ptr, col_idx, out_val, w_hat);
                 for (int64_t m = 0; m < M; ++m) {
                     double acc = 0.0;
                     for (int64_t k = 0; k < K; ++k) acc += Xd[m * K + k] * w_hat[k];
@@ -435,18 +445,18 @@ int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, const uint32_t *qweigh
  *                              when `score` is the gradient g)
  *   out[2] = max |D|
  * Every D is computed in fp64 from exact operands; the sums run in fp64 over n, then k, ascending. */
-int gwq_oracle_quality(int64_t N, int64_t K, int bits, const uint32_t *qweight,
+int gwq_oracle_quality(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
                        const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
                        const uint16_t *col_idx, const uint16_t *out_val,
                        const uint16_t *W, const void *score, int score_is_f16, double *out)
 {
     if (!qweight || !scales || !zeros || !row_ptr || !W || !score || !out) return GWQ_ORACLE_BAD_ARG;
-    if (N <= 0 || K <= 0 || K % GWQ_GROUP || (bits != 3 && bits != 4)) return GWQ_ORACLE_BAD_ARG;
+    if (N <= 0 || K <= 0 || K % GWQ_GROUP || (bits != 3 && bits != 4) || !group_ok(group)) return GWQ_ORACLE_BAD_ARG;
     double *w_hat = (double *)malloc((size_t)K * sizeof(double));
     if (!w_hat) return GWQ_ORACLE_NO_MEM;
     double sq = 0.0, first = 0.0, mx = 0.0;
     for (int64_t n = 0; n < N; ++n) {
-        decode_row(n, K, bits, qweight, scales, zeros, row_ptr, col_idx, out_val, w_hat);
+        decode_row(n, K, bits, group, qweight, scales, zeros, row_ptr, col_idx, out_val, w_hat);
         for (int64_t k = 0; k < K; ++k) {
             double d = gwq_oracle_half_to_double(W[n * K + k]) - w_hat[k];
             double g = score_is_f16 ? gwq_oracle_half_to_double(((const uint16_t *)score)[n * K + k])

@@ -27,11 +27,11 @@ def _load():
     lib.gwq_oracle_quant_group.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.gwq_oracle_pack_codes.argtypes = [vp, i64, i64, i32, vp]
     lib.gwq_oracle_unpack_codes.argtypes = [vp, i64, i64, i32, vp]
-    lib.gwq_oracle_encode.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp, vp, vp, vp]
-    lib.gwq_oracle_pack.argtypes = [vp, vp, i32, i64, i64, i32, u32, vp, vp, vp, vp, vp, vp, vp]
-    lib.gwq_oracle_decode.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp]
-    lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
-    lib.gwq_oracle_quality.argtypes = [i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
+    lib.gwq_oracle_encode.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.gwq_oracle_pack.argtypes = [vp, vp, i32, i64, i64, i32, i32, u32, vp, vp, vp, vp, vp, vp, vp]
+    lib.gwq_oracle_decode.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    lib.gwq_oracle_quality.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.gwq_oracle_gate_up.argtypes = [vp, vp, i64, vp]
     lib.gwq_oracle_score.argtypes = [vp, vp, i64, i64, i64, ctypes.c_double, ctypes.c_double, vp, vp]
     return lib
@@ -131,51 +131,50 @@ class Packed:
     bits: int
     ppm: int
     qweight: np.ndarray   # uint32 [N, K/128, words_per_group]
-    scales: np.ndarray    # uint16 (FP16 bits) [N, K/128]
-    zeros: np.ndarray     # uint8 [N, K/128]
+    scales: np.ndarray    # uint16 (FP16 bits) [N, K/group]
+    zeros: np.ndarray     # uint8 [N, K/group]
     row_ptr: np.ndarray   # int32 [N+1]
     col_idx: np.ndarray   # uint16 [k_out]
     out_val: np.ndarray   # uint16 (FP16 bits) [k_out]
     mask: np.ndarray      # uint8 [N, K] outlier indicator (not part of the stored format)
+    group: int = GROUP    # weights per scale and zero point: 16, 32, 64 or 128
 
 
-def pack(W, score, bits, ppm=10000):
+def pack(W, score, bits, ppm=10000, group=GROUP):
     Wb = _f16_bits(W)
     score, is16 = _score(score)
     N, K = Wb.shape
     assert score.shape == (N, K)
     k_out = outlier_count(N, K, ppm)
-    gpr = K // GROUP
     P = Packed(N, K, bits, ppm,
-               np.empty((N, gpr, words_per_group(bits)), np.uint32),
-               np.empty((N, gpr), np.uint16), np.empty((N, gpr), np.uint8),
+               np.empty((N, K // GROUP, words_per_group(bits)), np.uint32),
+               np.empty((N, K // group), np.uint16), np.empty((N, K // group), np.uint8),
                np.empty(N + 1, np.int32), np.empty(k_out, np.uint16), np.empty(k_out, np.uint16),
-               np.empty((N, K), np.uint8))
-    _chk(_lib.gwq_oracle_pack(_p(Wb), _p(score), is16, N, K, bits, ppm, _p(P.qweight), _p(P.scales),
+               np.empty((N, K), np.uint8), group)
+    _chk(_lib.gwq_oracle_pack(_p(Wb), _p(score), is16, N, K, bits, group, ppm, _p(P.qweight), _p(P.scales),
                               _p(P.zeros), _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(P.mask)),
          "pack")
     return P
 
 
-def encode(W, mask, bits, ppm=-1):
+def encode(W, mask, bits, ppm=-1, group=GROUP):
     """Everything after the selection, for a given outlier indicator `mask` [N, K]."""
     Wb = _f16_bits(W)
     N, K = Wb.shape
     mask = np.ascontiguousarray(mask, np.uint8)
     nnz = int(mask.sum())
-    gpr = K // GROUP
     P = Packed(N, K, bits, ppm,
-               np.empty((N, gpr, words_per_group(bits)), np.uint32),
-               np.empty((N, gpr), np.uint16), np.empty((N, gpr), np.uint8),
-               np.empty(N + 1, np.int32), np.empty(nnz, np.uint16), np.empty(nnz, np.uint16), mask)
-    _chk(_lib.gwq_oracle_encode(_p(Wb), _p(mask), N, K, bits, _p(P.qweight), _p(P.scales), _p(P.zeros),
+               np.empty((N, K // GROUP, words_per_group(bits)), np.uint32),
+               np.empty((N, K // group), np.uint16), np.empty((N, K // group), np.uint8),
+               np.empty(N + 1, np.int32), np.empty(nnz, np.uint16), np.empty(nnz, np.uint16), mask, group)
+    _chk(_lib.gwq_oracle_encode(_p(Wb), _p(mask), N, K, bits, group, _p(P.qweight), _p(P.scales), _p(P.zeros),
                                 _p(P.row_ptr), _p(P.col_idx), _p(P.out_val)), "encode")
     return P
 
 
 def decode(P):
     out = np.empty((P.N, P.K), np.float64)
-    _chk(_lib.gwq_oracle_decode(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros),
+    _chk(_lib.gwq_oracle_decode(P.N, P.K, P.bits, P.group, _p(P.qweight), _p(P.scales), _p(P.zeros),
                                 _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(out)), "decode")
     return out
 
@@ -191,7 +190,7 @@ def linear_f64(P, X, rows=None):
         rows_arr = np.ascontiguousarray(rows, np.int32)
         n_rows = rows_arr.size
     Y = np.empty((M, n_rows), np.float64)
-    _chk(_lib.gwq_oracle_linear_f64(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros),
+    _chk(_lib.gwq_oracle_linear_f64(P.N, P.K, P.bits, P.group, _p(P.qweight), _p(P.scales), _p(P.zeros),
                                     _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(Xb), M,
                                     _p(rows_arr), n_rows, _p(Y)), "linear_f64")
     return Y
@@ -203,7 +202,7 @@ def quality(P, W, score):
     score, is16 = _score(score)
     assert Wb.shape == (P.N, P.K) and score.shape == (P.N, P.K)
     out = np.empty(3, np.float64)
-    _chk(_lib.gwq_oracle_quality(P.N, P.K, P.bits, _p(P.qweight), _p(P.scales), _p(P.zeros), _p(P.row_ptr),
+    _chk(_lib.gwq_oracle_quality(P.N, P.K, P.bits, P.group, _p(P.qweight), _p(P.scales), _p(P.zeros), _p(P.row_ptr),
                                  _p(P.col_idx), _p(P.out_val), _p(Wb), _p(score), is16, _p(out)), "quality")
     return float(out[0]), float(out[1]), float(out[2])
 

@@ -362,12 +362,17 @@ def _small_problem(seed, N=12, K=384, planted=True):
     return W, S
 
 
+@pytest.mark.parametrize("group", [128, 64, 32, 16])
 @pytest.mark.parametrize("bits", [3, 4])
 @pytest.mark.parametrize("ppm", [0, 10000, 300000])
-def test_pack_is_composition_of_pinned_steps(bits, ppm):
+def test_pack_is_composition_of_pinned_steps(bits, ppm, group):
+    """Every group size of Sec. 3.2 (beta: the paper's 16, and 32, 64, 128): scale, zero point and codes of every
+    group equal the exact-rational quantiser on that group's `group` weights; the word layout (128-code blocks)
+    and the CSR do not depend on the group size."""
     W, S = _small_problem(bits * 10 + ppm % 7)
     N, K = W.shape
-    P = orc.pack(W, S, bits, ppm)
+    P = orc.pack(W, S, bits, ppm, group)
+    assert P.scales.shape == P.zeros.shape == (N, K // group)
     k_out = orc.outlier_count(N, K, ppm)
     mask = numpy_select(S, k_out)
     assert np.array_equal(P.mask, mask)
@@ -375,8 +380,8 @@ def test_pack_is_composition_of_pinned_steps(bits, ppm):
     codes = py_unpack(P.qweight, N, K, bits)
     Wb = W.view(np.uint16)
     for n in range(N):
-        for g in range(K // 128):
-            sl = slice(128 * g, 128 * g + 128)
+        for g in range(K // group):
+            sl = slice(group * g, group * g + group)
             s, z, q = exact_group(Wb[n, sl], mask[n, sl], bits)
             assert (int(P.scales[n, g]), int(P.zeros[n, g])) == (s, z)
             assert list(codes[n, sl]) == q
@@ -387,16 +392,17 @@ def test_pack_is_composition_of_pinned_steps(bits, ppm):
         assert np.array_equal(P.out_val[P.row_ptr[n]:P.row_ptr[n + 1]], Wb[n, c])
 
 
+@pytest.mark.parametrize("group", [128, 64, 32, 16])
 @pytest.mark.parametrize("bits", [3, 4])
-def test_no_outliers_is_plain_group_rtn(bits):
+def test_no_outliers_is_plain_group_rtn(bits, group):
     """ppm = 0 reduces to group-wise min-max round-to-nearest (the quantiser the paper's first
     table names), written here with numpy: s from the minimal-FP16 rule, codes by np.rint."""
     W, S = _small_problem(77)
     N, K = W.shape
     maxq = (1 << bits) - 1
-    P = orc.pack(W, S, bits, 0)
+    P = orc.pack(W, S, bits, 0, group)
     assert P.row_ptr[-1] == 0 and not P.mask.any()
-    Wd = W.astype(np.float64).reshape(N, K // 128, 128)
+    Wd = W.astype(np.float64).reshape(N, K // group, group)
     mn = np.minimum(Wd.min(-1), 0.0)
     mx = np.maximum(Wd.max(-1), 0.0)
     s = P.scales.view(np.float16).astype(np.float64)
@@ -473,15 +479,16 @@ def test_non_finite_weights_stay_local_and_keep_the_invariants(bits):
 
 # ----------------------------------------------------------------------------- Eq. 10 + the layer
 
+@pytest.mark.parametrize("group", [128, 64, 32, 16])
 @pytest.mark.parametrize("bits", [3, 4])
-def test_decode_and_linear_match_numpy(bits):
+def test_decode_and_linear_match_numpy(bits, group):
     W, S = _small_problem(21 + bits, N=20, K=512)
     N, K = W.shape
     rng = np.random.default_rng(9)
     X = rng.standard_normal((5, K)).astype(np.float16)
-    P = orc.pack(W, S, bits, 10000)
+    P = orc.pack(W, S, bits, 10000, group)
     # independent decode: Python index map, s*(q-z), outliers from the CSR arrays
-    q = py_unpack(P.qweight, N, K, bits).astype(np.float64).reshape(N, K // 128, 128)
+    q = py_unpack(P.qweight, N, K, bits).astype(np.float64).reshape(N, K // group, group)
     s = P.scales.view(np.float16).astype(np.float64)[..., None]
     z = P.zeros.astype(np.float64)[..., None]
     What = (s * (q - z)).reshape(N, K)
@@ -500,6 +507,24 @@ def test_decode_and_linear_match_numpy(bits):
     ref = X.astype(np.float64) @ W.astype(np.float64).T
     rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
     assert rel < (0.25 if bits == 3 else 0.12)
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_smaller_groups_quantise_no_worse(bits):
+    """A group's range can only shrink when the group is cut in two, so the squared error (Eq. 4) of the paper's
+    group size 16 is at most that of 32, 64, 128 up to the scale's FP16 rounding - here clearly below; and
+    the figures of merit follow the group size (max |W - W_Q| <= s / 2 of the group the weight lies in)."""
+    W, S = _small_problem(123, N=16, K=512)
+    sq = {}
+    for group in (128, 64, 32, 16):
+        P = orc.pack(W, S, bits, 10000, group)
+        sq[group], _, mx = orc.quality(P, W, S)
+        s = P.scales.view(np.float16).astype(np.float64)
+        assert mx <= s.max() / 2
+        D = np.abs(W.astype(np.float64) - orc.decode(P))
+        assert np.all(D <= np.repeat(s, group, axis=1) / 2)
+        assert np.isclose(sq[group], (D ** 2).sum(), rtol=1e-12)
+    assert sq[16] < sq[32] < sq[64] < sq[128]
 
 
 def test_four_bits_beat_three_bits():
