@@ -44,7 +44,7 @@ def algorithmic_bytes(P, M):
     """Bytes the method must move for one gwq_linear call: packed layer + X + Y."""
     gpr = P.K // 128
     wpg = 16 if P.bits == 4 else 13
-    packed = P.N * gpr * (wpg * 4 + 2 + 1) + (P.N + 1) * 4 + P.n_outliers * 4
+    packed = P.N * gpr * wpg * 4 + P.N * (P.K // P.group) * (2 + 1) + (P.N + 1) * 4 + P.n_outliers * 4
     return packed + 2 * M * P.K + 2 * M * P.N
 
 
@@ -56,7 +56,7 @@ def clone_layer(P):
     from paper_2411_00850_amd.binding import PackedLayer
     return PackedLayer(P.N, P.K, P.bits, P.ppm, P.n_outliers, P.qweight.clone(), P.scales.clone(),
                        P.zeros.clone(), P.row_ptr.clone(), P.col_idx.clone(), P.out_val.clone(),
-                       P.index.clone() if P.index is not None else None)
+                       P.index.clone() if P.index is not None else None, P.group)
 
 
 def settle(fn, seconds=0.1):
@@ -328,7 +328,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
     ap.add_argument("--extras", default="all", metavar="LIST",
-                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,pack,rows,loop (default: all)")
+                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,beta,pack,rows,loop (default: all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are out of scope.")
@@ -348,13 +348,17 @@ def main():
     # ---- inputs: generate on the host (seeded), pack on the GPU with gwq_pack -------------------
     t0 = time.time()
     want_int3 = not args.no_extras and (args.extras == "all" or "int3" in args.extras.split(","))
+    want_beta = not args.no_extras and (args.extras == "all" or "beta" in args.extras.split(","))
     layers, layers3, pack_inputs = [], [], []
+    layers_beta = {16: [], 32: [], 64: []}                # the same matrices in smaller quantisation groups
     for mid, (name, N, K) in enumerate(gs.SHAPES_7B):
         W, S = gs.layer_matrix(2, mid, N, K)
         Wd, Sd = torch.from_numpy(W).to(dev), torch.from_numpy(S).to(dev)
         layers.append(gwq.pack(Wd, Sd, 4, 10000))
         if want_int3:
             layers3.append(gwq.pack(Wd, Sd, 3, 10000))
+        for group, lst in layers_beta.items() if want_beta else ():
+            lst.append(gwq.pack(Wd, Sd, 4, 10000, group=group))
         if name in ("q", "gate", "down"):
             pack_inputs.append((name, Wd, Sd))
         else:
@@ -512,7 +516,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    legs = set("m,groups,big,fp16,prefill,int3,pack,rows,loop".split(",")) if args.extras == "all" else set(args.extras.split(","))
+    legs = set("m,groups,big,fp16,prefill,int3,beta,pack,rows,loop".split(",")) if args.extras == "all" else set(args.extras.split(","))
     if not args.no_extras:
         extra = {}
         for M in (4, 16) if "m" in legs else ():
@@ -754,6 +758,41 @@ def main():
             extra["int3"] = int3
             del indexes, calls, xs, ys
             torch.cuda.empty_cache()
+        # The same layer in groups of 16 (the size Sec. 3.2 names), 32 and 64 weights, 4 bits: decode M = 1 and 16 the
+        # way the headline is timed, and the prefill pass at 16.  More scales and zero points to read (3 bytes per
+        # group), and the kernels multiply FP16 operands s * (q - z) instead of scaling a group's sum.
+        if "beta" in legs and want_beta:
+            beta = {}
+            for group, lb in layers_beta.items():
+                copies_b = [lb] + [[clone_layer(P) for P in lb] for _ in range(args.copies - 1)]
+                row = {"weight_bytes": sum(P.nbytes() for P in lb)}
+                for M in (1, 16):
+                    s, _, b, _ = decode_leg(M, max(args.steps // 3, 12), max(args.warmup // 3, 12), args.launch, args.group, copies=copies_b)
+                    if decode_leg.median_step_ms:
+                        s = decode_leg.median_step_ms * 1e-3
+                    row[f"decode_M{M}"] = {"GB/s": round(b / s / 1e9, 1), "ms_per_step": round(s * 1e3, 5),
+                                           "pct_hbm_peak": round(100 * b / s / 1e9 / HBM_PEAK_GBS, 2),
+                                           "kernels": sorted({p.split(" ")[0] for p in decode_leg.plans})}
+                del copies_b
+                if group == 16:
+                    M = 2048
+                    xs, ys = make_xy(M)
+                    flb = sum(flops(P, M) for P in lb)
+                    calls = [gwq.prepare_linear(P, xs[P.K], ys[j]) for j, P in enumerate(lb)]
+                    settle(lambda: [c() for c in calls], 0.2)
+                    t = time.perf_counter()
+                    for _ in range(10):
+                        for c in calls:
+                            c()
+                    torch.cuda.synchronize()
+                    sb = (time.perf_counter() - t) / 10
+                    row["prefill_M2048"] = {"TFLOP/s": round(flb / sb / 1e12, 1), "ms_per_pass": round(sb * 1e3, 4),
+                                            "pct_mfma_f16_peak": round(100 * flb / sb / 1e12 / MFMA_F16_PEAK_TFLOPS, 2),
+                                            "kernels": sorted({gwq.linear_plan(P, M).split(" ")[0] for P in lb})}
+                    del calls, xs, ys
+                beta[f"group_{group}"] = row
+                torch.cuda.empty_cache()
+            extra["int4_smaller_groups"] = beta
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
         pk, qual = {}, {}
         for name, Wd, Sd in pack_inputs if "pack" in legs else ():

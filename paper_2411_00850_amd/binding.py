@@ -127,7 +127,7 @@ def prepare_linear_gate_up(Pg, Pu, X, out):
     assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape[1] == Pg.K == Pu.K
     M = X.shape[0]
     assert out.is_cuda and out.dtype == torch.float16 and out.is_contiguous() and tuple(out.shape) == (M, Pg.N) and Pg.N == Pu.N
-    ws = torch.empty(4 * M * Pg.N, dtype=torch.uint8, device=X.device) if (M > 4 or Pg.K > 16384) else None
+    ws = torch.empty(4 * M * Pg.N, dtype=torch.uint8, device=X.device) if (M > 4 or Pg.K > 16384 or Pg.group != 128) else None
     cg, cu = Pg.c_struct(), Pu.c_struct()
     rg, ru = ctypes.byref(cg), ctypes.byref(cu)
     xp, hp = ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(out.data_ptr())
@@ -195,15 +195,16 @@ class PackedLayer:
     ppm: int
     n_outliers: int
     qweight: "torch.Tensor"   # int32 view of the uint32 words [N, K/128, wpg]
-    scales: "torch.Tensor"    # int16 view of the FP16 bits [N * K/128], padded to 16 bytes
-    zeros: "torch.Tensor"     # uint8 [N * K/128], padded to 16 bytes
+    scales: "torch.Tensor"    # int16 view of the FP16 bits [N * K/group], padded to 16 bytes
+    zeros: "torch.Tensor"     # uint8 [N * K/group], padded to 16 bytes
     row_ptr: "torch.Tensor"   # int32 [N+1]
     col_idx: "torch.Tensor"   # int16 view of uint16 [n_outliers + padding]
     out_val: "torch.Tensor"   # int16 view of FP16 bits [n_outliers + padding]
     index: "torch.Tensor" = None   # optional uint8 [linear_index bytes]: filled by gwq_pack, read by gwq_linear for M > 16
+    group: int = 128               # weights per scale and zero point: 16, 32, 64 or 128 (scales, zeros: [N * K/group])
 
     def c_struct(self):
-        return _Packed(self.N, self.K, self.bits, 128, self.ppm, self.n_outliers,
+        return _Packed(self.N, self.K, self.bits, self.group, self.ppm, self.n_outliers,
                        self.qweight.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(),
                        self.row_ptr.data_ptr(), self.col_idx.data_ptr(), self.out_val.data_ptr(),
                        self.index.data_ptr() if self.index is not None else None)
@@ -213,9 +214,9 @@ class PackedLayer:
                    (self.qweight, self.scales, self.zeros, self.row_ptr, self.col_idx, self.out_val))
 
 
-def alloc_packed(N, K, bits, ppm=10000, device="cuda", with_index=True):
+def alloc_packed(N, K, bits, ppm=10000, device="cuda", with_index=True, group=128):
     import torch
-    sz = layout(N, K, bits, 128, ppm)
+    sz = layout(N, K, bits, group, ppm)
     gpr = K // 128
     wpg = 16 if bits == 4 else 13
     n_slots = sz["col_idx"] // 2
@@ -226,10 +227,11 @@ def alloc_packed(N, K, bits, ppm=10000, device="cuda", with_index=True):
                        torch.empty(N + 1, dtype=torch.int32, device=device),
                        torch.empty(n_slots, dtype=torch.int16, device=device),
                        torch.empty(n_slots, dtype=torch.int16, device=device),
-                       torch.empty(sz["linear_index"], dtype=torch.uint8, device=device) if with_index else None), sz
+                       torch.empty(sz["linear_index"], dtype=torch.uint8, device=device) if with_index else None,
+                       group), sz
 
 
-def pack(W, score, bits, ppm=10000, stream=None, workspace=None, with_index=True):
+def pack(W, score, bits, ppm=10000, stream=None, workspace=None, with_index=True, group=128):
     """gwq_pack: W FP16 [N, K] and score FP32/FP16 [N, K] on the GPU -> PackedLayer.  with_index: also fill the
     layer's index (8 bytes per group, +12 % memory), which gwq_linear then reads for M > 16 instead of building one
     on every call."""
@@ -243,7 +245,7 @@ def pack(W, score, bits, ppm=10000, stream=None, workspace=None, with_index=True
     else:
         raise TypeError("score must be float32 or float16")
     N, K = W.shape
-    P, sz = alloc_packed(N, K, bits, ppm, W.device, with_index)
+    P, sz = alloc_packed(N, K, bits, ppm, W.device, with_index, group)
     if workspace is None:
         workspace = torch.empty(sz["pack_workspace"], dtype=torch.uint8, device=W.device)
     cs = P.c_struct()
@@ -269,7 +271,7 @@ def quality(P, W, score, out=None, stream=None, workspace=None):
     if out is None:
         out = torch.empty(3, dtype=torch.float64, device=W.device)
     if workspace is None:
-        nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, 0)["quality_workspace"]
+        nbytes = layout(P.N, P.K, P.bits, P.group, P.ppm, 0)["quality_workspace"]
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
     cs = P.c_struct()
     rc = lib().gwq_quality(ctypes.byref(cs), W.data_ptr(), score.data_ptr(), st, out.data_ptr(), workspace.data_ptr(),
@@ -300,14 +302,14 @@ def score(dY, X, out=None, alpha=1.0, beta=0.0, stream=None):
 def linear_workspace(P, M, device="cuda"):
     """Scratch tensor gwq_linear needs for this layer at M rows (None for the decode path)."""
     import torch
-    nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, M)["linear_workspace"]
+    nbytes = layout(P.N, P.K, P.bits, P.group, P.ppm, M)["linear_workspace"]
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
 
 
 def linear_scratch(P, M, device="cuda"):
     """Scratch tensor gwq_linear_indexed may use for this layer at M rows (None for the decode path)."""
     import torch
-    nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, M)["linear_scratch"]
+    nbytes = layout(P.N, P.K, P.bits, P.group, P.ppm, M)["linear_scratch"]
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
 
 
@@ -315,7 +317,7 @@ def linear_index(P, stream=None):
     """gwq_linear_index: the per-layer index gwq_linear_indexed reads for M > 16 (a uint8 tensor).  Build it
     once per packed layer; it stays valid until the layer's buffers change."""
     import torch
-    nbytes = layout(P.N, P.K, P.bits, 128, P.ppm, 0)["linear_index"]
+    nbytes = layout(P.N, P.K, P.bits, P.group, P.ppm, 0)["linear_index"]
     index = torch.empty(nbytes, dtype=torch.uint8, device=P.qweight.device)
     cs = P.c_struct()
     rc = lib().gwq_linear_index(ctypes.byref(cs), index.data_ptr(), index.numel(), _stream_ptr(stream))

@@ -45,9 +45,10 @@ gwq::DecodeTuning decode_tuning() { return gwq::DecodeTuning{g_decode_waves, g_d
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
     if (bits != 3 && bits != 4) return GWQ_ERR_UNSUPPORTED;
-    if (group != gwq::kGroup) return GWQ_ERR_UNSUPPORTED;
+    if (group != 16 && group != 32 && group != 64 && group != gwq::kGroup) return GWQ_ERR_UNSUPPORTED;
     if (N < 1 || K < gwq::kGroup || K > 65536 || K % gwq::kGroup != 0) return GWQ_ERR_SHAPE;
     if (N * K >= ((int64_t)1 << 32)) return GWQ_ERR_SHAPE;
+    if (K / group > 2048) return GWQ_ERR_SHAPE;          // a tile's scales and zero points (48 bytes per group) are staged in LDS
     if (ppm > 1000000u) return GWQ_ERR_SHAPE;
     return GWQ_OK;
 }
@@ -88,7 +89,7 @@ gwq_status check_linear(const gwq_packed *P, const void *X_f16, int32_t M, const
 {
     gwq_status s = check_xy(P, X_f16, M, Y_f16);
     if (s != GWQ_OK) return s;
-    if (M > 16 && (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K))) return GWQ_ERR_WORKSPACE;
+    if (M > 16 && (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K, P->group))) return GWQ_ERR_WORKSPACE;
     if (M > 16 && ((uintptr_t)index & 15)) return GWQ_ERR_SHAPE;
     return GWQ_OK;
 }
@@ -132,10 +133,10 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     gwq_status s = check_shape(N, K, bits, group, outlier_ppm);
     if (s != GWQ_OK) return s;
     if (M_max < 0) return GWQ_ERR_SHAPE;
-    const int64_t groups = (int64_t)N * (K / gwq::kGroup);
+    const int64_t blocks = (int64_t)N * (K / gwq::kGroup), groups = (int64_t)N * (K / group);
     const int64_t k_out = outlier_count(N, K, outlier_ppm);
     memset(out, 0, sizeof(*out));
-    out->qweight = (size_t)groups * gwq::words_per_group(bits) * 4;
+    out->qweight = (size_t)blocks * gwq::words_per_group(bits) * 4;
     // Read with wide (partly unaligned) loads by the kernels: whole 16-byte vectors plus one spare.
     out->scales = ((size_t)groups * 2 + 15) / 16 * 16 + 16;
     out->zeros = ((size_t)groups + 15) / 16 * 16 + 16;
@@ -143,7 +144,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     out->col_idx = ((size_t)k_out * 2 + 15) / 16 * 16 + 16;
     out->out_val = out->col_idx;
     out->pack_workspace = gwq::pack_workspace_bytes(N);
-    out->linear_index = gwq::gemm_index_bytes(N, K);
+    out->linear_index = gwq::gemm_index_bytes(N, K, group);
     out->linear_scratch = gwq::gemm_scratch_bytes(N, M_max);
     out->linear_workspace = M_max > 16 ? out->linear_index + out->linear_scratch : 0;
     out->n_outliers = k_out;
@@ -204,7 +205,7 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     } else {
         // The workspace holds the index, then (whatever is left) the partial sums of a K-split launch.
         // A layer that carries its index (filled by gwq_pack) is not indexed again.
-        const size_t ib = gwq::gemm_index_bytes(P->N, P->K);
+        const size_t ib = gwq::gemm_index_bytes(P->N, P->K, P->group);
         e = P->index ? hipSuccess : gwq::launch_gemm_index(*P, workspace, st);
         if (e == hipSuccess)
             e = gwq::launch_gemm(*P, X_f16, M, Y_f16, P->index ? P->index : workspace,
@@ -217,7 +218,7 @@ gwq_status gwq_linear_index(const gwq_packed *P, void *index, size_t index_bytes
 {
     gwq_status s = check_packed(P);
     if (s != GWQ_OK) return s;
-    if (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K)) return GWQ_ERR_WORKSPACE;
+    if (!index || index_bytes < gwq::gemm_index_bytes(P->N, P->K, P->group)) return GWQ_ERR_WORKSPACE;
     if ((uintptr_t)index & 15) return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_gemm_index(*P, index, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
@@ -241,7 +242,7 @@ gwq_status gwq_linear_static(const gwq_packed *P, const void *X_f16, int32_t M, 
     gwq_status s = check_xy(P, X_f16, M, Y_f16);
     if (s != GWQ_OK) return s;
     // What gwq_linear would want as its workspace for this M (host arithmetic only).
-    const size_t ib = (M > 16 && !P->index) ? gwq::gemm_index_bytes(P->N, P->K) : 0;
+    const size_t ib = (M > 16 && !P->index) ? gwq::gemm_index_bytes(P->N, P->K, P->group) : 0;
     const size_t sb = M > 16 ? gwq::gemm_scratch_bytes(P->N, M) : 0;
     if (ib + sb > GWQ_STATIC_SCRATCH_BYTES) return GWQ_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -280,7 +281,7 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
         void *y[GWQ_MAX_BATCH];
         int n = 0;
         for (int32_t j = i; j < count; ++j)
-            if (!done[j] && P[j]->K == P[i]->K) {
+            if (!done[j] && P[j]->K == P[i]->K && P[j]->group == P[i]->group) {
                 p[n] = P[j]; x[n] = X_f16[j]; y[n] = Y_f16[j];
                 done[j] = true;
                 ++n;
@@ -299,7 +300,7 @@ gwq_status gwq_linear_gate_up(const gwq_packed *P_gate, const gwq_packed *P_up, 
     s = check_xy(P_up, X_f16, M, H_f16);
     if (s != GWQ_OK) return s;
     if (M > 16 || P_gate->N != P_up->N || P_gate->K != P_up->K) return GWQ_ERR_SHAPE;
-    if (P_gate->bits != P_up->bits) return GWQ_ERR_UNSUPPORTED;
+    if (P_gate->bits != P_up->bits || P_gate->group != P_up->group) return GWQ_ERR_UNSUPPORTED;
     if ((uintptr_t)workspace & 15) return GWQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const gwq_packed *p[2] = {P_gate, P_up};
@@ -329,7 +330,7 @@ gwq_status gwq_linear_plan(int32_t count, const gwq_packed *const *P, int32_t M,
     for (int32_t i = 0; i < count; ++i) {
         gwq_status s = check_packed(P[i]);
         if (s != GWQ_OK) return s;
-        if (P[i]->bits != P[0]->bits) return GWQ_ERR_UNSUPPORTED;
+        if (P[i]->bits != P[0]->bits || P[i]->group != P[0]->group) return GWQ_ERR_UNSUPPORTED;
         if (P[i]->K != P[0]->K) return GWQ_ERR_SHAPE;
     }
     gwq::PlanText plan;

@@ -106,6 +106,13 @@ template <> struct Slot<4> {
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
         decode_slot4(ww, z, d, f);
     }
+    // Zero points of the slot's two halves (groups of 16).
+    __device__ inline void decode_halves(uint32_t z_lo, uint32_t z_hi, int /*b*/, const DecodeConsts &d, u32x4 f[4],
+                                         int /*tail_lane4*/) const
+    {
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        decode_slot4_halves(ww, z_lo, z_hi, d, f);
+    }
 };
 // 3-bit: a group is 13 words, slot b owns words 3b .. 3b+2 and two codes of word 12 (the tail).  One
 // 16-byte load at byte 12b (4-byte aligned; gfx950 global memory takes that) brings a lane its three
@@ -130,6 +137,12 @@ template <> struct Slot<3> {
         const uint32_t tail = (uint32_t)__builtin_amdgcn_ds_bpermute(tail_lane4, (int)fourth);
         decode_slot3(w, tail >> (3 * b), z, d, f);
     }
+    __device__ inline void decode_halves(uint32_t z_lo, uint32_t z_hi, int b, const DecodeConsts &d, u32x4 f[4],
+                                         int tail_lane4) const
+    {
+        const uint32_t tail = (uint32_t)__builtin_amdgcn_ds_bpermute(tail_lane4, (int)fourth);
+        decode_slot3_halves(w, tail >> (3 * b), z_lo, z_hi, d, f);
+    }
 };
 
 constexpr int kPre = 4;        // outlier entries a lane handles without a loop
@@ -147,7 +160,8 @@ struct DecodeProblem {
     const uint16_t *out_val;
     const _Float16 *X;
     _Float16 *Y;
-    int N, K, sc_last_vec, zp_last_vec, csr_last_vec, reserved;
+    int N, K, sc_last_vec, zp_last_vec, csr_last_vec;
+    int group_shift;            // log2 of the layer's group size: 7, or 4 .. 6 (the wide kernel alone takes those)
 };
 struct DecodeBatch {
     int M, nwaves;
@@ -480,9 +494,15 @@ __global__ __launch_bounds__(1024) void decode_small_gate_up_kernel(const Decode
 // dropped).  Dynamic LDS: X [M][chunk] halves | scales [16][gpr] halves | zero points [16][gpr]
 // bytes | 96 guard bytes | CSR entries (column | value << 16), blockDim * 8 | partial sums
 // [waves][4][64] floats.
+//
+// FINE: layers whose groups are smaller than 128 (16, 32 or 64; Sec. 3.2 names 16).  The staged metadata
+// is [16][spr] with spr = K / group; a lane's slot of 32 codes lies in one group or, at 16, in two, so the
+// lane takes scale and zero point per half slot and multiplies them in before the MFMA, which sums over all
+// four slots of a block of 128: the operands are s * (q - z) rounded to FP16, as in the kernel for M > 16, and
+// the scale is capped likewise so that they stay finite.
 constexpr int kWideGuard = 96;
 
-template <int BITS, int U, int MR>
+template <int BITS, int U, int MR, bool FINE>
 __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -497,9 +517,10 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const _Float16 *__restrict__ X = pr.X;
     _Float16 *__restrict__ Y = pr.Y;
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+    const int shift = FINE ? pr.group_shift : 7;
     // The whole descriptor is requested in one go and only then looked at.
     asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
-                 "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec));
+                 "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec), "s"(shift));
     if ((int)blockIdx.x * 16 >= N) return;              // the grid is as wide as the largest layer needs
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -508,6 +529,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int r = lane & 15, b = lane >> 4;
     const int tail_lane4 = 4 * (lane | 48);             // where the 3-bit tail word of this lane's channel arrives
     const int gpr = K / kGroup;
+    const int spr = K >> shift;                         // scale / zero-point pairs per channel
     const int chunk_groups = nwaves * U;                // groups per phase
     const int chunk = chunk_groups * kGroup;            // columns per phase
     const int x_stride = chunk + kXPad;                 // row stride of the LDS copy of X
@@ -515,8 +537,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 
     _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
     const uint32_t sc_off = (uint32_t)M * x_stride * 2;
-    const uint32_t zp_off = sc_off + 32 * gpr;
-    const uint32_t guard_off = zp_off + 16 * gpr;
+    const uint32_t zp_off = sc_off + 32 * spr;
+    const uint32_t guard_off = zp_off + 16 * spr;
     const uint32_t ent_off = guard_off + kWideGuard;
     const uint32_t red_off = ent_off + 32 * nthreads;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
@@ -558,14 +580,14 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int e_begin = row_ptr_k[row0], e_end = row_ptr_k[last_row];
     const int rp0 = row_ptr[n_c], rp1 = row_ptr[n_c + 1];
 
-    // The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for 16
-    // consecutive channels and adjacent in LDS: vector t of that range, t < 2 gpr a scales vector.
+    // The block's scales (32 spr bytes) and zero points (16 spr bytes), contiguous in memory for 16
+    // consecutive channels and adjacent in LDS: vector t of that range, t < 2 spr a scales vector.
     auto meta_vec = [&](int t) -> u32x4 {
-        const bool is_sc = t < 2 * gpr;
-        const int v_sc = block * 2 * gpr + t < sc_last_vec ? block * 2 * gpr + t : sc_last_vec;
-        const int v_zp = block * gpr + (t - 2 * gpr) < zp_last_vec ? block * gpr + (t - 2 * gpr) : zp_last_vec;
+        const bool is_sc = t < 2 * spr;
+        const int v_sc = block * 2 * spr + t < sc_last_vec ? block * 2 * spr + t : sc_last_vec;
+        const int v_zp = block * spr + (t - 2 * spr) < zp_last_vec ? block * spr + (t - 2 * spr) : zp_last_vec;
         const u32x4 *src = is_sc ? reinterpret_cast<const u32x4 *>(scales) : reinterpret_cast<const u32x4 *>(zeros);
-        return src[is_sc ? v_sc : (t < 3 * gpr ? v_zp : 0)];
+        return src[is_sc ? v_sc : (t < 3 * spr ? v_zp : 0)];
     };
     const u32x4 meta0 = meta_vec(tid);
     // The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin: thread t
@@ -603,8 +625,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             }
         __builtin_amdgcn_sched_barrier(0);
         if (ph == 0) {                                  // what was requested above for the whole tile
-            if (tid < 3 * gpr) *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * tid) = meta0;
-            for (int t = tid + nthreads; t < 3 * gpr; t += nthreads)
+            if (tid < 3 * spr) *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * tid) = meta0;
+            for (int t = tid + nthreads; t < 3 * spr; t += nthreads)
                 *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = meta_vec(t);
             if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
             store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
@@ -622,7 +644,36 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             }
         __syncthreads();                                // X of the phase and, first time, the tile's metadata
 
-        {
+        if constexpr (FINE) {
+            const uint16_t *sc_row = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * spr;
+            const uint8_t *zp_row = lds_raw + zp_off + r * spr;
+            constexpr uint32_t cap = BITS == 4 ? 0x6C43u : 0x7091u;         // largest scale with s * (2^bits - 1) finite in FP16
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                u32x4 xa[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
+                const int g = g_begin + u;
+                const uint32_t keep = g < gpr ? ~0u : 0u;                   // uniform over the wave
+                const int c0 = (g < gpr ? g : gpr - 1) * kGroup + 32 * b;   // first column of the lane's slot
+                const int i_lo = c0 >> shift, i_hi = (c0 + 16) >> shift;
+                uint32_t s_lo = sc_row[i_lo], s_hi = sc_row[i_hi];
+                s_lo = (s_lo < cap ? s_lo : cap) & keep;
+                s_hi = (s_hi < cap ? s_hi : cap) & keep;
+                const uint32_t z_lo = BITS == 3 ? zp_row[i_lo] & keep : zp_row[i_lo];
+                const uint32_t z_hi = BITS == 3 ? zp_row[i_hi] & keep : zp_row[i_hi];
+                u32x4 wb[4];
+                slot[u].decode_halves(z_lo, z_hi, b, dc, wb, tail_lane4);
+                scale_halves(wb, s_lo * 0x10001u, s_hi * 0x10001u);
+                float4v part = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[jj]),
+                                                                  __builtin_bit_cast(half8, wb[jj]), part, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += part[e];
+            }
+        } else {
             const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
             const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
 #pragma unroll
@@ -1112,7 +1163,8 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     const int waves_override = tune.waves;
     DecodeBatch batch;
     batch.M = M;
-    int blocks = 0, max_gpr = 1;
+    int blocks = 0, max_gpr = 1, max_spr = 1;
+    bool fine = false;                                  // groups below 128 (the caller passes layers of one group size)
     for (int i = 0; i < count; ++i) {
         const gwq_packed &L = *P[i];
         const int gpr = L.K / kGroup;
@@ -1123,7 +1175,12 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         d.Y = static_cast<_Float16 *>(Y[i]);
         d.N = L.N; d.K = L.K;
         // Last 16-byte vector of each staged array (the buffers are padded, so clamped reads stay inside).
-        const int64_t groups = (int64_t)L.N * gpr;
+        int shift = 7;
+        while ((1 << shift) > L.group) --shift;
+        d.group_shift = shift;
+        if (L.group < kGroup) fine = true;
+        const int64_t groups = (int64_t)L.N * (L.K / L.group);
+        if (L.K / L.group > max_spr) max_spr = L.K / L.group;
         d.sc_last_vec = (int)((groups * 2 + 15) / 16) - 1;
         d.zp_last_vec = (int)((groups + 15) / 16) - 1;
         d.csr_last_vec = (int)((L.n_outliers * 2 + 15) / 16);
@@ -1135,7 +1192,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     const size_t meta = (size_t)48 * max_gpr + 16;
 
     // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
-    if (M <= 4 && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
+    if (M <= 4 && !fine && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
         int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
         if (waves_override > 0) {                       // the most waves that do not exceed the request
             u = 4;
@@ -1161,7 +1218,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 
     // The streaming kernel: rows of at most 32 groups (8 waves of 4), XT[K][rows] in LDS.  By default for
     // the batches the lean kernel does not take.
-    if (tune.stream != 1 && (M > 4 || tune.stream == 2) && max_gpr <= 8 * kStreamU) {
+    if (!fine && tune.stream != 1 && (M > 4 || tune.stream == 2) && max_gpr <= 8 * kStreamU) {
         const int nwaves = (max_gpr + kStreamU - 1) / kStreamU, nthreads = 64 * nwaves;
         const int mr = M <= 4 ? 4 : M <= 8 ? 8 : 16;
         const size_t xt = (size_t)max_gpr * kGroup * 2 * mr, red = (size_t)2 * nwaves * 1024;
@@ -1216,7 +1273,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         size_t best_lds = 0;
         for (int u = 4; u <= (M <= 8 ? 8 : 4); u *= 2)   // 16 rows of 8 groups would not fit the registers
             for (int w = 1; w <= 8; ++w) {
-                const size_t lds = (size_t)M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_gpr + kWideGuard +
+                const size_t lds = (size_t)M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_spr + kWideGuard +
                                    2 * 16 * (size_t)w * 64 + (size_t)w * 1024;
                 if (lds > kMaxLds) continue;
                 const int ph = (max_gpr + w * u - 1) / (w * u);
@@ -1233,13 +1290,14 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
                 if (blocks > cap) blocks = cap;
             }
             if (describe) {
-                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d> grid %dx%d block %d lds %zu phases %d",
-                         bits, best_u, mr, blocks, count, 64 * best_w, best_lds, best_ph);
+                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d,%s> grid %dx%d block %d lds %zu phases %d",
+                         bits, best_u, mr, fine ? "true" : "false", blocks, count, 64 * best_w, best_lds, best_ph);
                 return hipSuccess;
             }
 #define GWQ_WIDE(B, UU, RR) \
     if (bits == B && best_u == UU && mr == RR) \
-        return launch_kernel<&decode_wide_kernel<B, UU, RR>>(batch, count, blocks, best_w, best_lds, st)
+        return fine ? launch_kernel<&decode_wide_kernel<B, UU, RR, true>>(batch, count, blocks, best_w, best_lds, st) \
+                    : launch_kernel<&decode_wide_kernel<B, UU, RR, false>>(batch, count, blocks, best_w, best_lds, st)
             GWQ_WIDE(4, 4, 8); GWQ_WIDE(4, 4, 16); GWQ_WIDE(4, 8, 8);
             GWQ_WIDE(3, 4, 8); GWQ_WIDE(3, 4, 16); GWQ_WIDE(3, 8, 8);
 #undef GWQ_WIDE

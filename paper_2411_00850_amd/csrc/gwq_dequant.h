@@ -106,6 +106,16 @@ __device__ inline void decode_slot4(const uint32_t w[4], uint32_t z, const Decod
     for (int j = 0; j < 4; ++j) f[j] = decode_word4(w[j], c, d);
 }
 
+// The same for a slot whose two halves (codes 0..15 and 16..31) have zero points of their own: groups of 16.
+__device__ inline void decode_slot4_halves(const uint32_t w[4], uint32_t z_lo, uint32_t z_hi, const DecodeConsts &d, u32x4 f[4])
+{
+    const ZeroConsts<4> c_lo(z_lo), c_hi(z_hi);
+    f[0] = decode_word4(w[0], c_lo, d);
+    f[1] = decode_word4(w[1], c_lo, d);
+    f[2] = decode_word4(w[2], c_hi, d);
+    f[3] = decode_word4(w[3], c_hi, d);
+}
+
 // 3-bit slot: words w[0..2] hold codes 0..29 (five pairs each), `tail_pair` holds codes 30, 31 in
 // bits 0..2 and 16..18 (the caller shifts the group's tail word by 3 * slot).
 __device__ inline void decode_slot3(const uint32_t w[3], uint32_t tail_pair, uint32_t z, const DecodeConsts &d,
@@ -125,6 +135,40 @@ __device__ inline void decode_slot3(const uint32_t w[3], uint32_t tail_pair, uin
     p[15] = pk_add(and_or(tail_pair, d.m0, d.k1024), c.c1024);
 #pragma unroll
     for (int j = 0; j < 4; ++j) f[j] = u32x4{p[4 * j], p[4 * j + 1], p[4 * j + 2], p[4 * j + 3]};
+}
+
+// The same with one zero point for codes 0..15 (pairs 0..7: word 0 and the first three pairs of word 1) and
+// one for codes 16..31.
+__device__ inline void decode_slot3_halves(const uint32_t w[3], uint32_t tail_pair, uint32_t z_lo, uint32_t z_hi,
+                                           const DecodeConsts &d, u32x4 f[4])
+{
+    const ZeroConsts<3> c_lo(z_lo), c_hi(z_hi);
+    uint32_t p[16];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t x = w[i], y = x >> 9;
+        const ZeroConsts<3> &c0 = i == 0 ? c_lo : c_hi;                     // pairs 5i+3, 5i+4
+        const ZeroConsts<3> &c1 = i <= 1 ? c_lo : c_hi;                     // pairs 5i .. 5i+2
+        p[5 * i + 0] = pk_add(and_or(x, d.m0, d.k1024), c1.c1024);
+        p[5 * i + 1] = pk_add(and_or(x, d.m1, d.kmid), c1.c128);
+        p[5 * i + 2] = pk_add(and_or(x, d.m2, d.k16), c1.c16);
+        p[5 * i + 3] = pk_add(and_or(y, d.m0, d.k1024), c0.c1024);
+        p[5 * i + 4] = pk_add(and_or(y, d.m1, d.kmid), c0.c128);
+    }
+    p[15] = pk_add(and_or(tail_pair, d.m0, d.k1024), c_hi.c1024);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f[j] = u32x4{p[4 * j], p[4 * j + 1], p[4 * j + 2], p[4 * j + 3]};
+}
+
+// f[0], f[1] (codes 0..15 of a slot) times the packed FP16 pair s_lo, f[2], f[3] times s_hi.
+__device__ inline void scale_halves(u32x4 f[4], uint32_t s_lo, uint32_t s_hi)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t s2 = j < 2 ? s_lo : s_hi;
+        f[j].x = pk_mul(f[j].x, s2); f[j].y = pk_mul(f[j].y, s2);
+        f[j].z = pk_mul(f[j].z, s2); f[j].w = pk_mul(f[j].w, s2);
+    }
 }
 
 }  // namespace gwq

@@ -100,12 +100,27 @@ __global__ __launch_bounds__(256) void group_index_kernel(const int32_t *__restr
             // The GEMM multiplies FP16 operands s * (q - z): a scale is capped at the largest FP16 value whose
             // product with 2^bits - 1 is still finite (only ranges beyond 65460 reach it; positive FP16
             // patterns order like integers).
-            const uint32_t sc = scales[row_group + g];
-            out[g] = GroupRecord{(int32_t)first, (sc < scale_cap ? sc : scale_cap) | (uint32_t)zeros[row_group + g] << 16};
+            const uint32_t sc = scales ? scales[row_group + g] : 0u, zp = scales ? zeros[row_group + g] : 0u;
+            out[g] = GroupRecord{(int32_t)first, (sc < scale_cap ? sc : scale_cap) | zp << 16};
         }
         first += mine[i];
     }
     if (lane == 0) out[gpr] = GroupRecord{row_ptr[n + 1], 0u};
+}
+
+// Layers quantised in groups of fewer than 128 weights (16, 32 or 64): per channel and block of 128 codes,
+// eight words scale bits | zero point << 16, one per 16 columns (a group's pair repeated over its columns),
+// so that a producer finds the two pairs of a slot's halves with one 8-byte load, whatever the group size.
+__global__ __launch_bounds__(256) void fine_index_kernel(const uint16_t *__restrict__ scales, const uint8_t *__restrict__ zeros,
+                                                         size_t count, int K, int group, uint32_t scale_cap,
+                                                         uint32_t *__restrict__ fine)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;           // (channel, 16-column piece)
+    if (i >= count) return;
+    const size_t n = i / (K / 16), piece = i % (K / 16);
+    const size_t g = n * (K / group) + piece * 16 / group;
+    const uint32_t sc = scales[g];
+    fine[i] = (sc < scale_cap ? sc : scale_cap) | (uint32_t)zeros[g] << 16;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -147,6 +162,7 @@ template <int BITS> struct GroupRegs {
     uint32_t col_lo, col_hi, val_lo, val_hi;
     int32_t next_first;
     uint32_t next_scale_zero;
+    uint32_t sub[4];                                    // small groups only: scale | zero << 16 of the halves of the two slots
 };
 
 // Fragment j (8 codes -> 8 FP16 values s*(q - z)) of a slot.
@@ -186,11 +202,14 @@ template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcn
 // split as well: `splits` blocks share a tile, block s of them takes groups s * split_groups onwards
 // and writes its FP32 sums to partial[s][M][N] instead of Y; splitk_reduce_kernel adds them up in
 // the order of s.
-template <int BITS, int MSW, int WN, int WM>
+// FINE: the layer's groups are smaller than 128; the producers take scale and zero point per half slot from `fine`
+// (fine_index_kernel) instead of the group's record.
+template <int BITS, int MSW, int WN, int WM, bool FINE>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
                                                         const uint16_t *__restrict__ col_idx,
                                                         const uint16_t *__restrict__ out_val,
                                                         const GroupRecord *__restrict__ rec,
+                                                        const uint32_t *__restrict__ fine,
                                                         const _Float16 *__restrict__ X, _Float16 *__restrict__ Y,
                                                         float *__restrict__ partial, int split_groups,
                                                         int N, int K, int M, int tiles_m, int tiles_n, int last_entry)
@@ -247,6 +266,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
         const uint32_t *q_row = qweight + ((size_t)b_n * gpr + g_first) * wpg;       // group numbers below are local
         const GroupRecord *r_row = rec + (size_t)b_n * (gpr + 1) + g_first;
+        const uint32_t *f_row = fine + ((size_t)b_n * gpr + g_first) * 8 + 2 * b_h;
         _Float16 *const b_dst = lds_w + b_n_local * kLd;                    // + buffer
 
         // Requests for group g (clamped: the last trips ask for groups past the row's end and use
@@ -261,6 +281,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             G.col_lo = c.lo; G.col_hi = c.hi; G.val_lo = v.lo; G.val_hi = v.hi;
             const GroupRecord r = r_row[g + 1];
             G.next_first = r.first; G.next_scale_zero = r.scale_zero;
+            if constexpr (FINE) {
+                const uint2 a = *reinterpret_cast<const uint2 *>(f_row + (uint32_t)g * 8);
+                const uint2 c2 = *reinterpret_cast<const uint2 *>(f_row + (uint32_t)g * 8 + 4);
+                G.sub[0] = a.x; G.sub[1] = a.y; G.sub[2] = c2.x; G.sub[3] = c2.y;
+            }
         };
 
         // Staging of step `step` (of a group with scale and zero point sz, `cnt` outliers from CSR
@@ -275,7 +300,19 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             _Float16 *brow = b_dst + buf * kWBufHalves;
             const int half = step & 1;
             const uint32_t s2 = (sz & 0xFFFFu) * 0x10001u, z = sz >> 16;
-            if constexpr (BITS == 4) {
+            if constexpr (FINE) {
+                const uint32_t lo = G.sub[2 * half], hi = G.sub[2 * half + 1];
+                u32x4 f[4];
+                if constexpr (BITS == 4) {
+                    decode_slot4_halves(G.slot[half].w, lo >> 16, hi >> 16, dc, f);
+                } else {
+                    const uint32_t tail = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)G.slot[1].fourth, 0xF5, 0xF, 0xF, false);
+                    decode_slot3_halves(G.slot[half].w, tail >> (3 * (2 * half + b_h)), lo >> 16, hi >> 16, dc, f);
+                }
+                scale_halves(f, (lo & 0xFFFFu) * 0x10001u, (hi & 0xFFFFu) * 0x10001u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = f[j];
+            } else if constexpr (BITS == 4) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = dequant_frag(G.slot[half], j, z, s2, dc);
@@ -507,6 +544,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 // kCUs is the compute-unit count of the MI355X, which the scratch size reported by gwq_layout (a pure host
 // call) is based on; a launch plans with the current device's count, never beyond kCUs.
 constexpr int kMaxSplits = 8, kSplitBelowTiles = 160, kCUs = 256;
+size_t record_bytes(int64_t N, int64_t K) { return ((size_t)(N * (K / kGroup + 1)) * sizeof(GroupRecord) + 255) / 256 * 256; }
 int launch_cus()
 {
     const int n = device_cus();
@@ -565,7 +603,7 @@ int choose_rows(int M, int N, int K, bool have_scratch)
     return best;
 }
 
-template <int BITS, int MSW, int WN, int WM>
+template <int BITS, int MSW, int WN, int WM, bool FINE>
 hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, float *partial,
                      size_t partial_bytes, hipStream_t st, PlanText *describe)
 {
@@ -578,17 +616,19 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
     if (splits == 1) partial = nullptr;
     const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
     if (describe) {
-        snprintf(describe->text, sizeof(describe->text), "gemm_kernel<%d,%d,%d,%d> tile %dx%d grid %d block %d lds %zu k_splits %d",
-                 BITS, MSW, WN, WM, BM, kBN, tiles_m * tiles_n * splits, kThreads, lds, splits);
+        snprintf(describe->text, sizeof(describe->text), "gemm_kernel<%d,%d,%d,%d,%s> tile %dx%d grid %d block %d lds %zu k_splits %d",
+                 BITS, MSW, WN, WM, FINE ? "true" : "false", BM, kBN, tiles_m * tiles_n * splits, kThreads, lds, splits);
         return hipSuccess;
     }
     static std::atomic<uint32_t> lds_allowed{0};        // per instantiation
     {
-        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM>), (int)lds, lds_allowed);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM, FINE>), (int)lds, lds_allowed);
         if (e != hipSuccess) return e;
     }
-    gemm_kernel<BITS, MSW, WN, WM><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
-        P.qweight, P.col_idx, P.out_val, rec, static_cast<const _Float16 *>(X),
+    // The half-slot pairs of a layer with small groups follow the records.
+    const uint32_t *fine = reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(rec) + record_bytes(P.N, P.K));
+    gemm_kernel<BITS, MSW, WN, WM, FINE><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
+        P.qweight, P.col_idx, P.out_val, rec, fine, static_cast<const _Float16 *>(X),
         static_cast<_Float16 *>(Y), partial, split_groups, P.N, P.K, M, tiles_m, tiles_n,
         P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
     hipError_t e = hipGetLastError();
@@ -600,7 +640,10 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
 
 }  // namespace
 
-size_t gemm_index_bytes(int64_t N, int64_t K) { return ((size_t)(N * (K / kGroup + 1)) * sizeof(GroupRecord) + 255) / 256 * 256; }
+size_t gemm_index_bytes(int64_t N, int64_t K, int group)
+{
+    return record_bytes(N, K) + (group < kGroup ? ((size_t)N * (K / 16) * 4 + 255) / 256 * 256 : 0);
+}
 
 // Scratch for the FP32 partial sums of a K-split launch with up to M_max rows.  Splitting stops
 // where splits x tiles reaches the CU count, so splits * M * N never exceeds that many tiles' worth.
@@ -616,8 +659,18 @@ hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t s
 {
     // 4364 * 15 = 65460 and 9352 * 7 = 65464: the last scales on the FP16 grid that keep s * (q - z) finite.
     const uint32_t scale_cap = P.bits == 4 ? 0x6C43u : 0x7091u;
-    group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.scales, P.zeros, P.N, P.K / kGroup,
+    if (P.group == kGroup) {
+        group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, P.scales, P.zeros, P.N, P.K / kGroup,
+                                                         scale_cap, static_cast<GroupRecord *>(workspace));
+        return hipGetLastError();
+    }
+    // Small groups: the records carry the outlier index alone (scale and zero point come from the pairs behind them).
+    group_index_kernel<<<(P.N + 3) / 4, 256, 0, st>>>(P.row_ptr, P.col_idx, nullptr, nullptr, P.N, P.K / kGroup,
                                                      scale_cap, static_cast<GroupRecord *>(workspace));
+    const size_t count = (size_t)P.N * (P.K / 16);
+    fine_index_kernel<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(
+        P.scales, P.zeros, count, P.K, P.group, scale_cap,
+        reinterpret_cast<uint32_t *>(static_cast<char *>(workspace) + record_bytes(P.N, P.K)));
     return hipGetLastError();
 }
 
@@ -632,13 +685,17 @@ hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const
     // LDS is what bounds a step.
     const int rows = ms_override ? ms_override : choose_rows(M, (int)P.N, (int)P.K, part != nullptr);
     const int shape = rows == 256 ? 2 : rows == 128 ? 1 : rows == 64 ? 0 : 3;
-#define GWQ_GEMM(B) \
-    return shape == 2   ? launch_ms<B, 2, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
-           : shape == 1 ? launch_ms<B, 1, 2, 4>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
-           : shape == 0 ? launch_ms<B, 1, 4, 2>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
-                        : launch_ms<B, 1, 4, 1>(P, X, M, Y, rec, part, scratch_bytes, st, describe)
-    if (P.bits == 4) GWQ_GEMM(4);
-    GWQ_GEMM(3);
+#define GWQ_GEMM(B, F) \
+    return shape == 2   ? launch_ms<B, 2, 2, 4, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+           : shape == 1 ? launch_ms<B, 1, 2, 4, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+           : shape == 0 ? launch_ms<B, 1, 4, 2, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+                        : launch_ms<B, 1, 4, 1, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe)
+    if (P.group == kGroup) {
+        if (P.bits == 4) GWQ_GEMM(4, false);
+        GWQ_GEMM(3, false);
+    }
+    if (P.bits == 4) GWQ_GEMM(4, true);
+    GWQ_GEMM(3, true);
 #undef GWQ_GEMM
 }
 

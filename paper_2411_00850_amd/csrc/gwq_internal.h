@@ -51,10 +51,11 @@ struct PlanText {
 };
 hipError_t launch_decode(int count, const gwq_packed *const *P, const void *const *X, int M, void *const *Y,
                          const DecodeTuning &tune, hipStream_t stream, PlanText *describe = nullptr);
-// index: gemm_index_bytes(N, K) bytes, 16-byte aligned (one record per channel and group: index of the
-// group's first outlier, scale, zero point; a multiple of 256 bytes).  scratch: gemm_scratch_bytes(N, M_max)
+// index: gemm_index_bytes(N, K, group) bytes, 16-byte aligned (one record per channel and block of 128 codes:
+// index of the block's first outlier, scale, zero point; for groups below 128 also a scale / zero-point pair
+// per 16 columns; a multiple of 256 bytes).  scratch: gemm_scratch_bytes(N, M_max)
 // bytes for the partial sums of launches that also split K (may be NULL: then K is never split).
-size_t gemm_index_bytes(int64_t N, int64_t K);
+size_t gemm_index_bytes(int64_t N, int64_t K, int group);
 size_t gemm_scratch_bytes(int64_t N, int64_t M_max);
 hipError_t launch_gemm_index(const gwq_packed &P, void *index, hipStream_t stream);        // fills the records
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,

@@ -1,5 +1,5 @@
 // gwq_pack on gfx950: outlier selection (Sec. 3.2, Eq. 8) as a three-pass (FP16 scores: two-pass) radix select over the
-// bit patterns of |score|, CSR build in flat-index order, then per (row, group of 128) the scale,
+// bit patterns of |score|, CSR build in flat-index order, then per (row, group of 16 to 128) the scale,
 // zero point and codes of Eq. 6, 7 and 9 and the word layout documented in gwq.h.
 //
 // Everything is integer work or exactly specified IEEE arithmetic (fp64 division, round half to
@@ -252,11 +252,11 @@ template <int BITS> __device__ inline void scale_and_zero(float mn, float mx, ui
 }
 
 // One block per output channel n.  Walks the row in flat-index order: marks the kept entries,
-// appends them to the CSR arrays, and quantises + packs each group of 128.
+// appends them to the CSR arrays, and quantises each group (16 to 128 weights: 2 to 16 consecutive threads) and packs each block of 128 codes.
 template <int BITS, bool F16>
 __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__restrict__ W,
                                                           const void *__restrict__ score, int N, int K,
-                                                          const uint32_t *__restrict__ ws,
+                                                          int group, const uint32_t *__restrict__ ws,
                                                           const int32_t *__restrict__ row_ptr,
                                                           uint32_t *__restrict__ qweight,
                                                           uint16_t *__restrict__ scales,
@@ -271,6 +271,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
 
     const int n = blockIdx.x, tid = threadIdx.x;
     const int gpr = K / kGroup;
+    const int spr = K / group, lanes = group / 8;       // scale groups per row; threads that share one
     const uint32_t thr = ws[kWsPrefix];
     const uint32_t take = ws[kWsRows + 2 * N + n];
     uint32_t ties_seen = 0, gt_seen = 0;                // of the chunks before the current one
@@ -319,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
         ties_seen += both_total >> 16;
         gt_seen += both_total & 0xFFFFu;
 
-        // Masked min / max of the group (range always contains 0), reduced over 16 lanes.
+        // Masked min / max of the group (range always contains 0), reduced over the group's 2 to 16 lanes.
         float mn = 0.f, mx = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -331,8 +332,8 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
 #pragma unroll
         for (int d = 1; d < 16; d <<= 1) {
             const float a = __shfl_xor(mn, d), b = __shfl_xor(mx, d);
-            mn = a < mn ? a : mn;
-            mx = b > mx ? b : mx;
+            mn = d < lanes && a < mn ? a : mn;
+            mx = d < lanes && b > mx ? b : mx;
         }
         uint16_t s_bits;
         int z;
@@ -353,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
             code[i] = (sel_mask >> i & 1) ? (uint32_t)z : (uint32_t)q;
         }
 
-        const int g = k / kGroup;           // group index within the row
+        const int g = k / kGroup;           // block of 128 codes within the row
         const int j = tid & 15;             // this thread's 8 codes are k_local = 8j .. 8j+7
         if (BITS == 4) {
             uint32_t word = 0;
@@ -380,9 +381,9 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
                 qweight[((size_t)n * gpr + g) * wpg + j] = word;
             }
         }
-        if (active && j == 0) {
-            scales[(size_t)n * gpr + g] = s_bits;
-            zeros[(size_t)n * gpr + g] = (uint8_t)z;
+        if (active && (tid & (lanes - 1)) == 0) {
+            scales[(size_t)n * spr + k / group] = s_bits;
+            zeros[(size_t)n * spr + k / group] = (uint8_t)z;
         }
     }
 }
@@ -415,7 +416,7 @@ hipError_t run_select(const void *score, int N, int K, uint32_t *ws, int32_t *ro
 template <int BITS, bool F16>
 hipError_t run_encode(const void *W, const void *score, const gwq_packed &P, const uint32_t *ws, hipStream_t st)
 {
-    encode_kernel<BITS, F16><<<P.N, kThreads, 0, st>>>(static_cast<const uint16_t *>(W), score, P.N, P.K, ws,
+    encode_kernel<BITS, F16><<<P.N, kThreads, 0, st>>>(static_cast<const uint16_t *>(W), score, P.N, P.K, P.group, ws,
                                                        P.row_ptr, P.qweight, P.scales, P.zeros, P.col_idx,
                                                        P.out_val);
     return hipGetLastError();

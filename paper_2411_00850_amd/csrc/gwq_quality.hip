@@ -80,12 +80,12 @@ __global__ __launch_bounds__(kQThreads) void quality_kernel(const uint32_t *__re
                                                             const uint16_t *__restrict__ col_idx,
                                                             const uint16_t *__restrict__ out_val,
                                                             const _Float16 *__restrict__ W, const void *__restrict__ score,
-                                                            int K, Merit *__restrict__ partial)
+                                                            int K, int group, Merit *__restrict__ partial)
 {
     __shared__ uint32_t kept[65536 / 32];               // one bit per column: kept as an outlier
     __shared__ Merit wave_part[kQThreads / 64];
     const int n = blockIdx.x, tid = threadIdx.x;
-    const int gpr = K / kGroup;
+    const int gpr = K / kGroup, spr = K / group;        // blocks of 128 codes and scale groups per row
     const size_t row = (size_t)n * K;
     Merit m{0.0, 0.0, 0.0};
 
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kQThreads) void quality_kernel(const uint32_t *__re
     auto fetch = [&](int k0, Chunk<BITS, F16> &c) {
         k0 = k0 < K ? k0 : K - 8;
         const int g = k0 / kGroup, slot = (k0 % kGroup) >> 5, j8 = (k0 & 31) >> 3;
-        const uint32_t *group = qweight + ((size_t)n * gpr + g) * words_per_group(BITS);
+        const uint32_t *words = qweight + ((size_t)n * gpr + g) * words_per_group(BITS);
         c.w = *reinterpret_cast<const uint4 *>(W + row + k0);
         if (F16) {
             c.g[0] = *reinterpret_cast<const uint4 *>(static_cast<const _Float16 *>(score) + row + k0);
@@ -102,13 +102,13 @@ __global__ __launch_bounds__(kQThreads) void quality_kernel(const uint32_t *__re
             c.g[F16 ? 0 : 1] = *reinterpret_cast<const uint4 *>(static_cast<const float *>(score) + row + k0 + 4);
         }
         if (BITS == 4) {
-            c.code[0] = group[4 * slot + j8];
+            c.code[0] = words[4 * slot + j8];
         } else {
-            c.code[0] = group[3 * slot]; c.code[1] = group[3 * slot + 1]; c.code[2] = group[3 * slot + 2];
-            c.code[BITS == 4 ? 0 : 3] = group[12];
+            c.code[0] = words[3 * slot]; c.code[BITS == 4 ? 0 : 1] = words[3 * slot + 1]; c.code[BITS == 4 ? 0 : 2] = words[3 * slot + 2];
+            c.code[BITS == 4 ? 0 : 3] = words[12];
         }
-        c.scale = scales[(size_t)n * gpr + g];
-        c.zero = zeros[(size_t)n * gpr + g];
+        c.scale = scales[(size_t)n * spr + k0 / group];
+        c.zero = zeros[(size_t)n * spr + k0 / group];
     };
     auto consume = [&](int k0, const Chunk<BITS, F16> &c) {
         if (k0 >= K) return;
@@ -202,7 +202,7 @@ hipError_t launch_quality(const gwq_packed &P, const void *W, const void *score,
     const _Float16 *w = static_cast<const _Float16 *>(W);
 #define GWQ_QUALITY(B, F) \
     quality_kernel<B, F><<<P.N, kQThreads, 0, st>>>(P.qweight, P.scales, P.zeros, P.row_ptr, P.col_idx, P.out_val, w, \
-                                                    score, P.K, partial)
+                                                    score, P.K, P.group, partial)
     if (P.bits == 4) {
         if (score_is_f16) GWQ_QUALITY(4, true); else GWQ_QUALITY(4, false);
     } else {

@@ -20,7 +20,8 @@ def upload_packed(P, pad_byte=0x5A):
     import torch
 
     n_out = int(P.row_ptr[-1])
-    sizes = gwq.layout(P.N, P.K, P.bits, 128, 0)       # scales / zeros sizes do not depend on ppm
+    group = getattr(P, "group", 128)
+    sizes = gwq.layout(P.N, P.K, P.bits, group, 0)     # scales / zeros sizes do not depend on ppm
 
     def dev(a, dt, nbytes=None):
         a = np.ascontiguousarray(a).ravel()
@@ -35,14 +36,14 @@ def upload_packed(P, pad_byte=0x5A):
                     dev(P.qweight, np.int32).view(P.N, P.K // 128, -1),
                     dev(P.scales, np.int16, sizes["scales"]), dev(P.zeros, np.uint8, sizes["zeros"]),
                     dev(P.row_ptr, np.int32), dev(P.col_idx, np.int16, csr_bytes),
-                    dev(P.out_val, np.int16, csr_bytes))
+                    dev(P.out_val, np.int16, csr_bytes), None, group)
     return D
 
 
 def download_packed(D):
     """Device PackedLayer -> dict of numpy arrays with the unsigned dtypes of the format."""
     k = D.n_outliers
-    g = D.N * (D.K // 128)
+    g = D.N * (D.K // D.group)
     return dict(qweight=D.qweight.cpu().numpy().view(np.uint32),
                 scales=D.scales.cpu().numpy().view(np.uint16).ravel()[:g],
                 zeros=D.zeros.cpu().numpy().ravel()[:g],

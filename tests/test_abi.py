@@ -52,12 +52,28 @@ def test_layout_sizes_7b_shapes():
 @pytest.mark.parametrize("args, status", [
     ((0, 128, 4, 128, 10000, 1), -2), ((4, 100, 4, 128, 10000, 1), -2), ((4, 0, 4, 128, 10000, 1), -2),
     ((4, 65536 + 128, 4, 128, 10000, 1), -2), ((70000, 65536, 4, 128, 10000, 1), -2),
-    ((4, 128, 5, 128, 10000, 1), -3), ((4, 128, 2, 128, 10000, 1), -3), ((4, 128, 4, 64, 10000, 1), -3),
+    ((4, 128, 5, 128, 10000, 1), -3), ((4, 128, 2, 128, 10000, 1), -3), ((4, 128, 4, 48, 10000, 1), -3),
+    ((4, 128, 4, 8, 10000, 1), -3), ((4, 128, 4, 256, 10000, 1), -3), ((4, 128, 4, 0, 10000, 1), -3),
+    ((4, 65536, 4, 16, 10000, 1), -2), ((4, 32768 + 128, 4, 16, 10000, 1), -2),        # more than 2048 groups per channel
     ((4, 128, 4, 128, 1000001, 1), -2), ((4, 128, 4, 128, 10000, -1), -2),
 ])
 def test_layout_rejects_bad_arguments(args, status):
     s = binding._Sizes()
     assert binding.lib().gwq_layout(*args, ctypes.byref(s)) == status
+
+
+def test_layout_sizes_of_small_groups():
+    """Group sizes 16, 32 and 64 (Sec. 3.2 sets 16): the code words do not change, scales and zero points
+    are one per group, and the index for M > 16 grows by one 4-byte pair per 16 columns."""
+    base = gwq.layout(4096, 4096, 4)
+    for group in (16, 32, 64):
+        s = gwq.layout(4096, 4096, 4, group)
+        per_row = 4096 // group
+        assert s["qweight"] == base["qweight"] and s["col_idx"] == base["col_idx"] and s["n_outliers"] == base["n_outliers"]
+        assert s["scales"] == 4096 * per_row * 2 + 16 and s["zeros"] == 4096 * per_row + 16
+        assert s["linear_index"] == base["linear_index"] + 4096 * (4096 // 16) * 4
+    assert gwq.layout(4, 32768, 3, 16)["scales"] == 4 * 2048 * 2 + 16          # the most groups per channel
+    assert gwq.layout(4, 65536, 3, 32)["zeros"] == 4 * 2048 + 16
 
 
 def test_layout_null_out():
@@ -94,7 +110,7 @@ def test_pack_and_linear_validate_before_touching_the_device():
     assert L.gwq_linear(ctypes.byref(ok), None, 1, fake, None, 0, None) == -1
     assert L.gwq_linear(ctypes.byref(ok), fake, 1, None, None, 0, None) == -1
     assert L.gwq_linear(ctypes.byref(ok), fake, 0, fake, None, 0, None) == -2
-    assert L.gwq_linear(ctypes.byref(_packed(group=64)), fake, 1, fake, None, 0, None) == -3
+    assert L.gwq_linear(ctypes.byref(_packed(group=48)), fake, 1, fake, None, 0, None) == -3
     assert L.gwq_linear(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4       # M > 16 needs scratch
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, fake, 8, None) == -4
@@ -153,9 +169,11 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert plan([q, q, q], 1).startswith("decode_small_kernel<4,8,1> grid 256x3")
     assert plan([down], 1).startswith("decode_small_kernel<4,8,1> grid 256x1 block 704")
     assert plan([gate, gate], 16).startswith("decode_stream_kernel<4,16>")          # several tiles per block
-    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16>")                  # one tile per block
+    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16,false>")                  # one tile per block
     assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_wide_kernel<3,")
-    assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4> tile 256x128 grid 256 ")
+    assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4,false> tile 256x128 grid 256 ")
+    q16 = _packed(N=4096, K=4096, group=16)               # groups of 16: the wide decode kernel and the GEMM in their small-group forms
+    assert plan([q16], 1).startswith("decode_wide_kernel<4,4,8,true>") and plan([q16], 2048).startswith("gemm_kernel<4,2,2,4,true>")
     assert "k_splits 1" in plan([q], 64, scratch=0) and "k_splits 1" not in plan([q], 64, scratch=1)
     arr = (ctypes.POINTER(binding._Packed) * 2)(ctypes.pointer(q), ctypes.pointer(down))
     assert L.gwq_linear_plan(2, arr, 1, 1, buf, 256) == -2                          # one K per launch
