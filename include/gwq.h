@@ -58,6 +58,7 @@ typedef enum {
     GWQ_ERR_DEVICE = -5       /* a HIP call failed                                        */
 } gwq_status;
 
+/* Passed as int32_t: a value outside the enumeration is answered with GWQ_ERR_UNSUPPORTED, not undefined. */
 typedef enum { GWQ_SCORE_F32 = 0, GWQ_SCORE_F16 = 1 } gwq_score_dtype;
 
 /* View of one packed layer.  Scalars are filled by the caller (n_outliers from gwq_layout). */
@@ -110,7 +111,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
  *           when it is not NULL)
  *   workspace device scratch of >= pack_workspace bytes, 4-byte aligned; W_f16 and score 16-byte aligned
  * The result is a function of the inputs only (bit-exact, run-to-run identical). */
-gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_dtype,
+gwq_status gwq_pack(const void *W_f16, const void *score, int32_t score_dtype,
                     gwq_packed *dst, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Y[M][N] = X[M][K] * (Q(W) + outliers)^T with Q(W) = s*(q-z) (Eq. 10), FP32 accumulation,
@@ -186,7 +187,7 @@ gwq_status gwq_linear_batch(int32_t count, const gwq_packed *const *P, const voi
  *   workspace device, >= quality_workspace bytes as gwq_layout reports, 8-byte aligned.
  * Every D is exact (fp64 from FP16 operands); the sums are fp64 in a fixed order, so the results are
  * identical from run to run.  Inputs are expected to be finite. */
-gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, gwq_score_dtype score_dtype,
+gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, int32_t score_dtype,
                        double *out_f64, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The score that gwq_pack ranks, for one linear layer (Sec. 3.1, Eq. 2: the gradient of the loss with

@@ -11,7 +11,8 @@ import os
 from dataclasses import dataclass
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libgwq.so")
+# GWQ_SANITIZE_HOST=1: the checking build of the library (host code under the sanitizers; see build.py), CPU-side tests only
+_LIB_PATH = os.path.join(HERE, "libgwq_san.so" if os.environ.get("GWQ_SANITIZE_HOST", "") == "1" else "libgwq.so")
 
 GWQ_OK = 0
 SCORE_F32, SCORE_F16 = 0, 1
@@ -58,7 +59,7 @@ def lib():
             if torch is not None and torch.cuda.is_initialized():
                 raise RuntimeError("libgwq.so is not built and this process already uses the GPU: run "
                                    "__graft_entry__.build() (or python -m paper_2411_00850_amd.build) first")
-            _build.build()
+            _build.build(sanitize_host=_LIB_PATH.endswith("libgwq_san.so"))
         elif _build.stale():
             import warnings
             warnings.warn("libgwq.so is older than its sources: rebuild with __graft_entry__.build()")

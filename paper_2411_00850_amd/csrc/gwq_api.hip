@@ -152,7 +152,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     return GWQ_OK;
 }
 
-gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_dtype, gwq_packed *dst,
+gwq_status gwq_pack(const void *W_f16, const void *score, int32_t score_dtype, gwq_packed *dst,
                     void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!W_f16 || !score) return GWQ_ERR_NULL;
@@ -167,7 +167,7 @@ gwq_status gwq_pack(const void *W_f16, const void *score, gwq_score_dtype score_
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 
-gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, gwq_score_dtype score_dtype,
+gwq_status gwq_quality(const gwq_packed *P, const void *W_f16, const void *score, int32_t score_dtype,
                        double *out_f64, void *workspace, size_t workspace_bytes, void *stream)
 {
     gwq_status s = check_packed(P);
