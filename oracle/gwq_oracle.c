@@ -394,22 +394,52 @@ int gwq_oracle_decode(int64_t N, int64_t K, int bits, int group, const uint32_t 
 
 /* Y[m, j] = sum_k X[m, k] * W_hat[rows[j], k] in fp64, k ascending; Y is [M][n_rows].
  * rows == NULL means rows 0..n_rows-1 (n_rows = N gives the full product Y[M][N]). */
+static int linear_checked(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
+                          const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
+                          const uint16_t *col_idx, const uint16_t *out_val,
+                          const double *Xd, int64_t M, const int32_t *rows, int64_t n_rows,
+                          double *Y);
+
 int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
                           const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
                           const uint16_t *col_idx, const uint16_t *out_val,
                           const uint16_t *X, int64_t M, const int32_t *rows, int64_t n_rows,
                           double *Y)
 {
-    if (!qweight || !scales || !zeros || !row_ptr || !X || !Y) return GWQ_ORACLE_BAD_ARG;
+    if (!X || M <= 0 || K <= 0) return GWQ_ORACLE_BAD_ARG;
+    double *Xd = (double *)malloc((size_t)(M * K) * sizeof(double));
+    if (!Xd) return GWQ_ORACLE_NO_MEM;
+    for (int64_t i = 0; i < M * K; ++i) Xd[i] = gwq_oracle_half_to_double(X[i]);
+    int rc = linear_checked(N, K, bits, group, qweight, scales, zeros, row_ptr, col_idx, out_val, Xd, M, rows, n_rows, Y);
+    free(Xd);
+    return rc;
+}
+
+/* The same product for activations given as fp64 values (any 16-bit type widens to fp64 exactly; the caller
+ * widens): the method fixes the weights' format, not the activations' (Sec. 3.2 quantises W only). */
+int gwq_oracle_linear_f64_x(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
+                            const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
+                            const uint16_t *col_idx, const uint16_t *out_val,
+                            const double *Xd, int64_t M, const int32_t *rows, int64_t n_rows,
+                            double *Y)
+{
+    if (!Xd) return GWQ_ORACLE_BAD_ARG;
+    return linear_checked(N, K, bits, group, qweight, scales, zeros, row_ptr, col_idx, out_val, Xd, M, rows, n_rows, Y);
+}
+
+static int linear_checked(int64_t N, int64_t K, int bits, int group, const uint32_t *qweight,
+                          const uint16_t *scales, const uint8_t *zeros, const int32_t *row_ptr,
+                          const uint16_t *col_idx, const uint16_t *out_val,
+                          const double *Xd, int64_t M, const int32_t *rows, int64_t n_rows,
+                          double *Y)
+{
+    if (!qweight || !scales || !zeros || !row_ptr || !Xd || !Y) return GWQ_ORACLE_BAD_ARG;
     if (N <= 0 || K <= 0 || K % GWQ_GROUP || M <= 0 || n_rows < 0 || (bits != 3 && bits != 4) || !group_ok(group))
         return GWQ_ORACLE_BAD_ARG;
     if (rows)
         for (int64_t j = 0; j < n_rows; ++j)
             if (rows[j] < 0 || rows[j] >= N) return GWQ_ORACLE_BAD_ARG;
     if (!rows && n_rows > N) return GWQ_ORACLE_BAD_ARG;
-    double *Xd = (double *)malloc((size_t)(M * K) * sizeof(double));
-    if (!Xd) return GWQ_ORACLE_NO_MEM;
-    for (int64_t i = 0; i < M * K; ++i) Xd[i] = gwq_oracle_half_to_double(X[i]);
     int failed = 0;
 #pragma omp parallel
     {
@@ -433,7 +463,6 @@ int gwq_oracle_linear_f64(int64_t N, int64_t K, int bits, int group, const uint3
         }
         free(w_hat);
     }
-    free(Xd);
     return failed ? GWQ_ORACLE_NO_MEM : GWQ_ORACLE_OK;
 }
 

@@ -31,6 +31,7 @@ def _load():
     lib.gwq_oracle_pack.argtypes = [vp, vp, i32, i64, i64, i32, i32, u32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_decode.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.gwq_oracle_linear_f64.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
+    lib.gwq_oracle_linear_f64_x.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, vp]
     lib.gwq_oracle_quality.argtypes = [i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
     lib.gwq_oracle_gate_up.argtypes = [vp, vp, i64, vp]
     lib.gwq_oracle_score.argtypes = [vp, vp, i64, i64, i64, ctypes.c_double, ctypes.c_double, vp, vp]
@@ -193,6 +194,28 @@ def linear_f64(P, X, rows=None):
     _chk(_lib.gwq_oracle_linear_f64(P.N, P.K, P.bits, P.group, _p(P.qweight), _p(P.scales), _p(P.zeros),
                                     _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(Xb), M,
                                     _p(rows_arr), n_rows, _p(Y)), "linear_f64")
+    return Y
+
+
+def bf16_bits_to_f64(bits):
+    """The values of bfloat16 bit patterns (uint16: the upper half of a binary32) as fp64: an exact widening."""
+    return (np.ascontiguousarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def linear_f64_x(P, Xd, rows=None):
+    """linear_f64 for activations given as an fp64 array [M, K] (bfloat16 inputs widened by bf16_bits_to_f64)."""
+    Xd = np.ascontiguousarray(Xd, np.float64)
+    M, K = Xd.shape
+    assert K == P.K
+    if rows is None:
+        rows_arr, n_rows = None, P.N
+    else:
+        rows_arr = np.ascontiguousarray(rows, np.int32)
+        n_rows = rows_arr.size
+    Y = np.empty((M, n_rows), np.float64)
+    _chk(_lib.gwq_oracle_linear_f64_x(P.N, P.K, P.bits, P.group, _p(P.qweight), _p(P.scales), _p(P.zeros),
+                                      _p(P.row_ptr), _p(P.col_idx), _p(P.out_val), _p(Xd), M,
+                                      _p(rows_arr), n_rows, _p(Y)), "linear_f64_x")
     return Y
 
 

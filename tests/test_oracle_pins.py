@@ -503,6 +503,16 @@ def test_decode_and_linear_match_numpy(bits, group):
     assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
     rows = np.array([19, 0, 7], np.int32)
     assert np.allclose(orc.linear_f64(P, X, rows), want[:, rows], rtol=1e-12, atol=1e-12)
+    # activations handed over as fp64 values: the same sums bit for bit when they are FP16 values, and the numpy
+    # product for bfloat16 values (widened exactly from their bit patterns: 1.0, -2.5, 2^-20, 3 * 2^100)
+    assert np.array_equal(orc.linear_f64_x(P, X.astype(np.float64)), got)
+    assert np.array_equal(orc.bf16_bits_to_f64(np.array([0x3F80, 0xC020, 0x3580, 0x7240, 0x0000, 0x8000], np.uint16)),
+                          np.array([1.0, -2.5, 2.0 ** -20, 3 * 2.0 ** 100, 0.0, -0.0]))
+    Xb = (rng.standard_normal((3, K)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    Xb[0, :4] = [0x7240, 0x0A00, 0x3F80, 0xC020]          # far outside the FP16 range on both ends
+    Xd = orc.bf16_bits_to_f64(Xb)
+    assert np.allclose(orc.linear_f64_x(P, Xd), Xd @ What.T, rtol=1e-12, atol=0)
+    assert np.allclose(orc.linear_f64_x(P, Xd, rows), (Xd @ What.T)[:, rows], rtol=1e-12, atol=0)
     # sanity, not parity: the quantised layer is close to the FP16 layer, closer at 4 bits than at 3
     ref = X.astype(np.float64) @ W.astype(np.float64).T
     rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
