@@ -328,7 +328,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the M=4/16, prefill and pack legs")
     ap.add_argument("--extras", default="all", metavar="LIST",
-                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,beta,pack,rows,loop (default: all)")
+                    help="comma-separated extra legs to run: m,groups,big,fp16,prefill,int3,beta,bf16,pack,rows,loop (default: all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU runs are out of scope.")
@@ -516,7 +516,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    legs = set("m,groups,big,fp16,prefill,int3,beta,pack,rows,loop".split(",")) if args.extras == "all" else set(args.extras.split(","))
+    legs = set("m,groups,big,fp16,prefill,int3,beta,bf16,pack,rows,loop".split(",")) if args.extras == "all" else set(args.extras.split(","))
     if not args.no_extras:
         extra = {}
         for M in (4, 16) if "m" in legs else ():
@@ -793,6 +793,40 @@ def main():
                 beta[f"group_{group}"] = row
                 torch.cuda.empty_cache()
             extra["int4_smaller_groups"] = beta
+        # gwq_linear_bf16 on the 4-bit layer: bfloat16 activations and results.  Decode M = 1 and 16 (the kernel for any
+        # M <= 16 takes these; rotating copies, one launch per matrix, replayed from a graph) and the prefill pass.
+        if "bf16" in legs:
+            bf = {}
+            for M in (1, 16, 2048):
+                xs = {K: torch.from_numpy(gs.activations(M, K, gs.rng_for(2, 100, K))).to(dev).to(torch.bfloat16) for K in (4096, 11008)}
+                ys = [torch.empty((M, P.N), dtype=torch.bfloat16, device=dev) for P in layers]
+                ws = [gwq.linear_workspace(P, M, dev) for P in layers]
+                sets = copies if M <= 16 else copies[:1]
+
+                def one_pass(c):
+                    for j, P in enumerate(c):
+                        gwq.linear_bf16(P, xs[P.K], ys[j], workspace=ws[j])
+                for c in sets:
+                    one_pass(c)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for c in sets:
+                        one_pass(c)
+                settle(graph.replay, 0.2)
+                ms = median_replay_ms(graph, 30) / len(sets)
+                del graph
+                if M <= 16:
+                    b = sum(algorithmic_bytes(P, M) for P in layers)
+                    bf[f"decode_M{M}"] = {"GB/s": round(b / ms / 1e6, 1), "ms_per_step": round(ms, 5),
+                                          "pct_hbm_peak": round(100 * b / ms / 1e6 / HBM_PEAK_GBS, 2), "launches_per_step": 7}
+                else:
+                    fl = sum(flops(P, M) for P in layers)
+                    bf["prefill_M2048"] = {"TFLOP/s": round(fl / ms / 1e9, 1), "ms_per_pass": round(ms, 4),
+                                           "pct_mfma_bf16_peak": round(100 * fl / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, 2)}
+                del xs, ys, ws
+            extra["bf16_activations"] = bf
+            torch.cuda.empty_cache()
         # gwq_pack: score (4 B) + W (2 B) read once, packed layer written
         pk, qual = {}, {}
         for name, Wd, Sd in pack_inputs if "pack" in legs else ():

@@ -15,11 +15,14 @@
  *   - Arguments are validated on the host before the first HIP call; errors are returned as
  *     a gwq_status, never raised or aborted.  A failed launch returns GWQ_ERR_DEVICE.
  *   - Weights are W[N][K] row-major FP16 (N = output features, K = input features),
- *     activations X[M][K] row-major FP16, outputs Y[M][N] row-major FP16.  No bias
- *     (Sec. 3.1 disables it).
+ *     activations X[M][K] row-major FP16, outputs Y[M][N] row-major FP16 (bfloat16 for both in
+ *     gwq_linear_bf16).  No bias (Sec. 3.1 disables it).
  *
- * Packed format (group = 128 consecutive k of one output channel n; gpr = K / 128)
- *   qweight  uint32 [N][gpr][wpg], wpg = 16 (4-bit) or 13 (3-bit).  A group is cut into four
+ * Packed format.  The codes of an output channel n lie in blocks of 128 consecutive k (gpr = K / 128 blocks per
+ * channel), whatever the group size; scale and zero point belong to a group of `group` consecutive k of one
+ * channel (Sec. 3.2, first paragraph: the group size beta, 16 in the paper; 16, 32, 64 or 128 here, spr = K / group
+ * groups per channel, at most 2048).
+ *   qweight  uint32 [N][gpr][wpg], wpg = 16 (4-bit) or 13 (3-bit).  A block is cut into four
  *            slots of 32 codes, slot b = k_local / 32.  Inside a word, codes at even positions
  *            sit in the low 16 bits and codes at odd positions in the high 16 bits, `bits`
  *            bits apiece, ascending.
@@ -28,9 +31,9 @@
  *            3-bit: word 3b+i (i = 0..2) holds codes 32b+10i+t (t = 0..9):
  *                   t even -> bit 3*(t/2), t odd -> bit 16+3*(t/2); bits 15 and 31 are zero.
  *                   Word 12 (tail) holds code 32b+30 at bit 3b and code 32b+31 at bit 16+3b.
- *   scales   FP16 bits [N][gpr]: the smallest FP16 s with s*(2^bits-1) >= max-min of the
+ *   scales   FP16 bits [N][spr]: the smallest FP16 s with s*(2^bits-1) >= max-min of the
  *            group's non-outlier weights (range widened to contain 0); 1.0 for an empty range.
- *   zeros    uint8 [N][gpr]: clamp(rint(-min/s), 0, 2^bits-1).
+ *   zeros    uint8 [N][spr]: clamp(rint(-min/s), 0, 2^bits-1).
  *   codes    clamp(rint(w/s) + z, 0, 2^bits-1), round half to even; the code under an outlier
  *            is z, so it decodes to 0 and the outlier value is added on top.
  *   row_ptr  int32 [N+1], col_idx uint16 [n_outliers] (ascending within a row), out_val FP16
@@ -53,7 +56,7 @@ typedef enum {
     GWQ_OK = 0,
     GWQ_ERR_NULL = -1,        /* a required pointer is NULL                               */
     GWQ_ERR_SHAPE = -2,       /* N, K, M out of range, K not a multiple of the group, ... */
-    GWQ_ERR_UNSUPPORTED = -3, /* bits not in {3,4}, group != 128, unknown score type      */
+    GWQ_ERR_UNSUPPORTED = -3, /* bits not in {3,4}, group not in {16,32,64,128}, unknown score type */
     GWQ_ERR_WORKSPACE = -4,   /* workspace missing or smaller than gwq_layout reports     */
     GWQ_ERR_DEVICE = -5       /* a HIP call failed                                        */
 } gwq_status;
@@ -65,7 +68,7 @@ typedef enum { GWQ_SCORE_F32 = 0, GWQ_SCORE_F16 = 1 } gwq_score_dtype;
 typedef struct {
     int32_t N, K;             /* 1 <= N, 128 <= K <= 65536, K % 128 == 0, N*K < 2^32      */
     int32_t bits;             /* 3 or 4                                                   */
-    int32_t group;            /* 128                                                      */
+    int32_t group;            /* 16, 32, 64 or 128; K / group <= 2048                     */
     uint32_t outlier_ppm;     /* 0..1000000; 10000 = 1 %                                  */
     int64_t n_outliers;       /* ceil(outlier_ppm*N*K/1e6)                                */
     uint32_t *qweight;
@@ -125,12 +128,22 @@ gwq_status gwq_pack(const void *W_f16, const void *score, int32_t score_dtype,
  * untouched).  The rest holds FP32 partial sums when a launch also splits K, which it does where
  * rows and channels alone give too few tiles to fill the chip; with less than that the call
  * still works, without the split.
- * For M > 16 the weights enter the MFMA as FP16 numbers s*(q-z), with s capped at the largest FP16 value for
- * which s*(2^bits-1) is finite (4364 at 4 bits, 9352 at 3; only groups whose range exceeds 65460 reach the
- * cap, which moves such a weight by < 0.1 %); for M <= 16 the scale multiplies FP32 sums.
+ * For M > 16, and for every M when group < 128, the weights enter the MFMA as FP16 numbers s*(q-z), with s capped
+ * at the largest FP16 value for which s*(2^bits-1) is finite (4364 at 4 bits, 9352 at 3; only groups whose range
+ * exceeds 65460 reach the cap, which moves such a weight by < 0.1 %); for M <= 16 and group = 128 the scale
+ * multiplies FP32 sums of exact products.
  * Results are deterministic (no floating-point atomics). */
 gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y_f16,
                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* gwq_linear for bfloat16 activations (the upper half of a binary32): X_bf16 [M][K] in, Y_bf16 [M][N] out, rounded to
+ * nearest even from the FP32 sums; arguments, workspace and errors as gwq_linear.  group = 128 only (else
+ * GWQ_ERR_UNSUPPORTED).  Sec. 3.2 fixes the weights' format, not the activations' type; bfloat16 MFMA operands keep the
+ * range of FP32 where FP16 activations overflow at 65504.  M <= 16: the MFMAs multiply x with the exact values 128 + q and
+ * the scale and zero point are applied to FP32 sums.  M > 16: the weights s*(q-z) and the outliers are rounded to bfloat16
+ * (8 significant bits) before the MFMA. */
+gwq_status gwq_linear_bf16(const gwq_packed *P, const void *X_bf16, int32_t M, void *Y_bf16,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* gwq_linear in two parts, for weights that stay while activations change.  What gwq_linear writes
  * into its workspace for M > 16 depends on the packed layer alone (per channel and group: where the

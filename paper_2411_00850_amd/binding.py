@@ -75,6 +75,8 @@ def lib():
         L.gwq_score.argtypes = [vp, vp, i32, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp]
         L.gwq_linear.restype = ctypes.c_int
         L.gwq_linear.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.gwq_linear_bf16.restype = ctypes.c_int
+        L.gwq_linear_bf16.argtypes = [ctypes.POINTER(_Packed), vp, i32, vp, vp, ctypes.c_size_t, vp]
         L.gwq_linear_index.restype = ctypes.c_int
         L.gwq_linear_index.argtypes = [ctypes.POINTER(_Packed), vp, ctypes.c_size_t, vp]
         L.gwq_linear_indexed.restype = ctypes.c_int
@@ -353,6 +355,25 @@ def linear(P, X, out=None, stream=None, workspace=None, index=None, scratch="aut
     rc = lib().gwq_linear(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(), ws_ptr, ws_len, _stream_ptr(stream))
     if rc != GWQ_OK:
         raise GwqError(rc, "gwq_linear")
+    return out
+
+
+def linear_bf16(P, X, out=None, stream=None, workspace=None):
+    """gwq_linear_bf16: X bfloat16 [M, K] on the GPU -> Y bfloat16 [M, N] (layers with groups of 128)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous() and X.shape[1] == P.K
+    M = X.shape[0]
+    if out is None:
+        out = torch.empty((M, P.N), dtype=torch.bfloat16, device=X.device)
+    assert out.is_cuda and out.dtype == torch.bfloat16 and out.is_contiguous() and tuple(out.shape) == (M, P.N)
+    if workspace is None:
+        workspace = linear_workspace(P, M, X.device)
+    cs = P.c_struct()
+    rc = lib().gwq_linear_bf16(ctypes.byref(cs), X.data_ptr(), M, out.data_ptr(),
+                               workspace.data_ptr() if workspace is not None else None,
+                               workspace.numel() if workspace is not None else 0, _stream_ptr(stream))
+    if rc != GWQ_OK:
+        raise GwqError(rc, "gwq_linear_bf16")
     return out
 
 

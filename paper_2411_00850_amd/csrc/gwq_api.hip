@@ -214,6 +214,28 @@ gwq_status gwq_linear(const gwq_packed *P, const void *X_f16, int32_t M, void *Y
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
 
+gwq_status gwq_linear_bf16(const gwq_packed *P, const void *X_bf16, int32_t M, void *Y_bf16, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    gwq_status s = check_linear(P, X_bf16, M, Y_bf16, workspace, workspace_bytes);
+    if (s != GWQ_OK) return s;
+    if (P->group != gwq::kGroup) return GWQ_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (M <= 16) {
+        gwq::DecodeTuning t = decode_tuning();
+        t.bf16 = true;
+        e = gwq::launch_decode(1, &P, &X_bf16, M, &Y_bf16, t, st);
+    } else {
+        const size_t ib = gwq::gemm_index_bytes(P->N, P->K, P->group);
+        e = P->index ? hipSuccess : gwq::launch_gemm_index(*P, workspace, st);
+        if (e == hipSuccess)
+            e = gwq::launch_gemm(*P, X_bf16, M, Y_bf16, P->index ? P->index : workspace,
+                                 static_cast<char *>(workspace) + ib, workspace_bytes - ib, g_gemm_ms, st, nullptr, true);
+    }
+    return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
+}
+
 gwq_status gwq_linear_index(const gwq_packed *P, void *index, size_t index_bytes, void *stream)
 {
     gwq_status s = check_packed(P);

@@ -113,6 +113,11 @@ template <> struct Slot<4> {
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
         decode_slot4_halves(ww, z_lo, z_hi, d, f);
     }
+    __device__ inline void decode_bf16(int /*b*/, const DecodeConstsBf16 &d, u32x4 f[4], int /*tail_lane4*/) const
+    {
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        decode_slot4_bf16(ww, d, f);
+    }
 };
 // 3-bit: a group is 13 words, slot b owns words 3b .. 3b+2 and two codes of word 12 (the tail).  One
 // 16-byte load at byte 12b (4-byte aligned; gfx950 global memory takes that) brings a lane its three
@@ -142,6 +147,11 @@ template <> struct Slot<3> {
     {
         const uint32_t tail = (uint32_t)__builtin_amdgcn_ds_bpermute(tail_lane4, (int)fourth);
         decode_slot3_halves(w, tail >> (3 * b), z_lo, z_hi, d, f);
+    }
+    __device__ inline void decode_bf16(int b, const DecodeConstsBf16 &d, u32x4 f[4], int tail_lane4) const
+    {
+        const uint32_t tail = (uint32_t)__builtin_amdgcn_ds_bpermute(tail_lane4, (int)fourth);
+        decode_slot3_bf16(w, tail >> (3 * b), d, f);
     }
 };
 
@@ -500,11 +510,17 @@ __global__ __launch_bounds__(1024) void decode_small_gate_up_kernel(const Decode
 // lane takes scale and zero point per half slot and multiplies them in before the MFMA, which sums over all
 // four slots of a block of 128: the operands are s * (q - z) rounded to FP16, as in the kernel for M > 16, and
 // the scale is capped likewise so that they stay finite.
+//
+// BF16: X and Y are bfloat16 (groups of 128 only).  The MFMA operands are the exact values 128 + q; a second set of
+// MFMAs against ones gives the group's sum of x per row, and the lane folds s * (sum - (128 + z) * sum_x) into its
+// FP32 result, so the weights enter exactly, as in the FP16 kernel.
 constexpr int kWideGuard = 96;
 
-template <int BITS, int U, int MR, bool FINE>
+template <int BITS, int U, int MR, bool FINE, bool BF16>
 __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batch)
 {
+    static_assert(!(FINE && BF16), "bfloat16 activations: groups of 128 only");
+    typedef std::conditional_t<BF16, __bf16, _Float16> act_t;          // X and Y; both 16 bits wide
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const DecodeProblem &pr = batch.p[blockIdx.y];
     const int N = pr.N, K = pr.K;
@@ -514,8 +530,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int32_t *__restrict__ row_ptr = pr.row_ptr;
     const uint16_t *__restrict__ col_idx = pr.col_idx;
     const uint16_t *__restrict__ out_val = pr.out_val;
-    const _Float16 *__restrict__ X = pr.X;
-    _Float16 *__restrict__ Y = pr.Y;
+    const act_t *__restrict__ X = reinterpret_cast<const act_t *>(pr.X);
+    act_t *__restrict__ Y = reinterpret_cast<act_t *>(pr.Y);
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
     const int shift = FINE ? pr.group_shift : 7;
     // The whole descriptor is requested in one go and only then looked at.
@@ -535,7 +551,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int x_stride = chunk + kXPad;                 // row stride of the LDS copy of X
     const int phases = (gpr + chunk_groups - 1) / chunk_groups;
 
-    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
+    act_t *xs = reinterpret_cast<act_t *>(lds_raw);
     const uint32_t sc_off = (uint32_t)M * x_stride * 2;
     const uint32_t zp_off = sc_off + 32 * spr;
     const uint32_t guard_off = zp_off + 16 * spr;
@@ -548,8 +564,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
     constexpr int kQ = U / 4;                           // 64-vector rounds covering U groups
     const int x_row = r < M ? r : 0;
-    const _Float16 *x_lane = xs + (uint32_t)x_row * x_stride + wave * (U * kGroup) + 32 * b;
-    const _Float16 *x_out[4];
+    const act_t *x_lane = xs + (uint32_t)x_row * x_stride + wave * (U * kGroup) + 32 * b;
+    const act_t *x_out[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(4 * b + e < M ? 4 * b + e : 0) * x_stride;   // rows m >= M are not stored
     const uint32_t *entries = reinterpret_cast<const uint32_t *>(lds_raw + ent_off);
@@ -673,6 +689,32 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[e] += part[e];
             }
+        } else if constexpr (BF16) {
+            const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
+            const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
+            const DecodeConstsBf16 dbf(BITS);
+            const u32x4 ones = u32x4{kBf16Ones, kBf16Ones, kBf16Ones, kBf16Ones};
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                u32x4 xa[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
+                const uint32_t keep = g_begin + u < gpr ? ~0u : 0u; // uniform over the wave: a scalar mask
+                const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)(sc_lane[u] & keep));
+                const float zc = -(float)(128u + zp_lane[u]);       // any byte gives a finite constant
+                u32x4 wb[4];
+                slot[u].decode_bf16(b, dbf, wb, tail_lane4);
+                float4v part = float4v{0.f, 0.f, 0.f, 0.f}, xsum = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[jj]),
+                                                                   __builtin_bit_cast(bf16x8, wb[jj]), part, 0, 0, 0);
+                    xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[jj]),
+                                                                   __builtin_bit_cast(bf16x8, ones), xsum, 0, 0, 0);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(s, __builtin_fmaf(zc, xsum[e], part[e]), acc[e]);
+            }
         } else {
             const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
             const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
@@ -724,7 +766,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 col[i] = ok[i] ? c - c0 : 0;
             }
             __builtin_amdgcn_sched_barrier(0);          // all four reads above are in flight together, ...
-            _Float16 xv[4][4];
+            act_t xv[4][4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -757,7 +799,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
         for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
         const int e = idx >> 6, l = idx & 63;
         const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
-        if (nn < N && m < M) Y[(size_t)m * N + nn] = (_Float16)sum;
+        if (nn < N && m < M) Y[(size_t)m * N + nn] = (act_t)sum;
     }
     }   // tiles
 }
@@ -1171,7 +1213,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         DecodeProblem &d = batch.p[i];
         d.qweight = L.qweight; d.scales = L.scales; d.zeros = L.zeros;
         d.row_ptr = L.row_ptr; d.col_idx = L.col_idx; d.out_val = L.out_val;
-        d.X = static_cast<const _Float16 *>(X[i]);
+        d.X = static_cast<const _Float16 *>(X[i]);       // bfloat16 when tune.bf16: the wide kernel reinterprets
         d.Y = static_cast<_Float16 *>(Y[i]);
         d.N = L.N; d.K = L.K;
         // Last 16-byte vector of each staged array (the buffers are padded, so clamped reads stay inside).
@@ -1192,7 +1234,8 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     const size_t meta = (size_t)48 * max_gpr + 16;
 
     // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
-    if (M <= 4 && !fine && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
+    if (tune.bf16 && fine) return hipErrorNotSupported;
+    if (M <= 4 && !fine && !tune.bf16 && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
         int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
         if (waves_override > 0) {                       // the most waves that do not exceed the request
             u = 4;
@@ -1218,7 +1261,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 
     // The streaming kernel: rows of at most 32 groups (8 waves of 4), XT[K][rows] in LDS.  By default for
     // the batches the lean kernel does not take.
-    if (!fine && tune.stream != 1 && (M > 4 || tune.stream == 2) && max_gpr <= 8 * kStreamU) {
+    if (!fine && !tune.bf16 && tune.stream != 1 && (M > 4 || tune.stream == 2) && max_gpr <= 8 * kStreamU) {
         const int nwaves = (max_gpr + kStreamU - 1) / kStreamU, nthreads = 64 * nwaves;
         const int mr = M <= 4 ? 4 : M <= 8 ? 8 : 16;
         const size_t xt = (size_t)max_gpr * kGroup * 2 * mr, red = (size_t)2 * nwaves * 1024;
@@ -1290,14 +1333,16 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
                 if (blocks > cap) blocks = cap;
             }
             if (describe) {
-                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d,%s> grid %dx%d block %d lds %zu phases %d",
-                         bits, best_u, mr, fine ? "true" : "false", blocks, count, 64 * best_w, best_lds, best_ph);
+                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d,%s,%s> grid %dx%d block %d lds %zu phases %d",
+                         bits, best_u, mr, fine ? "true" : "false", tune.bf16 ? "true" : "false", blocks, count, 64 * best_w,
+                         best_lds, best_ph);
                 return hipSuccess;
             }
 #define GWQ_WIDE(B, UU, RR) \
     if (bits == B && best_u == UU && mr == RR) \
-        return fine ? launch_kernel<&decode_wide_kernel<B, UU, RR, true>>(batch, count, blocks, best_w, best_lds, st) \
-                    : launch_kernel<&decode_wide_kernel<B, UU, RR, false>>(batch, count, blocks, best_w, best_lds, st)
+        return tune.bf16 ? launch_kernel<&decode_wide_kernel<B, UU, RR, false, true>>(batch, count, blocks, best_w, best_lds, st) \
+               : fine    ? launch_kernel<&decode_wide_kernel<B, UU, RR, true, false>>(batch, count, blocks, best_w, best_lds, st) \
+                         : launch_kernel<&decode_wide_kernel<B, UU, RR, false, false>>(batch, count, blocks, best_w, best_lds, st)
             GWQ_WIDE(4, 4, 8); GWQ_WIDE(4, 4, 16); GWQ_WIDE(4, 8, 8);
             GWQ_WIDE(3, 4, 8); GWQ_WIDE(3, 4, 16); GWQ_WIDE(3, 8, 8);
 #undef GWQ_WIDE

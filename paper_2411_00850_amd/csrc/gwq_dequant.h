@@ -18,6 +18,7 @@ namespace gwq {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // A constant the optimiser cannot see through.  With mask and magic in registers, (x & mask) | magic
@@ -156,6 +157,43 @@ __device__ inline void decode_slot3_halves(const uint32_t w[3], uint32_t tail_pa
         p[5 * i + 4] = pk_add(and_or(y, d.m1, d.kmid), c0.c128);
     }
     p[15] = pk_add(and_or(tail_pair, d.m0, d.k1024), c_hi.c1024);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f[j] = u32x4{p[4 * j], p[4 * j + 1], p[4 * j + 2], p[4 * j + 3]};
+}
+
+// ---- bfloat16 operands -------------------------------------------------------------------------
+// bfloat16 has 7 mantissa bits, so only a code that sits in bits 0..3 of its half-word can be turned into a number
+// by an OR: ((x >> shift) & mask) | 0x4300 is 128 + q (ulp 1 in [128, 256)), one shift and one and-or per pair of
+// codes.  gfx950 has no packed bfloat16 add to take 128 + z off again: the kernels multiply with 128 + q and
+// subtract (128 + z) * sum_k x from the FP32 sum of the group, which they get from one more MFMA against ones.
+struct DecodeConstsBf16 {
+    uint32_t m, k128;
+    __device__ inline explicit DecodeConstsBf16(int bits)
+    {
+        m = opaque(bits == 4 ? 0x000F000Fu : 0x00070007u);
+        k128 = opaque_v(0x43004300u);
+    }
+};
+constexpr uint32_t kBf16Ones = 0x3F803F80u;            // the pair (1.0, 1.0)
+
+// 4-bit slot: words w[0..3] -> operands f[0..3], eight values 128 + q each in position order.
+__device__ inline void decode_slot4_bf16(const uint32_t w[4], const DecodeConstsBf16 &d, u32x4 f[4])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        f[j] = u32x4{and_or(w[j], d.m, d.k128), and_or(w[j] >> 4, d.m, d.k128), and_or(w[j] >> 8, d.m, d.k128),
+                     and_or(w[j] >> 12, d.m, d.k128)};
+}
+
+// 3-bit slot (layout as decode_slot3): pair t of word i sits at bits 3t of both half-words.
+__device__ inline void decode_slot3_bf16(const uint32_t w[3], uint32_t tail_pair, const DecodeConstsBf16 &d, u32x4 f[4])
+{
+    uint32_t p[16];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int t = 0; t < 5; ++t) p[5 * i + t] = and_or(w[i] >> (3 * t), d.m, d.k128);
+    p[15] = and_or(tail_pair, d.m, d.k128);
 #pragma unroll
     for (int j = 0; j < 4; ++j) f[j] = u32x4{p[4 * j], p[4 * j + 1], p[4 * j + 2], p[4 * j + 3]};
 }

@@ -184,6 +184,24 @@ __device__ inline void dequant_all(const SlotRegs<3> &r, uint32_t tail_pair, uin
     }
 }
 
+// bfloat16 operands: the eight exact FP16 integers q - z of a fragment times the scale in FP32, rounded once to
+// bfloat16 (round to nearest even).
+__device__ inline uint32_t scale_pair_bf16(uint32_t h2, float s)
+{
+    const half2v h = __builtin_bit_cast(half2v, h2);
+    const __bf16 lo = (__bf16)((float)h.x * s), hi = (__bf16)((float)h.y * s);
+    return (uint32_t)__builtin_bit_cast(uint16_t, lo) | (uint32_t)__builtin_bit_cast(uint16_t, hi) << 16;
+}
+__device__ inline u32x4 scale_frag_bf16(u32x4 f, float s)
+{
+    return u32x4{scale_pair_bf16(f.x, s), scale_pair_bf16(f.y, s), scale_pair_bf16(f.z, s), scale_pair_bf16(f.w, s)};
+}
+// An FP16 bit pattern as the nearest bfloat16's (the stored outliers, for bfloat16 MFMA operands).
+__device__ inline uint16_t half_bits_to_bf16_bits(uint32_t h)
+{
+    return __builtin_bit_cast(uint16_t, (__bf16)(float)__builtin_bit_cast(_Float16, (uint16_t)h));
+}
+
 // X rows lie in LDS 128 bytes apart, so the 16-byte chunk c of row r is kept at position
 // c ^ x_swizzle(r): the 16 rows a fragment read touches per cycle then hit 16 different bank groups,
 // whichever of the two plausible lane groupings the hardware uses.
@@ -204,7 +222,9 @@ template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcn
 // the order of s.
 // FINE: the layer's groups are smaller than 128; the producers take scale and zero point per half slot from `fine`
 // (fine_index_kernel) instead of the group's record.
-template <int BITS, int MSW, int WN, int WM, bool FINE>
+// BF16: X and Y are bfloat16 and the MFMAs take bfloat16 operands: the producers round s * (q - z), formed in FP32, and
+// the stored outliers to bfloat16 (groups of 128 only).
+template <int BITS, int MSW, int WN, int WM, bool FINE, bool BF16>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restrict__ qweight,
                                                         const uint16_t *__restrict__ col_idx,
                                                         const uint16_t *__restrict__ out_val,
@@ -215,6 +235,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                                                         int N, int K, int M, int tiles_m, int tiles_n, int last_entry)
 {
     static_assert(WM * WN <= kConsumers, "consumer waves");
+    static_assert(!(FINE && BF16), "bfloat16 activations: groups of 128 only");
+    typedef std::conditional_t<BF16, __bf16, _Float16> act_t;
     constexpr int BM = 32 * MSW * WM;                   // WM x WN consumer waves work; with fewer than eight the rest idle
     constexpr int NB = kBN / 32 / WN;                   // 32-column sub-tiles per consumer wave
     constexpr int wpg = words_per_group(BITS);
@@ -300,7 +322,18 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             _Float16 *brow = b_dst + buf * kWBufHalves;
             const int half = step & 1;
             const uint32_t s2 = (sz & 0xFFFFu) * 0x10001u, z = sz >> 16;
-            if constexpr (FINE) {
+            if constexpr (BF16) {
+                const float sf = (float)__builtin_bit_cast(_Float16, (uint16_t)(sz & 0xFFFFu));
+                u32x4 f[4];
+                if constexpr (BITS == 4) {
+                    decode_slot4(G.slot[half].w, z, dc, f);
+                } else {
+                    const uint32_t tail = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)G.slot[1].fourth, 0xF5, 0xF, 0xF, false);
+                    decode_slot3(G.slot[half].w, tail >> (3 * (2 * half + b_h)), z, dc, f);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(brow + 32 * b_h + 8 * j) = scale_frag_bf16(f[j], sf);
+            } else if constexpr (FINE) {
                 const uint32_t lo = G.sub[2 * half], hi = G.sub[2 * half + 1];
                 u32x4 f[4];
                 if constexpr (BITS == 4) {
@@ -336,12 +369,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const uint32_t t = out_col[i] - k_lo;   // >= 64 for 0x10000 (k_lo <= 65536 - 64) and for other steps' columns
-                brow[t < (uint32_t)kBK ? t : (uint32_t)kBK] = __builtin_bit_cast(_Float16, (uint16_t)(vs[i >> 1] >> (16 * (i & 1))));
+                const uint32_t vbits = (vs[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+                brow[t < (uint32_t)kBK ? t : (uint32_t)kBK] = __builtin_bit_cast(_Float16, BF16 ? half_bits_to_bf16_bits(vbits) : (uint16_t)vbits);
             }
             if (b_h == 0)
                 for (int i = kAhead; i < cnt; ++i) {    // rare: more than kAhead outliers in one group
                     const uint32_t c = load_u16_now(col_idx + first + i) - k_lo;
-                    if (c < (uint32_t)kBK) brow[c] = __builtin_bit_cast(_Float16, (uint16_t)load_u16_now(out_val + first + i));
+                    if (c < (uint32_t)kBK) {
+                        const uint32_t vbits = load_u16_now(out_val + first + i);
+                        brow[c] = __builtin_bit_cast(_Float16, BF16 ? half_bits_to_bf16_bits(vbits) : (uint16_t)vbits);
+                    }
                 }
         };
 
@@ -471,9 +508,14 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
         for (int i = 0; i < MSW; ++i)
 #pragma unroll
             for (int j = 0; j < NB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[set][i]),
-                                                                   __builtin_bit_cast(half8, fb[set][j]),
-                                                                   acc[i][j], 0, 0, 0);
+                if constexpr (BF16)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[set][i]),
+                                                                        __builtin_bit_cast(bf16x8, fb[set][j]),
+                                                                        acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, fa[set][i]),
+                                                                       __builtin_bit_cast(half8, fb[set][j]),
+                                                                       acc[i][j], 0, 0, 0);
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
     // One step whose number is p modulo 3.
@@ -521,7 +563,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
                 const int m = m0 + wm * (32 * MSW) + i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
                 if (m < M && n < N) {
                     if (partial) partial[((size_t)split * M + m) * N + n] = acc[i][j][v];
-                    else Y[(size_t)m * N + n] = (_Float16)acc[i][j][v];
+                    else reinterpret_cast<act_t *>(Y)[(size_t)m * N + n] = (act_t)acc[i][j][v];
                 }
             }
         }
@@ -529,14 +571,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
 
 // Y = sum over the splits of partial[s], added in the order of s (so the result does not depend on
 // which block finished first), rounded to FP16 once.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, _Float16 *__restrict__ Y,
+template <typename act_t>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, act_t *__restrict__ Y,
                                                             size_t count, int splits)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
     float sum = partial[i];
     for (int s = 1; s < splits; ++s) sum += partial[(size_t)s * count + i];
-    Y[i] = (_Float16)sum;
+    Y[i] = (act_t)sum;
 }
 
 // How many ways K is split for a launch of `tiles` tiles over rows of `gpr` groups: as many as keep
@@ -603,7 +646,7 @@ int choose_rows(int M, int N, int K, bool have_scratch)
     return best;
 }
 
-template <int BITS, int MSW, int WN, int WM, bool FINE>
+template <int BITS, int MSW, int WN, int WM, bool FINE, bool BF16>
 hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const GroupRecord *rec, float *partial,
                      size_t partial_bytes, hipStream_t st, PlanText *describe)
 {
@@ -616,25 +659,26 @@ hipError_t launch_ms(const gwq_packed &P, const void *X, int M, void *Y, const G
     if (splits == 1) partial = nullptr;
     const size_t lds = ((size_t)3 * BM * kBK + (size_t)3 * kBN * kLd) * sizeof(_Float16);
     if (describe) {
-        snprintf(describe->text, sizeof(describe->text), "gemm_kernel<%d,%d,%d,%d,%s> tile %dx%d grid %d block %d lds %zu k_splits %d",
-                 BITS, MSW, WN, WM, FINE ? "true" : "false", BM, kBN, tiles_m * tiles_n * splits, kThreads, lds, splits);
+        snprintf(describe->text, sizeof(describe->text), "gemm_kernel<%d,%d,%d,%d,%s,%s> tile %dx%d grid %d block %d lds %zu k_splits %d",
+                 BITS, MSW, WN, WM, FINE ? "true" : "false", BF16 ? "true" : "false", BM, kBN, tiles_m * tiles_n * splits, kThreads, lds, splits);
         return hipSuccess;
     }
     static std::atomic<uint32_t> lds_allowed{0};        // per instantiation
     {
-        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM, FINE>), (int)lds, lds_allowed);
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_kernel<BITS, MSW, WN, WM, FINE, BF16>), (int)lds, lds_allowed);
         if (e != hipSuccess) return e;
     }
     // The half-slot pairs of a layer with small groups follow the records.
     const uint32_t *fine = reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(rec) + record_bytes(P.N, P.K));
-    gemm_kernel<BITS, MSW, WN, WM, FINE><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
+    gemm_kernel<BITS, MSW, WN, WM, FINE, BF16><<<tiles_m * tiles_n * splits, kThreads, lds, st>>>(
         P.qweight, P.col_idx, P.out_val, rec, fine, static_cast<const _Float16 *>(X),
         static_cast<_Float16 *>(Y), partial, split_groups, P.N, P.K, M, tiles_m, tiles_n,
         P.n_outliers > 0 ? (int)P.n_outliers - 1 : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     const size_t count = (size_t)M * P.N;
-    splitk_reduce_kernel<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(partial, static_cast<_Float16 *>(Y), count, splits);
+    if (BF16) splitk_reduce_kernel<__bf16><<<(unsigned)((count + 255) / 256), 256, 0, st>>>(partial, static_cast<__bf16 *>(Y), count, splits);
+    else splitk_reduce_kernel<_Float16><<<(unsigned)((count + 255) / 256), 256, 0, st>>>(partial, static_cast<_Float16 *>(Y), count, splits);
     return hipGetLastError();
 }
 
@@ -675,8 +719,9 @@ hipError_t launch_gemm_index(const gwq_packed &P, void *workspace, hipStream_t s
 }
 
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
-                       size_t scratch_bytes, int ms_override, hipStream_t st, PlanText *describe)
+                       size_t scratch_bytes, int ms_override, hipStream_t st, PlanText *describe, bool bf16)
 {
+    if (bf16 && P.group != kGroup) return hipErrorNotSupported;
     const GroupRecord *rec = static_cast<const GroupRecord *>(index);
     float *part = static_cast<float *>(scratch);
     // Rows per tile (the override is in rows): 256 (consumer waves 4 x 2, 64 x 64 each), 128 (4 x 2, 32 x 64
@@ -685,17 +730,21 @@ hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const
     // LDS is what bounds a step.
     const int rows = ms_override ? ms_override : choose_rows(M, (int)P.N, (int)P.K, part != nullptr);
     const int shape = rows == 256 ? 2 : rows == 128 ? 1 : rows == 64 ? 0 : 3;
-#define GWQ_GEMM(B, F) \
-    return shape == 2   ? launch_ms<B, 2, 2, 4, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
-           : shape == 1 ? launch_ms<B, 1, 2, 4, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
-           : shape == 0 ? launch_ms<B, 1, 4, 2, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
-                        : launch_ms<B, 1, 4, 1, F>(P, X, M, Y, rec, part, scratch_bytes, st, describe)
-    if (P.group == kGroup) {
-        if (P.bits == 4) GWQ_GEMM(4, false);
-        GWQ_GEMM(3, false);
+#define GWQ_GEMM(B, F, A) \
+    return shape == 2   ? launch_ms<B, 2, 2, 4, F, A>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+           : shape == 1 ? launch_ms<B, 1, 2, 4, F, A>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+           : shape == 0 ? launch_ms<B, 1, 4, 2, F, A>(P, X, M, Y, rec, part, scratch_bytes, st, describe) \
+                        : launch_ms<B, 1, 4, 1, F, A>(P, X, M, Y, rec, part, scratch_bytes, st, describe)
+    if (bf16) {
+        if (P.bits == 4) GWQ_GEMM(4, false, true);
+        GWQ_GEMM(3, false, true);
     }
-    if (P.bits == 4) GWQ_GEMM(4, true);
-    GWQ_GEMM(3, true);
+    if (P.group == kGroup) {
+        if (P.bits == 4) GWQ_GEMM(4, false, false);
+        GWQ_GEMM(3, false, false);
+    }
+    if (P.bits == 4) GWQ_GEMM(4, true, false);
+    GWQ_GEMM(3, true, false);
 #undef GWQ_GEMM
 }
 

@@ -43,6 +43,7 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
 struct DecodeTuning {
     int waves, stream, tiles;
     bool gated_pairs = false;   // layers (2i, 2i+1) are gate and up of a gated pair: one launch writes silu(gate) * up into Y[2i+1]
+    bool bf16 = false;          // X and Y are bfloat16 (groups of 128 only; the kernel for any M <= 16 takes these)
 };
 // With `describe` set a launcher only writes there which kernel, template arguments and launch shape it
 // would use for these arguments, and launches nothing.
@@ -60,7 +61,7 @@ size_t gemm_scratch_bytes(int64_t N, int64_t M_max);
 hipError_t launch_gemm_index(const gwq_packed &P, void *index, hipStream_t stream);        // fills the records
 hipError_t launch_gemm(const gwq_packed &P, const void *X, int M, void *Y, const void *index, void *scratch,
                        size_t scratch_bytes, int ms_override, hipStream_t stream,
-                       PlanText *describe = nullptr);                                      // reads them
+                       PlanText *describe = nullptr, bool bf16 = false);                   // reads them; bf16: X, Y bfloat16
 
 // workspace: quality_workspace_bytes(N) bytes, 8-byte aligned (one partial result per channel); out: 3 doubles.
 size_t quality_workspace_bytes(int64_t N);

@@ -14,11 +14,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "gwq.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gwq_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(gwq_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_expected_calls():
-    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_gate_up",
+    assert declared_functions() == ["gwq_layout", "gwq_linear", "gwq_linear_batch", "gwq_linear_bf16", "gwq_linear_gate_up",
                                     "gwq_linear_index", "gwq_linear_indexed", "gwq_linear_plan", "gwq_linear_static", "gwq_pack",
                                     "gwq_probe_mfma", "gwq_probe_stream", "gwq_quality", "gwq_score",
                                     "gwq_status_string", "gwq_tuning_set", "gwq_version"]
@@ -113,6 +113,12 @@ def test_pack_and_linear_validate_before_touching_the_device():
     assert L.gwq_linear(ctypes.byref(_packed(group=48)), fake, 1, fake, None, 0, None) == -3
     assert L.gwq_linear(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4       # M > 16 needs scratch
+    assert L.gwq_linear_bf16(None, fake, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear_bf16(ctypes.byref(ok), None, 1, fake, None, 0, None) == -1
+    assert L.gwq_linear_bf16(ctypes.byref(ok), fake, 0, fake, None, 0, None) == -2
+    assert L.gwq_linear_bf16(ctypes.byref(ok), ctypes.c_void_p(0x1002), 1, fake, None, 0, None) == -2
+    assert L.gwq_linear_bf16(ctypes.byref(ok), fake, 17, fake, None, 0, None) == -4
+    assert L.gwq_linear_bf16(ctypes.byref(_packed(group=32)), fake, 1, fake, None, 0, None) == -3   # groups of 128 only
     assert L.gwq_linear(ctypes.byref(ok), fake, 17, fake, fake, 8, None) == -4
 
 
@@ -169,11 +175,11 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert plan([q, q, q], 1).startswith("decode_small_kernel<4,8,1> grid 256x3")
     assert plan([down], 1).startswith("decode_small_kernel<4,8,1> grid 256x1 block 704")
     assert plan([gate, gate], 16).startswith("decode_stream_kernel<4,16>")          # several tiles per block
-    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16,false>")                  # one tile per block
+    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16,false,false>")                  # one tile per block
     assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_wide_kernel<3,")
-    assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4,false> tile 256x128 grid 256 ")
+    assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4,false,false> tile 256x128 grid 256 ")
     q16 = _packed(N=4096, K=4096, group=16)               # groups of 16: the wide decode kernel and the GEMM in their small-group forms
-    assert plan([q16], 1).startswith("decode_wide_kernel<4,4,8,true>") and plan([q16], 2048).startswith("gemm_kernel<4,2,2,4,true>")
+    assert plan([q16], 1).startswith("decode_wide_kernel<4,4,8,true,false>") and plan([q16], 2048).startswith("gemm_kernel<4,2,2,4,true,false>")
     assert "k_splits 1" in plan([q], 64, scratch=0) and "k_splits 1" not in plan([q], 64, scratch=1)
     arr = (ctypes.POINTER(binding._Packed) * 2)(ctypes.pointer(q), ctypes.pointer(down))
     assert L.gwq_linear_plan(2, arr, 1, 1, buf, 256) == -2                          # one K per launch
