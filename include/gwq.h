@@ -252,11 +252,12 @@ gwq_status gwq_probe_mfma(int32_t blocks, int32_t iters, void *sink, void *strea
 /* Launch-shape overrides for measurement sweeps; value 0 restores the built-in heuristic.  The values are
  * process-wide (atomic, read once per call by every thread's calls): a hook for benchmarks and tests, not a
  * per-call option.
- * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 4:
+ * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 8:
  * it picks 4, 8 or 16 groups per wave accordingly; the kernels for larger M size themselves),
  * "decode_stream" (1: never the streaming decode kernel; 2: also for M <= 4, wherever K <= 4096 lets it
  * run; by default it takes 5 <= M <= 16 there), "decode_tiles" (16-channel tiles per block of the streaming
- * kernel, 1..4096), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
+ * kernel, 1..4096), "decode_lean_rows" (1..8: the largest M handled by the kernel that keeps all of X[M][K] in LDS,
+ * where it fits), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
  * M = 512 and below that the shape a cost model of the launch expects to be fastest).  Unknown keys or
  * out-of-range values return GWQ_ERR_UNSUPPORTED. */
 gwq_status gwq_tuning_set(const char *key, int32_t value);

@@ -357,9 +357,11 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
     __builtin_amdgcn_sched_barrier(0);
 
-    float acc[MS];
+    // A lane's MFMA results are rows 4b .. 4b+3 of its channel: rows below MS are kept.
+    constexpr int RA = MS < 4 ? MS : 4;
+    float acc[RA];
 #pragma unroll
-    for (int e = 0; e < MS; ++e) acc[e] = 0.f;
+    for (int e = 0; e < RA; ++e) acc[e] = 0.f;
     {
         const int x_row = r < MS ? r : 0;
         const _Float16 *x_lane = xs + (uint32_t)x_row * k_pad + g_begin * kGroup + 32 * b;
@@ -384,7 +386,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
                 part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[j]),
                                                               __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
 #pragma unroll
-            for (int e = 0; e < MS; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
+            for (int e = 0; e < RA; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
         }
     }
 
@@ -433,11 +435,33 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     }
 
     // Fixed-order reduction over the waves and the four lanes of a channel, then FP16 store.
-    // Only lanes b = 0 of a wave that owns groups hold dense results (rows m < 4).
+    // Lane b of a wave that owns groups holds the dense results of rows 4b .. 4b+3.
     GWQ_TS(4);                                          // outliers added
+    if constexpr (MS > 4) {
+        // More than four rows: the four lanes of a channel meet first (in the order b = 0, 1, 2, 3 for every
+        // lane), so that a wave leaves 16 partial sums per row instead of 64 and two blocks fit the LDS of a CU.
+#pragma unroll
+        for (int e = 0; e < MS; ++e) {
+            float v = ((active && b == (e >> 2)) ? acc[e & 3] : 0.f) + oacc[e];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (lane < 16) red[(wave * MS + e) * 16 + lane] = v;
+        }
+        __syncthreads();
+        GWQ_TS(5);
+        for (int idx = tid; idx < MS * 16; idx += nthreads) {
+            const int e = idx >> 4, c = idx & 15;
+            float sum = 0.f;
+            for (int w = 0; w < nwaves; ++w) sum += red[(w * MS + e) * 16 + c];
+            if (row0 + c < N) Y[(size_t)e * N + row0 + c] = (_Float16)sum;
+        }
+        GWQ_TS(6);
+        GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < MS; ++e) {
-        const float dense = (active && b == 0) ? acc[e] : 0.f;
+        const float dense = (active && b == (e >> 2)) ? acc[e & 3] : 0.f;
         red[(wave * MS + e) * 64 + lane] = dense + oacc[e];
     }
     __syncthreads();
@@ -1169,6 +1193,7 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
 
 constexpr size_t kMaxLds = 160 * 1024;                  // LDS a block may use on gfx950
 constexpr size_t kXLdsBudget = 128 * 1024;              // X[M][k_pad] is staged in LDS up to this size
+constexpr int kLeanRows = 8;                            // the lean kernel takes M up to here (where X fits the LDS)
 
 template <auto Kernel>
 hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nwaves, size_t lds, hipStream_t st)
@@ -1188,10 +1213,15 @@ hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwa
     if (u == UU && ms == MM) \
         return gated_pairs ? launch_kernel<&decode_small_gate_up_kernel<BITS, UU, MM>>(batch, count / 2, blocks, nwaves, lds, st) \
                            : launch_kernel<&decode_small_kernel<BITS, UU, MM>>(batch, count, blocks, nwaves, lds, st)
+#define GWQ_SMALL_PLAIN(UU, MM) \
+    if (u == UU && ms == MM && !gated_pairs) return launch_kernel<&decode_small_kernel<BITS, UU, MM>>(batch, count, blocks, nwaves, lds, st)
     GWQ_SMALL(4, 1); GWQ_SMALL(4, 2); GWQ_SMALL(4, 3); GWQ_SMALL(4, 4);
     GWQ_SMALL(8, 1); GWQ_SMALL(8, 2); GWQ_SMALL(8, 3); GWQ_SMALL(8, 4);
     GWQ_SMALL(16, 1); GWQ_SMALL(16, 2);
+    GWQ_SMALL_PLAIN(4, 5); GWQ_SMALL_PLAIN(4, 6); GWQ_SMALL_PLAIN(4, 7); GWQ_SMALL_PLAIN(4, 8);
+    GWQ_SMALL_PLAIN(8, 5); GWQ_SMALL_PLAIN(8, 6); GWQ_SMALL_PLAIN(8, 7); GWQ_SMALL_PLAIN(8, 8);
 #undef GWQ_SMALL
+#undef GWQ_SMALL_PLAIN
     return hipErrorInvalidValue;
 }
 
@@ -1235,7 +1265,8 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
 
     // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
     if (tune.bf16 && fine) return hipErrorNotSupported;
-    if (M <= 4 && !fine && !tune.bf16 && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
+    const int lean_rows = tune.lean_rows > 0 ? tune.lean_rows : kLeanRows;
+    if (M <= lean_rows && (M <= 4 || !tune.gated_pairs) && !fine && !tune.bf16 && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
         int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
         if (waves_override > 0) {                       // the most waves that do not exceed the request
             u = 4;
@@ -1244,8 +1275,14 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         while (u < 16 && (max_gpr + u - 1) / u > 16) u *= 2;
         const int nwaves = (max_gpr + u - 1) / u;
         const size_t x_bytes = (size_t)M * (nwaves * u * kGroup + kXPad) * 2;
-        const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * 256 + 64 * (size_t)M;
-        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds) {
+        const size_t lds = x_bytes + meta + 2 * (16 * (size_t)nwaves * 64 + 16) + (size_t)nwaves * M * (M > 4 ? 64 : 256) + 64 * (size_t)M;
+        // Beyond four rows X is most of a block's LDS: the kernel is taken where two blocks still share a CU, or
+        // where the launch is at most three rounds of single blocks (more rounds: a kernel whose blocks stage X
+        // once for several tiles is faster).
+        int total_blocks = 0;
+        for (int i = 0; i < count; ++i) total_blocks += (P[i]->N + 15) / 16;
+        const bool roomy = M <= 4 || 2 * lds <= kMaxLds || total_blocks <= 3 * device_cus();
+        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds && (M <= 4 || u <= 8) && roomy) {
             batch.nwaves = nwaves;
             if (describe) {
                 snprintf(describe->text, sizeof(describe->text), "%s<%d,%d,%d> grid %dx%d block %d lds %zu",

@@ -42,6 +42,7 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
 // streaming kernel 1 = never, 2 = for every M <= 16 it can take; its tiles per block.
 struct DecodeTuning {
     int waves, stream, tiles;
+    int lean_rows = 0;          // largest M the kernel with X[M][K] in LDS takes (0 = built-in choice, at most 8)
     bool gated_pairs = false;   // layers (2i, 2i+1) are gate and up of a gated pair: one launch writes silu(gate) * up into Y[2i+1]
     bool bf16 = false;          // X and Y are bfloat16 (groups of 128 only; the kernel for any M <= 16 takes these)
 };

@@ -176,7 +176,8 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert plan([down], 1).startswith("decode_small_kernel<4,8,1> grid 256x1 block 704")
     assert plan([gate, gate], 16).startswith("decode_stream_kernel<4,16>")          # several tiles per block
     assert plan([q], 16).startswith("decode_wide_kernel<4,4,16,false,false>")                  # one tile per block
-    assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_wide_kernel<3,")
+    assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_small_kernel<3,8,8> grid 256x1 block 256 lds 78000")   # two blocks per CU
+    assert plan([_packed(N=4096, K=4096, bits=3)], 9).startswith("decode_wide_kernel<3,")
     assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4,false,false> tile 256x128 grid 256 ")
     q16 = _packed(N=4096, K=4096, group=16)               # groups of 16: the wide decode kernel and the GEMM in their small-group forms
     assert plan([q16], 1).startswith("decode_wide_kernel<4,4,8,true,false>") and plan([q16], 2048).startswith("gemm_kernel<4,2,2,4,true,false>")
