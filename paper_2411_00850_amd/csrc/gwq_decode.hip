@@ -211,9 +211,14 @@ __device__ inline float silu(float x)
     return x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * x));
 }
 
-template <int BITS, int U, int MS, int MODE>
+//
+// FINE: groups below 128.  The staged metadata is [16][spr] (up to three vectors per thread); a lane takes scale and
+// zero point per half slot, with the indices of a group at or beyond gpr clamped into the row and its scales masked,
+// and multiplies FP16 operands s * (q - z), as the wide kernel does for such layers.
+template <int BITS, int U, int MS, int MODE, bool FINE = false>
 __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, const int layer)
 {
+    static_assert(!FINE || MODE == 0, "gated pairs: groups of 128 only");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const DecodeProblem &pr = batch.p[layer];
     const int N = pr.N, K = pr.K;
@@ -227,10 +232,11 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const _Float16 *__restrict__ X = pr.X;
     _Float16 *__restrict__ Y = pr.Y;
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
+    const int shift = FINE ? pr.group_shift : 7;
     // The whole descriptor is requested in one go and only then looked at (the empty statement
     // keeps the compiler from moving the other loads behind the branch on N).
     asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
-                 "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec));
+                 "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec), "s"(shift));
     if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -241,6 +247,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const int r = lane & 15, b = lane >> 4;
     const int tail_lane4 = 4 * (lane | 48);             // where the 3-bit tail word of this lane's channel arrives
     const int gpr = K / kGroup;
+    const int spr = K >> shift;                         // scale / zero-point pairs per channel
     const int my_waves = (gpr + U - 1) / U;             // waves of this layer that own groups
     const bool active = wave < my_waves;
     const int g_begin = active ? wave * U : 0;
@@ -251,8 +258,8 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
 
     _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
     const uint32_t sc_off = (uint32_t)MS * k_pad * 2;
-    const uint32_t zp_off = sc_off + 32 * gpr;
-    const uint32_t spare_off = zp_off + 16 * gpr;
+    const uint32_t zp_off = sc_off + 32 * spr;
+    const uint32_t spare_off = zp_off + 16 * spr;
     const uint32_t ent_off = spare_off + 16;
     const uint32_t red_off = ent_off + 32 * nthreads + 32;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
@@ -286,7 +293,21 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     // (the spare slot follows at vector 3 gpr).
     u32x4 meta;
     int meta_valid;                                     // bytes of `meta` that lie inside the array
-    {
+    u32x4 meta_fine[FINE ? 3 : 1];                      // small groups: vectors tid, tid + blockDim, tid + 2 blockDim of 3 spr
+    if constexpr (FINE) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int t = tid + i * nthreads;
+            const bool is_zp = t >= 2 * spr;
+            const int u_sc = block * 2 * spr + t, u_zp = block * spr + (t - 2 * spr);
+            const int v_sc = u_sc < sc_last_vec ? u_sc : sc_last_vec;
+            const int v_zp = u_zp < zp_last_vec ? u_zp : zp_last_vec;
+            const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
+            meta_fine[i] = src[is_zp ? (t < 3 * spr ? v_zp : 0) : v_sc];
+        }
+        meta = meta_fine[0];
+        meta_valid = 16;
+    } else {
         const bool is_sc = tid < 2 * gpr, is_zp = !is_sc && tid < 3 * gpr;
         const int u_sc = block * 2 * gpr + tid, u_zp = block * gpr + (tid - 2 * gpr);
         const int v_sc = u_sc < sc_last_vec ? u_sc : sc_last_vec;
@@ -329,15 +350,23 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
         }
     // Bytes beyond the end of scales or zeros (the last block of a ragged N, and the spare slot) are
     // stored as zeros: the groups at or beyond gpr of the last channel and of channel 15 read them.
-    if (meta_valid < 16) {
-        uint32_t *m = reinterpret_cast<uint32_t *>(&meta);
+    if constexpr (FINE) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int nb = meta_valid - 4 * i;
-            m[i] &= nb >= 4 ? ~0u : nb <= 0 ? 0u : (1u << (8 * nb)) - 1u;
+        for (int i = 0; i < 3; ++i) {
+            const int t = tid + i * nthreads;
+            if (t < 3 * spr) *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = meta_fine[i];
         }
+    } else {
+        if (meta_valid < 16) {
+            uint32_t *m = reinterpret_cast<uint32_t *>(&meta);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int nb = meta_valid - 4 * i;
+                m[i] &= nb >= 4 ? ~0u : nb <= 0 ? 0u : (1u << (8 * nb)) - 1u;
+            }
+        }
+        *reinterpret_cast<u32x4 *>(lds_raw + meta_dst) = meta;
     }
-    *reinterpret_cast<u32x4 *>(lds_raw + meta_dst) = meta;
     __syncthreads();
     GWQ_TS(2);                                          // X, scales and zero points are in LDS
 
@@ -376,17 +405,33 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
             u32x4 xa[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) xa[j] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * j);
-            const _Float16 s = __builtin_bit_cast(_Float16, sc_lane[u]);
-            const uint32_t z = zp_lane[u];
             u32x4 wb[4];
-            slot[u].decode(z, b, dc, wb, tail_lane4);
             float4v part = float4v{0.f, 0.f, 0.f, 0.f};
+            if constexpr (FINE) {
+                constexpr uint32_t cap = BITS == 4 ? 0x6C43u : 0x7091u;     // largest scale with s * (2^bits - 1) finite in FP16
+                const uint16_t *sc_row = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * spr;
+                const uint8_t *zp_row = lds_raw + zp_off + r * spr;
+                const int g = g_begin + u;
+                const uint32_t keep = g < gpr ? ~0u : 0u;                   // uniform over the wave
+                const int c0 = (g < gpr ? g : gpr - 1) * kGroup + 32 * b;   // first column of the lane's slot
+                const int i_lo = c0 >> shift, i_hi = (c0 + 16) >> shift;
+                uint32_t s_lo = sc_row[i_lo], s_hi = sc_row[i_hi];
+                s_lo = (s_lo < cap ? s_lo : cap) & keep;
+                s_hi = (s_hi < cap ? s_hi : cap) & keep;
+                const uint32_t z_lo = BITS == 3 ? zp_row[i_lo] & keep : zp_row[i_lo];
+                const uint32_t z_hi = BITS == 3 ? zp_row[i_hi] & keep : zp_row[i_hi];
+                slot[u].decode_halves(z_lo, z_hi, b, dc, wb, tail_lane4);
+                scale_halves(wb, s_lo * 0x10001u, s_hi * 0x10001u);
+            } else {
+                slot[u].decode(zp_lane[u], b, dc, wb, tail_lane4);
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[j]),
                                                               __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
+            const float s = FINE ? 1.f : (float)__builtin_bit_cast(_Float16, sc_lane[u]);
 #pragma unroll
-            for (int e = 0; e < RA; ++e) acc[e] = __builtin_fmaf((float)s, part[e], acc[e]);
+            for (int e = 0; e < RA; ++e) acc[e] = __builtin_fmaf(s, part[e], acc[e]);
         }
     }
 
@@ -491,10 +536,10 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
 }
 
-template <int BITS, int U, int MS>
+template <int BITS, int U, int MS, bool FINE = false>
 __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
 {
-    decode_small_body<BITS, U, MS, 0>(batch, blockIdx.y);
+    decode_small_body<BITS, U, MS, 0, FINE>(batch, blockIdx.y);
 }
 
 // Grid row y multiplies layers 2y (gate) and 2y + 1 (up, whose Y receives H) of the batch, one after the other
@@ -1207,8 +1252,18 @@ hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nw
 
 template <int BITS>
 hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwaves, int u, int ms, size_t lds,
-                        bool gated_pairs, hipStream_t st)
+                        bool gated_pairs, bool fine, hipStream_t st)
 {
+    if (fine) {
+#define GWQ_SMALL_FINE(UU, MM) \
+    if (u == UU && ms == MM && !gated_pairs) return launch_kernel<&decode_small_kernel<BITS, UU, MM, true>>(batch, count, blocks, nwaves, lds, st)
+        GWQ_SMALL_FINE(4, 1); GWQ_SMALL_FINE(4, 2); GWQ_SMALL_FINE(4, 3); GWQ_SMALL_FINE(4, 4);
+        GWQ_SMALL_FINE(4, 5); GWQ_SMALL_FINE(4, 6); GWQ_SMALL_FINE(4, 7); GWQ_SMALL_FINE(4, 8);
+        GWQ_SMALL_FINE(8, 1); GWQ_SMALL_FINE(8, 2); GWQ_SMALL_FINE(8, 3); GWQ_SMALL_FINE(8, 4);
+        GWQ_SMALL_FINE(8, 5); GWQ_SMALL_FINE(8, 6); GWQ_SMALL_FINE(8, 7); GWQ_SMALL_FINE(8, 8);
+#undef GWQ_SMALL_FINE
+        return hipErrorInvalidValue;
+    }
 #define GWQ_SMALL(UU, MM) \
     if (u == UU && ms == MM) \
         return gated_pairs ? launch_kernel<&decode_small_gate_up_kernel<BITS, UU, MM>>(batch, count / 2, blocks, nwaves, lds, st) \
@@ -1261,12 +1316,13 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     }
     for (int i = count; i < kMaxBatch; ++i) batch.p[i] = batch.p[0];
     const int bits = P[0]->bits;
-    const size_t meta = (size_t)48 * max_gpr + 16;
+    const size_t meta = (size_t)48 * max_spr + 16;
 
     // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
     if (tune.bf16 && fine) return hipErrorNotSupported;
     const int lean_rows = tune.lean_rows > 0 ? tune.lean_rows : kLeanRows;
-    if (M <= lean_rows && (M <= 4 || !tune.gated_pairs) && !fine && !tune.bf16 && !(tune.stream == 2 && max_gpr <= 8 * kStreamU)) {
+    if (M <= lean_rows && (M <= 4 || !tune.gated_pairs) && !(fine && tune.gated_pairs) && !tune.bf16 &&
+        !(tune.stream == 2 && !fine && max_gpr <= 8 * kStreamU)) {
         int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
         if (waves_override > 0) {                       // the most waves that do not exceed the request
             u = 4;
@@ -1282,16 +1338,18 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         int total_blocks = 0;
         for (int i = 0; i < count; ++i) total_blocks += (P[i]->N + 15) / 16;
         const bool roomy = M <= 4 || 2 * lds <= kMaxLds || total_blocks <= 3 * device_cus();
-        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds && (M <= 4 || u <= 8) && roomy) {
+        // Small groups: at most three metadata vectors per thread (3 spr <= 3 blockDim).
+        const bool fine_ok = !fine || (u <= 8 && max_spr <= 64 * nwaves);
+        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds && (M <= 4 || u <= 8) && roomy && fine_ok) {
             batch.nwaves = nwaves;
             if (describe) {
-                snprintf(describe->text, sizeof(describe->text), "%s<%d,%d,%d> grid %dx%d block %d lds %zu",
-                         tune.gated_pairs ? "decode_small_gate_up_kernel" : "decode_small_kernel", bits, u, M, blocks,
-                         tune.gated_pairs ? count / 2 : count, 64 * nwaves, lds);
+                snprintf(describe->text, sizeof(describe->text), "%s<%d,%d,%d%s> grid %dx%d block %d lds %zu",
+                         tune.gated_pairs ? "decode_small_gate_up_kernel" : "decode_small_kernel", bits, u, M,
+                         fine ? ",true" : "", blocks, tune.gated_pairs ? count / 2 : count, 64 * nwaves, lds);
                 return hipSuccess;
             }
-            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, st)
-                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, st);
+            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, st)
+                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, st);
         }
     }
     if (tune.gated_pairs) return hipErrorNotSupported;  // only the kernel above multiplies gated pairs
