@@ -215,10 +215,13 @@ __device__ inline float silu(float x)
 // FINE: groups below 128.  The staged metadata is [16][spr] (up to three vectors per thread); a lane takes scale and
 // zero point per half slot, with the indices of a group at or beyond gpr clamped into the row and its scales masked,
 // and multiplies FP16 operands s * (q - z), as the wide kernel does for such layers.
-template <int BITS, int U, int MS, int MODE, bool FINE = false>
+// BF16: X and Y are bfloat16; operands 128 + q and a second set of MFMAs against ones, as in the wide kernel.
+template <int BITS, int U, int MS, int MODE, bool FINE = false, bool BF16 = false>
 __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, const int layer)
 {
     static_assert(!FINE || MODE == 0, "gated pairs: groups of 128 only");
+    static_assert(!BF16 || (MODE == 0 && !FINE), "bfloat16 activations: plain products with groups of 128 only");
+    typedef std::conditional_t<BF16, __bf16, _Float16> act_t;          // X and Y; both 16 bits wide
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const DecodeProblem &pr = batch.p[layer];
     const int N = pr.N, K = pr.K;
@@ -229,8 +232,8 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const int32_t *__restrict__ row_ptr = pr.row_ptr;
     const uint16_t *__restrict__ col_idx = pr.col_idx;
     const uint16_t *__restrict__ out_val = pr.out_val;
-    const _Float16 *__restrict__ X = pr.X;
-    _Float16 *__restrict__ Y = pr.Y;
+    const act_t *__restrict__ X = reinterpret_cast<const act_t *>(pr.X);
+    act_t *__restrict__ Y = reinterpret_cast<act_t *>(pr.Y);
     const int sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec, csr_last_vec = pr.csr_last_vec;
     const int shift = FINE ? pr.group_shift : 7;
     // The whole descriptor is requested in one go and only then looked at (the empty statement
@@ -256,7 +259,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
 
-    _Float16 *xs = reinterpret_cast<_Float16 *>(lds_raw);
+    act_t *xs = reinterpret_cast<act_t *>(lds_raw);
     const uint32_t sc_off = (uint32_t)MS * k_pad * 2;
     const uint32_t zp_off = sc_off + 32 * spr;
     const uint32_t spare_off = zp_off + 16 * spr;
@@ -393,7 +396,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     for (int e = 0; e < RA; ++e) acc[e] = 0.f;
     {
         const int x_row = r < MS ? r : 0;
-        const _Float16 *x_lane = xs + (uint32_t)x_row * k_pad + g_begin * kGroup + 32 * b;
+        const act_t *x_lane = xs + (uint32_t)x_row * k_pad + g_begin * kGroup + 32 * b;
         const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * gpr + g_begin;
         const uint8_t *zp_lane = lds_raw + zp_off + r * gpr + g_begin;
 #pragma unroll
@@ -422,13 +425,29 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
                 const uint32_t z_hi = BITS == 3 ? zp_row[i_hi] & keep : zp_row[i_hi];
                 slot[u].decode_halves(z_lo, z_hi, b, dc, wb, tail_lane4);
                 scale_halves(wb, s_lo * 0x10001u, s_hi * 0x10001u);
+            } else if constexpr (BF16) {
+                const DecodeConstsBf16 dbf(BITS);
+                const u32x4 ones = u32x4{kBf16Ones, kBf16Ones, kBf16Ones, kBf16Ones};
+                slot[u].decode_bf16(b, dbf, wb, tail_lane4);
+                float4v xsum = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    part = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[j]),
+                                                                   __builtin_bit_cast(bf16x8, wb[j]), part, 0, 0, 0);
+                    xsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[j]),
+                                                                   __builtin_bit_cast(bf16x8, ones), xsum, 0, 0, 0);
+                }
+                const float zc = -(float)(128u + zp_lane[u]);
+#pragma unroll
+                for (int e = 0; e < RA; ++e) part[e] = __builtin_fmaf(zc, xsum[e], part[e]);
             } else {
                 slot[u].decode(zp_lane[u], b, dc, wb, tail_lane4);
             }
+            if constexpr (!BF16)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[j]),
-                                                              __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xa[j]),
+                                                                  __builtin_bit_cast(half8, wb[j]), part, 0, 0, 0);
             const float s = FINE ? 1.f : (float)__builtin_bit_cast(_Float16, sc_lane[u]);
 #pragma unroll
             for (int e = 0; e < RA; ++e) acc[e] = __builtin_fmaf(s, part[e], acc[e]);
@@ -498,7 +517,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
             const int e = idx >> 4, c = idx & 15;
             float sum = 0.f;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * MS + e) * 16 + c];
-            if (row0 + c < N) Y[(size_t)e * N + row0 + c] = (_Float16)sum;
+            if (row0 + c < N) Y[(size_t)e * N + row0 + c] = (act_t)sum;
         }
         GWQ_TS(6);
         GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
@@ -529,17 +548,17 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
             if (lane < 16) *stash = sum;
         } else {
             if (MODE == 2) sum = silu(*stash) * sum;
-            if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (_Float16)sum;
+            if (lane < 16 && row0 + lane < N) Y[(size_t)e * N + row0 + lane] = (act_t)sum;
         }
     }
     GWQ_TS(6);                                          // stored
     GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
 }
 
-template <int BITS, int U, int MS, bool FINE = false>
+template <int BITS, int U, int MS, bool FINE = false, bool BF16 = false>
 __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
 {
-    decode_small_body<BITS, U, MS, 0, FINE>(batch, blockIdx.y);
+    decode_small_body<BITS, U, MS, 0, FINE, BF16>(batch, blockIdx.y);
 }
 
 // Grid row y multiplies layers 2y (gate) and 2y + 1 (up, whose Y receives H) of the batch, one after the other
@@ -1252,8 +1271,20 @@ hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nw
 
 template <int BITS>
 hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwaves, int u, int ms, size_t lds,
-                        bool gated_pairs, bool fine, hipStream_t st)
+                        bool gated_pairs, bool fine, bool bf16, hipStream_t st)
 {
+    if (bf16) {
+#define GWQ_SMALL_BF16(UU, MM) \
+    if (u == UU && ms == MM && !gated_pairs && !fine) \
+        return launch_kernel<&decode_small_kernel<BITS, UU, MM, false, true>>(batch, count, blocks, nwaves, lds, st)
+        GWQ_SMALL_BF16(4, 1); GWQ_SMALL_BF16(4, 2); GWQ_SMALL_BF16(4, 3); GWQ_SMALL_BF16(4, 4);
+        GWQ_SMALL_BF16(4, 5); GWQ_SMALL_BF16(4, 6); GWQ_SMALL_BF16(4, 7); GWQ_SMALL_BF16(4, 8);
+        GWQ_SMALL_BF16(8, 1); GWQ_SMALL_BF16(8, 2); GWQ_SMALL_BF16(8, 3); GWQ_SMALL_BF16(8, 4);
+        GWQ_SMALL_BF16(8, 5); GWQ_SMALL_BF16(8, 6); GWQ_SMALL_BF16(8, 7); GWQ_SMALL_BF16(8, 8);
+        GWQ_SMALL_BF16(16, 1); GWQ_SMALL_BF16(16, 2);
+#undef GWQ_SMALL_BF16
+        return hipErrorInvalidValue;
+    }
     if (fine) {
 #define GWQ_SMALL_FINE(UU, MM) \
     if (u == UU && ms == MM && !gated_pairs) return launch_kernel<&decode_small_kernel<BITS, UU, MM, true>>(batch, count, blocks, nwaves, lds, st)
@@ -1321,7 +1352,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     // The lean kernel: M <= 4, every wave owning exactly U groups, at most 16 waves, X in LDS.
     if (tune.bf16 && fine) return hipErrorNotSupported;
     const int lean_rows = tune.lean_rows > 0 ? tune.lean_rows : kLeanRows;
-    if (M <= lean_rows && (M <= 4 || !tune.gated_pairs) && !(fine && tune.gated_pairs) && !tune.bf16 &&
+    if (M <= lean_rows && (M <= 4 || !tune.gated_pairs) && !(fine && tune.gated_pairs) && !(tune.bf16 && tune.gated_pairs) &&
         !(tune.stream == 2 && !fine && max_gpr <= 8 * kStreamU)) {
         int u = max_gpr > 128 ? 16 : max_gpr > 16 ? 8 : 4;
         if (waves_override > 0) {                       // the most waves that do not exceed the request
@@ -1345,11 +1376,12 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
             if (describe) {
                 snprintf(describe->text, sizeof(describe->text), "%s<%d,%d,%d%s> grid %dx%d block %d lds %zu",
                          tune.gated_pairs ? "decode_small_gate_up_kernel" : "decode_small_kernel", bits, u, M,
-                         fine ? ",true" : "", blocks, tune.gated_pairs ? count / 2 : count, 64 * nwaves, lds);
+                         tune.bf16 ? ",false,true" : fine ? ",true" : "", blocks, tune.gated_pairs ? count / 2 : count,
+                         64 * nwaves, lds);
                 return hipSuccess;
             }
-            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, st)
-                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, st);
+            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, tune.bf16, st)
+                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, tune.bf16, st);
         }
     }
     if (tune.gated_pairs) return hipErrorNotSupported;  // only the kernel above multiplies gated pairs
