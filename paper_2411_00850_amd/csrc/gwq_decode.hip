@@ -1281,7 +1281,7 @@ hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwa
         GWQ_SMALL_BF16(4, 5); GWQ_SMALL_BF16(4, 6); GWQ_SMALL_BF16(4, 7); GWQ_SMALL_BF16(4, 8);
         GWQ_SMALL_BF16(8, 1); GWQ_SMALL_BF16(8, 2); GWQ_SMALL_BF16(8, 3); GWQ_SMALL_BF16(8, 4);
         GWQ_SMALL_BF16(8, 5); GWQ_SMALL_BF16(8, 6); GWQ_SMALL_BF16(8, 7); GWQ_SMALL_BF16(8, 8);
-        GWQ_SMALL_BF16(16, 1); GWQ_SMALL_BF16(16, 2);
+        GWQ_SMALL_BF16(16, 1);                           // (16, 2) would need more than the 128 registers of a 16-wave block
 #undef GWQ_SMALL_BF16
         return hipErrorInvalidValue;
     }
@@ -1371,7 +1371,7 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         const bool roomy = M <= 4 || 2 * lds <= kMaxLds || total_blocks <= 3 * device_cus();
         // Small groups: at most three metadata vectors per thread (3 spr <= 3 blockDim).
         const bool fine_ok = !fine || (u <= 8 && max_spr <= 64 * nwaves);
-        if (nwaves <= 16 && (u < 16 || M <= 2) && x_bytes <= kXLdsBudget && lds <= kMaxLds && (M <= 4 || u <= 8) && roomy && fine_ok) {
+        if (nwaves <= 16 && (u < 16 || M <= (tune.bf16 ? 1 : 2)) && x_bytes <= kXLdsBudget && lds <= kMaxLds && (M <= 4 || u <= 8) && roomy && fine_ok) {
             batch.nwaves = nwaves;
             if (describe) {
                 snprintf(describe->text, sizeof(describe->text), "%s<%d,%d,%d%s> grid %dx%d block %d lds %zu",
