@@ -444,7 +444,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             row_off[j] = (uint32_t)rc * (uint32_t)K * 2u + 16u * (uint32_t)((lane & 7) ^ x_swizzle(r));
         }
         const char *tile = reinterpret_cast<const char *>(X + (size_t)m0 * K + k_first);
-        const uint32_t lds_x = (uint32_t)(uintptr_t)lds + (uint32_t)(lw * kInstr) * 1024u;
+        typedef __attribute__((address_space(3))) unsigned char lds_byte;
+        const uint32_t lds_x = (uint32_t)(uintptr_t)(lds_byte *)lds + (uint32_t)(lw * kInstr) * 1024u;   // LDS byte offset of the wave's first KB
         auto issue_x = [&](int step, int buf) {
             const char *src = tile + (size_t)step * (kBK * 2);
             const uint32_t dst = lds_x + (uint32_t)buf * (uint32_t)(kXBufHalves * 2);
@@ -452,7 +453,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint32_t *__restri
             // Written out instead of __builtin_amdgcn_global_load_lds: with the scalar base and a 32-bit lane offset
             // the load needs no address arithmetic; the builtin forms a 64-bit address per lane and load, and the
             // whole GEMM measured 4.5 % slower with it (7B layer, M = 2048: 895 against 935 TFLOP/s on one machine).
-            // m0 (the LDS base of the wave's 1 KB) is written here only: nothing else in this kernel uses it.
+            // m0 (the LDS base of the wave's 1 KB) is written here only and nothing else in a loader wave reads it (no
+            // other LDS-destination load, no indexed register move, no message); the compiler does not accept m0 in
+            // a clobber list (it warns that the register is reserved), so this is stated rather than declared.
             for (int j = 0; j < kInstr; ++j)
                 asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                              :: "s"(dst + j * 1024u), "v"(row_off[j]), "s"(src) : "memory");

@@ -57,6 +57,54 @@ def test_linear_calls_replay_from_a_graph(bits):
     assert np.abs(ys[3].cpu().numpy() - ref).max() <= 1e-2 * np.abs(ref).max()
 
 
+def test_gate_up_bf16_and_small_groups_replay_from_a_graph():
+    """gwq_linear_gate_up (fused for M <= 4, two products and an elementwise kernel beyond), gwq_linear_bf16 (decode and
+    GEMM) and gwq_linear on a layer with groups of 16, captured together and replayed after the inputs changed."""
+    import torch
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import to_gpu, upload_packed
+    N, K = 176, 1024
+    W, S, rng = _layer(31, N, K, 4)
+    W2, S2, _ = _layer(32, N, K, 4)
+    Dg, Du = upload_packed(orc.pack(W, S, 4, 10000)), upload_packed(orc.pack(W2, S2, 4, 10000))
+    P16 = orc.pack(W, S, 4, 10000, 16)
+    D16 = upload_packed(P16)
+    Ms = (2, 12, 40)
+    xs = [to_gpu(gs.activations(M, K, rng)) for M in Ms]
+    xb = [x.to(torch.bfloat16) for x in xs]
+    hs = [torch.empty((M, N), dtype=torch.float16, device="cuda") for M in Ms[:2]]
+    yb = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for M in Ms]
+    y16 = [torch.empty((M, N), dtype=torch.float16, device="cuda") for M in Ms]
+    wsb = [gwq.linear_workspace(Dg, M) for M in Ms]
+    calls = [gwq.prepare_linear_gate_up(Dg, Du, xs[i], hs[i]) for i in range(2)]
+    calls += [(lambda i=i: gwq.linear_bf16(Dg, xb[i], yb[i], workspace=wsb[i])) for i in range(3)]
+    calls += [gwq.prepare_linear(D16, xs[i], y16[i]) for i in range(3)]
+    outs = hs + yb + y16
+    for c in calls:
+        c()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in calls:
+            c()
+    for trial in range(3):
+        for x, b in zip(xs, xb):
+            x.copy_(to_gpu(gs.activations(x.shape[0], K, rng)))
+            b.copy_(x)
+        for y in outs:
+            y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = [y.clone() for y in outs]
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        for got, want in zip(replayed, outs):
+            assert torch.equal(got, want), f"replay {trial} differs from the eager result"
+    ref = orc.linear_f64(P16, xs[2].cpu().numpy())
+    assert np.abs(y16[2].cpu().numpy() - ref).max() <= 1e-2 * np.abs(ref).max()
+
+
 def test_pack_and_quality_replay_from_a_graph():
     import torch
     import paper_2411_00850_amd as gwq
