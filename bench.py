@@ -832,20 +832,20 @@ def main():
         for name, Wd, Sd in pack_inputs if "pack" in legs else ():
             settle(lambda: gwq.pack(Wd, Sd, 4, 10000))
             t = time.perf_counter()
-            for _ in range(5):
+            for _ in range(20):
                 P = gwq.pack(Wd, Sd, 4, 10000)
             torch.cuda.synchronize()
-            s = (time.perf_counter() - t) / 5
+            s = (time.perf_counter() - t) / 20
             b = Wd.numel() * 6 + P.nbytes()
             pk[name] = {"ms": round(s * 1e3, 3), "GB/s": round(b / s / 1e9, 1)}
             if name == "gate":                          # the same layer ranked by FP16 scores: two select passes, 2-byte reads
                 Sh = Sd.half()
                 settle(lambda: gwq.pack(Wd, Sh, 4, 10000))
                 t = time.perf_counter()
-                for _ in range(5):
+                for _ in range(20):
                     Ph = gwq.pack(Wd, Sh, 4, 10000)
                 torch.cuda.synchronize()
-                sh = (time.perf_counter() - t) / 5
+                sh = (time.perf_counter() - t) / 20
                 bh = Wd.numel() * 4 + Ph.nbytes()
                 pk["gate_f16_score"] = {"ms": round(sh * 1e3, 3), "GB/s": round(bh / sh / 1e9, 1)}
                 del Sh, Ph

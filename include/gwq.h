@@ -257,7 +257,8 @@ gwq_status gwq_probe_mfma(int32_t blocks, int32_t iters, void *sink, void *strea
  * "decode_stream" (1: never the streaming decode kernel; 2: also for M <= 4, wherever K <= 4096 lets it
  * run; by default it takes 5 <= M <= 16 there), "decode_tiles" (16-channel tiles per block of the streaming
  * kernel, 1..4096), "decode_lean_rows" (1..8: the largest M handled by the kernel that keeps all of X[M][K] in LDS,
- * where it fits), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
+ * where it fits), "pack_full_passes" (1: gwq_pack finds the threshold and the per-row counts by passes over all
+ * scores even where the short list of candidate keys would do), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
  * M = 512 and below that the shape a cost model of the launch expects to be fastest).  Unknown keys or
  * out-of-range values return GWQ_ERR_UNSUPPORTED. */
 gwq_status gwq_tuning_set(const char *key, int32_t value);

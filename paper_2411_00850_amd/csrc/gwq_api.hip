@@ -40,6 +40,7 @@ std::atomic<int> g_gemm_ms{0};        // rows of Y per GEMM block; 0 = heuristic
 std::atomic<int> g_decode_stream{0};  // 0 = heuristic, 1 = never the streaming kernel, 2 = wherever it can run
 std::atomic<int> g_decode_tiles{0};   // tiles per block of the streaming kernel; 0 = heuristic
 std::atomic<int> g_decode_lean{0};    // largest M of the kernel that keeps X[M][K] in LDS; 0 = built-in
+std::atomic<int> g_pack_full{0};      // 1: gwq_pack always runs its passes over all scores (never the candidate list)
 
 gwq::DecodeTuning decode_tuning() { return gwq::DecodeTuning{g_decode_waves, g_decode_stream, g_decode_tiles, g_decode_lean}; }
 
@@ -144,7 +145,7 @@ gwq_status gwq_layout(int32_t N, int32_t K, int32_t bits, int32_t group, uint32_
     out->row_ptr = (size_t)(N + 1) * 4;
     out->col_idx = ((size_t)k_out * 2 + 15) / 16 * 16 + 16;
     out->out_val = out->col_idx;
-    out->pack_workspace = gwq::pack_workspace_bytes(N);
+    out->pack_workspace = gwq::pack_workspace_bytes(N, K);
     out->linear_index = gwq::gemm_index_bytes(N, K, group);
     out->linear_scratch = gwq::gemm_scratch_bytes(N, M_max);
     out->linear_workspace = M_max > 16 ? out->linear_index + out->linear_scratch : 0;
@@ -160,10 +161,10 @@ gwq_status gwq_pack(const void *W_f16, const void *score, int32_t score_dtype, g
     gwq_status s = check_packed(dst);
     if (s != GWQ_OK) return s;
     if (score_dtype != GWQ_SCORE_F32 && score_dtype != GWQ_SCORE_F16) return GWQ_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < gwq::pack_workspace_bytes(dst->N)) return GWQ_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < gwq::pack_workspace_bytes(dst->N, dst->K)) return GWQ_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 3) || ((uintptr_t)W_f16 & 15) || ((uintptr_t)score & 15)) return GWQ_ERR_SHAPE;
     hipError_t e = gwq::launch_pack(W_f16, score, score_dtype == GWQ_SCORE_F16, *dst,
-                                    static_cast<uint32_t *>(workspace), static_cast<hipStream_t>(stream));
+                                    static_cast<uint32_t *>(workspace), g_pack_full != 0, static_cast<hipStream_t>(stream));
     if (e == hipSuccess && dst->index) e = gwq::launch_gemm_index(*dst, dst->index, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GWQ_OK : GWQ_ERR_DEVICE;
 }
@@ -409,6 +410,11 @@ gwq_status gwq_tuning_set(const char *key, int32_t value)
     if (!strcmp(key, "decode_lean_rows")) {
         if (value < 0 || value > 8) return GWQ_ERR_UNSUPPORTED;
         g_decode_lean = value;
+        return GWQ_OK;
+    }
+    if (!strcmp(key, "pack_full_passes")) {
+        if (value < 0 || value > 1) return GWQ_ERR_UNSUPPORTED;
+        g_pack_full = value;
         return GWQ_OK;
     }
     if (!strcmp(key, "gemm_rows")) {

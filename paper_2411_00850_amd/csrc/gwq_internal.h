@@ -29,15 +29,29 @@ hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<uint32_t
 // kWsRows + 0*N ..       per row: count of keys above the threshold
 // kWsRows + 1*N ..       per row: count of keys equal to the threshold
 // kWsRows + 2*N ..       per row: how many of its threshold ties are kept
+// kWsRows + 3*N ..       kSelBins words: histogram of the second digit over the candidates (below)
+// then                   per row: number of candidates; then the candidates' keys, [N][pack_candidates_per_row(K)]
+// kWsCandOverflow        nonzero when some row had more candidates than its share of the list holds
+// Candidates are the keys whose first digit equals the threshold's: after the first pass over the scores only
+// they can still decide the threshold, so the second and third digit and the per-row counts are worked out on
+// that short list instead of in three more passes over all scores.  Every row has its own part of the list (no
+// counter shared between blocks).  When a row's part does not hold its candidates (scores with very many equal or
+// nearly equal magnitudes) the full passes run instead; both ways give the same result.
 constexpr int kWsPrefix = 3 * kSelBins;
 constexpr int kWsRemaining = kWsPrefix + 1;
+constexpr int kWsCandOverflow = kWsPrefix + 3;
 constexpr int kWsRows = kWsPrefix + 16;
 
-inline size_t pack_workspace_bytes(int64_t N) { return (size_t)(kWsRows + 3 * N) * 4 + 256; }
+inline int pack_candidates_per_row(int64_t K) { return K / 32 < 32 ? 32 : (int)(K / 32); }
+inline size_t pack_workspace_bytes(int64_t N, int64_t K)
+{
+    return (size_t)(kWsRows + 3 * N + kSelBins + N + N * pack_candidates_per_row(K)) * 4 + 256;
+}
 
 // Launchers (defined in the .hip files).  Each enqueues on `stream` and returns the last HIP error.
+// full_passes: measurement and test hook - never use the candidate list (always the passes over all scores).
 hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
-                       uint32_t *ws, hipStream_t stream);
+                       uint32_t *ws, bool full_passes, hipStream_t stream);
 // Measurement overrides of the decode launch (0 = built-in choice): waves per block of the kernel for M <= 4;
 // streaming kernel 1 = never, 2 = for every M <= 16 it can take; its tiles per block.
 struct DecodeTuning {

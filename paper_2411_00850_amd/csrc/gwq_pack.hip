@@ -58,10 +58,12 @@ template <bool F16> __device__ inline void load_keys8(const void *score, size_t 
     }
 }
 
-__global__ void init_ws_kernel(uint32_t *ws, uint32_t k_out)
+__global__ void init_ws_kernel(uint32_t *ws, uint32_t k_out, int N)
 {
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kWsRows; i += gridDim.x * blockDim.x)
         ws[i] = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kSelBins; i += gridDim.x * blockDim.x)
+        ws[kWsRows + 3 * N + i] = 0;                    // the candidates' histogram
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         // With nothing to select the threshold sits above every key, so no entry qualifies.
         ws[kWsPrefix] = k_out ? 0u : 0xFFFFFFFFu;
@@ -74,9 +76,35 @@ __global__ void init_ws_kernel(uint32_t *ws, uint32_t k_out)
 // every block flushes its non-empty bins with global atomics, in the first pass a few hundred bins
 // per block and all blocks on the same addresses, which with 2048 blocks took longer than the pass
 // over the keys.
-template <int PASS, bool F16>
-__global__ __launch_bounds__(kThreads) void hist_kernel(const void *score, size_t total, uint32_t *ws)
+// Which way a launch belongs to: both ways are enqueued (the choice is made on the device, by the pass that
+// collects the candidates) and the kernels of the way not taken return at once.
+enum When { kAlways = 0, kWithCandidates = 1, kWithoutCandidates = 2 };
+__device__ inline bool not_my_turn(const uint32_t *ws, int when)
 {
+    const bool overflow = ws[kWsCandOverflow] != 0;
+    return (when == kWithCandidates && overflow) || (when == kWithoutCandidates && !overflow);
+}
+
+// With candidates (PASS 2 only, per_row > 0): when the candidates fitted, the third digit is counted over them instead
+// (one wave per row of the list, global atomics: they are few), and the scores are not read.
+template <int PASS, bool F16>
+__global__ __launch_bounds__(kThreads) void hist_kernel(const void *score, size_t total, uint32_t *ws, int when, int N = 0,
+                                                        int per_row = 0)
+{
+    if (PASS == 2 && per_row > 0 && ws[kWsCandOverflow] == 0) {
+        const uint32_t prefix = ws[kWsPrefix];
+        const uint32_t *counts = ws + kWsRows + 3 * N + kSelBins, *keys = counts + N;
+        const int lane = threadIdx.x & 63;
+        for (int n = blockIdx.x * kWaves + (threadIdx.x >> 6); n < N; n += gridDim.x * kWaves) {
+            const uint32_t count = counts[n];
+            for (uint32_t i = lane; i < count; i += 64) {
+                const uint32_t key = keys[(size_t)n * per_row + i];
+                if (prefix_matches<2>(key, prefix)) atomicAdd(&ws[2 * kSelBins + digit_of<2>(key)], 1u);
+            }
+        }
+        return;
+    }
+    if (not_my_turn(ws, when)) return;
     __shared__ uint32_t h[kSelBins];
     for (int i = threadIdx.x; i < kSelBins; i += kThreads) h[i] = 0;
     __syncthreads();
@@ -97,10 +125,12 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(const void *score, size_
 
 // Pick the digit d of this pass: (#keys with digit > d) < remaining <= (#keys with digit >= d).
 // One block of kSelBins / 2 threads; suffix sums by a doubling scan in LDS.
-template <int PASS> __global__ __launch_bounds__(kSelBins / 2) void pick_kernel(uint32_t *ws)
+// hist: word offset of the histogram in ws; hist_candidates (when not negative): the one to read instead when the
+// candidates fitted.
+template <int PASS> __global__ __launch_bounds__(kSelBins / 2) void pick_kernel(uint32_t *ws, int hist, int hist_candidates)
 {
     __shared__ uint32_t a[2][kSelBins + 1];
-    const uint32_t *g = ws + PASS * kSelBins;
+    const uint32_t *g = ws + (hist_candidates >= 0 && ws[kWsCandOverflow] == 0 ? hist_candidates : hist);
     const int t = threadIdx.x;
     a[0][t] = g[t];
     a[0][t + kSelBins / 2] = g[t + kSelBins / 2];
@@ -163,12 +193,29 @@ __device__ inline uint32_t block_exclusive_scan(uint32_t v, uint32_t *smem, uint
 }
 
 // Per row: how many keys are above the threshold and how many are equal to it.
+// With candidates (per_row > 0) and when they fitted: only the row's candidates are looked at - the keys with a larger
+// first digit are counted already (candidates_kernel) - and the scores are not read.
 template <bool F16>
-__global__ __launch_bounds__(kThreads) void row_count_kernel(const void *score, int K, uint32_t *ws, int N)
+__global__ __launch_bounds__(kThreads) void row_count_kernel(const void *score, int K, uint32_t *ws, int N, int per_row)
 {
     __shared__ uint32_t red[2][kWaves];
     const int n = blockIdx.x;
     const uint32_t thr = ws[kWsPrefix];
+    if (per_row > 0 && ws[kWsCandOverflow] == 0) {
+        if (threadIdx.x >= 64) return;                  // a row's candidates are few: one wave
+        const uint32_t *counts = ws + kWsRows + 3 * N + kSelBins, *keys = counts + N + (size_t)n * per_row;
+        const uint32_t count = counts[n];
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t i = threadIdx.x; i < count; i += 64) {
+            const uint32_t key = keys[i];
+            gt += key > thr;
+            eq += key == thr;
+        }
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d); eq += __shfl_xor(eq, d); }
+        if (threadIdx.x == 0) { ws[kWsRows + n] += gt; ws[kWsRows + N + n] = eq; }
+        return;
+    }
     uint32_t gt = 0, eq = 0;
     for (int k = threadIdx.x * 8; k < K; k += kElemsPerIter) {
         uint32_t key[8];
@@ -188,23 +235,90 @@ __global__ __launch_bounds__(kThreads) void row_count_kernel(const void *score, 
     }
 }
 
+// The second pass over the scores when candidates are collected: per row the count of keys whose first digit is above
+// the threshold's (they are above the threshold whatever its other digits are), and the keys whose first digit equals
+// it - the candidates - written to the row's part of the list and entered into the histogram of the second digit.  A
+// row with more candidates than its part holds raises the overflow flag (then the full passes run).
+template <bool F16>
+__global__ __launch_bounds__(kThreads) void candidates_kernel(const void *score, int K, uint32_t *ws, int N, int per_row,
+                                                              int force_overflow)
+{
+    __shared__ uint32_t red[kWaves];
+    __shared__ uint32_t count_s;
+    const int n = blockIdx.x;
+    if (threadIdx.x == 0) count_s = 0;
+    __syncthreads();
+    const uint32_t p0 = ws[kWsPrefix] >> 20;
+    uint32_t *hist = ws + kWsRows + 3 * N, *counts = hist + kSelBins, *keys = counts + N + (size_t)n * per_row;
+    uint32_t gt = 0;
+    for (int k = threadIdx.x * 8; k < K; k += kElemsPerIter) {
+        uint32_t key[8];
+        load_keys8<F16>(score, (size_t)n * K + k, key);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t d0 = key[i] >> 20;
+            gt += d0 > p0;
+            // One LDS atomic per wave and position: the first candidate lane reserves the slots, the others take
+            // theirs by their rank among the wave's candidate lanes.
+            const bool cand = d0 == p0;
+            const unsigned long long m = __ballot(cand);
+            if (m) {
+                const int leader = __builtin_ctzll(m);
+                uint32_t first = 0;
+                if ((int)(threadIdx.x & 63) == leader) first = atomicAdd(&count_s, (uint32_t)__builtin_popcountll(m));
+                first = __shfl(first, leader);
+                if (cand) {
+                    const uint32_t slot = first + (uint32_t)__builtin_popcountll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
+                    if (slot < (uint32_t)per_row) {
+                        keys[slot] = key[i];
+                        atomicAdd(&hist[digit_of<1>(key[i])], 1u);
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) gt += __shfl_xor(gt, d);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = gt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t a = 0;
+        for (int i = 0; i < kWaves; ++i) a += red[i];
+        ws[kWsRows + n] = a;                            // row_count_kernel adds the candidates above the threshold (or counts anew)
+        ws[kWsRows + N + n] = 0;
+        const uint32_t count = count_s;
+        counts[n] = count < (uint32_t)per_row ? count : (uint32_t)per_row;
+        if (force_overflow || count > (uint32_t)per_row) ws[kWsCandOverflow] = 1u;
+    }
+}
+
 // Ties at the threshold are kept in flat-index order until `remaining` of them are taken;
 // row_ptr is the running count of kept entries.  One block; a thread takes kRowsPerThread
-// consecutive rows per round, so that a round of two block scans covers 1024 rows.
-constexpr int kRowsPerThread = 4;
+// consecutive rows per round, so that a round of two block scans covers 2048 rows.  The rows' counts go
+// through LDS: read from memory with consecutive threads on consecutive rows, handed to the thread that owns them.
+constexpr int kRowsPerThread = 8;
 __global__ __launch_bounds__(kThreads) void row_scan_kernel(uint32_t *ws, int N, int32_t *row_ptr)
 {
+    constexpr int kRound = kThreads * kRowsPerThread;
     __shared__ uint32_t smem[kWaves];
+    __shared__ uint32_t s_gt[kRound], s_eq[kRound];
     const uint32_t need = ws[kWsRemaining];
     uint32_t eq_before = 0, kept_before = 0;
-    for (int n0 = 0; n0 < N; n0 += kThreads * kRowsPerThread) {
-        const int base = n0 + threadIdx.x * kRowsPerThread;
+    for (int n0 = 0; n0 < N; n0 += kRound) {
+        __syncthreads();                                // the round before is done with the LDS arrays
+#pragma unroll
+        for (int i = 0; i < kRowsPerThread; ++i) {
+            const int l = i * kThreads + threadIdx.x, n = n0 + l;
+            s_gt[l] = n < N ? ws[kWsRows + n] : 0u;
+            s_eq[l] = n < N ? ws[kWsRows + N + n] : 0u;
+        }
+        __syncthreads();
+        const int local = threadIdx.x * kRowsPerThread, base = n0 + local;
         uint32_t gt[kRowsPerThread], eq[kRowsPerThread], eq_sum = 0;
 #pragma unroll
         for (int i = 0; i < kRowsPerThread; ++i) {
-            const int n = base + i;
-            gt[i] = n < N ? ws[kWsRows + n] : 0u;
-            eq[i] = n < N ? ws[kWsRows + N + n] : 0u;
+            gt[i] = s_gt[local + i];
+            eq[i] = s_eq[local + i];
             eq_sum += eq[i];
         }
         uint32_t eq_total, kept_total;
@@ -217,11 +331,18 @@ __global__ __launch_bounds__(kThreads) void row_scan_kernel(uint32_t *ws, int N,
             kept_sum += gt[i] + take[i];
         }
         uint32_t pos = kept_before + block_exclusive_scan(kept_sum, smem, kept_total);
+        // results back through LDS, written out with consecutive threads on consecutive rows
 #pragma unroll
         for (int i = 0; i < kRowsPerThread; ++i) {
-            const int n = base + i;
-            if (n < N) { ws[kWsRows + 2 * N + n] = take[i]; row_ptr[n] = (int32_t)pos; }
+            s_gt[local + i] = take[i];
+            s_eq[local + i] = pos;
             pos += gt[i] + take[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kRowsPerThread; ++i) {
+            const int l = i * kThreads + threadIdx.x, n = n0 + l;
+            if (n < N) { ws[kWsRows + 2 * N + n] = s_gt[l]; row_ptr[n] = (int32_t)s_eq[l]; }
         }
         eq_before += eq_total;
         kept_before += kept_total;
@@ -389,26 +510,33 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const uint16_t *__rest
 }
 
 template <bool F16>
-hipError_t run_select(const void *score, int N, int K, uint32_t *ws, int32_t *row_ptr, bool any, hipStream_t st)
+hipError_t run_select(const void *score, int N, int K, uint32_t *ws, int32_t *row_ptr, bool any, bool full_passes,
+                      hipStream_t st)
 {
     const size_t total = (size_t)N * K;
     const size_t want = (total / 8 + kThreads - 1) / kThreads;
     const int blocks = (int)(want < 512 ? (want ? want : 1) : 512);
+    const int per_row = pack_candidates_per_row(K);
     if (any) {
         // With nothing to keep the threshold set by init_ws_kernel already sits above every key.
-        hist_kernel<0, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
-        pick_kernel<0><<<1, kSelBins / 2, 0, st>>>(ws);
-        hist_kernel<1, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
-        pick_kernel<1><<<1, kSelBins / 2, 0, st>>>(ws);
-        // The key of an FP16 score is its exact binary32 widening, whose low 13 bits are zero (payloads of
-        // NaNs included): the third pass would find every key in bin 0 and change nothing, so FP16 scores
-        // are selected in two passes.
+        hist_kernel<0, F16><<<blocks, kThreads, 0, st>>>(score, total, ws, kAlways);
+        pick_kernel<0><<<1, kSelBins / 2, 0, st>>>(ws, 0, -1);
+        // Second pass over the scores: the first digit's share of the per-row counts, and the candidates.
+        candidates_kernel<F16><<<N, kThreads, 0, st>>>(score, K, ws, N, per_row, full_passes ? 1 : 0);
+        // Every launch from here on takes the candidates where they fitted and the scores where not; the one pass
+        // that only the second way needs returns at once on the first.
+        hist_kernel<1, F16><<<blocks, kThreads, 0, st>>>(score, total, ws, kWithoutCandidates);
+        pick_kernel<1><<<1, kSelBins / 2, 0, st>>>(ws, 1 * kSelBins, kWsRows + 3 * N);
+        // (The key of an FP16 score is its exact binary32 widening, whose low 13 bits are zero, payloads of NaNs
+        // included: the third digit is 0 for every key, so FP16 scores are selected by two digits.)
         if (!F16) {
-            hist_kernel<2, F16><<<blocks, kThreads, 0, st>>>(score, total, ws);
-            pick_kernel<2><<<1, kSelBins / 2, 0, st>>>(ws);
+            hist_kernel<2, F16><<<blocks, kThreads, 0, st>>>(score, total, ws, kAlways, N, per_row);
+            pick_kernel<2><<<1, kSelBins / 2, 0, st>>>(ws, 2 * kSelBins, -1);
         }
+        row_count_kernel<F16><<<N, kThreads, 0, st>>>(score, K, ws, N, per_row);
+    } else {
+        row_count_kernel<F16><<<N, kThreads, 0, st>>>(score, K, ws, N, 0);
     }
-    row_count_kernel<F16><<<N, kThreads, 0, st>>>(score, K, ws, N);
     row_scan_kernel<<<1, kThreads, 0, st>>>(ws, N, row_ptr);
     return hipGetLastError();
 }
@@ -425,13 +553,13 @@ hipError_t run_encode(const void *W, const void *score, const gwq_packed &P, con
 }  // namespace
 
 hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const gwq_packed &P,
-                       uint32_t *ws, hipStream_t st)
+                       uint32_t *ws, bool full_passes, hipStream_t st)
 {
-    init_ws_kernel<<<8, kThreads, 0, st>>>(ws, (uint32_t)P.n_outliers);
+    init_ws_kernel<<<8, kThreads, 0, st>>>(ws, (uint32_t)P.n_outliers, P.N);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = score_is_f16 ? run_select<true>(score, P.N, P.K, ws, P.row_ptr, P.n_outliers > 0, st)
-                     : run_select<false>(score, P.N, P.K, ws, P.row_ptr, P.n_outliers > 0, st);
+    e = score_is_f16 ? run_select<true>(score, P.N, P.K, ws, P.row_ptr, P.n_outliers > 0, full_passes, st)
+                     : run_select<false>(score, P.N, P.K, ws, P.row_ptr, P.n_outliers > 0, full_passes, st);
     if (e != hipSuccess) return e;
     if (P.bits == 4)
         return score_is_f16 ? run_encode<4, true>(W, score, P, ws, st) : run_encode<4, false>(W, score, P, ws, st);

@@ -219,3 +219,79 @@ def test_pack_7b_shapes_full(name, N, K, mid):
     mask = orc.select(S, 10000)
     for bits in (4, 3):
         assert_packed_equal(_gpu_pack(W, S, bits, 10000), orc.encode(W, mask, bits, 10000))
+
+
+# ---- the two ways gwq_pack finds the threshold ---------------------------------------------------------------------
+# After the first pass over the scores only the keys whose leading 11 bits equal the threshold's can still decide it:
+# gwq_pack collects them (a row's part of the list holds K / 32 keys, at least 32) and works out the remaining digits
+# and the per-row counts on that list; when some row's candidates do not fit it runs its passes over all scores instead.
+# Both ways must give the oracle's bytes.
+
+@pytest.fixture
+def full_passes():
+    import paper_2411_00850_amd as gwq
+    gwq.tuning_set("pack_full_passes", 1)
+    yield
+    gwq.tuning_set("pack_full_passes", 0)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("kind", ["plain", "ties_f32", "f16_scores", "all_equal", "signed_zero_nan_inf"])
+def test_pack_with_full_passes_forced(bits, kind, full_passes):
+    from gpu_helpers import assert_packed_equal
+    N, K = 96, 1280
+    W, S = _small(20, N, K, score_dtype=np.float16 if kind == "f16_scores" else np.float32, ties=kind == "ties_f32")
+    if kind == "all_equal":
+        S[:] = 0.125
+    if kind == "signed_zero_nan_inf":
+        idx = np.random.default_rng(1).choice(N * K, 400, replace=False)
+        S.ravel()[idx[:100]] = np.nan
+        S.ravel()[idx[100:200]] = np.inf
+        S.ravel()[idx[200:300]] = -0.0
+        S.ravel()[idx[300:]] = -np.inf
+    for ppm in (1, 10000, 50000, 999999):
+        assert_packed_equal(_gpu_pack(W, S, bits, ppm), orc.pack(W, S, bits, ppm))
+
+
+@pytest.mark.parametrize("score_dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("kind", ["all_equal", "one_row_equal", "narrow_band", "just_fits"])
+def test_pack_when_the_candidates_do_not_fit(kind, score_dtype):
+    """Scores that put more keys next to the threshold than the list holds: all magnitudes equal (every key is a
+    candidate), one row of 11008 equal magnitudes at the threshold, magnitudes within one eighth of an octave (all share
+    the leading 11 bits) - and a band of such keys thin enough to fit (about 31 of a row's 72 places), for the boundary."""
+    from gpu_helpers import assert_packed_equal
+    rng = np.random.default_rng(77)
+    N, K = (40, 11008) if kind == "one_row_equal" else (64, 2304)
+    W = gs.weight(N, K, rng, planted_cols=2)
+    if kind == "all_equal":
+        S = np.full((N, K), 0.375, np.float32) * rng.choice([-1.0, 1.0], (N, K)).astype(np.float32)
+    elif kind == "one_row_equal":
+        S = (rng.random((N, K)) * 0.5).astype(np.float32)
+        S[17] = 0.75                                       # the top 2.5 % of the matrix: the threshold falls into this row
+    elif kind == "narrow_band":
+        S = (1.0 + rng.random((N, K)) * 0.06).astype(np.float32)          # all keys share exponent and three mantissa bits
+    else:
+        S = (rng.random((N, K)) * 0.5).astype(np.float32)
+        band = rng.choice(N * K, 2000, replace=False)
+        S.ravel()[band] = (1.0 + rng.random(2000) * 0.06).astype(np.float32)
+    S = S.astype(score_dtype)
+    for bits, ppm in ((4, 10000), (3, 25000), (4, 500)):
+        assert_packed_equal(_gpu_pack(W, S, bits, ppm), orc.pack(W, S, bits, ppm))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_pack_7b_shape_both_ways(bits):
+    """A 7B projection at full size through the candidate list and through the full passes: the same bytes."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_packed_equal, download_packed
+    W, S = gs.layer_matrix(2, 0, 4096, 4096)
+    P = orc.pack(W, S, bits, 10000)
+    D = _gpu_pack(W, S, bits, 10000)
+    assert_packed_equal(D, P)
+    gwq.tuning_set("pack_full_passes", 1)
+    try:
+        D2 = _gpu_pack(W, S, bits, 10000)
+    finally:
+        gwq.tuning_set("pack_full_passes", 0)
+    a, b = download_packed(D), download_packed(D2)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
