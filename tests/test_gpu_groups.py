@@ -214,3 +214,19 @@ def test_grouped_launch_and_gate_up_with_small_groups(M):
     from gpu_helpers import assert_close
     H = gwq.linear_gate_up(D[0], D[1], Xg).cpu().numpy()
     assert_close(H, orc.gate_up(orc.linear_f64(layers[0], X), orc.linear_f64(layers[1], X)), f"gate_up M={M}")
+
+
+@pytest.mark.parametrize("group", GROUPS)
+def test_small_groups_7b_shape_full(group):
+    """One 7B projection at full size (4096 x 4096, 4 bits) packed on the GPU (byte-exact) and multiplied at M = 1 and 8
+    (lean kernel), 16 (wide kernel) and 256 (GEMM, the index carried by the layer): every result compared."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_packed_equal, to_gpu
+    W, S = gs.layer_matrix(2, 0, 4096, 4096)
+    P = orc.pack(W, S, 4, 10000, group)
+    D = gwq.pack(to_gpu(W), to_gpu(S), 4, 10000, group=group)
+    assert_packed_equal(D, P)
+    rng = np.random.default_rng(group)
+    for M in (1, 8, 16, 256):
+        X = gs.activations(M, 4096, rng)
+        _assert_elementwise(gwq.linear(D, to_gpu(X)).cpu().numpy(), P, X, f"4096x4096 group={group} M={M}")
