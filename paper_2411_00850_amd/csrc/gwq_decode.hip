@@ -175,6 +175,7 @@ struct DecodeProblem {
 };
 struct DecodeBatch {
     int M, nwaves;
+    int wide_window = 8;        // wide kernel: CSR entries staged per thread, 8, or 4 where the LDS is short
     DecodeProblem p[kMaxBatch];
 };
 
@@ -644,7 +645,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const uint32_t zp_off = sc_off + 32 * spr;
     const uint32_t guard_off = zp_off + 16 * spr;
     const uint32_t ent_off = guard_off + kWideGuard;
-    const uint32_t red_off = ent_off + 32 * nthreads;
+    const int window = batch.wide_window * nthreads;    // staged CSR entries: the first 8 or 4 per thread
+    const uint32_t red_off = ent_off + 4 * window;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
 
     const DecodeConsts dc(BITS);
@@ -695,7 +697,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     };
     const u32x4 meta0 = meta_vec(tid);
     // The block's CSR segment [e_begin, e_end), from the 16-byte boundary below e_begin: thread t
-    // brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond blockDim * 8 stay in memory.
+    // brings entries e0 + 8t .. e0 + 8t + 7.  Entries beyond the staged window (blockDim * 8, or * 4) stay in memory.
     const int e0 = e_begin & ~7;
     u32x4 seg_col, seg_val;
     {
@@ -706,7 +708,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
         seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
         seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
     }
-    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+    const int staged_end = e0 + window < e_end ? e0 + window : e_end;
 
     const bool o_live = n < N && 4 * b < M;
     int j = rp0 + wave;                                 // cursor into this lane's share of the channel's outliers
@@ -733,7 +735,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             for (int t = tid + nthreads; t < 3 * spr; t += nthreads)
                 *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * t) = meta_vec(t);
             if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
-            store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
+            if (8 * tid < window) store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
         }
         if (stage_x)
 #pragma unroll
@@ -1439,18 +1441,24 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     // The wide kernel.  Among the shapes (U, waves <= 8) whose LDS footprint fits, the one with the
     // fewest phases, then the most waves, then the shorter waves.
     {
-        int best_u = 0, best_w = 0, best_ph = 1 << 30;
+        int best_u = 0, best_w = 0, best_ph = 1 << 30, best_window = 8;
         size_t best_lds = 0;
-        for (int u = 4; u <= (M <= 8 ? 8 : 4); u *= 2)   // 16 rows of 8 groups would not fit the registers
-            for (int w = 1; w <= 8; ++w) {
-                const size_t lds = (size_t)M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_spr + kWideGuard +
-                                   2 * 16 * (size_t)w * 64 + (size_t)w * 1024;
-                if (lds > kMaxLds) continue;
-                const int ph = (max_gpr + w * u - 1) / (w * u);
-                if (ph < best_ph || (ph == best_ph && w > best_w)) { best_ph = ph; best_u = u; best_w = w; best_lds = lds; }
-            }
+        // The staged window of CSR entries is 8 per thread (a tile has about 650 at 1 %, the window 4096 with eight
+        // waves); where that costs a phase, 4 per thread are tried as well.
+        for (int window = 8; window >= 4; window -= 4)
+            for (int u = 4; u <= (M <= 8 ? 8 : 4); u *= 2)   // 16 rows of 8 groups would not fit the registers
+                for (int w = 1; w <= 8; ++w) {
+                    const size_t lds = (size_t)M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_spr + kWideGuard +
+                                       (size_t)window * 4 * w * 64 + (size_t)w * 1024;
+                    if (lds > kMaxLds) continue;
+                    const int ph = (max_gpr + w * u - 1) / (w * u);
+                    if (ph < best_ph || (ph == best_ph && window == best_window && w > best_w)) {
+                        best_ph = ph; best_u = u; best_w = w; best_lds = lds; best_window = window;
+                    }
+                }
         if (best_u) {
             batch.nwaves = best_w;
+            batch.wide_window = best_window;
             const int mr = M <= 8 ? 8 : 16;
             // One resident block per CU (X fills most of the LDS): with a single phase, fewer blocks
             // that loop over tiles stage X once each.
