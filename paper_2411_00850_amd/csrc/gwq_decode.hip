@@ -672,6 +672,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 #pragma unroll
         for (int u = 0; u < U; ++u) slot[u].load_clamped(qweight, code_off + u * group_bytes, b, code_end);
     };
+    GWQ_STAMP_AT(0);
+    GWQ_STAMP_AT(1);                                    // descriptor has arrived
     load_codes(blockIdx.x, 0);
     for (int block = blockIdx.x; block * 16 < N; block += gridDim.x) {
     const bool stage_x = phases > 1 || block == (int)blockIdx.x;
@@ -749,6 +751,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
                 }
             }
         __syncthreads();                                // X of the phase and, first time, the tile's metadata
+        if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(2 + 3 * ph);    // X of the phase is in LDS
 
         if constexpr (FINE) {
             const uint16_t *sc_row = reinterpret_cast<const uint16_t *>(lds_raw + sc_off) + r * spr;
@@ -828,6 +831,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(3 + 3 * ph);    // multiplied
         if (ph + 1 < phases) load_codes(block, ph + 1);
         else if ((block + (int)gridDim.x) * 16 < N) load_codes(block + gridDim.x, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -877,6 +881,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)x_out[e][col - c0], acc[e]);
             j += nwaves;
         }
+        if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(4 + 3 * ph);    // outliers added
         if (ph + 1 < phases) __syncthreads();           // everybody is done with this X chunk
     }
 
@@ -891,6 +896,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
         const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
         if (nn < N && m < M) Y[(size_t)m * N + nn] = (act_t)sum;
     }
+    if (block == (int)blockIdx.x) GWQ_STAMP_AT(12);     // first tile stored
     }   // tiles
 }
 
