@@ -907,7 +907,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 // row.  It also stages X per tile and stops at several block-wide barriers per tile.  This kernel
 // keeps X where each use wants it:
 //   * wave w owns groups [4w, 4w + 4) of every tile, so the X operands of its MFMAs never change: they
-//     are loaded once per block into registers (64 per lane), in operand layout, straight from memory;
+//     are loaded once per block (one coalesced 1 KB load per row) and kept in registers (64 per lane);
 //   * the outliers read a transposed copy XT[k][MR] in LDS (MR = 4, 8 or 16 rows, staged once per
 //     block): the lanes (r, b) of channel r take one entry each and fetch four rows of its column with
 //     one 8-byte read.  With MR = 16 the four lanes of a channel share an entry (four rows each), with
@@ -915,7 +915,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 //   * a block walks `tiles_per_block` consecutive 16-channel tiles.  Codes, scales, zero points and CSR
 //     bounds of a tile are requested three tiles ahead into one of three register sets (the loop is
 //     unrolled over them), its CSR segment two tiles ahead; one block barrier per tile publishes the
-//     segment in LDS and the previous tile's partial sums, which a quarter or half of the block then
+//     segment and the next tile's scales and zero points in LDS (the block fetches those together, 48 gpr
+//     contiguous bytes) and the previous tile's partial sums, which a quarter or half of the block then
 //     adds in a fixed order while the others go on.
 // XT is written by the waves from their X operands, with the matrix cores doing the transposition: an
 // operand times a 32 x 16 selection matrix (a single 1.0 per column) returns sixteen of the operand's 32
@@ -926,12 +927,9 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 // a store instruction (columns 32 apart) fall into different banks.
 //
 // Dynamic LDS: XT [K][MR] halves | CSR entries (column | value << 16) [2][ent_cap] + 8 zero words |
-// partial sums [2][waves][4][64] floats.
+// partial sums [2][waves][4][64] floats | scales [16][gpr] halves and zero points [16][gpr] bytes of two tiles.
 constexpr int kStreamU = 4;                             // groups per wave
 
-
-struct __attribute__((packed, aligned(2))) U64a2 { uint32_t lo, hi; };
-struct __attribute__((packed, aligned(1))) U32a1 { uint32_t v; };
 
 // A load that is complete when it returns, invisible to the compiler's bookkeeping of outstanding loads
 // (for the rare path below, whose loads would otherwise make every trip wait for all prefetches).
@@ -952,8 +950,7 @@ template <int MR> __device__ inline uint32_t xt_offset(uint32_t col, int q)
 // Everything a wave needs from memory for one tile.
 template <int BITS> struct TileRegs {
     Slot<BITS> slot[kStreamU];
-    U64a2 sc;                                           // four scales
-    uint32_t zp;                                        // four zero points
+    u32x4 meta;                                         // this thread's 16 bytes of the tile's scales and zero points
     int rp0, rp1;                                       // CSR range of this lane's channel
     int e_begin, e_end;                                 // CSR range of the tile (wave-uniform)
     u32x4 seg_col, seg_val;                             // this thread's eight entries of the tile's segment
@@ -975,9 +972,9 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
     const uint16_t *__restrict__ out_val = pr.out_val;
     const _Float16 *__restrict__ X = pr.X;
     _Float16 *__restrict__ Y = pr.Y;
-    const int csr_last_vec = pr.csr_last_vec;
+    const int csr_last_vec = pr.csr_last_vec, sc_last_vec = pr.sc_last_vec, zp_last_vec = pr.zp_last_vec;
     asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
-                 "s"(K), "s"(csr_last_vec));
+                 "s"(K), "s"(csr_last_vec), "s"(sc_last_vec), "s"(zp_last_vec));
     const int tiles = (N + 15) >> 4;
     const int tile0 = (int)blockIdx.x * tiles_per_block;
     if (tile0 >= tiles) return;                         // the grid is as wide as the largest layer needs
@@ -997,6 +994,8 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
     uint32_t *const ent = reinterpret_cast<uint32_t *>(lds_raw + (uint32_t)K * (2 * MR));
     float *const red = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(ent) + 8 * (uint32_t)ent_cap + 32);
     const int zero_entry = 2 * ent_cap;                 // an entry with value 0 in column 0
+    unsigned char *const meta_lds = reinterpret_cast<unsigned char *>(red) + 2 * (uint32_t)nwaves * 1024;
+    const uint32_t meta_bytes = 48u * gpr;              // scales [16][gpr] halves, then zero points [16][gpr] bytes
 
     const DecodeConsts dc(BITS);
     constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
@@ -1020,10 +1019,23 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
         const uint32_t first_group = (uint32_t)n_c * gpr + g0;
 #pragma unroll
         for (int u = 0; u < U; ++u) T.slot[u].load_clamped(qweight, (first_group + u) * group_bytes, b, code_end);
-        T.sc = *reinterpret_cast<const U64a2 *>(scales + first_group);       // the arrays carry 16 spare bytes
-        T.zp = reinterpret_cast<const U32a1 *>(zeros + first_group)->v;
         T.rp0 = row_ptr[n_c];
         T.rp1 = row_ptr[n_c + 1];
+    };
+    // The tile's scales (32 gpr bytes) and zero points (16 gpr bytes) are contiguous in memory for 16 consecutive
+    // channels: thread t < 3 gpr brings vector t of them (one coalesced load of a wave or two, where a load per
+    // lane of its own four scales and zero points costs the CU's address unit four times as long); the
+    // other threads repeat vector 0.
+    auto issue_meta = [&](TileRegs<BITS> &T, int it) {
+        const int tile = tile0 + (it < nt ? it : nt - 1);
+        const bool is_sc = tid < 2 * gpr, is_zp = !is_sc && tid < 3 * gpr;
+        const int v_sc = tile * 2 * gpr + tid < sc_last_vec ? tile * 2 * gpr + tid : sc_last_vec;
+        const int v_zp = tile * gpr + (tid - 2 * gpr) < zp_last_vec ? tile * gpr + (tid - 2 * gpr) : zp_last_vec;
+        const u32x4 *src = is_zp ? reinterpret_cast<const u32x4 *>(zeros) : reinterpret_cast<const u32x4 *>(scales);
+        T.meta = src[is_sc ? v_sc : is_zp ? v_zp : 0];
+    };
+    auto store_meta = [&](const TileRegs<BITS> &T, int it) {
+        if (tid < 3 * gpr) *reinterpret_cast<u32x4 *>(meta_lds + (it & 1) * meta_bytes + 16 * tid) = T.meta;
     };
     // The tile's CSR segment [e_begin, e_end) from the 16-byte boundary below e_begin: thread t brings
     // entries e0 + 8t .. e0 + 8t + 7 (idle threads repeat the last vector: no extra traffic).
@@ -1037,27 +1049,32 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
         T.seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
     };
 
-    // Order of the first requests: tile 0, X, tiles 1 and 2 - none of which waits for anything - and, once
-    // the CSR bounds of the first two tiles have come in through the scalar cache (requested first of all),
-    // their segments.  X is consumed before the first tile, with everything behind it still in flight.
+    // Order of the first requests: the first tile's scales and zero points, X, tiles 0, 1 and 2 - none of which
+    // waits for anything - and, once the CSR bounds of the first two tiles have come in through the scalar cache
+    // (requested first of all), their segments.  X is consumed before the first tile, with everything behind it
+    // still in flight.
     TileRegs<BITS> A, B, C;
     issue_bounds(A, 0);
     issue_bounds(B, 1);
     issue_bounds(C, 2);
-    issue_tile(A, 0);
+    issue_meta(A, 0);
 
-    // X operands of this wave's MFMAs: lane (r, b) holds row r, columns 32 b + 8 j .. + 7 of each group.
-    u32x4 xa[U][4];
-    const bool x_row_live = r < M;
+    // X for this wave's MFMAs.  Its four groups are 512 consecutive columns, 1 KB of a row: one coalesced
+    // load per row (a load in operand layout touches sixteen rows at once and costs the address unit four times
+    // as long).  The rows then pass through the part of LDS that will hold this wave's columns of XT (at most MR KB,
+    // private to the wave until the first block barrier) to reach the lanes that use them.
+    u32x4 xrow[MR];
+    {
+        const int kv = g0 * (kGroup / 8) + lane;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int g = g0 + u < gpr ? g0 + u : gpr - 1;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            xa[u][j] = reinterpret_cast<const u32x4 *>(X)[(x_row_live ? r : 0) * K8 + g * (kGroup / 8) + 4 * b + j];
+        for (int e = 0; e < MR; ++e)
+            xrow[e] = reinterpret_cast<const u32x4 *>(X)[(e < M ? e : 0) * K8 + (kv < K8 ? kv : 0)];
     }
     __builtin_amdgcn_sched_barrier(0);
+    issue_tile(A, 0);
+    issue_meta(B, 1);
     issue_tile(B, 1);
+    issue_meta(C, 2);
     issue_tile(C, 2);
     __builtin_amdgcn_sched_barrier(0);
     issue_seg(A);
@@ -1066,16 +1083,41 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
     GWQ_STAMP_AT(2);                                    // everything requested
 
     if (tid < 8) ent[zero_entry + tid] = 0u;
-    // Rows at or beyond M and groups at or beyond gpr multiply zeros.  Every register is masked, with no
-    // branch, so that X has arrived on every path into the loop.
+    store_meta(A, 0);
+
+    // The rows lie back to back in the wave's part (256 bytes per group that exists), the 16-byte pieces of row e
+    // permuted by e (piece c at position c ^ e), so that the sixteen rows of one piece - what an operand read
+    // fetches - fall into different banks.  Rows at or beyond M and groups at or beyond gpr are zeros.
+    u32x4 xa[U][4];
+    {
+        const int ng = gpr - g0 < U ? gpr - g0 : U;     // this wave's groups that exist (uniform; at least one)
+        const uint32_t row_bytes = 256u * ng;
+        unsigned char *const mine = xt + (uint32_t)g0 * (kGroup * 2 * MR);
+        if (lane < 16 * ng)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t keep = (x_row_live && g0 + u < gpr) ? ~0u : 0u;
+            for (int e = 0; e < MR; ++e)
+                *reinterpret_cast<u32x4 *>(mine + e * row_bytes + ((lane ^ e) << 4)) = e < M ? xrow[e] : u32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xa[u][j] &= u32x4{keep, keep, keep, keep};
+        for (int u = 0; u < U; ++u) {
+            const bool live = u < ng && r < MR;         // other lanes multiply zeros
+            const uint32_t keep = live ? ~0u : 0u;
+            const int rr = live ? r : 0, piece0 = live ? 16 * u + 4 * b : 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(mine + rr * row_bytes + (((piece0 + j) ^ rr) << 4));
+                xa[u][j] = v & u32x4{keep, keep, keep, keep};
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
     __builtin_amdgcn_sched_barrier(0);
     GWQ_STAMP_AT(3);                                    // X has arrived
+
+    if (tid < 8) ent[zero_entry + tid] = 0u;
+    store_meta(A, 0);
 
     // XT from the operands.  Operand (u, j) holds, as its MFMA column 8 b' + t, the X column
     // 128 (g0 + u) + 32 b' + 8 j + t; selection matrix s picks MFMA columns 16 s .. 16 s + 15, so lane
@@ -1116,6 +1158,7 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
             }
     }
 
+    __syncthreads();                                    // tile 0's scales and zero points are in LDS (and XT, for later)
     GWQ_STAMP_AT(4);                                    // XT written
     const int xq = b % RB;                              // which four rows of XT this lane adds
     const int sub = wave * SPLIT + b / RB;              // this lane's share of its channel's entries
@@ -1144,10 +1187,11 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
         }
     };
 
-    // One tile: T holds it, T2 is the set of the tile two further on (its CSR segment is requested here).
-    // Requests are unconditional (past the block's last tile they repeat it): a trip always leaves the same
-    // queue of requests behind, which is what lets the waits inside the loop be exact.
-    auto step = [&](TileRegs<BITS> &T, TileRegs<BITS> &T2, int it) {
+    // One tile: T holds it, T1 and T2 are the sets of the next tile (its scales and zero points go to LDS here) and
+    // of the one after (its CSR segment is requested here).  Requests are unconditional (past the block's last
+    // tile they repeat it): a trip always leaves the same queue of requests behind, which is what lets the waits
+    // inside the loop be exact.
+    auto step = [&](TileRegs<BITS> &T, TileRegs<BITS> &T1, TileRegs<BITS> &T2, int it) {
         const int buf = it & 1;
         const int e0 = T.e_begin & ~7;
         const int staged_end = e0 + ent_cap < T.e_end ? e0 + ent_cap : T.e_end;
@@ -1155,18 +1199,17 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
         // refilled value must land in the register the next trip reads it from (otherwise the compiler moves
         // it there at the end of the trip, and a move of a value still on its way waits for it).
         int rp0, rp1;
-        uint32_t sc2[2], zp;
         asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3" : "=&v"(rp0), "=&v"(rp1) : "v"(T.rp0), "v"(T.rp1));
-        asm volatile("v_mov_b32 %0, %3\n\tv_mov_b32 %1, %4\n\tv_mov_b32 %2, %5"
-                     : "=&v"(sc2[0]), "=&v"(sc2[1]), "=&v"(zp) : "v"(T.sc.lo), "v"(T.sc.hi), "v"(T.zp));
         if (it == 0) GWQ_STAMP_AT(5);                   // tile 0 has arrived
 
+        const uint16_t *sc_lane = reinterpret_cast<const uint16_t *>(meta_lds + buf * meta_bytes) + r * gpr + g0;
+        const uint8_t *zp_lane = meta_lds + buf * meta_bytes + 32 * gpr + r * gpr + g0;
         float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t keep = g0 + u < gpr ? ~0u : 0u;      // uniform over the wave
-            const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)((sc2[u >> 1] >> (16 * (u & 1))) & keep));
-            const uint32_t z = (zp >> (8 * u)) & 0xFFu & (BITS == 3 ? keep : ~0u);
+            const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc_lane[u] & keep));
+            const uint32_t z = BITS == 3 ? zp_lane[u] & keep : zp_lane[u];
             u32x4 wb[4];
             T.slot[u].decode(z, b, dc, wb, tail_lane4);
             float4v part = float4v{0.f, 0.f, 0.f, 0.f};
@@ -1182,9 +1225,11 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
         u32x4 seg_col = T.seg_col, seg_val = T.seg_val;
         issue_seg(T2);
         issue_bounds(T, it + 3);
+        issue_meta(T, it + 3);
         issue_tile(T, it + 3);
         __builtin_amdgcn_sched_barrier(0);
         if (8 * tid < ent_cap) store_entries(reinterpret_cast<u32x4 *>(ent + buf * ent_cap) + 2 * tid, seg_col, seg_val);
+        store_meta(T1, it + 1);
         if (it == 0) GWQ_STAMP_AT(7);                   // its CSR segment has arrived
         __syncthreads();                                // this tile's entries and the previous tile's sums are in LDS
         if (it == 0) GWQ_STAMP_AT(8);                   // through the barrier
@@ -1239,20 +1284,20 @@ __global__ __launch_bounds__(512) void decode_stream_kernel(const DecodeBatch ba
 
     // The first three trips stand outside the loop: after them the requests in flight are those a trip of
     // the loop leaves behind, in the same order, so the loop's waits hold from its first trip on.
-    step(A, C, 0);
+    step(A, B, C, 0);
     if (nt > 1) {
-        step(B, A, 1);
+        step(B, C, A, 1);
         if (nt > 2) {
-            step(C, B, 2);
+            step(C, A, B, 2);
             int it = 3;
             for (; it + 3 <= nt; it += 3) {
-                step(A, C, it);
-                step(B, A, it + 1);
-                step(C, B, it + 2);
+                step(A, B, C, it);
+                step(B, C, A, it + 1);
+                step(C, A, B, it + 2);
             }
             if (it < nt) {
-                step(A, C, it);
-                if (it + 1 < nt) step(B, A, it + 1);
+                step(A, B, C, it);
+                if (it + 1 < nt) step(B, C, A, it + 1);
             }
         }
     }
@@ -1400,11 +1445,12 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         const int nwaves = (max_gpr + kStreamU - 1) / kStreamU, nthreads = 64 * nwaves;
         const int mr = M <= 4 ? 4 : M <= 8 ? 8 : 16;
         const size_t xt = (size_t)max_gpr * kGroup * 2 * mr, red = (size_t)2 * nwaves * 1024;
-        const size_t avail = kMaxLds - xt - red - 32;
+        const size_t meta_lds = (size_t)2 * 48 * max_gpr + 16;   // scales and zero points of two tiles
+        const size_t avail = kMaxLds - xt - red - meta_lds - 32;
         int ent_cap = (int)(avail / 8) & ~7;
         if (ent_cap > 8 * nthreads) ent_cap = 8 * nthreads;
         if (ent_cap >= 64) {
-            const size_t lds = xt + (size_t)8 * ent_cap + 32 + red;
+            const size_t lds = xt + (size_t)8 * ent_cap + 32 + red + meta_lds;
             // Blocks a CU holds at once: the kernel's registers allow eight waves.
             int bpc = (int)(kMaxLds / lds);
             if (bpc > 8 / nwaves) bpc = 8 / nwaves;
