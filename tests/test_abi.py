@@ -191,6 +191,56 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert L.gwq_probe_mfma(0, 10, ctypes.c_void_p(0x1000), None) == -2
 
 
+def test_launch_plans_stay_within_the_machine():
+    """Every launch the dispatcher plans - seeded sweep over shapes, M, bit widths, group sizes, layers per launch and
+    the tuning keys - names a kernel and stays within what a gfx950 CU takes: at most 160 KB of LDS and 1024
+    threads per block (512 for the kernels built for that), a grid of at least one block and at most the layers asked
+    for along y.  Host arithmetic only: this is the check that a shape the library accepts has a launch that fits."""
+    import numpy as np
+    L = binding.lib()
+    buf = ctypes.create_string_buffer(256)
+    rng = np.random.default_rng(2024)
+    keys = ["decode_waves", "decode_stream", "decode_tiles", "decode_lean_rows", "gemm_rows"]
+    seen = set()
+    try:
+        for case in range(1500):
+            bits = int(rng.choice([3, 4]))
+            group = int(rng.choice([16, 32, 64, 128, 128]))
+            K = 128 * int(rng.choice([1, 2, 3, 5, 8, 16, 31, 32, 33, 64, 86, 128, 224, 256, 511, 512]))
+            if K // group > 2048:
+                group = 128
+            count = int(rng.choice([1, 1, 1, 2, 3, 8]))
+            Ns = [int(rng.choice([1, 15, 16, 17, 100, 1000, 4096, 11008, 28672, 50000])) for _ in range(count)]
+            M = int(rng.choice([1, 2, 4, 5, 8, 9, 16, 17, 33, 64, 200, 2048])) if count == 1 else int(rng.integers(1, 17))
+            for k in keys:
+                L.gwq_tuning_set(k.encode(), 0)
+            if case % 3 == 1:
+                L.gwq_tuning_set(b"decode_waves", int(rng.choice([1, 2, 3, 6, 12, 16])))
+                L.gwq_tuning_set(b"decode_stream", int(rng.choice([0, 1, 2])))
+                L.gwq_tuning_set(b"decode_tiles", int(rng.choice([0, 1, 3, 7])))
+                L.gwq_tuning_set(b"decode_lean_rows", int(rng.choice([0, 1, 4, 8])))
+            if case % 3 == 2:
+                L.gwq_tuning_set(b"gemm_rows", int(rng.choice([0, 32, 64, 128, 256])))
+            layers = [_packed(N=n, K=K, bits=bits, group=group) for n in Ns]
+            arr = (ctypes.POINTER(binding._Packed) * count)(*[ctypes.pointer(p) for p in layers])
+            what = f"bits={bits} group={group} K={K} Ns={Ns} M={M} case={case}"
+            assert L.gwq_linear_plan(count, arr, M, int(rng.integers(0, 2)), buf, 256) == 0, what
+            text = buf.value.decode()
+            seen.add(text.split("<")[0])
+            lds = int(re.search(r" lds (\d+)", text).group(1))
+            block = int(re.search(r" block (\d+)", text).group(1))
+            assert 0 < lds <= 160 * 1024, (what, text)
+            assert block % 64 == 0 and 64 <= block <= (1024 if text.startswith(("decode_small", "gemm_kernel")) else 512), (what, text)
+            grid = re.search(r" grid (\d+)(?:x(\d+))?", text)
+            assert int(grid.group(1)) >= 1, (what, text)
+            if grid.group(2):
+                assert 1 <= int(grid.group(2)) <= count, (what, text)
+    finally:
+        for k in keys:
+            L.gwq_tuning_set(k.encode(), 0)
+    assert {"decode_small_kernel", "decode_stream_kernel", "decode_wide_kernel", "gemm_kernel"} <= seen
+
+
 def test_linear_gate_up_validates_before_touching_the_device():
     L = binding.lib()
     fake = ctypes.c_void_p(0x1000)
