@@ -72,6 +72,19 @@ __device__ unsigned long long g_stamps[kStampBlocks * kStampSlots];
 #endif
 
 
+// Sixteen bytes per lane from memory straight into LDS, no registers in between: lane l's bytes land at LDS byte
+// `lds_byte` + 16 l (wave-uniform, in m0 while the instruction issues; the old m0 is put back), read from `base` +
+// the lane's 32-bit byte offset.  The load counts in vmcnt like any other but the compiler does not see it: whoever
+// reads the LDS bytes waits with wait_all_loads() first.  (Extra loads in flight only make the compiler's own
+// waits, which count from the youngest load backwards, wait for more than they need.)
+__device__ inline void load_to_lds_16(uint32_t lds_byte, uint32_t lane_byte_offset, const void *base)
+{
+    uint32_t keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "s"(lds_byte), "v"(lane_byte_offset), "s"(base) : "memory");
+}
+__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ inline const uint32_t *at_byte(const uint32_t *base, uint32_t byte_off)
 {
     return reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + byte_off);
@@ -719,18 +732,23 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 
     for (int ph = 0; ph < phases; ++ph) {
         const int g_begin = (ph * nwaves + wave) * U;
-        // X columns of this wave's groups, all rows at once (16-byte coalesced loads; vectors
-        // beyond K are loaded from column 0 and stored as zeros).
-        u32x4 xstage[MR * kQ];
-        if (stage_x)
+        // X columns of this wave's groups, row by row, straight into LDS: a row's share is 1 KB (or 2) in memory
+        // and in the LDS copy alike, so lane l brings vector l of it.  Vectors beyond K are loaded from column 0
+        // and overwritten with zeros once they have landed.
+        if (stage_x) {
+            typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+            const uint32_t lds_row0 = (uint32_t)(uintptr_t)(lds_byte_t *)lds_raw + 16u * (uint32_t)(wave * (U * kGroup / 8));
 #pragma unroll
-        for (int e = 0; e < MR; ++e)
+            for (int e = 0; e < MR; ++e)
+                if (e < M) {
 #pragma unroll
-            for (int i = 0; i < kQ; ++i) {
-                const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
-                const int row = e < M ? e : M - 1;
-                xstage[e * kQ + i] = reinterpret_cast<const u32x4 *>(X)[row * (K / 8) + (kv < K / 8 ? kv : 0)];
-            }
+                    for (int i = 0; i < kQ; ++i) {
+                        const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+                        load_to_lds_16(lds_row0 + 16u * (uint32_t)(e * (x_stride / 8) + 64 * i),
+                                       16u * (uint32_t)(e * (K / 8) + (kv < K / 8 ? kv : 0)), X);
+                    }
+                }
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (ph == 0) {                                  // what was requested above for the whole tile
             if (tid < 3 * spr) *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * tid) = meta0;
@@ -739,17 +757,21 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             if (tid < kWideGuard / 4) reinterpret_cast<uint32_t *>(lds_raw + guard_off)[tid] = 0u;
             if (8 * tid < window) store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
         }
-        if (stage_x)
+        if (stage_x) {
+            wait_all_loads();
+            if ((g_begin + U) * (kGroup / 8) > K / 8)   // uniform: only the wave that holds the end of K
 #pragma unroll
-        for (int e = 0; e < MR; ++e)
-            if (e < M) {
+                for (int e = 0; e < MR; ++e)
+                    if (e < M) {
 #pragma unroll
-                for (int i = 0; i < kQ; ++i) {
-                    const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
-                    reinterpret_cast<u32x4 *>(xs)[e * (x_stride / 8) + wave * (U * kGroup / 8) + lane + 64 * i] =
-                        kv < K / 8 ? xstage[e * kQ + i] : u32x4{0u, 0u, 0u, 0u};
-                }
-            }
+                        for (int i = 0; i < kQ; ++i) {
+                            const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+                            if (kv >= K / 8)
+                                reinterpret_cast<u32x4 *>(xs)[e * (x_stride / 8) + wave * (U * kGroup / 8) + lane + 64 * i] =
+                                    u32x4{0u, 0u, 0u, 0u};
+                        }
+                    }
+        }
         __syncthreads();                                // X of the phase and, first time, the tile's metadata
         if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(2 + 3 * ph);    // X of the phase is in LDS
 
