@@ -255,7 +255,7 @@ gwq_status gwq_probe_mfma(int32_t blocks, int32_t iters, void *sink, void *strea
  * Keys: "decode_waves" (upper bound, 1..16, on the waves per block of the decode kernel for M <= 8:
  * it picks 4, 8 or 16 groups per wave accordingly; the kernels for larger M size themselves),
  * "decode_stream" (1: never the streaming decode kernel; 2: also for M <= 4, wherever K <= 4096 lets it
- * run; by default it takes 5 <= M <= 16 there), "decode_tiles" (16-channel tiles per block of the streaming
+ * run; by default it takes the launches of 5 <= M <= 16 there that the kernel for M <= 8 does not, with two or more tiles per block), "decode_tiles" (16-channel tiles per block of the streaming
  * kernel, 1..4096), "decode_lean_rows" (1..8: the largest M handled by the kernel that keeps all of X[M][K] in LDS,
  * where it fits), "pack_full_passes" (1: gwq_pack finds the threshold and the per-row counts by passes over all
  * scores even where the short list of candidate keys would do), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
