@@ -114,6 +114,8 @@ template <> struct Slot<4> {
         const uint32_t off = group_off + 16 * b;
         w = *reinterpret_cast<const uint4 *>(at_byte(q, off < end - 16 ? off : end - 16));
     }
+    // An empty statement that reads and "rewrites" the registers: the compiler waits for their load here and not later.
+    __device__ inline void claim() { asm volatile("" : "+v"(w.x), "+v"(w.y), "+v"(w.z), "+v"(w.w)); }
     __device__ inline void decode(uint32_t z, int /*b*/, const DecodeConsts &d, u32x4 f[4], int /*tail_lane4*/) const
     {
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
@@ -149,6 +151,7 @@ template <> struct Slot<3> {
         const U128a4 v = *reinterpret_cast<const U128a4 *>(at_byte(q, off < end - 16 ? off : end - 16));
         w[0] = v.x; w[1] = v.y; w[2] = v.z; fourth = v.w;
     }
+    __device__ inline void claim() { asm volatile("" : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(fourth)); }
     // tail_lane4 = 4 * (lane | 48): the byte index of the lane that holds slot 3 of the same channel.
     __device__ inline void decode(uint32_t z, int b, const DecodeConsts &d, u32x4 f[4], int tail_lane4) const
     {
@@ -618,9 +621,10 @@ __global__ __launch_bounds__(1024) void decode_small_gate_up_kernel(const Decode
 // FP32 result, so the weights enter exactly, as in the FP16 kernel.
 constexpr int kWideGuard = 96;
 
-template <int BITS, int U, int MR, bool FINE, bool BF16>
+template <int BITS, int U, int MR, bool FINE, bool BF16, int COPIES>
 __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batch)
 {
+    static_assert(COPIES == 1 || COPIES == 2, "copies of a phase's X in LDS");
     static_assert(!(FINE && BF16), "bfloat16 activations: groups of 128 only");
     typedef std::conditional_t<BF16, __bf16, _Float16> act_t;          // X and Y; both 16 bits wide
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -653,8 +657,14 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int x_stride = chunk + kXPad;                 // row stride of the LDS copy of X
     const int phases = (gpr + chunk_groups - 1) / chunk_groups;
 
+    // With two copies of a phase's X the next phase's columns arrive while this phase's are multiplied and its
+    // outliers added (taken for M <= 8, where the copies cost one phase more; at 16 rows they would double the
+    // phases, and a phase's outlier loop costs the same whatever its share of K).  When the copies hold all of X
+    // between them, later tiles of the block do not stage it again.
     act_t *xs = reinterpret_cast<act_t *>(lds_raw);
-    const uint32_t sc_off = (uint32_t)M * x_stride * 2;
+    constexpr int x_copies = COPIES;
+    const uint32_t x_copy = (uint32_t)M * x_stride;     // halves per copy
+    const uint32_t sc_off = (uint32_t)x_copies * x_copy * 2;
     const uint32_t zp_off = sc_off + 32 * spr;
     const uint32_t guard_off = zp_off + 16 * spr;
     const uint32_t ent_off = guard_off + kWideGuard;
@@ -665,7 +675,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const DecodeConsts dc(BITS);
     constexpr uint32_t group_bytes = words_per_group(BITS) * 4;
     const uint32_t code_end = (uint32_t)N * gpr * group_bytes;
-    constexpr int kQ = U / 4;                           // 64-vector rounds covering U groups
+    constexpr int kQ = (U + 3) / 4;                     // 64-vector rounds covering U groups (U = 2: half a round)
     const int x_row = r < M ? r : 0;
     const act_t *x_lane = xs + (uint32_t)x_row * x_stride + wave * (U * kGroup) + 32 * b;
     const act_t *x_out[4];
@@ -674,7 +684,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const uint32_t *entries = reinterpret_cast<const uint32_t *>(lds_raw + ent_off);
 
     // A block takes the 16-channel tiles blockIdx.x, blockIdx.x + gridDim.x, ...: when all of K is
-    // one phase, the copy of X staged for the first tile serves the others too.  The codes of a
+    // one or two phases, the copies of X staged for the first tile serve the others too.  The codes of a
     // phase are requested before the outliers of the phase (or tile) before it are added: by then
     // the registers that take them are free.
     Slot<BITS> slot[U];
@@ -689,7 +699,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     GWQ_STAMP_AT(1);                                    // descriptor has arrived
     load_codes(blockIdx.x, 0);
     for (int block = blockIdx.x; block * 16 < N; block += gridDim.x) {
-    const bool stage_x = phases > 1 || block == (int)blockIdx.x;
+    const bool stage_x = phases > x_copies || block == (int)blockIdx.x;
     const int row0 = block * 16;
     const int n = row0 + r;
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
@@ -730,25 +740,52 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     const int j_end = o_live ? rp1 : 0;
     float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
 
+    // X columns of this wave's groups in phase ph, row by row, straight into LDS copy ph % 2: a row's share is 512
+    // bytes to 2 KB in memory and in the LDS copy alike, so lane l brings vector l of it.  Vectors beyond K are
+    // loaded from column 0 and overwritten with zeros once they have landed (zero_x_tail, after the wait).
+    typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+    const uint32_t lds_row0 = (uint32_t)(uintptr_t)(lds_byte_t *)lds_raw + 16u * (uint32_t)(wave * (U * kGroup / 8));
+    auto request_x = [&](int ph) {
+        const int g_begin = (ph * nwaves + wave) * U;
+        const uint32_t copy_bytes = (uint32_t)(ph & (x_copies - 1)) * x_copy * 2u;
+#pragma unroll
+        for (int e = 0; e < MR; ++e)
+            if (e < M) {
+#pragma unroll
+                for (int i = 0; i < kQ; ++i) {
+                    const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+                    if (lane + 64 * i < 16 * U)
+                        load_to_lds_16(lds_row0 + copy_bytes + 16u * (uint32_t)(e * (x_stride / 8) + 64 * i),
+                                       16u * (uint32_t)(e * (K / 8) + (kv < K / 8 ? kv : 0)), X);
+                }
+            }
+    };
+    auto zero_x_tail = [&](int ph) {
+        const int g_begin = (ph * nwaves + wave) * U;
+        if ((g_begin + U) * (kGroup / 8) <= K / 8) return;      // uniform: only the wave that holds the end of K goes on
+        u32x4 *copy = reinterpret_cast<u32x4 *>(xs + (uint32_t)(ph & (x_copies - 1)) * x_copy);
+#pragma unroll
+        for (int e = 0; e < MR; ++e)
+            if (e < M) {
+#pragma unroll
+                for (int i = 0; i < kQ; ++i) {
+                    const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
+                    if (lane + 64 * i < 16 * U && kv >= K / 8)
+                        copy[e * (x_stride / 8) + wave * (U * kGroup / 8) + lane + 64 * i] = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+    };
+    if (COPIES == 2 && stage_x) request_x(0);
+    __builtin_amdgcn_sched_barrier(0);
+
     for (int ph = 0; ph < phases; ++ph) {
         const int g_begin = (ph * nwaves + wave) * U;
-        // X columns of this wave's groups, row by row, straight into LDS: a row's share is 1 KB (or 2) in memory
-        // and in the LDS copy alike, so lane l brings vector l of it.  Vectors beyond K are loaded from column 0
-        // and overwritten with zeros once they have landed.
-        if (stage_x) {
-            typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
-            const uint32_t lds_row0 = (uint32_t)(uintptr_t)(lds_byte_t *)lds_raw + 16u * (uint32_t)(wave * (U * kGroup / 8));
+        const uint32_t copy_off = (uint32_t)(ph & (x_copies - 1)) * x_copy;    // halves
+        const act_t *const xl = x_lane + copy_off;      // this phase's copy of X
+        const act_t *xo[4];
 #pragma unroll
-            for (int e = 0; e < MR; ++e)
-                if (e < M) {
-#pragma unroll
-                    for (int i = 0; i < kQ; ++i) {
-                        const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
-                        load_to_lds_16(lds_row0 + 16u * (uint32_t)(e * (x_stride / 8) + 64 * i),
-                                       16u * (uint32_t)(e * (K / 8) + (kv < K / 8 ? kv : 0)), X);
-                    }
-                }
-        }
+        for (int e = 0; e < 4; ++e) xo[e] = x_out[e] + copy_off;
+        if (COPIES == 1 && stage_x) request_x(ph);      // one copy: free since the barrier that ended the phase before
         __builtin_amdgcn_sched_barrier(0);
         if (ph == 0) {                                  // what was requested above for the whole tile
             if (tid < 3 * spr) *reinterpret_cast<u32x4 *>(lds_raw + sc_off + 16 * tid) = meta0;
@@ -758,21 +795,23 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             if (8 * tid < window) store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
         }
         if (stage_x) {
-            wait_all_loads();
-            if ((g_begin + U) * (kGroup / 8) > K / 8)   // uniform: only the wave that holds the end of K
-#pragma unroll
-                for (int e = 0; e < MR; ++e)
-                    if (e < M) {
-#pragma unroll
-                        for (int i = 0; i < kQ; ++i) {
-                            const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
-                            if (kv >= K / 8)
-                                reinterpret_cast<u32x4 *>(xs)[e * (x_stride / 8) + wave * (U * kGroup / 8) + lane + 64 * i] =
-                                    u32x4{0u, 0u, 0u, 0u};
-                        }
-                    }
+            wait_all_loads();                           // X of this phase (and, older than it, this phase's codes)
+            zero_x_tail(ph);
         }
-        __syncthreads();                                // X of the phase and, first time, the tile's metadata
+        // X of the phase and, first time, the tile's metadata are in LDS; every wave is done with the phase before,
+        // so the other copy of X (if there are two) is free.
+        __syncthreads();
+        // The next phase's X is requested now and arrives while this phase is worked on.  The compiler does not see
+        // these loads: its own wait for this phase's codes must come before them (it counts from the youngest load
+        // backwards and would wait for them too), hence the empty statements that claim the code registers here,
+        // where everything older has arrived anyway.
+        if constexpr (COPIES == 2) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) slot[u].claim();
+            __builtin_amdgcn_sched_barrier(0);
+            if (stage_x && ph + 1 < phases) request_x(ph + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(2 + 3 * ph);    // X of the phase is in LDS
 
         if constexpr (FINE) {
@@ -783,7 +822,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             for (int u = 0; u < U; ++u) {
                 u32x4 xa[4];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
+                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(xl + u * kGroup + 8 * jj);
                 const int g = g_begin + u;
                 const uint32_t keep = g < gpr ? ~0u : 0u;                   // uniform over the wave
                 const int c0 = (g < gpr ? g : gpr - 1) * kGroup + 32 * b;   // first column of the lane's slot
@@ -813,7 +852,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             for (int u = 0; u < U; ++u) {
                 u32x4 xa[4];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
+                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(xl + u * kGroup + 8 * jj);
                 const uint32_t keep = g_begin + u < gpr ? ~0u : 0u; // uniform over the wave: a scalar mask
                 const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)(sc_lane[u] & keep));
                 const float zc = -(float)(128u + zp_lane[u]);       // any byte gives a finite constant
@@ -837,7 +876,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             for (int u = 0; u < U; ++u) {
                 u32x4 xa[4];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(x_lane + u * kGroup + 8 * jj);
+                for (int jj = 0; jj < 4; ++jj) xa[jj] = *reinterpret_cast<const u32x4 *>(xl + u * kGroup + 8 * jj);
                 const uint32_t keep = g_begin + u < gpr ? ~0u : 0u; // uniform over the wave: a scalar mask
                 const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(sc_lane[u] & keep));
                 const uint32_t z = BITS == 3 ? zp_lane[u] & keep : zp_lane[u];
@@ -886,7 +925,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xv[i][e] = x_out[e][col[i]];
+                for (int e = 0; e < 4; ++e) xv[i][e] = xo[e][col[i]];
             __builtin_amdgcn_sched_barrier(0);          // ... and so are these sixteen
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -900,11 +939,11 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             if (col >= c1) break;
             const float v = (float)__builtin_bit_cast(_Float16, out_val[j]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)x_out[e][col - c0], acc[e]);
+            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)xo[e][col - c0], acc[e]);
             j += nwaves;
         }
         if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(4 + 3 * ph);    // outliers added
-        if (ph + 1 < phases) __syncthreads();           // everybody is done with this X chunk
+        if (x_copies == 1 && ph + 1 < phases) __syncthreads();                // everybody is done with the only copy of X
     }
 
     // Fixed-order reduction over the waves, then FP16 store.
@@ -1515,45 +1554,49 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
     // The wide kernel.  Among the shapes (U, waves <= 8) whose LDS footprint fits, the one with the
     // fewest phases, then the most waves, then the shorter waves.
     {
-        int best_u = 0, best_w = 0, best_ph = 1 << 30, best_window = 8;
+        int best_u = 0, best_w = 0, best_ph = 1 << 30, best_window = 8, best_copies = 1;
         size_t best_lds = 0;
         // The staged window of CSR entries is 8 per thread (a tile has about 650 at 1 %, the window 4096 with eight
         // waves); where that costs a phase, 4 per thread are tried as well.
         for (int window = 8; window >= 4; window -= 4)
-            for (int u = 4; u <= (M <= 8 ? 8 : 4); u *= 2)   // 16 rows of 8 groups would not fit the registers
+            for (int u = 2; u <= (M <= 8 ? 8 : 4); u *= 2)   // 16 rows of 8 groups would not fit the registers
                 for (int w = 1; w <= 8; ++w) {
-                    const size_t lds = (size_t)M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_spr + kWideGuard +
+                    const int ph = (max_gpr + w * u - 1) / (w * u);
+                    // Several phases at M <= 8: two copies, the next phase's X arrives during this one (4096 x 11008,
+                    // M = 8: 14.1 against 16.2 us; at M = 16 the copies double the phases: 20.1 against 16.4 us).
+                    const size_t copies = ph > 1 && M <= 8 ? 2 : 1;
+                    if ((u == 2 && copies == 1) || (u == 8 && copies == 2)) continue;    // forms that are not built
+                    const size_t lds = copies * M * (w * u * kGroup + kXPad) * 2 + (size_t)48 * max_spr + kWideGuard +
                                        (size_t)window * 4 * w * 64 + (size_t)w * 1024;
                     if (lds > kMaxLds) continue;
-                    const int ph = (max_gpr + w * u - 1) / (w * u);
                     if (ph < best_ph || (ph == best_ph && window == best_window && w > best_w)) {
-                        best_ph = ph; best_u = u; best_w = w; best_lds = lds; best_window = window;
+                        best_ph = ph; best_u = u; best_w = w; best_lds = lds; best_window = window; best_copies = (int)copies;
                     }
                 }
         if (best_u) {
             batch.nwaves = best_w;
             batch.wide_window = best_window;
             const int mr = M <= 8 ? 8 : 16;
-            // One resident block per CU (X fills most of the LDS): with a single phase, fewer blocks
-            // that loop over tiles stage X once each.
-            if (best_ph == 1) {
+            // One resident block per CU (X fills most of the LDS): when one or two phases cover K, all of X stays
+            // in LDS, and fewer blocks that loop over tiles stage it once each.
+            if (best_ph <= best_copies) {
                 const int cus = device_cus();
                 const int cap = cus / count > 0 ? cus / count : 1;
                 if (blocks > cap) blocks = cap;
             }
             if (describe) {
-                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d,%s,%s> grid %dx%d block %d lds %zu phases %d",
-                         bits, best_u, mr, fine ? "true" : "false", tune.bf16 ? "true" : "false", blocks, count, 64 * best_w,
-                         best_lds, best_ph);
+                snprintf(describe->text, sizeof(describe->text), "decode_wide_kernel<%d,%d,%d,%s,%s,%d> grid %dx%d block %d lds %zu phases %d",
+                         bits, best_u, mr, fine ? "true" : "false", tune.bf16 ? "true" : "false", best_copies, blocks, count,
+                         64 * best_w, best_lds, best_ph);
                 return hipSuccess;
             }
-#define GWQ_WIDE(B, UU, RR) \
-    if (bits == B && best_u == UU && mr == RR) \
-        return tune.bf16 ? launch_kernel<&decode_wide_kernel<B, UU, RR, false, true>>(batch, count, blocks, best_w, best_lds, st) \
-               : fine    ? launch_kernel<&decode_wide_kernel<B, UU, RR, true, false>>(batch, count, blocks, best_w, best_lds, st) \
-                         : launch_kernel<&decode_wide_kernel<B, UU, RR, false, false>>(batch, count, blocks, best_w, best_lds, st)
-            GWQ_WIDE(4, 4, 8); GWQ_WIDE(4, 4, 16); GWQ_WIDE(4, 8, 8);
-            GWQ_WIDE(3, 4, 8); GWQ_WIDE(3, 4, 16); GWQ_WIDE(3, 8, 8);
+#define GWQ_WIDE(B, UU, RR, CC) \
+    if (bits == B && best_u == UU && mr == RR && best_copies == CC) \
+        return tune.bf16 ? launch_kernel<&decode_wide_kernel<B, UU, RR, false, true, CC>>(batch, count, blocks, best_w, best_lds, st) \
+               : fine    ? launch_kernel<&decode_wide_kernel<B, UU, RR, true, false, CC>>(batch, count, blocks, best_w, best_lds, st) \
+                         : launch_kernel<&decode_wide_kernel<B, UU, RR, false, false, CC>>(batch, count, blocks, best_w, best_lds, st)
+            GWQ_WIDE(4, 4, 8, 1); GWQ_WIDE(4, 4, 16, 1); GWQ_WIDE(4, 8, 8, 1); GWQ_WIDE(4, 2, 8, 2); GWQ_WIDE(4, 4, 8, 2);
+            GWQ_WIDE(3, 4, 8, 1); GWQ_WIDE(3, 4, 16, 1); GWQ_WIDE(3, 8, 8, 1); GWQ_WIDE(3, 2, 8, 2); GWQ_WIDE(3, 4, 8, 2);
 #undef GWQ_WIDE
         }
     }

@@ -175,13 +175,14 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert plan([q, q, q], 1).startswith("decode_small_kernel<4,8,1> grid 256x3")
     assert plan([down], 1).startswith("decode_small_kernel<4,8,1> grid 256x1 block 704")
     assert plan([gate, gate], 16).startswith("decode_stream_kernel<4,16>")          # several tiles per block
-    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16,false,false>")                  # one tile per block
+    assert plan([q], 16).startswith("decode_wide_kernel<4,4,16,false,false,1>")                # one tile per block
     assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_small_kernel<3,8,8> grid 256x1 block 256 lds 78000")   # two blocks per CU
     assert plan([_packed(N=4096, K=4096, bits=3)], 9).startswith("decode_wide_kernel<3,")
+    assert plan([down], 8).startswith("decode_wide_kernel<4,4,8,false,false,2>")    # several phases at M <= 8: two copies of X
     assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4,false,false> tile 256x128 grid 256 ")
     q16 = _packed(N=4096, K=4096, group=16)               # groups of 16: the wide decode kernel and the GEMM in their small-group forms
     assert plan([q16], 1).startswith("decode_small_kernel<4,8,1,true>") and plan([q16], 2048).startswith("gemm_kernel<4,2,2,4,true,false>")
-    assert plan([q16], 16).startswith("decode_wide_kernel<4,4,16,true,false>")
+    assert plan([q16], 16).startswith("decode_wide_kernel<4,4,16,true,false,1>")
     assert "k_splits 1" in plan([q], 64, scratch=0) and "k_splits 1" not in plan([q], 64, scratch=1)
     arr = (ctypes.POINTER(binding._Packed) * 2)(ctypes.pointer(q), ctypes.pointer(down))
     assert L.gwq_linear_plan(2, arr, 1, 1, buf, 256) == -2                          # one K per launch
