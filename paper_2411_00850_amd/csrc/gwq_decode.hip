@@ -678,9 +678,15 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     constexpr int kQ = (U + 3) / 4;                     // 64-vector rounds covering U groups (U = 2: half a round)
     const int x_row = r < M ? r : 0;
     const act_t *x_lane = xs + (uint32_t)x_row * x_stride + wave * (U * kGroup) + 32 * b;
+    // Outliers: lane (r, b) adds rows rb .. rb + 3 of its share of channel r's entries.  With 16 rows staged the four
+    // lanes of a channel take the same entries, four rows each; with 8 the lanes b >= 2, whose MFMA rows do not
+    // exist, take every second entry instead (their sums meet those of lanes b - 2 in the final reduction).
+    constexpr bool kFold = MR == 8;
+    const int rb = kFold ? 4 * (b & 1) : 4 * b;
+    const int o_stride = kFold ? 2 * nwaves : nwaves;
     const act_t *x_out[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(4 * b + e < M ? 4 * b + e : 0) * x_stride;   // rows m >= M are not stored
+    for (int e = 0; e < 4; ++e) x_out[e] = xs + (uint32_t)(rb + e < M ? rb + e : 0) * x_stride;   // rows m >= M are not stored
     const uint32_t *entries = reinterpret_cast<const uint32_t *>(lds_raw + ent_off);
 
     // A block takes the 16-channel tiles blockIdx.x, blockIdx.x + gridDim.x, ...: when all of K is
@@ -735,10 +741,12 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
     }
     const int staged_end = e0 + window < e_end ? e0 + window : e_end;
 
-    const bool o_live = n < N && 4 * b < M;
-    int j = rp0 + wave;                                 // cursor into this lane's share of the channel's outliers
+    const bool o_live = n < N && rb < M;
+    int j = rp0 + (kFold ? 2 * wave + (b >> 1) : wave); // cursor into this lane's share of the channel's outliers
     const int j_end = o_live ? rp1 : 0;
     float4v acc = float4v{0.f, 0.f, 0.f, 0.f};
+    float4v oacc = float4v{0.f, 0.f, 0.f, 0.f};         // outlier sums, apart from the MFMA results where lanes fold
+    float4v &osum = kFold ? oacc : acc;
 
     // X columns of this wave's groups in phase ph, row by row, straight into LDS copy ph % 2: a row's share is 512
     // bytes to 2 KB in memory and in the LDS copy alike, so lane l brings vector l of it.  Vectors beyond K are
@@ -911,7 +919,7 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             bool ok[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int idx = j + i * nwaves;
+                const int idx = j + i * o_stride;
                 const bool in = idx < j_staged;
                 const int li = in ? idx - e0 : 0;
                 const uint32_t entry = entries[li];
@@ -930,8 +938,8 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(val[i], (float)xv[i][e], acc[e]);
-            j += ((int)ok[0] + (int)ok[1] + (int)ok[2] + (int)ok[3]) * nwaves;
+                for (int e = 0; e < 4; ++e) osum[e] = __builtin_fmaf(val[i], (float)xv[i][e], osum[e]);
+            j += ((int)ok[0] + (int)ok[1] + (int)ok[2] + (int)ok[3]) * o_stride;
             if (!ok[3]) break;
         }
         while (j >= staged_end && j < j_end) {          // very long rows only
@@ -939,21 +947,23 @@ __global__ __launch_bounds__(512) void decode_wide_kernel(const DecodeBatch batc
             if (col >= c1) break;
             const float v = (float)__builtin_bit_cast(_Float16, out_val[j]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(v, (float)xo[e][col - c0], acc[e]);
-            j += nwaves;
+            for (int e = 0; e < 4; ++e) osum[e] = __builtin_fmaf(v, (float)xo[e][col - c0], osum[e]);
+            j += o_stride;
         }
         if (block == (int)blockIdx.x && ph < 3) GWQ_STAMP_AT(4 + 3 * ph);    // outliers added
         if (x_copies == 1 && ph + 1 < phases) __syncthreads();                // everybody is done with the only copy of X
     }
 
-    // Fixed-order reduction over the waves, then FP16 store.
+    // Fixed-order reduction over the waves, then FP16 store.  Folded lanes (b >= 2 with 8 rows staged) hand over their
+    // outlier sums alone: their MFMA rows are copies of row 0.
 #pragma unroll
-    for (int e = 0; e < 4; ++e) red[(wave * 4 + e) * 64 + lane] = acc[e];
+    for (int e = 0; e < 4; ++e) red[(wave * 4 + e) * 64 + lane] = !kFold ? acc[e] : b >= 2 ? oacc[e] : acc[e] + oacc[e];
     __syncthreads();
     for (int idx = tid; idx < 256; idx += nthreads) {
-        float sum = 0.f;
-        for (int w = 0; w < nwaves; ++w) sum += red[w * 256 + idx];
         const int e = idx >> 6, l = idx & 63;
+        if (kFold && l >= 32) continue;
+        float sum = 0.f;
+        for (int w = 0; w < nwaves; ++w) sum += kFold ? red[w * 256 + idx] + red[w * 256 + idx + 32] : red[w * 256 + idx];
         const int nn = row0 + (l & 15), m = 4 * (l >> 4) + e;
         if (nn < N && m < M) Y[(size_t)m * N + nn] = (act_t)sum;
     }
