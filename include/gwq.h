@@ -257,7 +257,9 @@ gwq_status gwq_probe_mfma(int32_t blocks, int32_t iters, void *sink, void *strea
  * "decode_stream" (1: never the streaming decode kernel; 2: also for M <= 4, wherever K <= 4096 lets it
  * run; by default it takes the launches of 5 <= M <= 16 there that the kernel for M <= 8 does not, with two or more tiles per block), "decode_tiles" (16-channel tiles per block of the streaming
  * kernel, 1..4096), "decode_lean_rows" (1..8: the largest M handled by the kernel that keeps all of X[M][K] in LDS,
- * where it fits), "pack_full_passes" (1: gwq_pack finds the threshold and the per-row counts by passes over all
+ * where it fits), "decode_pairs" (that kernel with two neighbouring 16-channel tiles per block, which share one copy of X
+ * in LDS, for 5 <= M <= 8: 1 never, 2 wherever it fits; by default where the launch has at least four tiles per compute
+ * unit), "pack_full_passes" (1: gwq_pack finds the threshold and the per-row counts by passes over all
  * scores even where the short list of candidate keys would do), "gemm_rows" (rows of Y per block of the GEMM: 32, 64, 128 or 256; by default 256 beyond
  * M = 512 and below that the shape a cost model of the launch expects to be fastest).  Unknown keys or
  * out-of-range values return GWQ_ERR_UNSUPPORTED. */

@@ -40,9 +40,10 @@ std::atomic<int> g_gemm_ms{0};        // rows of Y per GEMM block; 0 = heuristic
 std::atomic<int> g_decode_stream{0};  // 0 = heuristic, 1 = never the streaming kernel, 2 = wherever it can run
 std::atomic<int> g_decode_tiles{0};   // tiles per block of the streaming kernel; 0 = heuristic
 std::atomic<int> g_decode_lean{0};    // largest M of the kernel that keeps X[M][K] in LDS; 0 = built-in
+std::atomic<int> g_decode_pairs{0};   // two tiles per block in that kernel for 5 <= M <= 8: 0 = heuristic, 1 = never, 2 = wherever it fits
 std::atomic<int> g_pack_full{0};      // 1: gwq_pack always runs its passes over all scores (never the candidate list)
 
-gwq::DecodeTuning decode_tuning() { return gwq::DecodeTuning{g_decode_waves, g_decode_stream, g_decode_tiles, g_decode_lean}; }
+gwq::DecodeTuning decode_tuning() { return gwq::DecodeTuning{g_decode_waves, g_decode_stream, g_decode_tiles, g_decode_lean, g_decode_pairs}; }
 
 gwq_status check_shape(int64_t N, int64_t K, int bits, int group, uint32_t ppm)
 {
@@ -410,6 +411,11 @@ gwq_status gwq_tuning_set(const char *key, int32_t value)
     if (!strcmp(key, "decode_lean_rows")) {
         if (value < 0 || value > 8) return GWQ_ERR_UNSUPPORTED;
         g_decode_lean = value;
+        return GWQ_OK;
+    }
+    if (!strcmp(key, "decode_pairs")) {
+        if (value < 0 || value > 2) return GWQ_ERR_UNSUPPORTED;
+        g_decode_pairs = value;
         return GWQ_OK;
     }
     if (!strcmp(key, "pack_full_passes")) {

@@ -229,20 +229,23 @@ __device__ inline float silu(float x)
 }
 
 //
+// PAIR (five to eight rows, plain products): two neighbouring tiles per block, one set of waves each, one copy of X
+// between them; each set stages every second row of X and half the CSR window.  What a tile costs beyond four rows
+// is mostly its copy of X, read from L2 by every block.
 // FINE: groups below 128.  The staged metadata is [16][spr] (up to three vectors per thread); a lane takes scale and
 // zero point per half slot, with the indices of a group at or beyond gpr clamped into the row and its scales masked,
 // and multiplies FP16 operands s * (q - z), as the wide kernel does for such layers.
 // BF16: X and Y are bfloat16; operands 128 + q and a second set of MFMAs against ones, as in the wide kernel.
-template <int BITS, int U, int MS, int MODE, bool FINE = false, bool BF16 = false>
+template <int BITS, int U, int MS, int MODE, bool FINE = false, bool BF16 = false, bool PAIR = false>
 __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, const int layer)
 {
+    static_assert(!PAIR || (MODE == 0 && !FINE && !BF16 && MS > 4), "paired tiles: plain products of more than four rows");
     static_assert(!FINE || MODE == 0, "gated pairs: groups of 128 only");
     static_assert(!BF16 || (MODE == 0 && !FINE), "bfloat16 activations: plain products with groups of 128 only");
     typedef std::conditional_t<BF16, __bf16, _Float16> act_t;          // X and Y; both 16 bits wide
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const DecodeProblem &pr = batch.p[layer];
     const int N = pr.N, K = pr.K;
-    const int block = blockIdx.x;
     const uint32_t *__restrict__ qweight = pr.qweight;
     const uint16_t *__restrict__ scales = pr.scales;
     const uint8_t *__restrict__ zeros = pr.zeros;
@@ -257,11 +260,21 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     // keeps the compiler from moving the other loads behind the branch on N).
     asm volatile("" ::"s"(qweight), "s"(scales), "s"(zeros), "s"(row_ptr), "s"(col_idx), "s"(out_val), "s"(X), "s"(Y),
                  "s"(K), "s"(sc_last_vec), "s"(zp_last_vec), "s"(csr_last_vec), "s"(shift));
-    if (block * 16 >= N) return;                        // the grid is as wide as the largest layer
+    if ((int)blockIdx.x * (PAIR ? 32 : 16) >= N) return;    // the grid is as wide as the largest layer
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nwaves = batch.nwaves, nthreads = nwaves * 64;
+    // PAIR: the block's waves form two sets that work on two neighbouring 16-channel tiles with one copy of X
+    // between them (each set stages every second row of it): half the reads of X per tile, which is what rows
+    // five to eight cost over fewer.  Below, tid, wave, nwaves and nthreads are those of the set; everything
+    // per tile in LDS exists once per set.  A set whose tile lies beyond N works on the last tile and stores nothing.
+    const int lane = threadIdx.x & 63;
+    const int block_wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int nwaves = PAIR ? batch.nwaves / 2 : batch.nwaves, nthreads = nwaves * 64;
+    const int set = PAIR ? block_wave / nwaves : 0;
+    const int wave = block_wave - set * nwaves;
+    const int tid = (int)threadIdx.x - set * nthreads;
+    const int tile = PAIR ? 2 * (int)blockIdx.x + set : (int)blockIdx.x;
+    const bool tile_live = !PAIR || tile * 16 < N;
+    const int block = tile_live ? tile : (N - 1) / 16;
     GWQ_TS_DECL;
     GWQ_TS(0);                                          // descriptor has arrived
     const int r = lane & 15, b = lane >> 4;
@@ -277,11 +290,15 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     const int n_c = n < N ? n : N - 1;                  // clamped channel: its results are not stored
 
     act_t *xs = reinterpret_cast<act_t *>(lds_raw);
-    const uint32_t sc_off = (uint32_t)MS * k_pad * 2;
+    // Staged CSR entries: eight per thread; in a pair four (the first half of the set's threads bring them), which
+    // is what lets two blocks share a CU at eight rows and K = 4096.
+    const int window = PAIR ? 4 * nthreads : 8 * nthreads;
+    const uint32_t set_bytes = PAIR ? 48u * spr + 16u + 4u * window + 32u + (uint32_t)nwaves * MS * 64u : 0u;
+    const uint32_t sc_off = (uint32_t)MS * k_pad * 2 + (uint32_t)set * set_bytes;
     const uint32_t zp_off = sc_off + 32 * spr;
     const uint32_t spare_off = zp_off + 16 * spr;
     const uint32_t ent_off = spare_off + 16;
-    const uint32_t red_off = ent_off + 32 * nthreads + 32;
+    const uint32_t red_off = ent_off + 4 * window + 32;
     float *red = reinterpret_cast<float *>(lds_raw + red_off);
 
     // CSR bounds of the block and of this lane's channel.  The block's bounds are read through a pointer to
@@ -298,13 +315,15 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     // Staging loads, all 16-byte and coalesced.  (1) X: each wave brings the columns of its own
     // groups; vectors beyond K are loaded from column 0 and replaced by zeros when stored.
     constexpr int kQ = U / 4;                           // 64-vector rounds covering U groups
-    u32x4 xstage[MS * kQ];
+    constexpr int kXRows = PAIR ? (MS + 1) / 2 : MS;    // rows of X a wave stages: all, or every second one from `set`
+    u32x4 xstage[kXRows * kQ];
 #pragma unroll
-    for (int e = 0; e < MS; ++e)
+    for (int ei = 0; ei < kXRows; ++ei)
 #pragma unroll
         for (int i = 0; i < kQ; ++i) {
+            const int e = PAIR ? (2 * ei + set < MS ? 2 * ei + set : 0) : ei;
             const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
-            xstage[e * kQ + i] = reinterpret_cast<const u32x4 *>(X)[e * (K / 8) + (kv < K / 8 ? kv : 0)];
+            xstage[ei * kQ + i] = reinterpret_cast<const u32x4 *>(X)[e * (K / 8) + (kv < K / 8 ? kv : 0)];
         }
     // (2) The block's scales (32 gpr bytes) and zero points (16 gpr bytes), contiguous in memory for
     // 16 consecutive channels: thread t < 2 gpr takes a scales vector, the next gpr threads a
@@ -361,12 +380,13 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     GWQ_TS(1);                                          // staging and the first codes requested
     const DecodeConsts dc(BITS);
 #pragma unroll
-    for (int e = 0; e < MS; ++e)
+    for (int ei = 0; ei < kXRows; ++ei)
 #pragma unroll
         for (int i = 0; i < kQ; ++i) {
+            const int e = PAIR ? (2 * ei + set < MS ? 2 * ei + set : 0) : ei;   // past the last row: row 0 again, same bytes
             const int kv = g_begin * (kGroup / 8) + lane + 64 * i;
             reinterpret_cast<u32x4 *>(xs)[e * (k_pad / 8) + kv] =
-                kv < K / 8 ? xstage[e * kQ + i] : u32x4{0u, 0u, 0u, 0u};
+                kv < K / 8 ? xstage[ei * kQ + i] : u32x4{0u, 0u, 0u, 0u};
         }
     // Bytes beyond the end of scales or zeros (the last block of a ragged N, and the spare slot) are
     // stored as zeros: the groups at or beyond gpr of the last channel and of channel 15 read them.
@@ -403,7 +423,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
         seg_col = reinterpret_cast<const u32x4 *>(col_idx)[v];
         seg_val = reinterpret_cast<const u32x4 *>(out_val)[v];
     }
-    const int staged_end = e0 + 8 * nthreads < e_end ? e0 + 8 * nthreads : e_end;
+    const int staged_end = e0 + window < e_end ? e0 + window : e_end;
     __builtin_amdgcn_sched_barrier(0);
 
     // A lane's MFMA results are rows 4b .. 4b+3 of its channel: rows below MS are kept.
@@ -474,17 +494,17 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     GWQ_TS(3);                                          // all codes multiplied
     // The CSR segment has arrived by now: publish it, followed by one vector of zero entries that
     // lanes without an entry read instead.
-    store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
+    if (!PAIR || 8 * tid < window) store_entries(reinterpret_cast<u32x4 *>(lds_raw + ent_off) + 2 * tid, seg_col, seg_val);
     if (tid == 0) {
-        reinterpret_cast<u32x4 *>(lds_raw + ent_off)[2 * nthreads] = u32x4{0u, 0u, 0u, 0u};
-        reinterpret_cast<u32x4 *>(lds_raw + ent_off)[2 * nthreads + 1] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4 *>(lds_raw + ent_off)[window / 4] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4 *>(lds_raw + ent_off)[window / 4 + 1] = u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
 
     // Outliers: the 4 * waves lanes of a channel split its entries and sum rows m = 0 .. MS-1.
     // Entry j sits at LDS index j - e0 when j < staged_end.
     const int o_stride = 4 * nwaves;
-    const bool o_live = n < N;
+    const bool o_live = n < N && tile_live;
     const int o_end = o_live ? (rp1 < staged_end ? rp1 : staged_end) : 0;   // end of the lane's staged entries
     const uint32_t *entries = reinterpret_cast<const uint32_t *>(lds_raw + ent_off);
     float oacc[MS];
@@ -503,7 +523,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
 #pragma unroll
     for (int i = 0; i < kPre; ++i) {
         const int j = j_first + i * o_stride;
-        staged(j < o_end ? j - e0 : 8 * nthreads);      // the zero entry when the lane has none
+        staged(j < o_end ? j - e0 : window);            // the zero entry when the lane has none
     }
     if (j_first + kPre * o_stride < o_end || (o_live && rp1 > staged_end)) {
         int j = j_first + kPre * o_stride;
@@ -534,7 +554,7 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
             const int e = idx >> 4, c = idx & 15;
             float sum = 0.f;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * MS + e) * 16 + c];
-            if (row0 + c < N) Y[(size_t)e * N + row0 + c] = (act_t)sum;
+            if (tile_live && row0 + c < N) Y[(size_t)e * N + row0 + c] = (act_t)sum;
         }
         GWQ_TS(6);
         GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
@@ -572,10 +592,10 @@ __device__ __forceinline__ void decode_small_body(const DecodeBatch &batch, cons
     GWQ_TS_FLUSH(wave == 0, wave == nwaves - 1);
 }
 
-template <int BITS, int U, int MS, bool FINE = false, bool BF16 = false>
+template <int BITS, int U, int MS, bool FINE = false, bool BF16 = false, bool PAIR = false>
 __global__ __launch_bounds__(1024) void decode_small_kernel(const DecodeBatch batch)
 {
-    decode_small_body<BITS, U, MS, 0, FINE, BF16>(batch, blockIdx.y);
+    decode_small_body<BITS, U, MS, 0, FINE, BF16, PAIR>(batch, blockIdx.y);
 }
 
 // Grid row y multiplies layers 2y (gate) and 2y + 1 (up, whose Y receives H) of the batch, one after the other
@@ -1395,8 +1415,17 @@ hipError_t launch_kernel(const DecodeBatch &batch, int count, int blocks, int nw
 
 template <int BITS>
 hipError_t launch_small(const DecodeBatch &batch, int count, int blocks, int nwaves, int u, int ms, size_t lds,
-                        bool gated_pairs, bool fine, bool bf16, hipStream_t st)
+                        bool gated_pairs, bool fine, bool bf16, bool pair, hipStream_t st)
 {
+    if (pair) {                                         // nwaves: both sets of waves
+#define GWQ_SMALL_PAIR(UU, MM) \
+    if (u == UU && ms == MM && !gated_pairs && !fine && !bf16) \
+        return launch_kernel<&decode_small_kernel<BITS, UU, MM, false, false, true>>(batch, count, blocks, nwaves, lds, st)
+        GWQ_SMALL_PAIR(4, 5); GWQ_SMALL_PAIR(4, 6); GWQ_SMALL_PAIR(4, 7); GWQ_SMALL_PAIR(4, 8);
+        GWQ_SMALL_PAIR(8, 5); GWQ_SMALL_PAIR(8, 6); GWQ_SMALL_PAIR(8, 7); GWQ_SMALL_PAIR(8, 8);
+#undef GWQ_SMALL_PAIR
+        return hipErrorInvalidValue;
+    }
     if (bf16) {
 #define GWQ_SMALL_BF16(UU, MM) \
     if (u == UU && ms == MM && !gated_pairs && !fine) \
@@ -1495,6 +1524,24 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
         const bool roomy = M <= 4 || 2 * lds <= kMaxLds || total_blocks <= 3 * device_cus();
         // Small groups: at most three metadata vectors per thread (3 spr <= 3 blockDim).
         const bool fine_ok = !fine || (u <= 8 && max_spr <= 64 * nwaves);
+        // Beyond four rows, two neighbouring tiles per block with one copy of X between them (half the reads of X
+        // per tile) where the launch still has two blocks for every CU and two such blocks share a CU's LDS.
+        const size_t set_bytes = meta + (size_t)16 * nwaves * 64 + 32 + (size_t)nwaves * M * 64;
+        const size_t lds_pair = x_bytes + 2 * set_bytes;
+        const bool pair = M > 4 && !fine && !tune.bf16 && !tune.gated_pairs && u <= 8 && 2 * nwaves <= 16 &&
+                          x_bytes <= kXLdsBudget && 2 * lds_pair <= kMaxLds && tune.pairs != 1 &&
+                          (tune.pairs == 2 || total_blocks >= 4 * device_cus());
+        if (pair) {
+            batch.nwaves = 2 * nwaves;
+            const int grid = (blocks + 1) / 2;
+            if (describe) {
+                snprintf(describe->text, sizeof(describe->text), "decode_small_kernel<%d,%d,%d,false,false,true> grid %dx%d block %d lds %zu",
+                         bits, u, M, grid, count, 128 * nwaves, lds_pair);
+                return hipSuccess;
+            }
+            return bits == 4 ? launch_small<4>(batch, count, grid, 2 * nwaves, u, M, lds_pair, false, false, false, true, st)
+                             : launch_small<3>(batch, count, grid, 2 * nwaves, u, M, lds_pair, false, false, false, true, st);
+        }
         if (nwaves <= 16 && (u < 16 || M <= (tune.bf16 ? 1 : 2)) && x_bytes <= kXLdsBudget && lds <= kMaxLds && (M <= 4 || u <= 8) && roomy && fine_ok) {
             batch.nwaves = nwaves;
             if (describe) {
@@ -1504,8 +1551,8 @@ hipError_t launch_decode(int count, const gwq_packed *const *P, const void *cons
                          64 * nwaves, lds);
                 return hipSuccess;
             }
-            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, tune.bf16, st)
-                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, tune.bf16, st);
+            return bits == 4 ? launch_small<4>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, tune.bf16, false, st)
+                             : launch_small<3>(batch, count, blocks, nwaves, u, M, lds, tune.gated_pairs, fine, tune.bf16, false, st);
         }
     }
     if (tune.gated_pairs) return hipErrorNotSupported;  // only the kernel above multiplies gated pairs

@@ -57,6 +57,7 @@ hipError_t launch_pack(const void *W, const void *score, int score_is_f16, const
 struct DecodeTuning {
     int waves, stream, tiles;
     int lean_rows = 0;          // largest M the kernel with X[M][K] in LDS takes (0 = built-in choice, at most 8)
+    int pairs = 0;              // that kernel with two tiles per block for 5 <= M <= 8: 0 = built-in choice, 1 = never, 2 = wherever it fits
     bool gated_pairs = false;   // layers (2i, 2i+1) are gate and up of a gated pair: one launch writes silu(gate) * up into Y[2i+1]
     bool bf16 = false;          // X and Y are bfloat16 (groups of 128 only; the kernel for any M <= 16 takes these)
 };

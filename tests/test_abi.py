@@ -179,6 +179,8 @@ def test_linear_plan_names_the_kernel_without_a_device():
     assert plan([_packed(N=4096, K=4096, bits=3)], 8).startswith("decode_small_kernel<3,8,8> grid 256x1 block 256 lds 78000")   # two blocks per CU
     assert plan([_packed(N=4096, K=4096, bits=3)], 9).startswith("decode_wide_kernel<3,")
     assert plan([down], 8).startswith("decode_wide_kernel<4,4,8,false,false,2>")    # several phases at M <= 8: two copies of X
+    assert plan([gate, gate], 8).startswith("decode_small_kernel<4,8,8,false,false,true> grid 344x2 block 512 lds 81120")   # two tiles per block
+    assert plan([q, q, q], 8).startswith("decode_small_kernel<4,8,8> grid 256x3")              # fewer than four tiles per CU: one
     assert plan([q], 2048).startswith("gemm_kernel<4,2,2,4,false,false> tile 256x128 grid 256 ")
     q16 = _packed(N=4096, K=4096, group=16)               # groups of 16: the wide decode kernel and the GEMM in their small-group forms
     assert plan([q16], 1).startswith("decode_small_kernel<4,8,1,true>") and plan([q16], 2048).startswith("gemm_kernel<4,2,2,4,true,false>")
@@ -201,7 +203,7 @@ def test_launch_plans_stay_within_the_machine():
     L = binding.lib()
     buf = ctypes.create_string_buffer(256)
     rng = np.random.default_rng(2024)
-    keys = ["decode_waves", "decode_stream", "decode_tiles", "decode_lean_rows", "gemm_rows"]
+    keys = ["decode_waves", "decode_stream", "decode_tiles", "decode_lean_rows", "decode_pairs", "gemm_rows"]
     seen = set()
     try:
         for case in range(1500):
@@ -220,6 +222,7 @@ def test_launch_plans_stay_within_the_machine():
                 L.gwq_tuning_set(b"decode_stream", int(rng.choice([0, 1, 2])))
                 L.gwq_tuning_set(b"decode_tiles", int(rng.choice([0, 1, 3, 7])))
                 L.gwq_tuning_set(b"decode_lean_rows", int(rng.choice([0, 1, 4, 8])))
+                L.gwq_tuning_set(b"decode_pairs", int(rng.choice([0, 1, 2])))
             if case % 3 == 2:
                 L.gwq_tuning_set(b"gemm_rows", int(rng.choice([0, 32, 64, 128, 256])))
             layers = [_packed(N=n, K=K, bits=bits, group=group) for n in Ns]
@@ -299,6 +302,7 @@ def test_tuning_and_strings():
     assert L.gwq_tuning_set(b"nonsense", 1) == -3
     assert L.gwq_tuning_set(None, 1) == -1
     assert L.gwq_tuning_set(b"decode_waves", 2) == 0 and L.gwq_tuning_set(b"decode_waves", 0) == 0
+    assert L.gwq_tuning_set(b"decode_pairs", 3) == -3 and L.gwq_tuning_set(b"decode_pairs", 2) == 0 and L.gwq_tuning_set(b"decode_pairs", 0) == 0
     assert L.gwq_tuning_set(b"gemm_rows", 48) == -3 and L.gwq_tuning_set(b"gemm_rows", 512) == -3
     for rows in (32, 64, 128, 256, 0):
         assert L.gwq_tuning_set(b"gemm_rows", rows) == 0

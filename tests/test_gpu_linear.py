@@ -95,6 +95,28 @@ def test_decode_streaming_kernel(bits, N, K, ppm, tiles):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,ppm", [(1, 128, 10000), (17, 256, 10000), (33, 1536, 10000), (47, 640, 300000), (150, 2048, 10000),
+                                     (333, 4096, 10000), (96, 512, 1000000), (100, 3968, 0)])
+def test_decode_two_tiles_per_block(bits, N, K, ppm):
+    """The kernel for M <= 8 in its paired form (two neighbouring tiles per block, one copy of X between two sets of
+    waves, each staging every second row; half the staged CSR window), forced on for every M it takes: odd tile counts
+    (the second set of the last block has no tile), ragged N, one to eight waves per set, rows with more outliers
+    than the window holds."""
+    import paper_2411_00850_amd as gwq
+    from gpu_helpers import assert_close, to_gpu, upload_packed
+    P, rng = _problem(N * 3 + K + bits + ppm % 11, N, K, bits, ppm=ppm)
+    D = upload_packed(P)
+    gwq.tuning_set("decode_pairs", 2)
+    try:
+        for M in (5, 6, 7, 8):
+            assert ",true> grid %dx1" % ((N + 31) // 32) in gwq.linear_plan(D, M)
+            X = gs.activations(M, K, rng)
+            assert_close(gwq.linear(D, to_gpu(X)).cpu().numpy(), orc.linear_f64(P, X), f"pairs N={N} K={K} M={M} bits={bits} ppm={ppm}")
+    finally:
+        gwq.tuning_set("decode_pairs", 0)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("ppm", [0, 1000000, 200000])
 def test_decode_outlier_extremes(bits, ppm):
     """No outliers, only outliers (a dense FP16 layer in CSR form), and a heavy 20 %."""
