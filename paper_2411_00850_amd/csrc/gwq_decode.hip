@@ -27,7 +27,9 @@
 //     in through the scalar cache;
 //   * the instructions a wave issues: wave-uniform values are kept in scalar registers, offsets
 //     are compile-time constants, and nothing in the multiply is predicated.
-// Two kernels: the lean one for M <= 4 with all of X in LDS, the wide one for everything else.
+// Three kernels: the lean one for M <= 8 with all of X in LDS, the streaming one for M <= 16 and K <= 4096 where a
+// block has several tiles (X in registers, its transpose in LDS), the wide one for everything else (X through LDS
+// in phases of K).
 #include <stdio.h>
 
 #include <type_traits>
@@ -622,13 +624,16 @@ __global__ __launch_bounds__(1024) void decode_small_gate_up_kernel(const Decode
 // last phase such a group can lie up to a whole chunk beyond gpr, so what it finds in LDS may be
 // anything, and a NaN scale, or a 3-bit zero point that carries the decoder's constants into the
 // NaN patterns, would turn its exact zero into a NaN.  (The 4-bit decoder's constants are finite
-// for every byte, so there the scale alone is masked.)  At most 8 waves, so that the staging
-// registers of X (MR * U / 4 vectors per lane) fit.
+// for every byte, so there the scale alone is masked.)  At most 8 waves.  X goes from memory straight into LDS
+// (load_to_lds_16), a row's share of the wave per instruction.
 //
-// MR = 8 or 16: rows of X staged (M <= MR; rows M .. MR-1 are loaded as copies of the last row and
-// dropped).  Dynamic LDS: X [M][chunk] halves | scales [16][gpr] halves | zero points [16][gpr]
-// bytes | 96 guard bytes | CSR entries (column | value << 16), blockDim * 8 | partial sums
-// [waves][4][64] floats.
+// MR = 8 or 16: rows the MFMA tiles and the outlier lanes are laid out for (M <= MR; rows M .. MR-1 are not staged:
+// their lanes read row 0 and their results are dropped).  With 8, the lanes b >= 2 have no rows of their own and
+// take every second outlier entry of their channel instead.
+// COPIES = 2 (M <= 8 with several phases): two LDS copies of a phase's X, the next phase's requested as soon as the
+// block is through this phase's barrier, so that it arrives during the multiply and the outliers.
+// Dynamic LDS: X [COPIES][M][chunk] halves | scales [16][gpr] halves | zero points [16][gpr] bytes | 96 guard bytes |
+// CSR entries (column | value << 16), blockDim * 8 or * 4 | partial sums [waves][4][64] floats.
 //
 // FINE: layers whose groups are smaller than 128 (16, 32 or 64; Sec. 3.2 names 16).  The staged metadata
 // is [16][spr] with spr = K / group; a lane's slot of 32 codes lies in one group or, at 16, in two, so the
